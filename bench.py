@@ -1,0 +1,317 @@
+#!/usr/bin/env python3
+"""Benchmark of the operator hot path on one MI355X.
+
+A "step" is one pass over the synthetic workloads of the benchmark spec: row softmax (the
+256x1024 parity shape and its 131072x1024 bandwidth companion), LayerNorm 8192x4096 bf16,
+GEMM 4096^3 bf16, the attention-score workload (batched Q K^T / 8, then softmax of the
+262144x512 scores) and the 3x3 convolution as implicit GEMM. Every launch goes through the
+C ABI (paper_2511_03586_amd -> libperf.so); torch only owns device memory and the stream.
+
+Timing follows the paper's protocol (Section 4.2: warm-up iterations, new input data in
+every iteration): each workload cycles through enough pre-filled buffer sets that at least
+512 MiB are touched between two uses of a set, so neither L2 nor the memory-side cache can
+hold a working set from one launch to the next. Per-kernel durations are measured with HIP
+events on the launch stream inside the timed region.
+
+Prints ONE JSON line (see the design doc for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published (2.5 PFLOP/s)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--only", default="", help="comma-separated workload names (profiling aid)")
+    return ap.parse_args()
+
+
+class Workload:
+    """One timed kernel launch over rotated buffer sets."""
+
+    def __init__(self, name, kernel, bound, unit_work, launch, nsets, note=""):
+        self.name, self.kernel, self.bound = name, kernel, bound
+        self.unit_work = unit_work      # algorithmic bytes (hbm) or flops (mfma) per launch
+        self.launch, self.nsets, self.note = launch, nsets, note
+        self.ms = None
+
+    def roofline(self):
+        sec = self.ms * 1e-3
+        if self.bound == "hbm":
+            ach, peak, unit = self.unit_work / sec / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = self.unit_work / sec / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
+        return {"kernel": self.kernel, "bound": self.bound, "achieved": round(ach, 2), "peak": peak,
+                "unit": unit, "frac": round(ach / peak, 4)}
+
+
+class G:
+    """numpy -> device, bit for bit (bf16 patterns travel as int16)."""
+
+    @staticmethod
+    def dev(a):
+        import torch
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint16:
+            a = a.view(np.int16)
+        return torch.from_numpy(a).cuda()
+
+
+def build_workloads(torch, perf):
+    """Allocate rotated device buffers and return the list of Workload objects."""
+    from workloads import configs
+    st = lambda: torch.cuda.current_stream().cuda_stream
+    F32, BF16, ROW, COL = perf.PERF_F32, perf.PERF_BF16, perf.PERF_ROW_MAJOR, perf.PERF_COL_MAJOR
+    wls = []
+
+    def rotated(t, nsets):
+        """Set 0 is the seeded host tensor; set i is set 0 rolled by i rows (same values and
+        distribution at distinct addresses), generated on the device."""
+        out = torch.empty((nsets,) + tuple(t.shape), dtype=t.dtype, device="cuda")
+        for i in range(nsets):
+            out[i] = torch.roll(t, shifts=i, dims=0)
+        return out
+
+    # -- config 1: softmax fp32 256x1024 (launch-latency bound; parity shape)
+    c1 = configs.CONFIG1
+    x1 = rotated(G.dev(c1.make()["x"]), 256)
+    y1 = torch.empty_like(x1)
+    wls.append(Workload("softmax_256x1024", "softmax_rows_kernel<4,2>", "hbm", c1.bytes_moved(),
+                        lambda i: perf.perf_softmax(x1[i % 256].data_ptr(), y1[i % 256].data_ptr(), c1.rows, c1.cols,
+                                                    c1.cols, c1.cols, F32, F32, 1.0, st()),
+                        256, "launch-latency bound: 2 MiB per launch"))
+
+    # -- config 1 companion: softmax fp32 131072x1024 (1 GiB moved per launch)
+    cl = configs.CONFIG1_LARGE
+    xl = G.dev(configs.SoftmaxWorkload(rows=8192, cols=1024).make()["x"]).repeat(16, 1)
+    xl += (torch.arange(cl.rows, device="cuda", dtype=torch.float32) % 5)[:, None]
+    yl = torch.empty_like(xl)
+    wls.append(Workload("softmax_131072x1024", "softmax_rows_kernel<4,2>", "hbm", cl.bytes_moved(),
+                        lambda i: perf.perf_softmax(xl.data_ptr(), yl.data_ptr(), cl.rows, cl.cols, cl.cols, cl.cols,
+                                                    F32, F32, 1.0, st()),
+                        1, "one set already moves 1 GiB"))
+
+    # -- config 2: LayerNorm bf16 8192x4096
+    c2 = configs.CONFIG2
+    d2 = c2.make()
+    x2 = rotated(G.dev(d2["x_bf16"]), 4)
+    y2 = torch.empty_like(x2)
+    g2, b2 = G.dev(d2["gamma"]), G.dev(d2["beta"])
+    wls.append(Workload("layernorm_8192x4096_bf16", "layernorm_rows_kernel<bf16,f32,bf16,8>", "hbm", c2.bytes_moved(),
+                        lambda i: perf.perf_layernorm(x2[i % 4].data_ptr(), g2.data_ptr(), b2.data_ptr(),
+                                                      y2[i % 4].data_ptr(), None, None, c2.rows, c2.cols, c2.cols,
+                                                      c2.cols, c2.eps, BF16, F32, BF16, st()), 4))
+
+    # -- config 3: GEMM bf16 4096^3, fp32 C
+    c3 = configs.CONFIG3
+    d3 = c3.make()
+    a3, b3 = rotated(G.dev(d3["a_bf16"]), 4), rotated(G.dev(d3["b_bf16"]), 4)
+    o3 = torch.empty((4, c3.M, c3.N), dtype=torch.float32, device="cuda")
+    wls.append(Workload("gemm_4096x4096x4096_bf16", "gemm_mfma_kernel<4,4,f32>", "mfma", c3.flops(),
+                        lambda i: perf.perf_gemm(a3[i % 4].data_ptr(), b3[i % 4].data_ptr(), o3[i % 4].data_ptr(),
+                                                 c3.M, c3.N, c3.K, ROW, c3.K, COL, c3.K, c3.N, 1, 0, 0, 0, 1.0,
+                                                 BF16, F32, st()), 4))
+
+    # -- config 4: batched Q K^T / 8 (store bound) then softmax over the scores
+    c4 = configs.CONFIG4
+    d4 = c4.make()
+    q4, k4 = G.dev(d4["q_bf16"]), G.dev(d4["k_bf16"])
+    s4 = torch.empty((c4.batch, c4.seq, c4.seq), dtype=torch.float32, device="cuda")
+    p4 = torch.empty_like(s4)
+    S, D = c4.seq, c4.d
+    qk_bytes = 2 * c4.batch * S * D * 2 + c4.batch * S * S * 4
+    wls.append(Workload("attn_scores_qk_512x(512x512x64)", "gemm_mfma_kernel<4,4,f32>", "hbm", qk_bytes,
+                        lambda i: perf.perf_gemm(q4.data_ptr(), k4.data_ptr(), s4.data_ptr(), S, S, D, ROW, D, COL, D,
+                                                 S, c4.batch, S * D, S * D, S * S, c4.alpha, BF16, F32, st()),
+                        1, "28 flop/byte: bound by the 512 MiB fp32 score store, not by MFMA"))
+    wls.append(Workload("attn_softmax_262144x512", "softmax_rows_kernel<2,4>", "hbm", 8 * c4.batch * S * S,
+                        lambda i: perf.perf_softmax(s4.data_ptr(), p4.data_ptr(), c4.batch * S, S, S, S, F32, F32,
+                                                    1.0, st()), 1))
+
+    # -- config 5: conv2d 3x3 as implicit GEMM, bf16 in / bf16 out
+    c5 = configs.CONFIG5
+    d5 = c5.make()
+    x5 = rotated(G.dev(d5["x_bf16"]), 16)
+    w5 = G.dev(d5["w_bf16"])
+    y5 = torch.empty((16, c5.N, c5.P, c5.Q, c5.K), dtype=torch.int16, device="cuda")
+    wls.append(Workload("conv2d_32x56x56x64_k128_3x3_bf16", "conv2d_mfma_kernel<bf16>", "mfma", c5.flops(),
+                        lambda i: perf.perf_conv2d(x5[i % 16].data_ptr(), w5.data_ptr(), y5[i % 16].data_ptr(), c5.N,
+                                                   c5.H, c5.W, c5.C, c5.K, c5.R, c5.S, 1, 1, 1, 1, BF16, BF16, st()),
+                        16))
+    keep = (x1, y1, xl, yl, x2, y2, g2, b2, a3, b3, o3, q4, k4, s4, p4, x5, w5, y5)
+    return wls, keep
+
+
+def measure_copy_ceiling(torch, perf, iters=20):
+    """Measured HBM ceiling: the library's streaming copy over 2 x 1 GiB."""
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(3)
+    dst = torch.empty_like(src)
+    st = torch.cuda.current_stream().cuda_stream
+    for _ in range(3):
+        perf.perf_copy(src.data_ptr(), dst.data_ptr(), n, st)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        perf.perf_copy(src.data_ptr(), dst.data_ptr(), n, st)
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * n * iters / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
+def cpu_baseline(wl_rooflines):
+    """Time the CPU oracle (as it stands) on a bounded sample of every workload."""
+    import oracle
+    from workloads import configs, rng
+    threads = oracle.max_threads()
+    res = {}
+
+    def timed(fn):
+        t0 = time.perf_counter()
+        fn()
+        return time.perf_counter() - t0
+
+    x = configs.SoftmaxWorkload(rows=8192, cols=1024).make()["x"].astype(np.float64)
+    res["softmax_131072x1024"] = ("hbm", 8 * x.size / timed(lambda: oracle.softmax(x)) / 1e9, "8192 of 131072 rows")
+    d = configs.LayerNormWorkload(rows=2048).make()
+    xw = oracle.widen(d["x_bf16"], True)
+    res["layernorm_8192x4096_bf16"] = ("hbm", 4 * xw.size / timed(lambda: oracle.layernorm(xw, d["gamma"], d["beta"], 1e-5)) / 1e9,
+                                       "2048 of 8192 rows")
+    d = configs.CONFIG3.make()
+    a, b = oracle.widen(d["a_bf16"][:256], True), oracle.widen(d["b_bf16"], True)
+    res["gemm_4096x4096x4096_bf16"] = ("mfma", 2 * 256 * 4096 * 4096 / timed(lambda: oracle.gemm(a, b, 256, 4096, 4096, b_col=True)) / 1e12,
+                                       "256 of 4096 rows of C")
+    c4 = configs.AttnScoreWorkload(batch=16)
+    d = c4.make()
+    q, k = oracle.widen(d["q_bf16"], True), oracle.widen(d["k_bf16"], True)
+    sc = {}
+    t = timed(lambda: sc.setdefault("s", oracle.gemm(q, k, 512, 512, 64, b_col=True, alpha=0.125, batch=16)))
+    res["attn_scores_qk_512x(512x512x64)"] = ("hbm", (2 * q.size * 2 + 4 * 16 * 512 * 512) / t / 1e9, "16 of 512 matrices")
+    t = timed(lambda: oracle.softmax(sc["s"].reshape(-1, 512)))
+    res["attn_softmax_262144x512"] = ("hbm", 8 * 16 * 512 * 512 / t / 1e9, "8192 of 262144 rows")
+    c5 = configs.ConvWorkload(N=2)
+    d = c5.make()
+    xx, ww = oracle.widen(d["x_bf16"], True), oracle.widen(d["w_bf16"], True)
+    res["conv2d_32x56x56x64_k128_3x3_bf16"] = ("mfma", c5.flops() / timed(lambda: oracle.conv2d(xx, ww, (1, 1), (1, 1))) / 1e12,
+                                               "2 of 32 images")
+    fracs, per = [], {}
+    for name, (bound, ach, sample) in res.items():
+        peak = HBM_PEAK_GBS if bound == "hbm" else MFMA_BF16_PEAK_TFLOPS
+        fracs.append(ach / peak)
+        per[name] = {"achieved": float(f"{ach:.4g}"), "unit": "GB/s" if bound == "hbm" else "TFLOP/s", "sample": sample}
+    geo = math.exp(sum(math.log(f) for f in fracs) / len(fracs)) * 100.0
+    return {"value": float(f"{geo:.4g}"), "unit": "% of MI355X roofline (geomean over the same workloads)",
+            "cores": threads, "kind": "oracle",
+            "sample": "; ".join(f"{k}: {v['sample']}" for k, v in per.items()), "per_workload": per}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2511_03586_amd as perf
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    perf.lib()  # fail loudly if the HIP library is missing
+
+    wls, keep = build_workloads(torch, perf)
+    if args.only:
+        names = set(args.only.split(","))
+        wls = [w for w in wls if w.name in names]
+    torch.cuda.synchronize()
+
+    for s in range(args.warmup):
+        for w in wls:
+            w.launch(s)
+    torch.cuda.synchronize()
+
+    # timed region: K steps; each workload's K launches are bracketed by HIP events on the
+    # launch stream, so the per-kernel durations and the step time come from the same runs
+    K = args.steps
+    t0 = time.perf_counter()
+    events = []
+    for w in wls:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for s in range(K):
+            w.launch(args.warmup + s)
+        e1.record()
+        events.append((e0, e1))
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    for w, (e0, e1) in zip(wls, events):
+        w.ms = e0.elapsed_time(e1) / K
+    ms_per_step = sum(w.ms for w in wls)
+
+    copy_gbs = measure_copy_ceiling(torch, perf)
+
+    traffic = {}
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath))
+
+    per = []
+    headline = []
+    for w in wls:
+        r = w.roofline()
+        r["traffic"] = traffic.get(w.name)
+        entry = {"workload": w.name, "us": round(w.ms * 1e3, 2), "buffer_sets": w.nsets, "roofline": r}
+        if w.bound == "mfma":
+            entry["tflops"] = r["achieved"]
+        else:
+            entry["gbs"] = r["achieved"]
+            entry["frac_of_measured_copy"] = round(r["achieved"] / copy_gbs, 4)
+        if w.note:
+            entry["note"] = w.note
+        per.append(entry)
+        if w.name != "softmax_256x1024":      # the 2 MiB parity shape measures launch latency
+            headline.append(r["frac"])
+    value = math.exp(sum(math.log(f) for f in headline) / len(headline)) * 100.0 if headline else 0.0
+    dominant = max(wls, key=lambda w: w.ms)
+    roof = dominant.roofline()
+    roof["workload"] = dominant.name
+    roof["traffic"] = traffic.get(dominant.name)
+
+    out = {
+        "metric": "GB/s (softmax, LayerNorm) and TFLOP/s (GEMM, conv) as % of MI355X roofline",
+        "value": round(value, 2),
+        "unit": "% of roofline (geomean: softmax 131072x1024, LayerNorm, GEMM, QK^T, score softmax, conv)",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "wall_ms_per_step": round(wall_ms / K, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 operands / f32 accumulate (GEMM, conv, LayerNorm I/O); f32 (softmax)",
+        "data": "synthetic",
+        "config": {"workload": "all five BASELINE.json configs, one launch each per step "
+                               "(softmax 256x1024 + 131072x1024 companion, LayerNorm 8192x4096 bf16, GEMM 4096^3 bf16, "
+                               "512x(512x512x64) QK^T/8 + softmax, conv 32x56x56x64->128 3x3 bf16)"},
+        "roofline": roof,
+        "copy_ceiling_gbs": round(copy_gbs, 1),
+        "workloads": per,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(per)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

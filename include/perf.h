@@ -1,0 +1,126 @@
+/*
+ * perf.h - C ABI of the MI355X (gfx950) operator library.
+ *
+ * The operators are the ML-library kernels that the paper's search emits and times
+ * (table "ML operators optimized using PerfLLM", Section 4.3): row softmax, LayerNorm,
+ * dense / batched GEMM and 2-D convolution.  The paper states them as compositions of
+ * element-wise, broadcast, reduction and expression-as-location operations over dense
+ * tensors (table "Supported representation features", Section 2.1); the formulas are
+ * the standard ones of the same names.
+ *
+ * Conventions shared by every entry point
+ *  - All data pointers are DEVICE pointers (HBM), owned by the caller.  The library
+ *    allocates no device memory and keeps no state between calls.
+ *  - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL = the default
+ *    stream) and return without synchronising.  Buffers must stay alive and unmodified
+ *    until the stream has run the enqueued kernels.
+ *  - Every argument check runs on the host before any HIP call; a failed check returns
+ *    a PERF_ERR_* code and touches neither the device nor the buffers.
+ *  - Leading dimensions and strides are in ELEMENTS of the tensor's dtype.
+ *  - bf16 is bfloat16 (1-8-7); conversions to bf16 round to nearest even.  Inputs must
+ *    be finite; NaN/Inf behaviour is unspecified.
+ *  - Outputs must not overlap inputs, except y == x exactly (same pointer, same ld, same
+ *    dtype) for perf_softmax and perf_layernorm.
+ *  - Kernels use no atomics: results are bit-identical from run to run.
+ */
+#ifndef PERF_H
+#define PERF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PERF_OK = 0,
+    PERF_ERR_NULL = 1,        /* a required pointer is NULL */
+    PERF_ERR_SHAPE = 2,       /* a dimension, leading dimension, stride or padding is out of range */
+    PERF_ERR_DTYPE = 3,       /* a dtype enum is out of range */
+    PERF_ERR_LAYOUT = 4,      /* a layout enum is out of range */
+    PERF_ERR_ALIGN = 5,       /* a pointer is not aligned to its element size */
+    PERF_ERR_UNSUPPORTED = 6, /* legal but not implemented combination */
+    PERF_ERR_LAUNCH = 7       /* the HIP runtime reported an error at launch */
+} perf_status;
+
+typedef enum { PERF_F32 = 0, PERF_BF16 = 1 } perf_dtype;
+typedef enum { PERF_ROW_MAJOR = 0, PERF_COL_MAJOR = 1 } perf_layout;
+typedef void *perf_stream;
+
+/* Row softmax (Fig. "Softmax kernel representations", Section 2.1; shape row of the
+ * operator table, Section 4.3).  For each row i of the rows x cols matrix x:
+ *     y[i][j] = exp(scale*(x[i][j] - m_i)) / sum_j exp(scale*(x[i][j] - m_i)),
+ * where m_i is the row maximum of scale*x divided by scale (the max for scale >= 0, the
+ * min for scale < 0).  Arithmetic is fp32.
+ *   x, y     device, rows x cols, row stride ldx / ldy (>= cols); dtype PERF_F32 only
+ *   scale    finite
+ * Errors: NULL (x or y), SHAPE (rows/cols < 1, ld < cols), DTYPE, ALIGN (pointer not
+ * 4-byte aligned), UNSUPPORTED (dtype other than f32), LAUNCH. */
+perf_status perf_softmax(const void *x, void *y, int64_t rows, int64_t cols,
+                         int64_t ldx, int64_t ldy, perf_dtype x_dt, perf_dtype y_dt,
+                         float scale, perf_stream stream);
+
+/* LayerNorm over the last dimension (operator table, Section 4.3).  For each row:
+ *     mu = mean_j x[j];  var = mean_j (x[j]-mu)^2  (biased);  r = 1/sqrt(var + eps);
+ *     y[j] = (x[j]-mu) * r * gamma[j] + beta[j].
+ * Statistics and the affine step are fp32; the result is rounded once to y_dt.
+ *   x, y             device, rows x cols, row stride ldx / ldy; dtypes f32 or bf16
+ *   gamma, beta      device, length cols, dtype param_dt (f32 or bf16)
+ *   mean_out, rstd_out  device fp32[rows] or NULL: receive mu and r
+ * Errors: NULL (x, gamma, beta, y), SHAPE (rows/cols < 1, ld < cols, eps < 0 or not
+ * finite), DTYPE, ALIGN (pointer not aligned to its element size), LAUNCH. */
+perf_status perf_layernorm(const void *x, const void *gamma, const void *beta, void *y,
+                           float *mean_out, float *rstd_out, int64_t rows, int64_t cols,
+                           int64_t ldx, int64_t ldy, float eps, perf_dtype x_dt,
+                           perf_dtype param_dt, perf_dtype y_dt, perf_stream stream);
+
+/* Dense and batched GEMM (operator table rows "matmul" and "bmm", Section 4.3):
+ *     C_b[m][n] = alpha * sum_{k<K} A_b[m][k] * B_b[k][n],   b = 0..batch-1,
+ * bf16 (or f32) operands, fp32 accumulation, one rounding to c_dt.
+ *   A   row-major: A[m*lda + k] (lda >= K);  column-major: A[k*lda + m] (lda >= M)
+ *   B   row-major: B[k*ldb + n] (ldb >= N);  column-major: B[n*ldb + k] (ldb >= K)
+ *   C   row-major, C[m*ldc + n] (ldc >= N), dtype f32 or bf16
+ *   batch >= 1; matrix b starts strideA/strideB/strideC elements after matrix b-1
+ *   (strides >= 0; strideC must be >= the extent of one C when batch > 1).
+ * The MFMA path is taken for bf16 operands with A row-major and B column-major (both
+ * K-contiguous), K a multiple of 64, lda/ldb/strides multiples of 8 and 16-byte aligned
+ * pointers; every other legal combination runs a slower general kernel.
+ * Errors: NULL, SHAPE, DTYPE, LAYOUT, ALIGN (pointer not aligned to its element size),
+ * UNSUPPORTED (f32 operands with bf16 C), LAUNCH. */
+perf_status perf_gemm(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K,
+                      perf_layout la, int64_t lda, perf_layout lb, int64_t ldb, int64_t ldc,
+                      int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC,
+                      float alpha, perf_dtype ab_dt, perf_dtype c_dt, perf_stream stream);
+
+/* 2-D convolution as an implicit GEMM (operator table rows "conv", Section 4.3;
+ * expression-as-location indexing, Section 2.1), cross-correlation with zero padding:
+ *     y[n][p][q][k] = sum_{r<R, s<S, c<C} x[n][p*stride_h - pad_h + r][q*stride_w - pad_w + s][c]
+ *                                          * w[k][r][s][c],
+ * taps outside the image contribute 0;  P = (H + 2*pad_h - R)/stride_h + 1, Q likewise.
+ *   x  device, NHWC dense;  w  device, KRSC dense;  y  device, NPQK dense
+ *   xw_dt  dtype of x and w (bf16 or f32);  y_dt  f32 or bf16;  fp32 accumulation.
+ * The MFMA path is taken for bf16 x/w with C a multiple of 64 and 16-byte aligned
+ * pointers; other legal cases run a slower direct kernel.
+ * Errors: NULL, SHAPE (any dim < 1, stride < 1, pad < 0, filter larger than the padded
+ * image, more than 2^31-1 output pixels), DTYPE, ALIGN, LAUNCH. */
+perf_status perf_conv2d(const void *x, const void *w, void *y, int64_t N, int64_t H, int64_t W,
+                        int64_t C, int64_t K, int64_t R, int64_t S, int64_t stride_h,
+                        int64_t stride_w, int64_t pad_h, int64_t pad_w, perf_dtype xw_dt,
+                        perf_dtype y_dt, perf_stream stream);
+
+/* Plain device-to-device streaming copy of `bytes` bytes (dst and src must not overlap).
+ * It is the measured HBM ceiling the benchmark prints beside each bandwidth figure and
+ * the known-size kernel against which profiler byte counters are scaled; it is not one
+ * of the paper's operators.  Errors: NULL, SHAPE (bytes < 0), LAUNCH. */
+perf_status perf_copy(const void *src, void *dst, int64_t bytes, perf_stream stream);
+
+/* Human-readable name of a status code; static storage, never freed. */
+const char *perf_status_string(perf_status s);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int perf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PERF_H */

@@ -1,0 +1,231 @@
+// Dense / batched GEMM for gfx950 ("matmul" and "bmm" rows of the operator table,
+// Section 4.3 of the paper):  C_b = alpha * A_b * B_b, fp32 accumulation.
+//
+//  * gemm_mfma_kernel: bf16 operands, A row-major and B column-major (both K-contiguous),
+//    K a multiple of 64.  256x256 (or 128x128) workgroup tile, see mfma_tile.h.
+//  * gemm_general_kernel: any layout / dtype / size; 64x64 tile of fp32 FMAs.
+#include "mfma_tile.h"
+#include "host_utils.h"
+
+namespace perf {
+
+// Workgroup id -> output tile.  Workgroups are dealt round-robin to the 8 XCDs, each
+// with a private L2, so ids that share an XCD (equal id mod 8) are given a contiguous
+// run of tiles, and runs walk the tile grid in column-major bands of 4 tile-rows: the
+// ~32 tiles an XCD works on at once then form a compact patch sharing A and B panels.
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    const int total = tiles_m * tiles_n;
+    int id = bid;
+    if (total % 8 == 0) id = (bid % 8) * (total / 8) + bid / 8;
+    constexpr int kBand = 4;
+    const int band_tiles = kBand * tiles_n;
+    const int band = id / band_tiles;
+    const int rows_in_band = min(kBand, tiles_m - band * kBand);
+    const int within = id - band * band_tiles;
+    tm = band * kBand + within % rows_in_band;
+    tn = within / rows_in_band;
+}
+
+template <int TM, int TN, typename CT>
+__global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(const uint16_t *__restrict__ A,
+                                                                 const uint16_t *__restrict__ B, CT *__restrict__ C,
+                                                                 int M, int N, int K, int64_t lda, int64_t ldb,
+                                                                 int64_t ldc, int64_t strideA, int64_t strideB,
+                                                                 int64_t strideC, float alpha, int tiles_m, int tiles_n)
+{
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    int tm, tn;
+    tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int ktiles = K / kBK;
+
+    {
+        const int bz = blockIdx.y;
+        const uint16_t *Ab = A + (int64_t)bz * strideA;
+        const uint16_t *Bb = B + (int64_t)bz * strideB;
+        CT *Cb = C + (int64_t)bz * strideC;
+
+        // global source of each direct-to-LDS load; rows past the edge re-read the last row
+        const char *a_src[BM / 32], *b_src[BN / 32];
+#pragma unroll
+        for (int i = 0; i < BM / 32; ++i) {
+            const int row = (i * 4 + wave) * 8 + (lane >> 3);
+            const int chunk = (lane & 7) ^ swz(row);
+            a_src[i] = reinterpret_cast<const char *>(Ab + (int64_t)min(m0 + row, M - 1) * lda + chunk * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < BN / 32; ++i) {
+            const int row = (i * 4 + wave) * 8 + (lane >> 3);
+            const int chunk = (lane & 7) ^ swz(row);
+            b_src[i] = reinterpret_cast<const char *>(Bb + (int64_t)min(n0 + row, N - 1) * ldb + chunk * 8);
+        }
+
+        WaveTile<TM, TN> t;
+        t.clear();
+        const int a_row0 = wm * 32 * TM, b_row0 = wn * 32 * TN;
+        mfma_mainloop<TM, TN>(
+            t, a_src, b_src, smem, ktiles, wave, lane, a_row0, b_row0,
+            [&](int) {
+#pragma unroll
+                for (int i = 0; i < BM / 32; ++i) a_src[i] += kRowBytes;
+            },
+            [&](int) {
+#pragma unroll
+                for (int i = 0; i < BN / 32; ++i) b_src[i] += kRowBytes;
+            });
+        store_tile<TM, TN, CT>(t, Cb, ldc, M, N, m0 + a_row0, n0 + b_row0, alpha, lane);
+    }
+}
+
+// ---- general kernel ---------------------------------------------------------------
+template <typename T> __device__ __forceinline__ float load_ab(const T *p);
+template <> __device__ __forceinline__ float load_ab<float>(const float *p) { return *p; }
+template <> __device__ __forceinline__ float load_ab<uint16_t>(const uint16_t *p) { return bf16_to_f32(*p); }
+
+// 64x64 output tile, K-step 16, 256 threads each owning a 4x4 patch.  Element (m,k) of A
+// is A[m*a_sm + k*a_sk]; element (k,n) of B is B[k*b_sk + n*b_sn].
+template <typename T, typename CT>
+__global__ __launch_bounds__(256) void gemm_general_kernel(const T *__restrict__ A, const T *__restrict__ B,
+                                                           CT *__restrict__ C, int64_t M, int64_t N, int64_t K,
+                                                           int64_t a_sm, int64_t a_sk, int64_t b_sk, int64_t b_sn,
+                                                           int64_t ldc, int64_t strideA, int64_t strideB,
+                                                           int64_t strideC, int64_t batch, float alpha)
+{
+    __shared__ float As[16][65], Bs[16][65];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int64_t m0 = (int64_t)blockIdx.x * 64, n0 = (int64_t)blockIdx.y * 64;
+    for (int64_t bz = blockIdx.z; bz < batch; bz += gridDim.z) {
+        const T *Ab = A + bz * strideA;
+        const T *Bb = B + bz * strideB;
+        CT *Cb = C + bz * strideC;
+        float acc[4][4] = {};
+        for (int64_t k0 = 0; k0 < K; k0 += 16) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = tid + i * 256;
+                // walk the contiguous dimension with consecutive threads
+                int am, ak, bn, bk;
+                if (a_sk == 1) { am = idx >> 4; ak = idx & 15; } else { am = idx & 63; ak = idx >> 6; }
+                if (b_sk == 1) { bn = idx >> 4; bk = idx & 15; } else { bn = idx & 63; bk = idx >> 6; }
+                As[ak][am] = (m0 + am < M && k0 + ak < K) ? load_ab<T>(Ab + (m0 + am) * a_sm + (k0 + ak) * a_sk) : 0.f;
+                Bs[bk][bn] = (n0 + bn < N && k0 + bk < K) ? load_ab<T>(Bb + (k0 + bk) * b_sk + (n0 + bn) * b_sn) : 0.f;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                float a[4], b[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) a[i] = As[k][ty * 4 + i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) b[j] = Bs[k][tx * 4 + j];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
+            }
+            __syncthreads();
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int64_t m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+                if (m < M && n < N) store_c<CT>(Cb + m * ldc + n, alpha * acc[i][j]);
+            }
+    }
+}
+
+struct GemmArgs {
+    const void *A, *B;
+    void *C;
+    int64_t M, N, K, lda, ldb, ldc, batch, strideA, strideB, strideC;
+    int la, lb;
+    float alpha;
+    hipStream_t st;
+};
+
+template <int TM, int TN, typename CT>
+static perf_status launch_mfma(const GemmArgs &g)
+{
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
+    const size_t lds = 2 * (size_t)(BM + BN) * kRowBytes;
+    auto kern = gemm_mfma_kernel<TM, TN, CT>;
+    static bool attr_done = false;  // raising the dynamic-LDS cap is a per-function, idempotent setting
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return PERF_ERR_LAUNCH;
+        attr_done = true;
+    }
+    // grid.y carries the batch index; batches beyond the grid limit take further launches
+    for (int64_t b0 = 0; b0 < g.batch; b0 += kMaxGridYZ) {
+        const unsigned gy = (unsigned)(g.batch - b0 < kMaxGridYZ ? g.batch - b0 : kMaxGridYZ);
+        hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n), gy), dim3(kGemmThreads), lds, g.st,
+                           (const uint16_t *)g.A + b0 * g.strideA, (const uint16_t *)g.B + b0 * g.strideB,
+                           (CT *)g.C + b0 * g.strideC, (int)g.M, (int)g.N, (int)g.K, g.lda, g.ldb, g.ldc, g.strideA,
+                           g.strideB, g.strideC, g.alpha, tiles_m, tiles_n);
+    }
+    return launch_status();
+}
+
+template <typename T, typename CT>
+static perf_status launch_general(const GemmArgs &g)
+{
+    const int64_t a_sm = g.la == PERF_ROW_MAJOR ? g.lda : 1, a_sk = g.la == PERF_ROW_MAJOR ? 1 : g.lda;
+    const int64_t b_sk = g.lb == PERF_ROW_MAJOR ? g.ldb : 1, b_sn = g.lb == PERF_ROW_MAJOR ? 1 : g.ldb;
+    const int64_t gx = (g.M + 63) / 64, gy = (g.N + 63) / 64;
+    if (gx > kMaxGridX || gy > kMaxGridYZ) return PERF_ERR_UNSUPPORTED;
+    const unsigned gz = (unsigned)(g.batch < kMaxGridYZ ? g.batch : kMaxGridYZ);
+    hipLaunchKernelGGL((gemm_general_kernel<T, CT>), dim3((unsigned)gx, (unsigned)gy, gz), dim3(256), 0, g.st,
+                       (const T *)g.A, (const T *)g.B, (CT *)g.C, g.M, g.N, g.K, a_sm, a_sk, b_sk, b_sn, g.ldc,
+                       g.strideA, g.strideB, g.strideC, g.batch, g.alpha);
+    return launch_status();
+}
+
+}  // namespace perf
+
+extern "C" perf_status perf_gemm(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K,
+                                 perf_layout la, int64_t lda, perf_layout lb, int64_t ldb, int64_t ldc, int64_t batch,
+                                 int64_t strideA, int64_t strideB, int64_t strideC, float alpha, perf_dtype ab_dt,
+                                 perf_dtype c_dt, perf_stream stream)
+{
+    using namespace perf;
+    if (!A || !B || !C) return PERF_ERR_NULL;
+    if (!dtype_ok(ab_dt) || !dtype_ok(c_dt)) return PERF_ERR_DTYPE;
+    if (!layout_ok(la) || !layout_ok(lb)) return PERF_ERR_LAYOUT;
+    if (M < 1 || N < 1 || K < 1 || batch < 1) return PERF_ERR_SHAPE;
+    if (lda < (la == PERF_ROW_MAJOR ? K : M) || ldb < (lb == PERF_ROW_MAJOR ? N : K) || ldc < N) return PERF_ERR_SHAPE;
+    if (strideA < 0 || strideB < 0 || strideC < 0 || !std::isfinite(alpha)) return PERF_ERR_SHAPE;
+    if (batch > 1 && strideC < (M - 1) * ldc + N) return PERF_ERR_SHAPE;
+    // extents must be addressable with 63-bit element offsets
+    const int64_t kLim = INT64_MAX / 8;
+    const int64_t a_rows = la == PERF_ROW_MAJOR ? M : K, b_rows = lb == PERF_ROW_MAJOR ? K : N;
+    if (a_rows > kLim / lda || b_rows > kLim / ldb || M > kLim / ldc) return PERF_ERR_SHAPE;
+    if (batch > 1 && (strideA > kLim / batch || strideB > kLim / batch || strideC > kLim / batch)) return PERF_ERR_SHAPE;
+    if (ab_dt == PERF_F32 && c_dt == PERF_BF16) return PERF_ERR_UNSUPPORTED;
+    if (!aligned(A, dtype_size(ab_dt)) || !aligned(B, dtype_size(ab_dt)) || !aligned(C, dtype_size(c_dt)))
+        return PERF_ERR_ALIGN;
+
+    GemmArgs g{A, B, C, M, N, K, lda, ldb, ldc, batch, strideA, strideB, strideC, la, lb, alpha,
+               static_cast<hipStream_t>(stream)};
+    const bool mfma_ok = ab_dt == PERF_BF16 && la == PERF_ROW_MAJOR && lb == PERF_COL_MAJOR && K % kBK == 0 &&
+                         lda % 8 == 0 && ldb % 8 == 0 && strideA % 8 == 0 && strideB % 8 == 0 && aligned(A, 16) &&
+                         aligned(B, 16) && M <= (1 << 30) && N <= (1 << 30) && K <= (1 << 30) &&
+                         ((M + 127) / 128) * ((N + 127) / 128) <= kMaxGridX;
+    if (mfma_ok) {
+        // the 256x256 tile needs enough tiles to occupy the 256 CUs; otherwise 128x128
+        const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * batch;
+        if (big_tiles >= 256)
+            return c_dt == PERF_F32 ? launch_mfma<4, 4, float>(g) : launch_mfma<4, 4, uint16_t>(g);
+        return c_dt == PERF_F32 ? launch_mfma<2, 2, float>(g) : launch_mfma<2, 2, uint16_t>(g);
+    }
+    if (ab_dt == PERF_BF16)
+        return c_dt == PERF_F32 ? launch_general<uint16_t, float>(g) : launch_general<uint16_t, uint16_t>(g);
+    return launch_general<float, float>(g);
+}

@@ -1,0 +1,296 @@
+// LayerNorm over the last dimension for gfx950 ("layernorm" rows of the operator table,
+// Section 4.3 of the paper; the mean -> variance -> scale -> shift staging is the one the
+// paper describes for its batch-normalisation kernel, Section 4.3).
+//
+//  * layernorm_rows_kernel: a wavefront owns a whole row.  The row is read once with
+//    128-bit loads into registers; each lane forms (mean, M2) of its own elements and the
+//    64 lanes are merged with the Welford/Chan pairwise update over a DPP / permlane
+//    butterfly (no LDS, no barrier per row).  gamma and beta are staged once per
+//    workgroup in LDS as fp32 and re-used for every row the workgroup processes.
+//  * layernorm_block_kernel: general fallback (any length, any alignment), one workgroup
+//    per row, three passes (mean, centred sum of squares, output).
+#include "device_utils.h"
+#include "host_utils.h"
+
+namespace perf {
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int kPerChunk = 4;  // elements in one 16-byte load
+    __device__ static __forceinline__ void unpack(uint4_t raw, float *v)
+    {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t bits = raw[e];  // a bit cast must not be applied to a vector element directly
+            v[e] = __builtin_bit_cast(float, bits);
+        }
+    }
+    __device__ static __forceinline__ float load1(const float *p) { return *p; }
+    __device__ static __forceinline__ void store1(float *p, float v) { *p = v; }
+};
+template <> struct Elem<uint16_t> {  // bf16 bit patterns
+    static constexpr int kPerChunk = 8;
+    __device__ static __forceinline__ void unpack(uint4_t raw, float *v)
+    {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v[2 * e] = bf16_lo(raw[e]);
+            v[2 * e + 1] = bf16_hi(raw[e]);
+        }
+    }
+    __device__ static __forceinline__ float load1(const uint16_t *p) { return bf16_to_f32(*p); }
+    __device__ static __forceinline__ void store1(uint16_t *p, float v) { *p = f32_to_bf16(v); }
+};
+
+// Store E fp32 values as YT starting at y (16-byte aligned for the group).
+template <typename YT, int E>
+__device__ __forceinline__ void store_chunk(YT *y, const float *v)
+{
+    if constexpr (sizeof(YT) == 4) {
+#pragma unroll
+        for (int q = 0; q < E / 4; ++q)
+            __builtin_nontemporal_store(float4_t{v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]},
+                                        reinterpret_cast<float4_t *>(y) + q);
+    } else if constexpr (E == 8) {
+        uint4_t o = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
+        __builtin_nontemporal_store(o, reinterpret_cast<uint4_t *>(y));
+    } else {
+        uint2_t o = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        __builtin_nontemporal_store(o, reinterpret_cast<uint2_t *>(y));
+    }
+}
+
+constexpr int kLnThreads = 512;
+constexpr int kLnWaves = kLnThreads / 64;
+
+// XT, YT: element types of x and y; PT: element type of gamma/beta; NC: 16-byte chunks of
+// the row held per lane (cols <= NC * 64 * E); EVEN: cols == NC * 64 * E exactly.
+template <typename XT, typename PT, typename YT, int NC, bool EVEN>
+__global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const XT *__restrict__ x,
+                                                                    const PT *__restrict__ gamma,
+                                                                    const PT *__restrict__ beta, YT *__restrict__ y,
+                                                                    float *__restrict__ mean_out,
+                                                                    float *__restrict__ rstd_out, int64_t rows,
+                                                                    int cols, int64_t ldx, int64_t ldy, float eps)
+{
+    constexpr int E = Elem<XT>::kPerChunk;
+    constexpr int NCH = NC * 64;  // chunks per (padded) row
+    // gamma / beta as fp32, split in planes of 4 floats per chunk so that lane l reads
+    // 16 bytes at stride 16: plane q of chunk c holds elements c*E + 4q .. c*E + 4q+3.
+    extern __shared__ float4_t lds[];
+    float4_t *g_lds = lds;                       // [E/4][NCH]
+    float4_t *b_lds = lds + (E / 4) * NCH;       // [E/4][NCH]
+    for (int i = threadIdx.x; i < (E / 4) * NCH; i += kLnThreads) {
+        const int q = i / NCH, c = i % NCH;
+        const int col = c * E + 4 * q;
+        float4_t g = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+        if (col < cols) {  // cols is a multiple of E, so a chunk is entirely valid or not
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                g[e] = Elem<PT>::load1(gamma + col + e);
+                b[e] = Elem<PT>::load1(beta + col + e);
+            }
+        }
+        g_lds[i] = g;
+        b_lds[i] = b;
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * kLnWaves + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * kLnWaves;
+    const float inv_cols = 1.0f / (float)cols;
+
+    for (int64_t r = wave; r < rows; r += nwaves) {
+        const XT *xr = x + r * ldx;
+        uint4_t raw[NC];
+#pragma unroll
+        for (int j = 0; j < NC; ++j) {
+            const int c = (j * 64 + lane) * E;
+            if (EVEN || c < cols)
+                raw[j] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xr + c));
+            else
+                raw[j] = uint4_t{0u, 0u, 0u, 0u};
+        }
+        float v[NC][E];
+        float s = 0.f;
+        int cnt = 0;
+#pragma unroll
+        for (int j = 0; j < NC; ++j) {
+            Elem<XT>::unpack(raw[j], v[j]);
+            const bool valid = EVEN || (j * 64 + lane) * E < cols;
+#pragma unroll
+            for (int e = 0; e < E; ++e) s += v[j][e];  // padding chunks hold zeros
+            cnt += valid ? E : 0;
+        }
+        // lane-local mean and centred sum of squares over the lane's own elements
+        float n_l = (float)cnt;
+        float mean = cnt > 0 ? s / n_l : 0.f;
+        float m2 = 0.f;
+#pragma unroll
+        for (int j = 0; j < NC; ++j) {
+            const bool valid = EVEN || (j * 64 + lane) * E < cols;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                float d = v[j][e] - mean;
+                m2 += valid ? d * d : 0.f;
+            }
+        }
+        if constexpr (EVEN) {
+            wave_stats_allreduce_equal(mean, m2, (float)(NC * E));
+        } else {
+            Stats st = wave_stats_allreduce(Stats{n_l, mean, m2});
+            mean = st.mean;
+            m2 = st.m2;
+        }
+        const float var = m2 * inv_cols;
+        const float rstd = 1.0f / __builtin_sqrtf(var + eps);
+        if (lane == 0) {
+            if (mean_out) mean_out[r] = mean;
+            if (rstd_out) rstd_out[r] = rstd;
+        }
+        YT *yr = y + r * ldy;
+#pragma unroll
+        for (int j = 0; j < NC; ++j) {
+            const int ch = j * 64 + lane;
+            if (EVEN || ch * E < cols) {
+                float o[E];
+#pragma unroll
+                for (int q = 0; q < E / 4; ++q) {
+                    const float4_t g = g_lds[q * NCH + ch];
+                    const float4_t b = b_lds[q * NCH + ch];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        o[4 * q + e] = __builtin_fmaf((v[j][4 * q + e] - mean) * rstd, g[e], b[e]);
+                }
+                store_chunk<YT, E>(yr + ch * E, o);
+            }
+        }
+    }
+}
+
+// General fallback: one workgroup (256 threads) per row, scalar accesses, three passes.
+__device__ __forceinline__ float block_sum_256(float v, float *red)
+{
+    v = wave_allreduce(v, OpSum{});
+    __syncthreads();  // red may still be read from the previous use
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+template <typename XT, typename PT, typename YT>
+__global__ __launch_bounds__(256) void layernorm_block_kernel(const XT *__restrict__ x, const PT *__restrict__ gamma,
+                                                              const PT *__restrict__ beta, YT *__restrict__ y,
+                                                              float *__restrict__ mean_out,
+                                                              float *__restrict__ rstd_out, int64_t rows,
+                                                              int64_t cols, int64_t ldx, int64_t ldy, float eps)
+{
+    __shared__ float red[4];
+    const float inv_cols = 1.0f / (float)cols;
+    for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
+        const XT *xr = x + r * ldx;
+        YT *yr = y + r * ldy;
+        float s = 0.f;
+        for (int64_t c = threadIdx.x; c < cols; c += 256) s += Elem<XT>::load1(xr + c);
+        const float mean = block_sum_256(s, red) * inv_cols;
+        float q = 0.f;
+        for (int64_t c = threadIdx.x; c < cols; c += 256) {
+            float d = Elem<XT>::load1(xr + c) - mean;
+            q += d * d;
+        }
+        const float var = block_sum_256(q, red) * inv_cols;
+        const float rstd = 1.0f / __builtin_sqrtf(var + eps);
+        if (threadIdx.x == 0) {
+            if (mean_out) mean_out[r] = mean;
+            if (rstd_out) rstd_out[r] = rstd;
+        }
+        for (int64_t c = threadIdx.x; c < cols; c += 256) {
+            float xv = Elem<XT>::load1(xr + c);
+            Elem<YT>::store1(yr + c, __builtin_fmaf((xv - mean) * rstd, Elem<PT>::load1(gamma + c),
+                                                     Elem<PT>::load1(beta + c)));
+        }
+    }
+}
+
+struct LnArgs {
+    const void *x, *gamma, *beta;
+    void *y;
+    float *mean_out, *rstd_out;
+    int64_t rows, cols, ldx, ldy;
+    float eps;
+    hipStream_t st;
+};
+
+template <typename XT, typename PT, typename YT, int NC>
+static void launch_rows_nc(const LnArgs &a)
+{
+    constexpr int E = Elem<XT>::kPerChunk;
+    const size_t lds_bytes = (size_t)2 * (E / 4) * NC * 64 * sizeof(float4_t);
+    int64_t blocks = (a.rows + kLnWaves - 1) / kLnWaves;
+    if (blocks > 512) blocks = 512;  // two workgroups per CU; waves then loop over rows
+    const bool even = a.cols == (int64_t)NC * 64 * E;
+    auto kern = even ? layernorm_rows_kernel<XT, PT, YT, NC, true> : layernorm_rows_kernel<XT, PT, YT, NC, false>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kLnThreads), lds_bytes, a.st, (const XT *)a.x,
+                       (const PT *)a.gamma, (const PT *)a.beta, (YT *)a.y, a.mean_out, a.rstd_out, a.rows, (int)a.cols,
+                       a.ldx, a.ldy, a.eps);
+}
+
+template <typename XT, typename PT, typename YT>
+static void launch_typed(const LnArgs &a, bool vec_ok)
+{
+    constexpr int E = Elem<XT>::kPerChunk;
+    const int64_t chunks = (a.cols + 64 * E - 1) / (64 * E);  // chunks per lane
+    if (vec_ok && chunks <= 16) {
+        if (chunks <= 1) launch_rows_nc<XT, PT, YT, 1>(a);
+        else if (chunks <= 2) launch_rows_nc<XT, PT, YT, 2>(a);
+        else if (chunks <= 4) launch_rows_nc<XT, PT, YT, 4>(a);
+        else if (chunks <= 8) launch_rows_nc<XT, PT, YT, 8>(a);
+        else launch_rows_nc<XT, PT, YT, 16>(a);
+    } else {
+        int64_t blocks = a.rows < 65536 ? a.rows : 65536;
+        hipLaunchKernelGGL((layernorm_block_kernel<XT, PT, YT>), dim3((unsigned)blocks), dim3(256), 0, a.st,
+                           (const XT *)a.x, (const PT *)a.gamma, (const PT *)a.beta, (YT *)a.y, a.mean_out, a.rstd_out,
+                           a.rows, a.cols, a.ldx, a.ldy, a.eps);
+    }
+}
+
+template <typename XT, typename PT>
+static void launch_y(const LnArgs &a, bool vec_ok, int y_dt)
+{
+    if (y_dt == PERF_F32) launch_typed<XT, PT, float>(a, vec_ok);
+    else launch_typed<XT, PT, uint16_t>(a, vec_ok);
+}
+
+template <typename XT>
+static void launch_p(const LnArgs &a, bool vec_ok, int p_dt, int y_dt)
+{
+    if (p_dt == PERF_F32) launch_y<XT, float>(a, vec_ok, y_dt);
+    else launch_y<XT, uint16_t>(a, vec_ok, y_dt);
+}
+
+}  // namespace perf
+
+extern "C" perf_status perf_layernorm(const void *x, const void *gamma, const void *beta, void *y, float *mean_out,
+                                      float *rstd_out, int64_t rows, int64_t cols, int64_t ldx, int64_t ldy, float eps,
+                                      perf_dtype x_dt, perf_dtype param_dt, perf_dtype y_dt, perf_stream stream)
+{
+    using namespace perf;
+    if (!x || !gamma || !beta || !y) return PERF_ERR_NULL;
+    if (!dtype_ok(x_dt) || !dtype_ok(param_dt) || !dtype_ok(y_dt)) return PERF_ERR_DTYPE;
+    if (rows < 1 || cols < 1 || ldx < cols || ldy < cols || !(eps >= 0.f) || !std::isfinite(eps)) return PERF_ERR_SHAPE;
+    if (rows > (INT64_MAX / 4) / ldx || rows > (INT64_MAX / 4) / ldy) return PERF_ERR_SHAPE;
+    if (!aligned(x, dtype_size(x_dt)) || !aligned(y, dtype_size(y_dt)) || !aligned(gamma, dtype_size(param_dt)) ||
+        !aligned(beta, dtype_size(param_dt)) || (mean_out && !aligned(mean_out, 4)) ||
+        (rstd_out && !aligned(rstd_out, 4)))
+        return PERF_ERR_ALIGN;
+
+    const int64_t ex = 16 / dtype_size(x_dt);  // elements per 16-byte chunk of x
+    // the register path needs whole 16-byte chunks of x and 16-byte aligned groups of y
+    const bool vec_ok = cols % ex == 0 && ldx % ex == 0 && aligned(x, 16) && aligned(y, 16) &&
+                        (ldy * dtype_size(y_dt)) % 16 == 0;
+    LnArgs a{x, gamma, beta, y, mean_out, rstd_out, rows, cols, ldx, ldy, eps, static_cast<hipStream_t>(stream)};
+    if (x_dt == PERF_F32) launch_p<float>(a, vec_ok, param_dt, y_dt);
+    else launch_p<uint16_t>(a, vec_ok, param_dt, y_dt);
+    return launch_status();
+}

@@ -1,0 +1,71 @@
+// Status strings, version, and the streaming copy used as the measured HBM ceiling.
+#include "device_utils.h"
+#include "host_utils.h"
+
+namespace perf {
+
+// Each thread moves kCopyUnroll 16-byte vectors per iteration; all loads of an iteration
+// are issued before the first store so every lane keeps several requests in flight.
+constexpr int kCopyUnroll = 4;
+
+__global__ __launch_bounds__(256) void copy_kernel(const uint4_t *__restrict__ src, uint4_t *__restrict__ dst,
+                                                   int64_t nvec)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256 * kCopyUnroll;
+    for (int64_t base = (int64_t)blockIdx.x * 256 * kCopyUnroll + threadIdx.x; base < nvec; base += stride) {
+        uint4_t v[kCopyUnroll];
+#pragma unroll
+        for (int u = 0; u < kCopyUnroll; ++u)
+            if (base + u * 256 < nvec) v[u] = __builtin_nontemporal_load(src + base + u * 256);
+#pragma unroll
+        for (int u = 0; u < kCopyUnroll; ++u)
+            if (base + u * 256 < nvec) __builtin_nontemporal_store(v[u], dst + base + u * 256);
+    }
+}
+
+__global__ __launch_bounds__(64) void copy_tail_kernel(const unsigned char *__restrict__ src,
+                                                       unsigned char *__restrict__ dst, int64_t n)
+{
+    for (int64_t i = threadIdx.x; i < n; i += 64) dst[i] = src[i];
+}
+
+}  // namespace perf
+
+extern "C" perf_status perf_copy(const void *src, void *dst, int64_t bytes, perf_stream stream)
+{
+    using namespace perf;
+    if (!src || !dst) return PERF_ERR_NULL;
+    if (bytes < 0) return PERF_ERR_SHAPE;
+    if (bytes == 0) return PERF_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool vec = aligned(src, 16) && aligned(dst, 16);
+    const int64_t nvec = vec ? bytes / 16 : 0;
+    if (nvec > 0) {
+        int64_t blocks = (nvec + 256 * kCopyUnroll - 1) / (256 * kCopyUnroll);
+        if (blocks > 256 * 32) blocks = 256 * 32;
+        hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const uint4_t *)src, (uint4_t *)dst,
+                           nvec);
+    }
+    const int64_t done = nvec * 16;
+    if (done < bytes)
+        hipLaunchKernelGGL(copy_tail_kernel, dim3(1), dim3(64), 0, st, (const unsigned char *)src + done,
+                           (unsigned char *)dst + done, bytes - done);
+    return launch_status();
+}
+
+extern "C" const char *perf_status_string(perf_status s)
+{
+    switch (s) {
+    case PERF_OK: return "ok";
+    case PERF_ERR_NULL: return "null pointer";
+    case PERF_ERR_SHAPE: return "bad shape, leading dimension, stride or padding";
+    case PERF_ERR_DTYPE: return "bad dtype";
+    case PERF_ERR_LAYOUT: return "bad layout";
+    case PERF_ERR_ALIGN: return "misaligned pointer";
+    case PERF_ERR_UNSUPPORTED: return "unsupported combination";
+    case PERF_ERR_LAUNCH: return "HIP launch error";
+    }
+    return "unknown status";
+}
+
+extern "C" int perf_version(void) { return 100; }

@@ -1,0 +1,107 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol declared in
+include/perf.h, and rejects bad arguments before touching a device (so these run on a
+machine without a GPU). No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2511_03586_amd as perf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000  # a non-null, 16-byte aligned fake device address; never dereferenced
+
+
+@pytest.fixture(scope="module", autouse=True)
+def built():
+    if not os.path.exists(perf.LIB_PATH):
+        from paper_2511_03586_amd import build
+        build.build(verbose=False)
+
+
+def test_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "perf.h")).read()
+    declared = set(re.findall(r"\b(perf_[a-z0-9_]+)\s*\(", header))
+    declared -= {"perf_status", "perf_dtype", "perf_layout", "perf_stream"}
+    assert {"perf_softmax", "perf_layernorm", "perf_gemm", "perf_conv2d", "perf_copy",
+            "perf_status_string", "perf_version"} <= declared
+    handle = ctypes.CDLL(perf.LIB_PATH)
+    for name in declared:
+        assert hasattr(handle, name), name
+    assert declared == set(perf.SIGNATURES)
+
+
+def test_version_and_status_strings():
+    assert perf.version() >= 100
+    names = {perf.status_string(s) for s in range(8)}
+    assert len(names) == 8 and perf.status_string(0) == "ok"
+    assert perf.status_string(99) == "unknown status"
+
+
+def test_softmax_argument_errors():
+    f = lambda **kw: perf.perf_softmax(**{**dict(x=FAKE, y=FAKE + 4096, rows=4, cols=8, ldx=8, ldy=8,
+                                                 check=False), **kw})
+    assert f(x=None) == perf.PERF_ERR_NULL and f(y=None) == perf.PERF_ERR_NULL
+    assert f(rows=0) == perf.PERF_ERR_SHAPE and f(cols=-1) == perf.PERF_ERR_SHAPE
+    assert f(ldx=7) == perf.PERF_ERR_SHAPE and f(ldy=3) == perf.PERF_ERR_SHAPE
+    assert f(scale=float("inf")) == perf.PERF_ERR_SHAPE and f(scale=float("nan")) == perf.PERF_ERR_SHAPE
+    assert f(x_dt=7) == perf.PERF_ERR_DTYPE and f(y_dt=-1) == perf.PERF_ERR_DTYPE
+    assert f(x_dt=perf.PERF_BF16) == perf.PERF_ERR_UNSUPPORTED
+    assert f(x=FAKE + 2) == perf.PERF_ERR_ALIGN
+    with pytest.raises(perf.PerfError):
+        perf.perf_softmax(None, FAKE, 1, 1, 1, 1)
+
+
+def test_layernorm_argument_errors():
+    base = dict(x=FAKE, gamma=FAKE + 4096, beta=FAKE + 8192, y=FAKE + 12288, mean_out=None, rstd_out=None,
+                rows=4, cols=8, ldx=8, ldy=8, eps=1e-5, x_dt=perf.PERF_BF16, param_dt=perf.PERF_F32,
+                y_dt=perf.PERF_BF16, check=False)
+    f = lambda **kw: perf.perf_layernorm(**{**base, **kw})
+    for k in ("x", "gamma", "beta", "y"):
+        assert f(**{k: None}) == perf.PERF_ERR_NULL
+    assert f(rows=0) == perf.PERF_ERR_SHAPE and f(cols=0) == perf.PERF_ERR_SHAPE
+    assert f(ldx=4) == perf.PERF_ERR_SHAPE and f(eps=-1.0) == perf.PERF_ERR_SHAPE
+    assert f(eps=float("nan")) == perf.PERF_ERR_SHAPE
+    assert f(param_dt=2) == perf.PERF_ERR_DTYPE
+    assert f(x=FAKE + 1) == perf.PERF_ERR_ALIGN and f(mean_out=FAKE + 2) == perf.PERF_ERR_ALIGN
+    assert f(gamma=FAKE + 2) == perf.PERF_ERR_ALIGN      # fp32 params need 4-byte alignment
+
+
+def test_gemm_argument_errors():
+    base = dict(A=FAKE, B=FAKE + 4096, C=FAKE + 8192, M=4, N=4, K=8, la=perf.PERF_ROW_MAJOR, lda=8,
+                lb=perf.PERF_COL_MAJOR, ldb=8, ldc=4, check=False)
+    f = lambda **kw: perf.perf_gemm(**{**base, **kw})
+    for k in ("A", "B", "C"):
+        assert f(**{k: None}) == perf.PERF_ERR_NULL
+    assert f(M=0) == perf.PERF_ERR_SHAPE and f(K=-3) == perf.PERF_ERR_SHAPE and f(batch=0) == perf.PERF_ERR_SHAPE
+    assert f(lda=7) == perf.PERF_ERR_SHAPE and f(ldb=7) == perf.PERF_ERR_SHAPE and f(ldc=3) == perf.PERF_ERR_SHAPE
+    assert f(la=perf.PERF_COL_MAJOR, lda=3) == perf.PERF_ERR_SHAPE    # col-major A needs lda >= M
+    assert f(lb=perf.PERF_ROW_MAJOR, ldb=3) == perf.PERF_ERR_SHAPE    # row-major B needs ldb >= N
+    assert f(batch=2, strideC=15) == perf.PERF_ERR_SHAPE              # C matrices would overlap
+    assert f(strideA=-1) == perf.PERF_ERR_SHAPE and f(alpha=float("nan")) == perf.PERF_ERR_SHAPE
+    assert f(la=2) == perf.PERF_ERR_LAYOUT and f(lb=-1) == perf.PERF_ERR_LAYOUT
+    assert f(ab_dt=5) == perf.PERF_ERR_DTYPE
+    assert f(ab_dt=perf.PERF_F32, c_dt=perf.PERF_BF16) == perf.PERF_ERR_UNSUPPORTED
+    assert f(A=FAKE + 1) == perf.PERF_ERR_ALIGN and f(C=FAKE + 2) == perf.PERF_ERR_ALIGN
+
+
+def test_conv2d_argument_errors():
+    base = dict(x=FAKE, w=FAKE + 4096, y=FAKE + 8192, N=1, H=8, W=8, C=64, K=64, R=3, S=3, stride_h=1,
+                stride_w=1, pad_h=1, pad_w=1, check=False)
+    f = lambda **kw: perf.perf_conv2d(**{**base, **kw})
+    for k in ("x", "w", "y"):
+        assert f(**{k: None}) == perf.PERF_ERR_NULL
+    for k in ("N", "H", "W", "C", "K", "R", "S", "stride_h", "stride_w"):
+        assert f(**{k: 0}) == perf.PERF_ERR_SHAPE
+    assert f(pad_h=-1) == perf.PERF_ERR_SHAPE
+    assert f(H=2, pad_h=0, R=3) == perf.PERF_ERR_SHAPE          # filter larger than padded image
+    assert f(N=1 << 23, H=1 << 10, W=1 << 10, pad_h=0, pad_w=0, R=1, S=1) == perf.PERF_ERR_SHAPE  # too many pixels
+    assert f(xw_dt=9) == perf.PERF_ERR_DTYPE
+    assert f(x=FAKE + 1) == perf.PERF_ERR_ALIGN
+
+
+def test_copy_argument_errors():
+    assert perf.perf_copy(None, FAKE, 16, check=False) == perf.PERF_ERR_NULL
+    assert perf.perf_copy(FAKE, FAKE + 64, -1, check=False) == perf.PERF_ERR_SHAPE
+    assert perf.perf_copy(FAKE, FAKE + 64, 0, check=False) == perf.PERF_OK    # nothing to do, no launch

@@ -1,0 +1,96 @@
+"""GPU parity: perf_conv2d (implicit-GEMM MFMA kernel and direct kernel) against the CPU
+oracle. Tolerances as for the GEMM with K = R*S*C; bf16 outputs additionally allow one
+bf16 rounding of the result."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import configs, rng
+from tests import gpu_helpers as G
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def _bits(a):
+    return rng.f32_to_bf16_bits(np.asarray(a, dtype=np.float32))
+
+
+def _check(wl, y_bf16=True, stride=None, pad=None):
+    d = wl.make()
+    stride = stride or (wl.stride, wl.stride)
+    pad = pad or (wl.pad, wl.pad)
+    y = G.run_conv2d(d["x_bf16"], d["w_bf16"], stride, pad, y_bf16=y_bf16)
+    ref, ad = oracle.conv2d(oracle.widen(d["x_bf16"], True), oracle.widen(d["w_bf16"], True), stride, pad,
+                            want_absdot=True)
+    yg = P.bf16_to_f64(y) if y_bf16 else y
+    P.assert_contraction_close(yg, ref, ad, wl.R * wl.S * wl.C, out_bf16=y_bf16)
+
+
+def test_config5_recipe_two_images_full_compare():
+    _check(configs.ConvWorkload(N=2))
+    _check(configs.ConvWorkload(N=2), y_bf16=False)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(N=1, H=5, W=7, C=64, K=128), dict(N=3, H=9, W=6, C=128, K=40), dict(N=1, H=12, W=12, C=64, K=130),
+    dict(N=2, H=8, W=8, C=64, K=64, R=1, S=1, pad=0), dict(N=1, H=10, W=9, C=64, K=32, R=5, S=5, pad=2),
+    dict(N=2, H=11, W=13, C=64, K=96, stride=2), dict(N=1, H=8, W=8, C=64, K=16, pad=0),
+])
+def test_mfma_path_shapes(kw):
+    _check(configs.ConvWorkload(**kw))
+
+
+def test_mfma_rectangular_filter_and_mixed_stride_pad():
+    wl = configs.ConvWorkload(N=2, H=9, W=14, C=64, K=48, R=1, S=3)
+    _check(wl, pad=(0, 1))
+    wl = configs.ConvWorkload(N=1, H=14, W=9, C=64, K=48, R=3, S=1)
+    _check(wl, pad=(1, 0), stride=(2, 1))
+
+
+@pytest.mark.parametrize("kw", [
+    dict(N=2, H=9, W=9, C=3, K=10, R=5, S=5, pad=2), dict(N=1, H=7, W=5, C=10, K=3, R=3, S=3, pad=1, stride=2),
+    dict(N=1, H=6, W=6, C=72, K=8),
+])
+def test_direct_path_shapes(kw):
+    _check(configs.ConvWorkload(**kw))
+    _check(configs.ConvWorkload(**kw), y_bf16=False)
+
+
+def test_delta_kernels_and_tap_counts_are_exact():
+    C = 64
+    x = rng.bf16_bits_to_f32(configs.ConvWorkload(N=1, H=5, W=7, C=C, K=C).make()["x_bf16"])
+    w = np.zeros((C, 3, 3, C), np.float32)
+    w[np.arange(C), 1, 1, np.arange(C)] = 1.0
+    y = G.run_conv2d(_bits(x), _bits(w), (1, 1), (1, 1), y_bf16=False)
+    assert np.array_equal(y, x)                                   # centre delta = identity
+    w = np.zeros((C, 3, 3, C), np.float32)
+    w[np.arange(C), 0, 2, np.arange(C)] = 1.0                      # tap (r=0, s=2): shift down and left
+    y = G.run_conv2d(_bits(x), _bits(w), (1, 1), (1, 1), y_bf16=True)
+    expect = np.zeros_like(x)
+    expect[:, 1:, :-1, :] = x[:, :-1, 1:, :]
+    assert np.array_equal(rng.bf16_bits_to_f32(y), expect)
+    ones = G.run_conv2d(_bits(np.ones((1, 6, 8, C))), _bits(np.ones((3, 3, 3, C))), (1, 1), (1, 1), y_bf16=False)
+    assert np.all(ones[0, 1:-1, 1:-1] == 9 * C) and np.all(ones[0, 0, 1:-1] == 6 * C)
+    assert ones[0, 0, 0, 0] == 4 * C and ones[0, -1, -1, 2] == 4 * C
+
+
+def test_config5_full_size_sampled():
+    """Batch 32 in the benchmark's launch configuration: images 0, 13 and 31 are recomputed
+    by the oracle in full (borders included)."""
+    wl = configs.CONFIG5
+    d = wl.make()
+    for y_bf16 in (True, False):
+        y = G.run_conv2d(d["x_bf16"], d["w_bf16"], (1, 1), (1, 1), y_bf16=y_bf16)
+        for n in (0, 13, 31):
+            ref, ad = oracle.conv2d(oracle.widen(d["x_bf16"][n:n + 1], True), oracle.widen(d["w_bf16"], True),
+                                    (1, 1), (1, 1), want_absdot=True)
+            yg = P.bf16_to_f64(y[n:n + 1]) if y_bf16 else y[n:n + 1]
+            P.assert_contraction_close(yg, ref, ad, 576, out_bf16=y_bf16)
+
+
+def test_deterministic():
+    d = configs.ConvWorkload(N=4).make()
+    a = G.run_conv2d(d["x_bf16"], d["w_bf16"], (1, 1), (1, 1))
+    b = G.run_conv2d(d["x_bf16"], d["w_bf16"], (1, 1), (1, 1))
+    assert np.array_equal(a, b)
