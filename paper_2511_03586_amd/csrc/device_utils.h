@@ -88,80 +88,4 @@ __device__ __forceinline__ float wave_allreduce(float v, Op op)
     return v;
 }
 
-// Welford / Chan statistics: (n, mean, M2) of a set; merge(a, b) is the statistics of
-// the union. The wave reduction applies the same butterfly to all three fields.
-struct Stats {
-    float n, mean, m2;
-};
-
-__device__ __forceinline__ Stats stats_merge(Stats a, Stats b)
-{
-    Stats r;
-    r.n = a.n + b.n;
-    float inv = r.n > 0.f ? 1.0f / r.n : 0.f;
-    float d = b.mean - a.mean;
-    float wb = b.n * inv;
-    r.mean = a.mean + d * wb;
-    r.m2 = a.m2 + b.m2 + d * d * a.n * wb;
-    return r;
-}
-
-// Equal-count merge (both sides hold n elements): no division.
-__device__ __forceinline__ void stats_merge_equal(float &mean, float &m2, float mean_b, float m2_b, float n_each)
-{
-    float d = mean_b - mean;
-    mean = mean + 0.5f * d;
-    m2 = m2 + m2_b + d * d * (0.5f * n_each);
-}
-
-template <int CTRL>
-__device__ __forceinline__ Stats stats_dpp(Stats s)
-{
-    Stats r;
-    r.n = dpp_move<CTRL>(s.n);
-    r.mean = dpp_move<CTRL>(s.mean);
-    r.m2 = dpp_move<CTRL>(s.m2);
-    return r;
-}
-
-// General-count wave merge; every lane ends with the statistics of all 64 lanes' sets.
-__device__ __forceinline__ Stats wave_stats_allreduce(Stats s)
-{
-    s = stats_merge(s, stats_dpp<0xB1>(s));
-    s = stats_merge(s, stats_dpp<0x4E>(s));
-    s = stats_merge(s, stats_dpp<0x141>(s));
-    s = stats_merge(s, stats_dpp<0x140>(s));
-    {
-        Stats a, b;
-        swap16(s.n, a.n, b.n); swap16(s.mean, a.mean, b.mean); swap16(s.m2, a.m2, b.m2);
-        s = stats_merge(a, b);
-    }
-    {
-        Stats a, b;
-        swap32(s.n, a.n, b.n); swap32(s.mean, a.mean, b.mean); swap32(s.m2, a.m2, b.m2);
-        s = stats_merge(a, b);
-    }
-    return s;
-}
-
-// Equal-count wave merge: every lane starts with n_lane elements.
-__device__ __forceinline__ void wave_stats_allreduce_equal(float &mean, float &m2, float n_lane)
-{
-    float n = n_lane;
-    stats_merge_equal(mean, m2, dpp_move<0xB1>(mean), dpp_move<0xB1>(m2), n); n *= 2.f;
-    stats_merge_equal(mean, m2, dpp_move<0x4E>(mean), dpp_move<0x4E>(m2), n); n *= 2.f;
-    stats_merge_equal(mean, m2, dpp_move<0x141>(mean), dpp_move<0x141>(m2), n); n *= 2.f;
-    stats_merge_equal(mean, m2, dpp_move<0x140>(mean), dpp_move<0x140>(m2), n); n *= 2.f;
-    {
-        float ma, mb, qa, qb;
-        swap16(mean, ma, mb); swap16(m2, qa, qb);
-        stats_merge_equal(ma, qa, mb, qb, n); mean = ma; m2 = qa; n *= 2.f;
-    }
-    {
-        float ma, mb, qa, qb;
-        swap32(mean, ma, mb); swap32(m2, qa, qb);
-        stats_merge_equal(ma, qa, mb, qb, n); mean = ma; m2 = qa;
-    }
-}
-
 }  // namespace perf

@@ -2,13 +2,17 @@
 // Section 4.3 of the paper; the mean -> variance -> scale -> shift staging is the one the
 // paper describes for its batch-normalisation kernel, Section 4.3).
 //
-//  * layernorm_rows_kernel: a wavefront owns a whole row.  The row is read once with
-//    128-bit loads into registers; each lane forms (mean, M2) of its own elements and the
-//    64 lanes are merged with the Welford/Chan pairwise update over a DPP / permlane
-//    butterfly (no LDS, no barrier per row).  gamma and beta are staged once per
-//    workgroup in LDS as fp32 and re-used for every row the workgroup processes.
+//  * layernorm_rows_kernel: a wavefront owns a whole row.  The row is read from HBM once
+//    with 128-bit loads into registers.  Statistics are the corrected two-pass form, both
+//    passes over registers: a provisional mean from the plain sum, then the first and
+//    second moments of the data shifted by it (the first moment corrects the provisional
+//    mean, the second gives the variance without cancellation).  Sums are reduced over the
+//    64 lanes with a DPP / permlane butterfly (no LDS, no barrier per row).  A pairwise
+//    Welford/Chan merge of per-lane (mean, M2) was measured less accurate: it rounds
+//    per-lane means to fp32, which costs |mean|/sigma * 2^-24 per merge.  gamma and beta
+//    are staged once per workgroup in LDS as fp32 and re-used for every row.
 //  * layernorm_block_kernel: general fallback (any length, any alignment), one workgroup
-//    per row, three passes (mean, centred sum of squares, output).
+//    per row, three passes over global memory with the same arithmetic.
 #include "device_utils.h"
 #include "host_utils.h"
 
@@ -112,38 +116,36 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const XT *__
             else
                 raw[j] = uint4_t{0u, 0u, 0u, 0u};
         }
+        // Pass 1 (registers): provisional mean from the plain sum.
         float v[NC][E];
         float s = 0.f;
-        int cnt = 0;
 #pragma unroll
         for (int j = 0; j < NC; ++j) {
             Elem<XT>::unpack(raw[j], v[j]);
-            const bool valid = EVEN || (j * 64 + lane) * E < cols;
 #pragma unroll
             for (int e = 0; e < E; ++e) s += v[j][e];  // padding chunks hold zeros
-            cnt += valid ? E : 0;
         }
-        // lane-local mean and centred sum of squares over the lane's own elements
-        float n_l = (float)cnt;
-        float mean = cnt > 0 ? s / n_l : 0.f;
-        float m2 = 0.f;
+        const float mean0 = wave_allreduce(s, OpSum{}) * inv_cols;
+        // Pass 2 (registers): shift by the provisional mean, then first and second moments
+        // of the shifted data.  The shifted values are small, so neither moment cancels, and
+        // the first moment corrects the rounding of mean0.
+        float s1 = 0.f, s2 = 0.f;
 #pragma unroll
         for (int j = 0; j < NC; ++j) {
             const bool valid = EVEN || (j * 64 + lane) * E < cols;
 #pragma unroll
             for (int e = 0; e < E; ++e) {
-                float d = v[j][e] - mean;
-                m2 += valid ? d * d : 0.f;
+                const float d = valid ? v[j][e] - mean0 : 0.f;
+                v[j][e] = d;
+                s1 += d;
+                s2 = __builtin_fmaf(d, d, s2);
             }
         }
-        if constexpr (EVEN) {
-            wave_stats_allreduce_equal(mean, m2, (float)(NC * E));
-        } else {
-            Stats st = wave_stats_allreduce(Stats{n_l, mean, m2});
-            mean = st.mean;
-            m2 = st.m2;
-        }
-        const float var = m2 * inv_cols;
+        s1 = wave_allreduce(s1, OpSum{});
+        s2 = wave_allreduce(s2, OpSum{});
+        const float dm = s1 * inv_cols;
+        const float mean = mean0 + dm;
+        const float var = __builtin_fmaxf(__builtin_fmaf(-dm, dm, s2 * inv_cols), 0.f);
         const float rstd = 1.0f / __builtin_sqrtf(var + eps);
         if (lane == 0) {
             if (mean_out) mean_out[r] = mean;
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const XT *__
                     const float4_t b = b_lds[q * NCH + ch];
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        o[4 * q + e] = __builtin_fmaf((v[j][4 * q + e] - mean) * rstd, g[e], b[e]);
+                        o[4 * q + e] = __builtin_fmaf((v[j][4 * q + e] - dm) * rstd, g[e], b[e]);
                 }
                 store_chunk<YT, E>(yr + ch * E, o);
             }
@@ -193,21 +195,23 @@ __global__ __launch_bounds__(256) void layernorm_block_kernel(const XT *__restri
         YT *yr = y + r * ldy;
         float s = 0.f;
         for (int64_t c = threadIdx.x; c < cols; c += 256) s += Elem<XT>::load1(xr + c);
-        const float mean = block_sum_256(s, red) * inv_cols;
-        float q = 0.f;
+        const float mean0 = block_sum_256(s, red) * inv_cols;
+        float s1 = 0.f, s2 = 0.f;
         for (int64_t c = threadIdx.x; c < cols; c += 256) {
-            float d = Elem<XT>::load1(xr + c) - mean;
-            q += d * d;
+            const float d = Elem<XT>::load1(xr + c) - mean0;
+            s1 += d;
+            s2 = __builtin_fmaf(d, d, s2);
         }
-        const float var = block_sum_256(q, red) * inv_cols;
+        const float dm = block_sum_256(s1, red) * inv_cols;
+        const float var = __builtin_fmaxf(__builtin_fmaf(-dm, dm, block_sum_256(s2, red) * inv_cols), 0.f);
         const float rstd = 1.0f / __builtin_sqrtf(var + eps);
         if (threadIdx.x == 0) {
-            if (mean_out) mean_out[r] = mean;
+            if (mean_out) mean_out[r] = mean0 + dm;
             if (rstd_out) rstd_out[r] = rstd;
         }
         for (int64_t c = threadIdx.x; c < cols; c += 256) {
-            float xv = Elem<XT>::load1(xr + c);
-            Elem<YT>::store1(yr + c, __builtin_fmaf((xv - mean) * rstd, Elem<PT>::load1(gamma + c),
+            const float d = Elem<XT>::load1(xr + c) - mean0;
+            Elem<YT>::store1(yr + c, __builtin_fmaf((d - dm) * rstd, Elem<PT>::load1(gamma + c),
                                                      Elem<PT>::load1(beta + c)));
         }
     }

@@ -102,20 +102,14 @@ def test_closed_forms_on_gpu():
 
 def test_large_offset_small_variance_rows():
     """Rows with mean 1e3 and variance 1e-2 (fp32 input). A one-pass E[x^2]-E[x]^2 in fp32
-    would lose the variance entirely (ulp(1e6) = 0.06 > 0.01); the merged (mean, M2)
-    statistics must keep rstd to 1e-5. The output itself cannot meet 1e-5 here: an fp32
-    mean carries up to 2 ulp(|mean|) = 2^-22 |mean| of rounding, which the normalisation
-    multiplies by rstd, so y is checked against that bound."""
+    would lose the variance entirely (ulp(1e6) = 0.06 > 0.01), and statistics that round
+    the mean to fp32 before centring lose |mean|/sigma * 2^-24 = 6e-4 in y; the shifted
+    two-pass form must keep the standard 1e-5 gates on all three outputs."""
     gen = np.random.default_rng(5)
     for cols in (2048, 1000, 20000):
         x = (1000.0 + 0.1 * gen.standard_normal((6, cols))).astype(np.float32)
         g, b = _params(cols)
-        y, mean, rstd = G.run_layernorm(x, g, b, 0.0, False, False, False)
-        ref, mref, rref = oracle.layernorm(x, g, b, 0.0)
-        assert np.max(np.abs(mean - mref) / np.abs(mref)) <= 1e-5
-        assert np.max(np.abs(rstd - rref) / rref) <= 1e-5
-        bound = (2.0 ** -22 * np.abs(mref) * rref)[:, None] * np.abs(g)[None, :] + 1e-5 * np.abs(ref) + 1e-6
-        assert np.all(np.abs(y - ref) <= bound)
+        _check(x, g, b, 0.0, False, False, False)
 
 
 def test_deterministic():
