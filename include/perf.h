@@ -83,7 +83,7 @@ perf_status perf_layernorm(const void *x, const void *gamma, const void *beta, v
  *   batch >= 1; matrix b starts strideA/strideB/strideC elements after matrix b-1
  *   (strides >= 0; strideC must be >= the extent of one C when batch > 1).
  * The MFMA path is taken for bf16 operands with A row-major and B column-major (both
- * K-contiguous), K a multiple of 64, lda/ldb/strides multiples of 8 and 16-byte aligned
+ * K-contiguous), K a multiple of 32, lda/ldb/strides multiples of 8 and 16-byte aligned
  * pointers; every other legal combination runs a slower general kernel.
  * Errors: NULL, SHAPE, DTYPE, LAYOUT, ALIGN (pointer not aligned to its element size),
  * UNSUPPORTED (f32 operands with bf16 C), LAUNCH. */
@@ -99,7 +99,7 @@ perf_status perf_gemm(const void *A, const void *B, void *C, int64_t M, int64_t 
  * taps outside the image contribute 0;  P = (H + 2*pad_h - R)/stride_h + 1, Q likewise.
  *   x  device, NHWC dense;  w  device, KRSC dense;  y  device, NPQK dense
  *   xw_dt  dtype of x and w (bf16 or f32);  y_dt  f32 or bf16;  fp32 accumulation.
- * The MFMA path is taken for bf16 x/w with C a multiple of 64 and 16-byte aligned
+ * The MFMA path is taken for bf16 x/w with C a multiple of 32 and 16-byte aligned
  * pointers; other legal cases run a slower direct kernel.
  * Errors: NULL, SHAPE (any dim < 1, stride < 1, pad < 0, filter larger than the padded
  * image, more than 2^31-1 output pixels), DTYPE, ALIGN, LAUNCH. */

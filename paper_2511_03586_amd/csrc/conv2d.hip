@@ -5,18 +5,18 @@
 // GEMM view: rows m = (n, p, q) output pixels, columns = output channels k, reduction
 // index = (r, s, c) with c fastest, which is contiguous in both NHWC activations and KRSC
 // weights.  The im2col matrix is never built: for each K-step (one filter tap and one
-// 64-channel block) every lane recomputes the global address of its 16-byte chunk, and
+// 32-channel block) every lane recomputes the global address of its 16-byte chunk, and
 // taps that fall in the zero padding are fetched from a small all-zero buffer instead.
 //
-//  * conv2d_mfma_kernel: bf16, C a multiple of 64; main loop shared with the GEMM.
+//  * conv2d_mfma_kernel: bf16, C a multiple of 32; main loop shared with the GEMM.
 //  * conv2d_direct_kernel: any other legal case; one thread per output element.
 #include "mfma_tile.h"
 #include "host_utils.h"
 
 namespace perf {
 
-// Source of padding taps: 128 zero bytes, one row of an LDS stage.
-__device__ __attribute__((aligned(128))) const uint32_t kZeroRow[32] = {};
+// Source of padding taps: 64 zero bytes, one row of an LDS stage.
+__device__ __attribute__((aligned(64))) const uint32_t kZeroRow[16] = {};
 
 struct ConvGeom {
     int N, H, W, C, K, R, S, sh, sw, ph, pw, P, Q;
@@ -39,48 +39,43 @@ __global__ __launch_bounds__(kGemmThreads) void conv2d_mfma_kernel(const uint16_
     const int64_t ldb = (int64_t)g.R * g.S * g.C;
 
     // per load: the pixel this lane fetches for, as (image base offset, top-left input coords)
-    int64_t pix_base[BM / 32];
-    int ih0[BM / 32], iw0[BM / 32], chunk_off[BM / 32];
-    const char *a_src[BM / 32], *b_src[BN / 32];
+    int64_t pix_base[TM];
+    int ih0[TM], iw0[TM], chunk_off[TM];
+    const char *b_src[TN];
     const char *xb = reinterpret_cast<const char *>(x);
     const char *zb = reinterpret_cast<const char *>(kZeroRow);
 #pragma unroll
-    for (int i = 0; i < BM / 32; ++i) {
-        const int row = (i * 4 + wave) * 8 + (lane >> 3);
+    for (int i = 0; i < TM; ++i) {
+        const int row = load_row(i, wave, lane);
         const int m = min(m0 + row, Mtot - 1);
         const int n = m / (g.P * g.Q), pq = m % (g.P * g.Q);
         const int p = pq / g.Q, q = pq % g.Q;
         pix_base[i] = (int64_t)n * g.H * g.W * g.C * 2;
         ih0[i] = p * g.sh - g.ph;
         iw0[i] = q * g.sw - g.pw;
-        chunk_off[i] = ((lane & 7) ^ swz(row)) * 16;
+        chunk_off[i] = load_chunk(row, lane) * 16;
     }
-    auto set_a = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+        const int row = load_row(i, wave, lane);
+        b_src[i] = reinterpret_cast<const char *>(w + (int64_t)min(n0 + row, g.K - 1) * ldb + load_chunk(row, lane) * 8);
+    }
+    const int last = ktiles - 1;
+    auto src_a = [&](int kt, int i) {
+        kt = min(kt, last);
         const int tap = kt / cblocks, cb = kt % cblocks;
         const int r = tap / g.S, s = tap % g.S;
-#pragma unroll
-        for (int i = 0; i < BM / 32; ++i) {
-            const int ih = ih0[i] + r, iw = iw0[i] + s;
-            const bool inside = ih >= 0 && ih < g.H && iw >= 0 && iw < g.W;
-            const char *src = xb + pix_base[i] + ((int64_t)(ih * g.W + iw) * g.C + cb * kBK) * 2;
-            a_src[i] = (inside ? src : zb) + chunk_off[i];
-        }
+        const int ih = ih0[i] + r, iw = iw0[i] + s;
+        const bool inside = ih >= 0 && ih < g.H && iw >= 0 && iw < g.W;
+        const char *src = xb + pix_base[i] + ((int64_t)(ih * g.W + iw) * g.C + cb * kBK) * 2;
+        return (inside ? src : zb) + chunk_off[i];
     };
-#pragma unroll
-    for (int i = 0; i < BN / 32; ++i) {
-        const int row = (i * 4 + wave) * 8 + (lane >> 3);
-        const int chunk = (lane & 7) ^ swz(row);
-        b_src[i] = reinterpret_cast<const char *>(w + (int64_t)min(n0 + row, g.K - 1) * ldb + chunk * 8);
-    }
-    set_a(0);
 
     WaveTile<TM, TN> t;
     t.clear();
     const int a_row0 = wm * 32 * TM, b_row0 = wn * 32 * TN;
-    mfma_mainloop<TM, TN>(t, a_src, b_src, smem, ktiles, wave, lane, a_row0, b_row0, set_a, [&](int) {
-#pragma unroll
-        for (int i = 0; i < BN / 32; ++i) b_src[i] += kRowBytes;
-    });
+    mfma_mainloop<TM, TN>(t, smem, ktiles, wave, lane, a_row0, b_row0, src_a,
+                          [&](int kt, int i) { return b_src[i] + (int64_t)min(kt, last) * kRowBytes; });
     store_tile<TM, TN, CT>(t, y, g.K, Mtot, g.K, m0 + a_row0, n0 + b_row0, 1.0f, lane);
 }
 
@@ -119,7 +114,7 @@ static perf_status launch_conv_mfma(const void *x, const void *w, void *y, const
     constexpr int BM = 64 * TM, BN = 64 * TN;
     const int64_t Mtot = (int64_t)g.N * g.P * g.Q;
     const int tiles_m = (int)((Mtot + BM - 1) / BM), tiles_n = (g.K + BN - 1) / BN;
-    const size_t lds = 2 * (size_t)(BM + BN) * kRowBytes;
+    const size_t lds = (size_t)kStages * (BM + BN) * kRowBytes;
     auto kern = conv2d_mfma_kernel<TM, TN, CT>;
     static bool attr_done = false;
     if (!attr_done) {

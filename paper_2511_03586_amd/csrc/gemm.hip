@@ -2,7 +2,7 @@
 // Section 4.3 of the paper):  C_b = alpha * A_b * B_b, fp32 accumulation.
 //
 //  * gemm_mfma_kernel: bf16 operands, A row-major and B column-major (both K-contiguous),
-//    K a multiple of 64.  256x256 (or 128x128) workgroup tile, see mfma_tile.h.
+//    K a multiple of 32.  256x256 (or 128x128) workgroup tile, see mfma_tile.h.
 //  * gemm_general_kernel: any layout / dtype / size; 64x64 tile of fp32 FMAs.
 #include "mfma_tile.h"
 #include "host_utils.h"
@@ -50,34 +50,30 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(const uint16_t 
         const uint16_t *Bb = B + (int64_t)bz * strideB;
         CT *Cb = C + (int64_t)bz * strideC;
 
-        // global source of each direct-to-LDS load; rows past the edge re-read the last row
-        const char *a_src[BM / 32], *b_src[BN / 32];
+        // global source of each direct-to-LDS load at K-step 0; rows past the edge re-read
+        // the last row (their products land in rows / columns that are never stored)
+        const char *a_src[TM], *b_src[TN];
 #pragma unroll
-        for (int i = 0; i < BM / 32; ++i) {
-            const int row = (i * 4 + wave) * 8 + (lane >> 3);
-            const int chunk = (lane & 7) ^ swz(row);
-            a_src[i] = reinterpret_cast<const char *>(Ab + (int64_t)min(m0 + row, M - 1) * lda + chunk * 8);
+        for (int i = 0; i < TM; ++i) {
+            const int row = load_row(i, wave, lane);
+            a_src[i] = reinterpret_cast<const char *>(Ab + (int64_t)min(m0 + row, M - 1) * lda +
+                                                      load_chunk(row, lane) * 8);
         }
 #pragma unroll
-        for (int i = 0; i < BN / 32; ++i) {
-            const int row = (i * 4 + wave) * 8 + (lane >> 3);
-            const int chunk = (lane & 7) ^ swz(row);
-            b_src[i] = reinterpret_cast<const char *>(Bb + (int64_t)min(n0 + row, N - 1) * ldb + chunk * 8);
+        for (int i = 0; i < TN; ++i) {
+            const int row = load_row(i, wave, lane);
+            b_src[i] = reinterpret_cast<const char *>(Bb + (int64_t)min(n0 + row, N - 1) * ldb +
+                                                      load_chunk(row, lane) * 8);
         }
 
         WaveTile<TM, TN> t;
         t.clear();
         const int a_row0 = wm * 32 * TM, b_row0 = wn * 32 * TN;
+        const int last = ktiles - 1;
         mfma_mainloop<TM, TN>(
-            t, a_src, b_src, smem, ktiles, wave, lane, a_row0, b_row0,
-            [&](int) {
-#pragma unroll
-                for (int i = 0; i < BM / 32; ++i) a_src[i] += kRowBytes;
-            },
-            [&](int) {
-#pragma unroll
-                for (int i = 0; i < BN / 32; ++i) b_src[i] += kRowBytes;
-            });
+            t, smem, ktiles, wave, lane, a_row0, b_row0,
+            [&](int kt, int i) { return a_src[i] + (int64_t)min(kt, last) * kRowBytes; },
+            [&](int kt, int i) { return b_src[i] + (int64_t)min(kt, last) * kRowBytes; });
         store_tile<TM, TN, CT>(t, Cb, ldc, M, N, m0 + a_row0, n0 + b_row0, alpha, lane);
     }
 }
@@ -154,7 +150,7 @@ static perf_status launch_mfma(const GemmArgs &g)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
-    const size_t lds = 2 * (size_t)(BM + BN) * kRowBytes;
+    const size_t lds = (size_t)kStages * (BM + BN) * kRowBytes;
     auto kern = gemm_mfma_kernel<TM, TN, CT>;
     static bool attr_done = false;  // raising the dynamic-LDS cap is a per-function, idempotent setting
     if (!attr_done) {

@@ -4,42 +4,68 @@
 // tiling / special-instruction / layout moves of Section 2.2 and the independent
 // accumulator chains of Section 4.1 are applied by hand here).
 //
-// Data path per K-step of 64:
-//   HBM/L2 --global_load_lds_dwordx4--> LDS (double buffered, XOR-swizzled 16-byte chunks)
+// Data path per K-step of 32:
+//   L2 --global_load_lds_dwordx4--> LDS ring of 4 stages (XOR-swizzled 16-byte chunks)
 //   LDS --ds_read_b128--> operand registers (double buffered per 16-wide k-substep)
 //   v_mfma_f32_32x32x16_bf16 into TM*TN independent 32x32 fp32 accumulators per wave.
-// One workgroup barrier per K-step, placed before the last k-substep's MFMAs so the first
-// operand reads of the next tile overlap with them.
+// Loads run three K-steps ahead of the MFMAs and are issued a few at a time between the
+// MFMA groups, so the L2 -> LDS stream is continuous instead of one burst per step; the
+// wait before a step's barrier is a partial vmcnt that leaves the two younger steps in
+// flight.  One workgroup barrier per K-step, placed before the last k-substep's MFMAs so
+// the first operand reads of the next step overlap with them.
 #pragma once
 #include "device_utils.h"
 
 namespace perf {
 
-constexpr int kBK = 64;                  // K elements per LDS stage (128 bytes per row)
+constexpr int kBK = 32;                  // K elements per LDS stage (64 bytes per row)
 constexpr int kRowBytes = kBK * 2;
+constexpr int kStages = 4;
 constexpr int kGemmThreads = 256;
 
-// Swizzle: the 16-byte chunk c of tile row r is stored at chunk position c ^ swz(r).
-// Rows are 128 bytes, so 16 consecutive rows at a fixed logical chunk land on 16 distinct
-// 16-byte slots of a 256-byte bank line (row parity picks the half, (r>>1)&7 the slot).
-__device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
+// Swizzle: the 16-byte chunk c (0..3) of tile row r is stored at chunk position c ^ swz(r).
+// Rows are 64 bytes, so 16 consecutive rows at one logical chunk land on 16 distinct
+// 16-byte slots of the 256-byte LDS bank line: slot = 4*(r%4) + (c ^ (r/4)%4).
+__device__ __forceinline__ int swz(int r) { return (r >> 2) & 3; }
 
-// s_waitcnt with vmcnt = 0 only (expcnt / lgkmcnt left at "no wait").
-__device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-
-// Issue the direct-to-LDS loads of one ROWS x 64 operand stage.  `src` holds, per load
-// issued by this lane, the global address of its 16-byte chunk for the current K-step.
-// Load i of wave w fills tile rows (i*4 + w)*8 .. +7: lane l writes row l/8, position l%8.
-template <int ROWS>
-__device__ __forceinline__ void issue_stage(const char *const (&src)[ROWS / 32], char *lds_stage, int wave)
+// s_waitcnt on vmcnt only (expcnt / lgkmcnt left at "no wait"); gfx9 encoding:
+// vmcnt[3:0] in bits 3:0, vmcnt[5:4] in bits 15:14.
+template <int N>
+__device__ __forceinline__ void wait_vmem()
 {
-#pragma unroll
-    for (int i = 0; i < ROWS / 32; ++i) {
-        char *dst = lds_stage + (i * 4 + wave) * 8 * kRowBytes;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src[i],
-                                         (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
-    }
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
+// Same, and also lgkmcnt = 0 (all of this wave's LDS reads have returned).
+template <int N>
+__device__ __forceinline__ void wait_vmem_and_lds()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0070 | (N & 15) | ((N >> 4) << 14));
+}
+
+// Bare s_barrier: unlike __syncthreads() it carries no fence, so the compiler does not
+// drain vmcnt to 0 in front of it; the waits the algorithm needs are written explicitly.
+// The empty asm statements stop the compiler from moving memory accesses across it.
+__device__ __forceinline__ void wg_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// One direct-to-LDS load of this wave: 16 tile rows (1 KiB of a stage).  Load i of wave w
+// fills rows (i*4 + w)*16 .. +15: lane l writes row l/4, chunk position l%4.
+__device__ __forceinline__ void issue_load(const char *src, char *lds_stage, int i, int wave)
+{
+    char *dst = lds_stage + (i * 4 + wave) * 16 * kRowBytes;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                     (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+}
+
+// Tile row and swizzled chunk this lane fetches in load i (see issue_load).
+__device__ __forceinline__ int load_row(int i, int wave, int lane) { return (i * 4 + wave) * 16 + (lane >> 2); }
+__device__ __forceinline__ int load_chunk(int row, int lane) { return (lane & 3) ^ swz(row); }
 
 // Byte offset inside a stage of the 16-byte operand fragment a lane feeds to the MFMA:
 // tile row `row`, logical chunk `chunk` (= 2*ksub + lane/32).
@@ -86,48 +112,53 @@ __device__ __forceinline__ void mma_step(WaveTile<TM, TN> &t, const bf16x8_t (&a
             t.acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], t.acc[i][j], 0, 0, 0);
 }
 
-// K loop shared by GEMM and implicit-GEMM convolution.  set_a(kt) / set_b(kt) must leave
-// in a_src / b_src the global chunk addresses of K-step kt; they are called once per step,
-// in increasing kt, starting at 1 (step 0's addresses are the caller's initial values).
-template <int TM, int TN, typename SetA, typename SetB>
-__device__ __forceinline__ void mfma_mainloop(WaveTile<TM, TN> &t, const char *(&a_src)[2 * TM],
-                                              const char *(&b_src)[2 * TN], char *smem, int ktiles, int wave, int lane,
-                                              int a_row0, int b_row0, SetA set_a, SetB set_b)
+// K loop shared by GEMM and implicit-GEMM convolution.
+//   src_a(kt, i) / src_b(kt, i): global address of the 16-byte chunk this lane fetches in
+//   load i (0 .. TM-1 / TN-1) of K-step kt; called for kt up to ktiles + 2 (steps past the
+//   end must still return a readable address: their data lands in a free stage and is never
+//   used, which keeps the number of loads in flight, and so the vmcnt waits, uniform).
+template <int TM, int TN, typename SrcA, typename SrcB>
+__device__ __forceinline__ void mfma_mainloop(WaveTile<TM, TN> &t, char *smem, int ktiles, int wave, int lane,
+                                              int a_row0, int b_row0, SrcA src_a, SrcB src_b)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     constexpr int kStageBytes = (BM + BN) * kRowBytes;
+    constexpr int kLoads = TM + TN;  // loads per lane per K-step
+    static_assert(2 * kLoads < 64, "two K-steps of loads must fit the vmcnt counter");
     bf16x8_t fa[2][TM], fb[2][TN];
 
-    issue_stage<BM>(a_src, smem, wave);
-    issue_stage<BN>(b_src, smem + BM * kRowBytes, wave);
-    wait_vmem_all();
-    __syncthreads();
+    auto issue = [&](int kt, int first, int count) {
+        char *stage = smem + (kt % kStages) * kStageBytes;
+#pragma unroll
+        for (int i = first; i < first + count; ++i) {
+            if (i < TM) issue_load(src_a(kt, i), stage, i, wave);
+            else issue_load(src_b(kt, i - TM), stage + BM * kRowBytes, i - TM, wave);
+        }
+    };
+
+    issue(0, 0, kLoads);
+    issue(1, 0, kLoads);
+    issue(2, 0, kLoads);
+    wait_vmem<2 * kLoads>();  // step 0 has landed
+    wg_barrier();
     read_frags<TM, TN>(fa[0], fb[0], smem, smem + BM * kRowBytes, a_row0, b_row0, 0, lane);
 
     for (int kt = 0; kt < ktiles; ++kt) {
-        char *cur = smem + (kt & 1) * kStageBytes;
-        char *nxt = smem + ((kt + 1) & 1) * kStageBytes;
-        if (kt + 1 < ktiles) {
-            set_a(kt + 1);
-            set_b(kt + 1);
-            issue_stage<BM>(a_src, nxt, wave);
-            issue_stage<BN>(b_src, nxt + BM * kRowBytes, wave);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int c = ks & 1, n = c ^ 1;
-            if (ks < 3) {
-                read_frags<TM, TN>(fa[n], fb[n], cur, cur + BM * kRowBytes, a_row0, b_row0, ks + 1, lane);
-            } else {
-                // the next stage has landed and every wave is done reading the other one
-                wait_vmem_all();
-                __syncthreads();
-                // (after the last K-step this reads stale LDS that is never used)
-                read_frags<TM, TN>(fa[n], fb[n], nxt, nxt + BM * kRowBytes, a_row0, b_row0, 0, lane);
-            }
-            mma_step<TM, TN>(t, fa[c], fb[c]);
-        }
+        const char *cur = smem + (kt % kStages) * kStageBytes;
+        const char *nxt = smem + ((kt + 1) % kStages) * kStageBytes;
+        // k-substep 0: fetch substep 1's operands, first half of step kt+3's loads
+        read_frags<TM, TN>(fa[1], fb[1], cur, cur + BM * kRowBytes, a_row0, b_row0, 1, lane);
+        issue(kt + 3, 0, kLoads / 2);
+        mma_step<TM, TN>(t, fa[0], fb[0]);
+        // k-substep 1: step kt+1 must have landed (younger loads: step kt+2 and half of kt+3),
+        // and every wave must be done reading step kt-1's stage before it is refilled
+        wait_vmem_and_lds<kLoads + kLoads / 2>();
+        wg_barrier();
+        read_frags<TM, TN>(fa[0], fb[0], nxt, nxt + BM * kRowBytes, a_row0, b_row0, 0, lane);
+        issue(kt + 3, kLoads / 2, kLoads - kLoads / 2);
+        mma_step<TM, TN>(t, fa[1], fb[1]);
     }
+    wait_vmem<0>();  // drain the over-issued loads before the stages are reused or released
 }
 
 template <typename CT> __device__ __forceinline__ void store_c(CT *p, float v);
