@@ -5,8 +5,9 @@
 // GEMM view: rows m = (n, p, q) output pixels, columns = output channels k, reduction
 // index = (r, s, c) with c fastest, which is contiguous in both NHWC activations and KRSC
 // weights.  The im2col matrix is never built: for each K-step (one filter tap and one
-// 32-channel block) every lane recomputes the global address of its 16-byte chunk, and
-// taps that fall in the zero padding are fetched from a small all-zero buffer instead.
+// 32-channel block) every lane recomputes the byte offset of its 16-byte chunk, and
+// taps that fall in the zero padding are given an out-of-range buffer offset, which the
+// hardware's buffer range check turns into zeros.
 //
 //  * conv2d_mfma_kernel: bf16, C a multiple of 32; main loop shared with the GEMM.
 //  * conv2d_direct_kernel: any other legal case; one thread per output element.
@@ -15,22 +16,21 @@
 
 namespace perf {
 
-// Source of padding taps: 64 zero bytes, one row of an LDS stage.
-__device__ __attribute__((aligned(64))) const uint32_t kZeroRow[16] = {};
-
 struct ConvGeom {
     int N, H, W, C, K, R, S, sh, sw, ph, pw, P, Q;
 };
 
-template <int TM, int TN, typename CT>
-__global__ __launch_bounds__(kGemmThreads) void conv2d_mfma_kernel(const uint16_t *__restrict__ x,
+template <int TM, int TN, int WM, int WN, typename CT>
+__global__ __launch_bounds__(64 * WM * WN) void conv2d_mfma_kernel(const uint16_t *__restrict__ x,
                                                                    const uint16_t *__restrict__ w, CT *__restrict__ y,
                                                                    ConvGeom g, int tiles_n)
 {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    using Shape = TileShape<TM, TN, WM, WN>;
+    constexpr int BM = Shape::BM, BN = Shape::BN, NW = Shape::kWaves, LA = Shape::kLoadsA, LB = Shape::kLoadsB;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: LDS addresses stay scalar
+    const int wm = wave / WN, wn = wave % WN;
     const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
     const int m0 = tm * BM, n0 = tn * BN;
     const int Mtot = g.N * g.P * g.Q;       // host guarantees this fits in int
@@ -38,44 +38,44 @@ __global__ __launch_bounds__(kGemmThreads) void conv2d_mfma_kernel(const uint16_
     const int ktiles = g.R * g.S * cblocks;
     const int64_t ldb = (int64_t)g.R * g.S * g.C;
 
-    // per load: the pixel this lane fetches for, as (image base offset, top-left input coords)
-    int64_t pix_base[TM];
-    int ih0[TM], iw0[TM], chunk_off[TM];
-    const char *b_src[TN];
-    const char *xb = reinterpret_cast<const char *>(x);
-    const char *zb = reinterpret_cast<const char *>(kZeroRow);
+    // Activations: per load, the pixel this lane fetches for, as the byte offset of its
+    // top-left tap (may be negative) and that tap's input coordinates.  Taps in the padding
+    // get an out-of-range voffset, which the buffer load turns into zeros.
+    struct ActSrc {
+        rsrc_t rsrc;
+        int64_t pix_off[LA];
+        int ih0[LA], iw0[LA];
+        int H, W, C, S, cblocks, last;
+        __device__ __forceinline__ uint32_t voffset(int kt, int i) const
+        {
+            kt = min(kt, last);
+            const int tap = kt / cblocks, cb = kt % cblocks;
+            const int r = tap / S, s = tap % S;
+            const int ih = ih0[i] + r, iw = iw0[i] + s;
+            const bool inside = ih >= 0 && ih < H && iw >= 0 && iw < W;
+            const int64_t off = pix_off[i] + ((int64_t)(r * W + s) * C + cb * kBK) * 2;
+            return inside ? (uint32_t)off : kOutOfRange;
+        }
+        __device__ __forceinline__ uint32_t soffset(int) const { return 0; }
+    };
+    ActSrc src_a{make_rsrc(x, (uint32_t)((int64_t)g.N * g.H * g.W * g.C * 2)), {}, {}, {}, g.H, g.W, g.C, g.S, cblocks,
+                 ktiles - 1};
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int row = load_row(i, wave, lane);
+    for (int i = 0; i < LA; ++i) {
+        const int row = load_row<NW>(i, wave, lane);
         const int m = min(m0 + row, Mtot - 1);
         const int n = m / (g.P * g.Q), pq = m % (g.P * g.Q);
         const int p = pq / g.Q, q = pq % g.Q;
-        pix_base[i] = (int64_t)n * g.H * g.W * g.C * 2;
-        ih0[i] = p * g.sh - g.ph;
-        iw0[i] = q * g.sw - g.pw;
-        chunk_off[i] = load_chunk(row, lane) * 16;
+        src_a.ih0[i] = p * g.sh - g.ph;
+        src_a.iw0[i] = q * g.sw - g.pw;
+        src_a.pix_off[i] = (((int64_t)n * g.H + src_a.ih0[i]) * g.W + src_a.iw0[i]) * g.C * 2 + load_chunk(row, lane) * 16;
     }
-#pragma unroll
-    for (int i = 0; i < TN; ++i) {
-        const int row = load_row(i, wave, lane);
-        b_src[i] = reinterpret_cast<const char *>(w + (int64_t)min(n0 + row, g.K - 1) * ldb + load_chunk(row, lane) * 8);
-    }
-    const int last = ktiles - 1;
-    auto src_a = [&](int kt, int i) {
-        kt = min(kt, last);
-        const int tap = kt / cblocks, cb = kt % cblocks;
-        const int r = tap / g.S, s = tap % g.S;
-        const int ih = ih0[i] + r, iw = iw0[i] + s;
-        const bool inside = ih >= 0 && ih < g.H && iw >= 0 && iw < g.W;
-        const char *src = xb + pix_base[i] + ((int64_t)(ih * g.W + iw) * g.C + cb * kBK) * 2;
-        return (inside ? src : zb) + chunk_off[i];
-    };
+    const RowMajorSrc<LB, NW> src_b(w + (int64_t)n0 * ldb, min(BN, g.K - n0), ldb, ktiles, wave, lane);
 
     WaveTile<TM, TN> t;
     t.clear();
     const int a_row0 = wm * 32 * TM, b_row0 = wn * 32 * TN;
-    mfma_mainloop<TM, TN>(t, smem, ktiles, wave, lane, a_row0, b_row0, src_a,
-                          [&](int kt, int i) { return b_src[i] + (int64_t)min(kt, last) * kRowBytes; });
+    mfma_mainloop<TM, TN, WM, WN>(t, smem, ktiles, wave, lane, a_row0, b_row0, src_a, src_b);
     store_tile<TM, TN, CT>(t, y, g.K, Mtot, g.K, m0 + a_row0, n0 + b_row0, 1.0f, lane);
 }
 
@@ -108,14 +108,15 @@ __global__ __launch_bounds__(256) void conv2d_direct_kernel(const T *__restrict_
     }
 }
 
-template <int TM, int TN, typename CT>
+template <int TM, int TN, int WM, int WN, typename CT>
 static perf_status launch_conv_mfma(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
 {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    using Shape = TileShape<TM, TN, WM, WN>;
+    constexpr int BM = Shape::BM, BN = Shape::BN;
     const int64_t Mtot = (int64_t)g.N * g.P * g.Q;
     const int tiles_m = (int)((Mtot + BM - 1) / BM), tiles_n = (g.K + BN - 1) / BN;
-    const size_t lds = (size_t)kStages * (BM + BN) * kRowBytes;
-    auto kern = conv2d_mfma_kernel<TM, TN, CT>;
+    const size_t lds = Shape::kLdsBytes;
+    auto kern = conv2d_mfma_kernel<TM, TN, WM, WN, CT>;
     static bool attr_done = false;
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -123,7 +124,7 @@ static perf_status launch_conv_mfma(const void *x, const void *w, void *y, const
             return PERF_ERR_LAUNCH;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)((int64_t)tiles_m * tiles_n)), dim3(kGemmThreads), lds, st,
+    hipLaunchKernelGGL(kern, dim3((unsigned)((int64_t)tiles_m * tiles_n)), dim3(Shape::kThreads), lds, st,
                        (const uint16_t *)x, (const uint16_t *)w, (CT *)y, g, tiles_n);
     return launch_status();
 }
@@ -166,10 +167,11 @@ extern "C" perf_status perf_conv2d(const void *x, const void *w, void *y, int64_
                (int)pad_h, (int)pad_w, (int)P, (int)Q};
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool mfma_ok = xw_dt == PERF_BF16 && C % kBK == 0 && aligned(x, 16) && aligned(w, 16) &&
+                         N * H * W * C < (int64_t(1) << 30) && K * R * S * C < (int64_t(1) << 30) &&
                          ((N * P * Q + 127) / 128) * ((K + 127) / 128) <= kMaxGridX;
     if (mfma_ok)
-        return y_dt == PERF_F32 ? launch_conv_mfma<2, 2, float>(x, w, y, g, st)
-                                : launch_conv_mfma<2, 2, uint16_t>(x, w, y, g, st);
+        return y_dt == PERF_F32 ? launch_conv_mfma<2, 2, 2, 2, float>(x, w, y, g, st)
+                                : launch_conv_mfma<2, 2, 2, 2, uint16_t>(x, w, y, g, st);
     if (xw_dt == PERF_BF16)
         return y_dt == PERF_F32 ? launch_conv_direct<uint16_t, float>(x, w, y, g, st)
                                 : launch_conv_direct<uint16_t, uint16_t>(x, w, y, g, st);

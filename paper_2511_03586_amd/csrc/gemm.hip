@@ -27,18 +27,20 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
     tn = within / rows_in_band;
 }
 
-template <int TM, int TN, typename CT>
-__global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(const uint16_t *__restrict__ A,
+template <int TM, int TN, int WM, int WN, typename CT>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t *__restrict__ A,
                                                                  const uint16_t *__restrict__ B, CT *__restrict__ C,
                                                                  int M, int N, int K, int64_t lda, int64_t ldb,
                                                                  int64_t ldc, int64_t strideA, int64_t strideB,
                                                                  int64_t strideC, float alpha, int tiles_m, int tiles_n)
 {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    using Shape = TileShape<TM, TN, WM, WN>;
+    constexpr int BM = Shape::BM, BN = Shape::BN, NW = Shape::kWaves;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: LDS addresses stay scalar
+    const int wm = wave / WN, wn = wave % WN;
     int tm, tn;
     tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
@@ -50,30 +52,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(const uint16_t 
         const uint16_t *Bb = B + (int64_t)bz * strideB;
         CT *Cb = C + (int64_t)bz * strideC;
 
-        // global source of each direct-to-LDS load at K-step 0; rows past the edge re-read
-        // the last row (their products land in rows / columns that are never stored)
-        const char *a_src[TM], *b_src[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int row = load_row(i, wave, lane);
-            a_src[i] = reinterpret_cast<const char *>(Ab + (int64_t)min(m0 + row, M - 1) * lda +
-                                                      load_chunk(row, lane) * 8);
-        }
-#pragma unroll
-        for (int i = 0; i < TN; ++i) {
-            const int row = load_row(i, wave, lane);
-            b_src[i] = reinterpret_cast<const char *>(Bb + (int64_t)min(n0 + row, N - 1) * ldb +
-                                                      load_chunk(row, lane) * 8);
-        }
+        const RowMajorSrc<Shape::kLoadsA, NW> src_a(Ab + (int64_t)m0 * lda, min(BM, M - m0), lda, ktiles, wave, lane);
+        const RowMajorSrc<Shape::kLoadsB, NW> src_b(Bb + (int64_t)n0 * ldb, min(BN, N - n0), ldb, ktiles, wave, lane);
 
         WaveTile<TM, TN> t;
         t.clear();
         const int a_row0 = wm * 32 * TM, b_row0 = wn * 32 * TN;
-        const int last = ktiles - 1;
-        mfma_mainloop<TM, TN>(
-            t, smem, ktiles, wave, lane, a_row0, b_row0,
-            [&](int kt, int i) { return a_src[i] + (int64_t)min(kt, last) * kRowBytes; },
-            [&](int kt, int i) { return b_src[i] + (int64_t)min(kt, last) * kRowBytes; });
+        mfma_mainloop<TM, TN, WM, WN>(t, smem, ktiles, wave, lane, a_row0, b_row0, src_a, src_b);
         store_tile<TM, TN, CT>(t, Cb, ldc, M, N, m0 + a_row0, n0 + b_row0, alpha, lane);
     }
 }
@@ -145,13 +130,14 @@ struct GemmArgs {
     hipStream_t st;
 };
 
-template <int TM, int TN, typename CT>
+template <int TM, int TN, int WM, int WN, typename CT>
 static perf_status launch_mfma(const GemmArgs &g)
 {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    using Shape = TileShape<TM, TN, WM, WN>;
+    constexpr int BM = Shape::BM, BN = Shape::BN;
     const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
-    const size_t lds = (size_t)kStages * (BM + BN) * kRowBytes;
-    auto kern = gemm_mfma_kernel<TM, TN, CT>;
+    const size_t lds = Shape::kLdsBytes;
+    auto kern = gemm_mfma_kernel<TM, TN, WM, WN, CT>;
     static bool attr_done = false;  // raising the dynamic-LDS cap is a per-function, idempotent setting
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -162,7 +148,7 @@ static perf_status launch_mfma(const GemmArgs &g)
     // grid.y carries the batch index; batches beyond the grid limit take further launches
     for (int64_t b0 = 0; b0 < g.batch; b0 += kMaxGridYZ) {
         const unsigned gy = (unsigned)(g.batch - b0 < kMaxGridYZ ? g.batch - b0 : kMaxGridYZ);
-        hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n), gy), dim3(kGemmThreads), lds, g.st,
+        hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n), gy), dim3(Shape::kThreads), lds, g.st,
                            (const uint16_t *)g.A + b0 * g.strideA, (const uint16_t *)g.B + b0 * g.strideB,
                            (CT *)g.C + b0 * g.strideC, (int)g.M, (int)g.N, (int)g.K, g.lda, g.ldb, g.ldc, g.strideA,
                            g.strideB, g.strideC, g.alpha, tiles_m, tiles_n);
@@ -212,14 +198,14 @@ extern "C" perf_status perf_gemm(const void *A, const void *B, void *C, int64_t 
                static_cast<hipStream_t>(stream)};
     const bool mfma_ok = ab_dt == PERF_BF16 && la == PERF_ROW_MAJOR && lb == PERF_COL_MAJOR && K % kBK == 0 &&
                          lda % 8 == 0 && ldb % 8 == 0 && strideA % 8 == 0 && strideB % 8 == 0 && aligned(A, 16) &&
-                         aligned(B, 16) && M <= (1 << 30) && N <= (1 << 30) && K <= (1 << 30) &&
+                         aligned(B, 16) && lda <= (1 << 21) && ldb <= (1 << 21) && M <= (1 << 30) && N <= (1 << 30) && K <= (1 << 30) &&
                          ((M + 127) / 128) * ((N + 127) / 128) <= kMaxGridX;
     if (mfma_ok) {
         // the 256x256 tile needs enough tiles to occupy the 256 CUs; otherwise 128x128
         const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * batch;
         if (big_tiles >= 256)
-            return c_dt == PERF_F32 ? launch_mfma<4, 4, float>(g) : launch_mfma<4, 4, uint16_t>(g);
-        return c_dt == PERF_F32 ? launch_mfma<2, 2, float>(g) : launch_mfma<2, 2, uint16_t>(g);
+            return c_dt == PERF_F32 ? launch_mfma<4, 4, 2, 2, float>(g) : launch_mfma<4, 4, 2, 2, uint16_t>(g);
+        return c_dt == PERF_F32 ? launch_mfma<2, 2, 2, 2, float>(g) : launch_mfma<2, 2, 2, 2, uint16_t>(g);
     }
     if (ab_dt == PERF_BF16)
         return c_dt == PERF_F32 ? launch_general<uint16_t, float>(g) : launch_general<uint16_t, uint16_t>(g);

@@ -1,11 +1,12 @@
-// Shared bf16 MFMA main loop for gfx950: a workgroup of 4 wavefronts (2 x 2) computes a
-// (64*TM) x (64*TN) tile of  sum_k A[m][k] * B[n][k]  with both operands K-contiguous
+// Shared bf16 MFMA main loop for gfx950: a workgroup of WM x WN wavefronts, each owning
+// TM x TN MFMA tiles of 32x32, computes a (32*TM*WM) x (32*TN*WN) tile of
+// sum_k A[m][k] * B[n][k]  with both operands K-contiguous
 // ("matmul", "bmm" and "conv" rows of the operator table, Section 4.3 of the paper; the
 // tiling / special-instruction / layout moves of Section 2.2 and the independent
 // accumulator chains of Section 4.1 are applied by hand here).
 //
 // Data path per K-step of 32:
-//   L2 --global_load_lds_dwordx4--> LDS ring of 4 stages (XOR-swizzled 16-byte chunks)
+//   L2 --buffer_load_dwordx4 ... lds--> LDS ring of 4 stages (XOR-swizzled 16-byte chunks)
 //   LDS --ds_read_b128--> operand registers (double buffered per 16-wide k-substep)
 //   v_mfma_f32_32x32x16_bf16 into TM*TN independent 32x32 fp32 accumulators per wave.
 // Loads run three K-steps ahead of the MFMAs and are issued a few at a time between the
@@ -21,7 +22,6 @@ namespace perf {
 constexpr int kBK = 32;                  // K elements per LDS stage (64 bytes per row)
 constexpr int kRowBytes = kBK * 2;
 constexpr int kStages = 4;
-constexpr int kGemmThreads = 256;
 
 // Swizzle: the 16-byte chunk c (0..3) of tile row r is stored at chunk position c ^ swz(r).
 // Rows are 64 bytes, so 16 consecutive rows at one logical chunk land on 16 distinct
@@ -54,17 +54,31 @@ __device__ __forceinline__ void wg_barrier()
     asm volatile("" ::: "memory");
 }
 
-// One direct-to-LDS load of this wave: 16 tile rows (1 KiB of a stage).  Load i of wave w
-// fills rows (i*4 + w)*16 .. +15: lane l writes row l/4, chunk position l%4.
-__device__ __forceinline__ void issue_load(const char *src, char *lds_stage, int i, int wave)
+// Buffer resource over [base, base + bytes): loads through it take a uniform 32-bit
+// soffset and a per-lane 32-bit voffset, so no 64-bit per-lane address arithmetic is
+// needed, and a voffset >= bytes reads as zero instead of touching memory.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void *base, uint32_t bytes)
 {
-    char *dst = lds_stage + (i * 4 + wave) * 16 * kRowBytes;
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                     (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+constexpr uint32_t kOutOfRange = 0x80000000u;  // voffset of a lane that must read zeros
+
+// One direct-to-LDS load of a wave: 16 tile rows (1 KiB of a stage).  In a workgroup of NW
+// waves, load i of wave w fills rows (i*NW + w)*16 .. +15: lane l writes row l/4, chunk
+// position l%4.  `wave` must be wave-uniform (an SGPR) so the LDS address is scalar.
+template <int NW>
+__device__ __forceinline__ void issue_load(rsrc_t rsrc, uint32_t voffset, uint32_t soffset, char *lds_stage, int i,
+                                           int wave)
+{
+    char *dst = lds_stage + (i * NW + wave) * 16 * kRowBytes;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void *)dst, 16, voffset, soffset,
+                                             0, 0);
 }
 
 // Tile row and swizzled chunk this lane fetches in load i (see issue_load).
-__device__ __forceinline__ int load_row(int i, int wave, int lane) { return (i * 4 + wave) * 16 + (lane >> 2); }
+template <int NW>
+__device__ __forceinline__ int load_row(int i, int wave, int lane) { return (i * NW + wave) * 16 + (lane >> 2); }
 __device__ __forceinline__ int load_chunk(int row, int lane) { return (lane & 3) ^ swz(row); }
 
 // Byte offset inside a stage of the 16-byte operand fragment a lane feeds to the MFMA:
@@ -102,28 +116,69 @@ __device__ __forceinline__ void read_frags(bf16x8_t (&a)[TM], bf16x8_t (&b)[TN],
         b[j] = *reinterpret_cast<const bf16x8_t *>(b_stage + frag_offset(b_row0 + j * 32 + (lane & 31), chunk));
 }
 
-template <int TM, int TN>
-__device__ __forceinline__ void mma_step(WaveTile<TM, TN> &t, const bf16x8_t (&a)[TM], const bf16x8_t (&b)[TN])
+// MFMAs of tile rows [I0, I1) of the wave tile for one 16-wide k-substep.
+template <int I0, int I1, int TM, int TN>
+__device__ __forceinline__ void mma_rows(WaveTile<TM, TN> &t, const bf16x8_t (&a)[TM], const bf16x8_t (&b)[TN])
 {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = I0; i < I1; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
             t.acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], t.acc[i][j], 0, 0, 0);
 }
 
+// Geometry of a workgroup tile.
+template <int TM, int TN, int WM, int WN>
+struct TileShape {
+    static constexpr int kWaves = WM * WN;
+    static constexpr int kThreads = 64 * kWaves;
+    static constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
+    static constexpr int kLoadsA = BM / (16 * kWaves), kLoadsB = BN / (16 * kWaves);  // per lane per K-step
+    static constexpr int kStageBytes = (BM + BN) * kRowBytes;
+    static constexpr int kLdsBytes = kStages * kStageBytes;
+    static_assert(BM % (16 * kWaves) == 0 && BN % (16 * kWaves) == 0, "stage rows must divide among the waves");
+};
+
+// Operand stored as rows of K-contiguous bf16 (GEMM A and B, convolution weights): the
+// resource starts at the workgroup tile's first row; rows past `rows_valid` re-read the
+// last valid row (their products land in outputs that are never stored).
+template <int NLOADS, int NW>
+struct RowMajorSrc {
+    rsrc_t rsrc;
+    uint32_t voff[NLOADS];
+    int last;
+
+    __device__ __forceinline__ RowMajorSrc(const uint16_t *tile_base, int rows_valid, int64_t ld, int ktiles, int wave,
+                                           int lane)
+        : rsrc(make_rsrc(tile_base, (uint32_t)(((int64_t)(rows_valid - 1) * ld + (int64_t)ktiles * kBK) * 2))),
+          last(ktiles - 1)
+    {
+#pragma unroll
+        for (int i = 0; i < NLOADS; ++i) {
+            const int row = load_row<NW>(i, wave, lane);
+            voff[i] = (uint32_t)(min(row, rows_valid - 1) * ld * 2) + load_chunk(row, lane) * 16;
+        }
+    }
+    __device__ __forceinline__ uint32_t voffset(int, int i) const { return voff[i]; }
+    __device__ __forceinline__ uint32_t soffset(int kt) const { return (uint32_t)min(kt, last) * kRowBytes; }
+};
+
 // K loop shared by GEMM and implicit-GEMM convolution.
-//   src_a(kt, i) / src_b(kt, i): global address of the 16-byte chunk this lane fetches in
-//   load i (0 .. TM-1 / TN-1) of K-step kt; called for kt up to ktiles + 2 (steps past the
-//   end must still return a readable address: their data lands in a free stage and is never
-//   used, which keeps the number of loads in flight, and so the vmcnt waits, uniform).
-template <int TM, int TN, typename SrcA, typename SrcB>
+//   SrcA / SrcB describe where an operand's stage comes from: a buffer resource `rsrc`,
+//   voffset(kt, i) = per-lane byte offset of the 16-byte chunk fetched by load i
+//   (0 .. kLoadsA-1 / kLoadsB-1) of K-step kt, and soffset(kt) = uniform byte offset of
+//   the step.  They are evaluated for kt up to ktiles + 2: steps past the end must still
+//   name readable (or out-of-range) bytes; their data lands in a free stage and is never
+//   used, which keeps the number of loads in flight, and so the vmcnt waits, uniform.
+//   a_row0 / b_row0: first tile row of this wave's operands.  `wave` must be uniform.
+template <int TM, int TN, int WM, int WN, typename SrcA, typename SrcB>
 __device__ __forceinline__ void mfma_mainloop(WaveTile<TM, TN> &t, char *smem, int ktiles, int wave, int lane,
-                                              int a_row0, int b_row0, SrcA src_a, SrcB src_b)
+                                              int a_row0, int b_row0, const SrcA &src_a, const SrcB &src_b)
 {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
-    constexpr int kStageBytes = (BM + BN) * kRowBytes;
-    constexpr int kLoads = TM + TN;  // loads per lane per K-step
+    using Shape = TileShape<TM, TN, WM, WN>;
+    constexpr int BM = Shape::BM;
+    constexpr int kStageBytes = Shape::kStageBytes;
+    constexpr int LA = Shape::kLoadsA, kLoads = Shape::kLoadsA + Shape::kLoadsB;
     static_assert(2 * kLoads < 64, "two K-steps of loads must fit the vmcnt counter");
     bf16x8_t fa[2][TM], fb[2][TN];
 
@@ -131,8 +186,11 @@ __device__ __forceinline__ void mfma_mainloop(WaveTile<TM, TN> &t, char *smem, i
         char *stage = smem + (kt % kStages) * kStageBytes;
 #pragma unroll
         for (int i = first; i < first + count; ++i) {
-            if (i < TM) issue_load(src_a(kt, i), stage, i, wave);
-            else issue_load(src_b(kt, i - TM), stage + BM * kRowBytes, i - TM, wave);
+            if (i < LA)
+                issue_load<Shape::kWaves>(src_a.rsrc, src_a.voffset(kt, i), src_a.soffset(kt), stage, i, wave);
+            else
+                issue_load<Shape::kWaves>(src_b.rsrc, src_b.voffset(kt, i - LA), src_b.soffset(kt),
+                                          stage + BM * kRowBytes, i - LA, wave);
         }
     };
 
@@ -143,26 +201,41 @@ __device__ __forceinline__ void mfma_mainloop(WaveTile<TM, TN> &t, char *smem, i
     wg_barrier();
     read_frags<TM, TN>(fa[0], fb[0], smem, smem + BM * kRowBytes, a_row0, b_row0, 0, lane);
 
+    // Each k-substep is ordered by hand with scheduling barriers: the first row of MFMAs
+    // goes out, then the operand reads for the next substep, then the remaining MFMAs with
+    // the global->LDS loads mixed in.  Reads issued in front of an MFMA group would make the
+    // group's own operand wait (an in-order counter) cover them too; reads left to the
+    // scheduler sink behind the whole group and their latency is exposed.
     for (int kt = 0; kt < ktiles; ++kt) {
         const char *cur = smem + (kt % kStages) * kStageBytes;
         const char *nxt = smem + ((kt + 1) % kStages) * kStageBytes;
-        // k-substep 0: fetch substep 1's operands, first half of step kt+3's loads
+        // k-substep 0
+        mma_rows<0, 1>(t, fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
         read_frags<TM, TN>(fa[1], fb[1], cur, cur + BM * kRowBytes, a_row0, b_row0, 1, lane);
+        __builtin_amdgcn_sched_barrier(0);
         issue(kt + 3, 0, kLoads / 2);
-        mma_step<TM, TN>(t, fa[0], fb[0]);
-        // k-substep 1: step kt+1 must have landed (younger loads: step kt+2 and half of kt+3),
-        // and every wave must be done reading step kt-1's stage before it is refilled
+        mma_rows<1, TM>(t, fa[0], fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        // step kt+1 must have landed (younger loads: step kt+2 and half of kt+3), and every
+        // wave must be done reading step kt-1's stage before it is refilled
         wait_vmem_and_lds<kLoads + kLoads / 2>();
         wg_barrier();
+        // k-substep 1
+        mma_rows<0, 1>(t, fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
         read_frags<TM, TN>(fa[0], fb[0], nxt, nxt + BM * kRowBytes, a_row0, b_row0, 0, lane);
+        __builtin_amdgcn_sched_barrier(0);
         issue(kt + 3, kLoads / 2, kLoads - kLoads / 2);
-        mma_step<TM, TN>(t, fa[1], fb[1]);
+        mma_rows<1, TM>(t, fa[1], fb[1]);
+        __builtin_amdgcn_sched_barrier(0);
     }
     wait_vmem<0>();  // drain the over-issued loads before the stages are reused or released
 }
 
 template <typename CT> __device__ __forceinline__ void store_c(CT *p, float v);
-template <> __device__ __forceinline__ void store_c<float>(float *p, float v) { *p = v; }
+// C is written once and not re-read by the kernel: stream it past the caches.
+template <> __device__ __forceinline__ void store_c<float>(float *p, float v) { __builtin_nontemporal_store(v, p); }
 template <> __device__ __forceinline__ void store_c<uint16_t>(uint16_t *p, float v) { *p = f32_to_bf16(v); }
 
 // Write a wave's accumulators to row-major C.  Accumulator element e of a 32x32 tile is
