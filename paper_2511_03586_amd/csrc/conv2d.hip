@@ -9,6 +9,7 @@
 // taps that fall in the zero padding are given an out-of-range buffer offset, which the
 // hardware's buffer range check turns into zeros.
 //
+//  * conv2d_wreg_kernel: bf16, 3x3 filter, 64 -> 128 channels: weights held in registers.
 //  * conv2d_mfma_kernel: bf16, C a multiple of 32; main loop shared with the GEMM.
 //  * conv2d_direct_kernel: any other legal case; one thread per output element.
 #include "mfma_tile.h"
@@ -45,21 +46,31 @@ __global__ __launch_bounds__(64 * WM * WN) void conv2d_mfma_kernel(const uint16_
         rsrc_t rsrc;
         int64_t pix_off[LA];
         int ih0[LA], iw0[LA];
-        int H, W, C, S, cblocks, last;
-        __device__ __forceinline__ uint32_t voffset(int kt, int i) const
+        int H, W, C, R, S, cblocks;
+        int r, s, cb;  // filter tap and channel block of the current K-step (uniform)
+        __device__ __forceinline__ uint32_t voffset(int i) const
         {
-            kt = min(kt, last);
-            const int tap = kt / cblocks, cb = kt % cblocks;
-            const int r = tap / S, s = tap % S;
             const int ih = ih0[i] + r, iw = iw0[i] + s;
             const bool inside = ih >= 0 && ih < H && iw >= 0 && iw < W;
             const int64_t off = pix_off[i] + ((int64_t)(r * W + s) * C + cb * kBK) * 2;
             return inside ? (uint32_t)off : kOutOfRange;
         }
-        __device__ __forceinline__ uint32_t soffset(int) const { return 0; }
+        __device__ __forceinline__ uint32_t soffset() const { return 0; }
+        // next K-step: channel block fastest, then s, then r; past the last step it stays there
+        __device__ __forceinline__ void advance()
+        {
+            if (r == R - 1 && s == S - 1 && cb == cblocks - 1) return;
+            if (++cb == cblocks) {
+                cb = 0;
+                if (++s == S) {
+                    s = 0;
+                    ++r;
+                }
+            }
+        }
     };
-    ActSrc src_a{make_rsrc(x, (uint32_t)((int64_t)g.N * g.H * g.W * g.C * 2)), {}, {}, {}, g.H, g.W, g.C, g.S, cblocks,
-                 ktiles - 1};
+    ActSrc src_a{make_rsrc(x, (uint32_t)((int64_t)g.N * g.H * g.W * g.C * 2)), {}, {}, {}, g.H, g.W, g.C, g.R, g.S,
+                 cblocks, 0, 0, 0};
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
         const int row = load_row<NW>(i, wave, lane);
@@ -70,13 +81,191 @@ __global__ __launch_bounds__(64 * WM * WN) void conv2d_mfma_kernel(const uint16_
         src_a.iw0[i] = q * g.sw - g.pw;
         src_a.pix_off[i] = (((int64_t)n * g.H + src_a.ih0[i]) * g.W + src_a.iw0[i]) * g.C * 2 + load_chunk(row, lane) * 16;
     }
-    const RowMajorSrc<LB, NW> src_b(w + (int64_t)n0 * ldb, min(BN, g.K - n0), ldb, ktiles, wave, lane);
+    RowMajorSrc<LB, NW> src_b(w + (int64_t)n0 * ldb, min(BN, g.K - n0), ldb, ktiles, wave, lane);
 
     WaveTile<TM, TN> t;
     t.clear();
     const int a_row0 = wm * 32 * TM, b_row0 = wn * 32 * TN;
     mfma_mainloop<TM, TN, WM, WN>(t, smem, ktiles, wave, lane, a_row0, b_row0, src_a, src_b);
     store_tile<TM, TN, CT>(t, y, g.K, Mtot, g.K, m0 + a_row0, n0 + b_row0, 1.0f, lane);
+}
+
+// ---- weights-in-registers kernel ---------------------------------------------------
+// For filters small enough that a wavefront can keep its share of them in registers
+// (here: 128 output channels, 4 waves x 32 channels, R*S*C = 576 -> 36 operand fragments
+// = 144 VGPRs per lane), the contraction is turned around: the weights never move after
+// the prologue, and the activations stream through LDS once per 32-pixel block.
+//   * one persistent workgroup per CU owns a contiguous range of output pixels;
+//   * per block of 32 pixels the four waves together fetch the 32 x 576 im2col slice into
+//     an LDS ring slot (global -> LDS, zero padding by buffer range check), as R*S*C/32
+//     swizzled sub-tiles of 32 pixels x 32 channels;
+//   * every wave reads the whole slice (one ds_read_b128 per MFMA) and multiplies it with
+//     its own 32 channels: 36 MFMAs chained on a single accumulator, the operand registers
+//     of block b being refilled with block b+1 as soon as each MFMA has consumed them;
+//   * one barrier per block; LDS holds 3 blocks so loads run two blocks ahead.
+// The MFMA takes the weights as its row operand, so a lane ends up with 4 consecutive
+// output channels of one pixel; the block's results are staged in LDS and written out
+// after the next barrier as whole pixel rows, 16 bytes per lane.
+template <int R, int S, int C, typename CT>
+__global__ __launch_bounds__(256) void conv2d_wreg_kernel(const uint16_t *__restrict__ x,
+                                                          const uint16_t *__restrict__ w, CT *__restrict__ y,
+                                                          ConvGeom g, int px_per_wg)
+{
+    constexpr int KOUT = 128;               // 4 waves x 32 channels
+    constexpr int KSUB = R * S * C / 16;    // MFMA k-substeps per pixel block
+    constexpr int CB = C / 32;              // 32-channel sub-tiles per filter tap
+    constexpr int NSUB = R * S * CB;        // LDS sub-tiles per block, 2 KiB each
+    constexpr int kSlot = NSUB * 2048;
+    constexpr int kSlots = 3;
+    constexpr int kLoads = NSUB * 2 / 4;    // direct-to-LDS loads per wave per block (1 KiB each)
+    // output staging: a block's 32 x 128 results go through LDS so that global stores write
+    // whole pixel rows (16 bytes per lane); the row pitch is padded by 16 bytes against bank
+    // conflicts of the column-wise writes
+    constexpr int kOutPitch = KOUT * (int)sizeof(CT) + 16;
+    constexpr int kOutBytes = 32 * kOutPitch;
+    constexpr int kRowLanes = KOUT * (int)sizeof(CT) / 16;  // lanes per pixel row of 16-byte pieces
+    constexpr int kStores = 8 * kRowLanes / 64;             // store instructions per wave per block (8 rows per wave)
+    static_assert(C % 32 == 0 && (NSUB * 2) % 4 == 0, "sub-tiles must divide among the four waves");
+    static_assert(kLoads + kStores < 64, "vmcnt is a 6-bit counter");
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int Mtot = g.N * g.P * g.Q;
+    const int start = blockIdx.x * px_per_wg, end = min(start + px_per_wg, Mtot);
+    const int nblocks = (end - start + 31) / 32;
+
+    // activation loads: a wave fills half `wave % 2` (16 pixels) of sub-tiles wave/2, wave/2 + 2, ...
+    // lane -> pixel row half*16 + lane/4 of the block, chunk position lane%4
+    const rsrc_t xr = make_rsrc(x, (uint32_t)((int64_t)g.N * g.H * g.W * g.C * 2));
+    const int half = wave & 1, row_l = half * 16 + (lane >> 2);
+    int n_l, p_l, q_l;  // pixel start + row_l of block 0 as (image, output row, output column)
+    {
+        const int m = start + row_l;
+        n_l = m / (g.P * g.Q);
+        const int pq = m - n_l * (g.P * g.Q);
+        p_l = pq / g.Q;
+        q_l = pq - p_l * g.Q;
+    }
+    int m_l = start + row_l;
+    const uint32_t chunk_l = load_chunk(row_l, lane) * 16;
+    // All offsets are 32-bit: the host admits this kernel only for tensors below 2 GiB, and
+    // an offset is used only when its tap lies inside the image (then it is the true one).
+    auto issue_block = [&](int b) {
+        char *slot = smem + (b % kSlots) * kSlot;
+        const int ih0 = p_l * g.sh - g.ph, iw0 = q_l * g.sw - g.pw;
+        const uint32_t pix = (uint32_t)(((n_l * g.H + ih0) * g.W + iw0) * C) * 2u + chunk_l;
+        const bool live = m_l < end;
+#pragma unroll
+        for (int t = 0; t < kLoads; ++t) {
+            const int sub = (wave >> 1) + 2 * t;  // uniform: sub-tile -> filter tap and channel block
+            const int tap = sub / CB, cb = sub % CB;
+            const int r = tap / S, sft = tap % S;
+            const uint32_t tap_off = (uint32_t)((r * g.W + sft) * C + cb * 32) * 2u;  // scalar
+            const bool inside = live && (unsigned)(ih0 + r) < (unsigned)g.H && (unsigned)(iw0 + sft) < (unsigned)g.W;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void *)(slot + sub * 2048 + half * 1024),
+                                                     16, inside ? pix + tap_off : kOutOfRange, 0, 0, 0);
+        }
+        // advance this lane's pixel by one block (32 pixels) without dividing
+        m_l += 32;
+        q_l += 32;
+        while (q_l >= g.Q) {
+            q_l -= g.Q;
+            if (++p_l == g.P) {
+                p_l = 0;
+                ++n_l;
+            }
+        }
+    };
+
+    // operand reads: fragment kk of a block lives in sub-tile kk / (2*... ) -- tap-major, then 16-channel group
+    const int frag_lo = frag_offset(lane & 31, lane >> 5);        // k-substep 0 of a sub-tile
+    const int frag_hi = frag_offset(lane & 31, 2 + (lane >> 5));  // k-substep 1
+    bf16x8_t af[KSUB];
+    auto read_frag = [&](const char *slot, int kk) {
+        const int sub = kk / 2;  // 32 channels per sub-tile = 2 k-substeps; sub-tiles are stored tap-major
+        return *reinterpret_cast<const bf16x8_t *>(slot + sub * 2048 + ((kk & 1) ? frag_hi : frag_lo));
+    };
+
+    issue_block(0);
+    issue_block(1);
+    issue_block(2);
+    // weights of this wave's 32 channels, fetched behind the first activation blocks so the two
+    // latencies overlap: fragment kk covers K indices kk*16 .. +15, a lane holds channel
+    // lane%32 and the 8 K values starting at 8*(lane/32)
+    bf16x8_t wf[KSUB];
+    {
+        const uint16_t *wl = w + (int64_t)(wave * 32 + (lane & 31)) * (R * S * C) + 8 * (lane >> 5);
+#pragma unroll
+        for (int kk = 0; kk < KSUB; ++kk) wf[kk] = *reinterpret_cast<const bf16x8_t *>(wl + kk * 16);
+    }
+    static_assert(kSlots * kLoads + KSUB < 64, "prologue loads must fit the vmcnt counter");
+    wait_vmem<KSUB + 2 * kLoads>();  // own part of block 0 has landed (loads complete in order)
+    wg_barrier();
+#pragma unroll
+    for (int kk = 0; kk < KSUB; ++kk) af[kk] = read_frag(smem, kk);
+
+    // output: lane holds channels wave*32 + 8a + 4*(lane/32) + 0..3 of pixel lane%32
+    char *const out_stage = smem + kSlots * kSlot;
+    const int stage_wr = (lane & 31) * kOutPitch + (wave * 32 + 4 * (lane >> 5)) * (int)sizeof(CT);
+    // write-out of the previous block: this wave stores pixel rows wave*8 .. wave*8+7
+    auto store_block = [&](int b) {
+        const char *stg = out_stage + (b & 1) * kOutBytes;
+#pragma unroll
+        for (int t = 0; t < kStores; ++t) {
+            const int row = wave * 8 + t * (64 / kRowLanes) + lane / kRowLanes;
+            const int m = start + b * 32 + row;
+            const uint4_t v = *reinterpret_cast<const uint4_t *>(stg + row * kOutPitch + (lane % kRowLanes) * 16);
+            if (m < end)
+                __builtin_nontemporal_store(v, reinterpret_cast<uint4_t *>(reinterpret_cast<char *>(y) +
+                                                                            (int64_t)m * (KOUT * sizeof(CT)) +
+                                                                            (lane % kRowLanes) * 16));
+        }
+    };
+    for (int b = 0; b < nblocks; ++b) {
+        // own loads of block b+1 have landed (younger: block b+2's loads and block b-1's stores),
+        // own reads of block b have returned
+        if (b < 2) wait_vmem_and_lds<kLoads>();
+        else wait_vmem_and_lds<kLoads + kStores>();
+        wg_barrier();
+        if (b > 0) store_block(b - 1);  // staged by all waves before the barrier
+        issue_block(b + 3);             // into the slot of block b, which every wave has finished reading
+        const char *nxt = smem + ((b + 1) % kSlots) * kSlot;
+        float16_t acc;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KSUB; ++kk) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk], acc, 0, 0, 0);
+            af[kk] = read_frag(nxt, kk);
+        }
+        // one operand read behind every MFMA, one global->LDS load behind every fourth
+#pragma unroll
+        for (int kk = 0; kk < KSUB; ++kk) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+            if (kk % 4 == 1 && kk / 4 < kLoads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // stage the block's results for the coalesced write-out after the next barrier
+        char *stg = out_stage + (b & 1) * kOutBytes + stage_wr;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            if constexpr (sizeof(CT) == 4) {
+                *reinterpret_cast<float4_t *>(stg + 8 * a * 4) =
+                    float4_t{acc[4 * a], acc[4 * a + 1], acc[4 * a + 2], acc[4 * a + 3]};
+            } else {
+                *reinterpret_cast<uint2_t *>(stg + 8 * a * 2) =
+                    uint2_t{pack_bf16(acc[4 * a], acc[4 * a + 1]), pack_bf16(acc[4 * a + 2], acc[4 * a + 3])};
+            }
+        }
+    }
+    if (nblocks > 0) {
+        wait_vmem_and_lds<0>();
+        wg_barrier();
+        store_block(nblocks - 1);
+    }
+    wait_vmem_and_lds<0>();
 }
 
 template <typename T> __device__ __forceinline__ float load_xw(const T *p);
@@ -129,6 +318,27 @@ static perf_status launch_conv_mfma(const void *x, const void *w, void *y, const
     return launch_status();
 }
 
+template <int R, int S, int C, typename CT>
+static perf_status launch_conv_wreg(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
+{
+    constexpr int kLds = 3 * (R * S * (C / 32)) * 2048 + 2 * 32 * (128 * (int)sizeof(CT) + 16);
+    const int64_t Mtot = (int64_t)g.N * g.P * g.Q;
+    int grid = 256;  // one persistent workgroup per CU
+    if ((Mtot + 31) / 32 < grid) grid = (int)((Mtot + 31) / 32);
+    const int px_per_wg = (int)((Mtot + grid - 1) / grid);
+    auto kern = conv2d_wreg_kernel<R, S, C, CT>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kLds) !=
+            hipSuccess)
+            return PERF_ERR_LAUNCH;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), kLds, st, (const uint16_t *)x, (const uint16_t *)w, (CT *)y,
+                       g, px_per_wg);
+    return launch_status();
+}
+
 template <typename T, typename CT>
 static perf_status launch_conv_direct(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
 {
@@ -169,6 +379,10 @@ extern "C" perf_status perf_conv2d(const void *x, const void *w, void *y, int64_
     const bool mfma_ok = xw_dt == PERF_BF16 && C % kBK == 0 && aligned(x, 16) && aligned(w, 16) &&
                          N * H * W * C < (int64_t(1) << 30) && K * R * S * C < (int64_t(1) << 30) &&
                          ((N * P * Q + 127) / 128) * ((K + 127) / 128) <= kMaxGridX;
+    // filter shapes with a weights-in-registers instance
+    if (mfma_ok && R == 3 && S == 3 && C == 64 && K == 128)
+        return y_dt == PERF_F32 ? launch_conv_wreg<3, 3, 64, float>(x, w, y, g, st)
+                                : launch_conv_wreg<3, 3, 64, uint16_t>(x, w, y, g, st);
     if (mfma_ok)
         return y_dt == PERF_F32 ? launch_conv_mfma<2, 2, 2, 2, float>(x, w, y, g, st)
                                 : launch_conv_mfma<2, 2, 2, 2, uint16_t>(x, w, y, g, st);

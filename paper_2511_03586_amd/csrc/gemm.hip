@@ -27,7 +27,7 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
     tn = within / rows_in_band;
 }
 
-template <int TM, int TN, int WM, int WN, typename CT>
+template <int TM, int TN, int WM, int WN, bool PINGPONG, typename CT>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t *__restrict__ A,
                                                                  const uint16_t *__restrict__ B, CT *__restrict__ C,
                                                                  int M, int N, int K, int64_t lda, int64_t ldb,
@@ -52,13 +52,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t 
         const uint16_t *Bb = B + (int64_t)bz * strideB;
         CT *Cb = C + (int64_t)bz * strideC;
 
-        const RowMajorSrc<Shape::kLoadsA, NW> src_a(Ab + (int64_t)m0 * lda, min(BM, M - m0), lda, ktiles, wave, lane);
-        const RowMajorSrc<Shape::kLoadsB, NW> src_b(Bb + (int64_t)n0 * ldb, min(BN, N - n0), ldb, ktiles, wave, lane);
+        RowMajorSrc<Shape::kLoadsA, NW> src_a(Ab + (int64_t)m0 * lda, min(BM, M - m0), lda, ktiles, wave, lane);
+        RowMajorSrc<Shape::kLoadsB, NW> src_b(Bb + (int64_t)n0 * ldb, min(BN, N - n0), ldb, ktiles, wave, lane);
 
         WaveTile<TM, TN> t;
         t.clear();
         const int a_row0 = wm * 32 * TM, b_row0 = wn * 32 * TN;
-        mfma_mainloop<TM, TN, WM, WN>(t, smem, ktiles, wave, lane, a_row0, b_row0, src_a, src_b);
+        if constexpr (PINGPONG)
+            mfma_mainloop_pingpong<TM, TN, WM, WN>(t, smem, ktiles, wave, lane, a_row0, b_row0, src_a, src_b);
+        else
+            mfma_mainloop<TM, TN, WM, WN>(t, smem, ktiles, wave, lane, a_row0, b_row0, src_a, src_b);
         store_tile<TM, TN, CT>(t, Cb, ldc, M, N, m0 + a_row0, n0 + b_row0, alpha, lane);
     }
 }
@@ -130,14 +133,14 @@ struct GemmArgs {
     hipStream_t st;
 };
 
-template <int TM, int TN, int WM, int WN, typename CT>
+template <int TM, int TN, int WM, int WN, bool PINGPONG, typename CT>
 static perf_status launch_mfma(const GemmArgs &g)
 {
     using Shape = TileShape<TM, TN, WM, WN>;
     constexpr int BM = Shape::BM, BN = Shape::BN;
     const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
     const size_t lds = Shape::kLdsBytes;
-    auto kern = gemm_mfma_kernel<TM, TN, WM, WN, CT>;
+    auto kern = gemm_mfma_kernel<TM, TN, WM, WN, PINGPONG, CT>;
     static bool attr_done = false;  // raising the dynamic-LDS cap is a per-function, idempotent setting
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -204,8 +207,8 @@ extern "C" perf_status perf_gemm(const void *A, const void *B, void *C, int64_t 
         // the 256x256 tile needs enough tiles to occupy the 256 CUs; otherwise 128x128
         const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * batch;
         if (big_tiles >= 256)
-            return c_dt == PERF_F32 ? launch_mfma<4, 4, 2, 2, float>(g) : launch_mfma<4, 4, 2, 2, uint16_t>(g);
-        return c_dt == PERF_F32 ? launch_mfma<2, 2, 2, 2, float>(g) : launch_mfma<2, 2, 2, 2, uint16_t>(g);
+            return c_dt == PERF_F32 ? launch_mfma<4, 4, 2, 2, false, float>(g) : launch_mfma<4, 4, 2, 2, false, uint16_t>(g);
+        return c_dt == PERF_F32 ? launch_mfma<2, 2, 2, 2, false, float>(g) : launch_mfma<2, 2, 2, 2, false, uint16_t>(g);
     }
     if (ab_dt == PERF_BF16)
         return c_dt == PERF_F32 ? launch_general<uint16_t, float>(g) : launch_general<uint16_t, uint16_t>(g);

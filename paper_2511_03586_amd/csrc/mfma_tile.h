@@ -7,13 +7,11 @@
 //
 // Data path per K-step of 32:
 //   L2 --buffer_load_dwordx4 ... lds--> LDS ring of 4 stages (XOR-swizzled 16-byte chunks)
-//   LDS --ds_read_b128--> operand registers (double buffered per 16-wide k-substep)
+//   LDS --ds_read_b128--> operand registers (double buffered per K-step)
 //   v_mfma_f32_32x32x16_bf16 into TM*TN independent 32x32 fp32 accumulators per wave.
-// Loads run three K-steps ahead of the MFMAs and are issued a few at a time between the
-// MFMA groups, so the L2 -> LDS stream is continuous instead of one burst per step; the
-// wait before a step's barrier is a partial vmcnt that leaves the two younger steps in
-// flight.  One workgroup barrier per K-step, placed before the last k-substep's MFMAs so
-// the first operand reads of the next step overlap with them.
+// Loads run several K-steps ahead of the MFMAs and are issued between them, so the
+// L2 -> LDS stream is continuous; the wait before a step's barrier is a partial vmcnt that
+// leaves the younger steps in flight.  One workgroup barrier per K-step.
 #pragma once
 #include "device_utils.h"
 
@@ -116,17 +114,6 @@ __device__ __forceinline__ void read_frags(bf16x8_t (&a)[TM], bf16x8_t (&b)[TN],
         b[j] = *reinterpret_cast<const bf16x8_t *>(b_stage + frag_offset(b_row0 + j * 32 + (lane & 31), chunk));
 }
 
-// MFMAs of tile rows [I0, I1) of the wave tile for one 16-wide k-substep.
-template <int I0, int I1, int TM, int TN>
-__device__ __forceinline__ void mma_rows(WaveTile<TM, TN> &t, const bf16x8_t (&a)[TM], const bf16x8_t (&b)[TN])
-{
-#pragma unroll
-    for (int i = I0; i < I1; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-            t.acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], t.acc[i][j], 0, 0, 0);
-}
-
 // Geometry of a workgroup tile.
 template <int TM, int TN, int WM, int WN>
 struct TileShape {
@@ -146,12 +133,12 @@ template <int NLOADS, int NW>
 struct RowMajorSrc {
     rsrc_t rsrc;
     uint32_t voff[NLOADS];
-    int last;
+    uint32_t soff, soff_last;
 
     __device__ __forceinline__ RowMajorSrc(const uint16_t *tile_base, int rows_valid, int64_t ld, int ktiles, int wave,
                                            int lane)
         : rsrc(make_rsrc(tile_base, (uint32_t)(((int64_t)(rows_valid - 1) * ld + (int64_t)ktiles * kBK) * 2))),
-          last(ktiles - 1)
+          soff(0), soff_last((uint32_t)(ktiles - 1) * kRowBytes)
     {
 #pragma unroll
         for (int i = 0; i < NLOADS; ++i) {
@@ -159,77 +146,177 @@ struct RowMajorSrc {
             voff[i] = (uint32_t)(min(row, rows_valid - 1) * ld * 2) + load_chunk(row, lane) * 16;
         }
     }
-    __device__ __forceinline__ uint32_t voffset(int, int i) const { return voff[i]; }
-    __device__ __forceinline__ uint32_t soffset(int kt) const { return (uint32_t)min(kt, last) * kRowBytes; }
+    __device__ __forceinline__ uint32_t voffset(int i) const { return voff[i]; }
+    __device__ __forceinline__ uint32_t soffset() const { return soff; }
+    // next K-step; past the last one it stays there
+    __device__ __forceinline__ void advance() { soff = min(soff + (uint32_t)kRowBytes, soff_last); }
 };
 
+// All MFMAs of one K-step (two 16-wide k-substeps).  The two substeps of an accumulator
+// are issued back to back: consecutive MFMAs on the same accumulator forward it inside the
+// matrix pipe instead of going through the register file, which measurably lowers power
+// (the chip is power-limited under MFMA load, so lower energy per MFMA is a higher clock).
+template <int TM, int TN>
+__device__ __forceinline__ void mma_kstep(WaveTile<TM, TN> &t, const bf16x8_t (&a)[2][TM], const bf16x8_t (&b)[2][TN])
+{
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            t.acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0][i], b[0][j], t.acc[i][j], 0, 0, 0);
+            t.acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1][i], b[1][j], t.acc[i][j], 0, 0, 0);
+        }
+}
+
 // K loop shared by GEMM and implicit-GEMM convolution.
-//   SrcA / SrcB describe where an operand's stage comes from: a buffer resource `rsrc`,
-//   voffset(kt, i) = per-lane byte offset of the 16-byte chunk fetched by load i
-//   (0 .. kLoadsA-1 / kLoadsB-1) of K-step kt, and soffset(kt) = uniform byte offset of
-//   the step.  They are evaluated for kt up to ktiles + 2: steps past the end must still
-//   name readable (or out-of-range) bytes; their data lands in a free stage and is never
-//   used, which keeps the number of loads in flight, and so the vmcnt waits, uniform.
+//   SrcA / SrcB describe where an operand's stage comes from and walk the K-steps in
+//   order: a buffer resource `rsrc`, voffset(i) = per-lane byte offset of the 16-byte chunk
+//   fetched by load i (0 .. kLoadsA-1 / kLoadsB-1) of the current step, soffset() = uniform
+//   byte offset of the current step, advance() = go to the next step.  The loop advances up
+//   to 3 steps past the last one: a source must then keep naming readable (or out-of-range)
+//   bytes; that data lands in a free stage and is never used, which keeps the number of
+//   loads in flight, and so the vmcnt waits, uniform.
 //   a_row0 / b_row0: first tile row of this wave's operands.  `wave` must be uniform.
+//
+// Schedule of step kt (operand registers F[kt&1] were filled during step kt-1):
+//   wait until this wave's loads of step kt+1 have landed and its reads of stage kt are back;
+//   barrier (now stage kt+1 is complete and stage kt is free for every wave);
+//   read stage kt+1 into F[(kt+1)&1], refill stage kt with step kt+4, and run the MFMAs of
+//   step kt, the three instruction kinds interleaved.
 template <int TM, int TN, int WM, int WN, typename SrcA, typename SrcB>
 __device__ __forceinline__ void mfma_mainloop(WaveTile<TM, TN> &t, char *smem, int ktiles, int wave, int lane,
-                                              int a_row0, int b_row0, const SrcA &src_a, const SrcB &src_b)
+                                              int a_row0, int b_row0, SrcA &src_a, SrcB &src_b)
 {
     using Shape = TileShape<TM, TN, WM, WN>;
     constexpr int BM = Shape::BM;
     constexpr int kStageBytes = Shape::kStageBytes;
     constexpr int LA = Shape::kLoadsA, kLoads = Shape::kLoadsA + Shape::kLoadsB;
-    static_assert(2 * kLoads < 64, "two K-steps of loads must fit the vmcnt counter");
-    bf16x8_t fa[2][TM], fb[2][TN];
+    static_assert(3 * kLoads < 64, "three K-steps of loads must fit the vmcnt counter");
+    bf16x8_t fa[2][2][TM], fb[2][2][TN];  // [buffer][k-substep][tile]
 
-    auto issue = [&](int kt, int first, int count) {
+    // loads of the sources' current K-step into ring slot kt % kStages; called with kt = 0, 1, 2, ...
+    auto issue = [&](int kt) {
         char *stage = smem + (kt % kStages) * kStageBytes;
 #pragma unroll
-        for (int i = first; i < first + count; ++i) {
+        for (int i = 0; i < kLoads; ++i) {
             if (i < LA)
-                issue_load<Shape::kWaves>(src_a.rsrc, src_a.voffset(kt, i), src_a.soffset(kt), stage, i, wave);
+                issue_load<Shape::kWaves>(src_a.rsrc, src_a.voffset(i), src_a.soffset(), stage, i, wave);
             else
-                issue_load<Shape::kWaves>(src_b.rsrc, src_b.voffset(kt, i - LA), src_b.soffset(kt),
-                                          stage + BM * kRowBytes, i - LA, wave);
+                issue_load<Shape::kWaves>(src_b.rsrc, src_b.voffset(i - LA), src_b.soffset(), stage + BM * kRowBytes,
+                                          i - LA, wave);
         }
+        src_a.advance();
+        src_b.advance();
+    };
+    auto read_step = [&](int kt, int buf) {
+        const char *stage = smem + (kt % kStages) * kStageBytes;
+        read_frags<TM, TN>(fa[buf][0], fb[buf][0], stage, stage + BM * kRowBytes, a_row0, b_row0, 0, lane);
+        read_frags<TM, TN>(fa[buf][1], fb[buf][1], stage, stage + BM * kRowBytes, a_row0, b_row0, 1, lane);
+    };
+    auto step = [&](int kt, int buf) {
+        wait_vmem_and_lds<2 * kLoads>();
+        wg_barrier();
+        read_step(kt + 1, buf ^ 1);
+        issue(kt + 4);
+        mma_kstep<TM, TN>(t, fa[buf], fb[buf]);
+        // interleave: one LDS read or one buffer load behind each of the first MFMAs
+#pragma unroll
+        for (int g = 0; g < 2 * (TM + TN); ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+        }
+#pragma unroll
+        for (int g = 0; g < kLoads; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
+        }
+        __builtin_amdgcn_sched_barrier(0);
     };
 
-    issue(0, 0, kLoads);
-    issue(1, 0, kLoads);
-    issue(2, 0, kLoads);
-    wait_vmem<2 * kLoads>();  // step 0 has landed
+    issue(0);
+    issue(1);
+    issue(2);
+    issue(3);
+    wait_vmem<3 * kLoads>();  // step 0 has landed
     wg_barrier();
-    read_frags<TM, TN>(fa[0], fb[0], smem, smem + BM * kRowBytes, a_row0, b_row0, 0, lane);
+    read_step(0, 0);
 
-    // Each k-substep is ordered by hand with scheduling barriers: the first row of MFMAs
-    // goes out, then the operand reads for the next substep, then the remaining MFMAs with
-    // the global->LDS loads mixed in.  Reads issued in front of an MFMA group would make the
-    // group's own operand wait (an in-order counter) cover them too; reads left to the
-    // scheduler sink behind the whole group and their latency is exposed.
+    int kt = 0;
+    for (; kt + 1 < ktiles; kt += 2) {
+        step(kt, 0);
+        step(kt + 1, 1);
+    }
+    if (kt < ktiles) step(kt, 0);
+    wait_vmem_and_lds<0>();  // drain the over-issued loads and reads before LDS is reused or released
+}
+
+// Ping-pong K loop for workgroups of two wave groups (WM == 2; group = wave / WN, so the
+// two waves that share a SIMD belong to different groups).  Each K-step of a wave is split
+// into a memory phase (all operand reads of the step, the global->LDS loads of step kt+3,
+// the waits) and a compute phase (only MFMAs, from registers).  The groups run half a
+// period apart: while one group's MFMAs own the matrix pipe, the other group does its
+// memory phase, so load issue, LDS latency and barrier waits hide behind MFMAs.  Barriers
+// separate the phases; group 1 executes one extra barrier before the loop (which shifts
+// its phase) and group 0 one after it, so every wave executes the same number.
+//
+// Stage safety (ring of 4, loads 3 steps ahead): the loads of step kt+3 overwrite the
+// stage of step kt-1.  A wave issues them in its memory phase kt, which starts after a
+// barrier that every wave reaches only when its own reads of stage kt-1 have returned
+// (lgkmcnt(0) ends each memory phase).  A wave reads stage kt after a barrier that every
+// wave reaches only when its own loads of step kt have landed (the vmcnt wait that ends
+// memory phase kt-1 leaves just two younger steps in flight).
+template <int TM, int TN, int WM, int WN, typename SrcA, typename SrcB>
+__device__ __forceinline__ void mfma_mainloop_pingpong(WaveTile<TM, TN> &t, char *smem, int ktiles, int wave,
+                                                       int lane, int a_row0, int b_row0, SrcA &src_a, SrcB &src_b)
+{
+    using Shape = TileShape<TM, TN, WM, WN>;
+    static_assert(WM == 2, "two wave groups");
+    constexpr int BM = Shape::BM;
+    constexpr int kStageBytes = Shape::kStageBytes;
+    constexpr int LA = Shape::kLoadsA, kLoads = Shape::kLoadsA + Shape::kLoadsB;
+    static_assert(2 * kLoads < 64, "two K-steps of loads must fit the vmcnt counter");
+    const int group = wave / WN;  // uniform
+    bf16x8_t fa[2][TM], fb[2][TN];
+
+    // loads of the sources' current K-step into ring slot kt % kStages; called with kt = 0, 1, 2, ...
+    auto issue = [&](int kt) {
+        char *stage = smem + (kt % kStages) * kStageBytes;
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) {
+            if (i < LA)
+                issue_load<Shape::kWaves>(src_a.rsrc, src_a.voffset(i), src_a.soffset(), stage, i, wave);
+            else
+                issue_load<Shape::kWaves>(src_b.rsrc, src_b.voffset(i - LA), src_b.soffset(), stage + BM * kRowBytes,
+                                          i - LA, wave);
+        }
+        src_a.advance();
+        src_b.advance();
+    };
+
+    issue(0);
+    issue(1);
+    issue(2);
+    wait_vmem<2 * kLoads>();  // own part of step 0 has landed
+    wg_barrier();
+    if (group == 1) wg_barrier();  // phase shift; balanced by group 0's barrier after the loop
+
     for (int kt = 0; kt < ktiles; ++kt) {
         const char *cur = smem + (kt % kStages) * kStageBytes;
-        const char *nxt = smem + ((kt + 1) % kStages) * kStageBytes;
-        // k-substep 0
-        mma_rows<0, 1>(t, fa[0], fb[0]);
-        __builtin_amdgcn_sched_barrier(0);
+        // memory phase
+        read_frags<TM, TN>(fa[0], fb[0], cur, cur + BM * kRowBytes, a_row0, b_row0, 0, lane);
         read_frags<TM, TN>(fa[1], fb[1], cur, cur + BM * kRowBytes, a_row0, b_row0, 1, lane);
+        issue(kt + 3);
+        wait_vmem_and_lds<2 * kLoads>();  // own loads of step kt+1 landed, own reads returned
         __builtin_amdgcn_sched_barrier(0);
-        issue(kt + 3, 0, kLoads / 2);
-        mma_rows<1, TM>(t, fa[0], fb[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        // step kt+1 must have landed (younger loads: step kt+2 and half of kt+3), and every
-        // wave must be done reading step kt-1's stage before it is refilled
-        wait_vmem_and_lds<kLoads + kLoads / 2>();
         wg_barrier();
-        // k-substep 1
-        mma_rows<0, 1>(t, fa[1], fb[1]);
+        // compute phase
+        __builtin_amdgcn_s_setprio(1);
+        mma_kstep<TM, TN>(t, fa, fb);
+        __builtin_amdgcn_s_setprio(0);
         __builtin_amdgcn_sched_barrier(0);
-        read_frags<TM, TN>(fa[0], fb[0], nxt, nxt + BM * kRowBytes, a_row0, b_row0, 0, lane);
-        __builtin_amdgcn_sched_barrier(0);
-        issue(kt + 3, kLoads / 2, kLoads - kLoads / 2);
-        mma_rows<1, TM>(t, fa[1], fb[1]);
-        __builtin_amdgcn_sched_barrier(0);
+        wg_barrier();
     }
+    if (group == 0) wg_barrier();
     wait_vmem<0>();  // drain the over-issued loads before the stages are reused or released
 }
 
