@@ -100,9 +100,10 @@ __global__ __launch_bounds__(64 * WM * WN) void conv2d_mfma_kernel(const uint16_
 //     an LDS ring slot (global -> LDS, zero padding by buffer range check), as R*S*C/32
 //     swizzled sub-tiles of 32 pixels x 32 channels;
 //   * every wave reads the whole slice (one ds_read_b128 per MFMA) and multiplies it with
-//     its own 32 channels: 36 MFMAs chained on a single accumulator, the operand registers
-//     of block b being refilled with block b+1 as soon as each MFMA has consumed them;
-//   * one barrier per block; LDS holds 3 blocks so loads run two blocks ahead.
+//     its own 32 channels: 36 MFMAs chained on a single accumulator, fed from a window of
+//     12 operand registers that is refilled as soon as each MFMA has consumed its slot;
+//   * one barrier per block (two thirds into its MFMAs, when the window moves on to the
+//     next block's slot); LDS holds 3 blocks, loads run up to three blocks ahead.
 // The MFMA takes the weights as its row operand, so a lane ends up with 4 consecutive
 // output channels of one pixel; the block's results are staged in LDS and written out
 // after the next barrier as whole pixel rows, 16 bytes per lane.
@@ -166,22 +167,27 @@ __global__ __launch_bounds__(256) void conv2d_wreg_kernel(const uint16_t *__rest
             __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void *)(slot + sub * 2048 + half * 1024),
                                                      16, inside ? pix + tap_off : kOutOfRange, 0, 0, 0);
         }
-        // advance this lane's pixel by one block (32 pixels) without dividing
+        // advance this lane's pixel by one block (32 pixels): Q >= 32 (checked by the host),
+        // so the column wraps at most once; written as selects to keep the loop body free of
+        // branches (the instruction interleaving below works inside one basic block only)
         m_l += 32;
         q_l += 32;
-        while (q_l >= g.Q) {
-            q_l -= g.Q;
-            if (++p_l == g.P) {
-                p_l = 0;
-                ++n_l;
-            }
-        }
+        const bool wrap_q = q_l >= g.Q;
+        q_l = wrap_q ? q_l - g.Q : q_l;
+        p_l = wrap_q ? p_l + 1 : p_l;
+        const bool wrap_p = p_l == g.P;
+        p_l = wrap_p ? 0 : p_l;
+        n_l = wrap_p ? n_l + 1 : n_l;
     };
 
     // operand reads: fragment kk of a block lives in sub-tile kk / (2*... ) -- tap-major, then 16-channel group
     const int frag_lo = frag_offset(lane & 31, lane >> 5);        // k-substep 0 of a sub-tile
     const int frag_hi = frag_offset(lane & 31, 2 + (lane >> 5));  // k-substep 1
-    bf16x8_t af[KSUB];
+    // operand window: MFMA kk uses slot kk % kWin, which is refilled at once with the fragment
+    // kWin positions further down the stream (this block's, or the next block's first ones)
+    constexpr int kWin = 12;
+    static_assert(KSUB % kWin == 0, "window must divide the fragment count");
+    bf16x8_t af[kWin];
     auto read_frag = [&](const char *slot, int kk) {
         const int sub = kk / 2;  // 32 channels per sub-tile = 2 k-substeps; sub-tiles are stored tap-major
         return *reinterpret_cast<const bf16x8_t *>(slot + sub * 2048 + ((kk & 1) ? frag_hi : frag_lo));
@@ -203,48 +209,64 @@ __global__ __launch_bounds__(256) void conv2d_wreg_kernel(const uint16_t *__rest
     wait_vmem<KSUB + 2 * kLoads>();  // own part of block 0 has landed (loads complete in order)
     wg_barrier();
 #pragma unroll
-    for (int kk = 0; kk < KSUB; ++kk) af[kk] = read_frag(smem, kk);
+    for (int kk = 0; kk < kWin; ++kk) af[kk] = read_frag(smem, kk);
 
     // output: lane holds channels wave*32 + 8a + 4*(lane/32) + 0..3 of pixel lane%32
     char *const out_stage = smem + kSlots * kSlot;
     const int stage_wr = (lane & 31) * kOutPitch + (wave * 32 + 4 * (lane >> 5)) * (int)sizeof(CT);
-    // write-out of the previous block: this wave stores pixel rows wave*8 .. wave*8+7
-    auto store_block = [&](int b) {
+    // write-out of a staged block: this wave stores pixel rows wave*8 .. wave*8+7 through a
+    // buffer resource; rows past the range (or a disabled call) get an out-of-range offset and
+    // are dropped by the hardware, so there is no branch
+    const rsrc_t yr = make_rsrc(y, (uint32_t)((int64_t)Mtot * KOUT * sizeof(CT)));
+    auto store_block = [&](int b, bool enable) {
         const char *stg = out_stage + (b & 1) * kOutBytes;
 #pragma unroll
         for (int t = 0; t < kStores; ++t) {
             const int row = wave * 8 + t * (64 / kRowLanes) + lane / kRowLanes;
             const int m = start + b * 32 + row;
             const uint4_t v = *reinterpret_cast<const uint4_t *>(stg + row * kOutPitch + (lane % kRowLanes) * 16);
-            if (m < end)
-                __builtin_nontemporal_store(v, reinterpret_cast<uint4_t *>(reinterpret_cast<char *>(y) +
-                                                                            (int64_t)m * (KOUT * sizeof(CT)) +
-                                                                            (lane % kRowLanes) * 16));
+            const uint32_t off = (uint32_t)m * (uint32_t)(KOUT * sizeof(CT)) + (lane % kRowLanes) * 16;
+            __builtin_amdgcn_raw_buffer_store_b128(v, yr, (enable && m < end) ? off : kOutOfRange, 0, 2 /* nt */);
         }
     };
     for (int b = 0; b < nblocks; ++b) {
-        // own loads of block b+1 have landed (younger: block b+2's loads and block b-1's stores),
-        // own reads of block b have returned
-        if (b < 2) wait_vmem_and_lds<kLoads>();
-        else wait_vmem_and_lds<kLoads + kStores>();
-        wg_barrier();
-        if (b > 0) store_block(b - 1);  // staged by all waves before the barrier
-        issue_block(b + 3);             // into the slot of block b, which every wave has finished reading
+        const char *cur = smem + (b % kSlots) * kSlot;
         const char *nxt = smem + ((b + 1) % kSlots) * kSlot;
         float16_t acc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+        // first part: the window is refilled from this block's own slot
 #pragma unroll
-        for (int kk = 0; kk < KSUB; ++kk) {
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk], acc, 0, 0, 0);
-            af[kk] = read_frag(nxt, kk);
+        for (int kk = 0; kk < KSUB - kWin; ++kk) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
+            af[kk % kWin] = read_frag(cur, kk + kWin);
         }
-        // one operand read behind every MFMA, one global->LDS load behind every fourth
 #pragma unroll
-        for (int kk = 0; kk < KSUB; ++kk) {
+        for (int kk = 0; kk < KSUB - kWin; ++kk) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
-            if (kk % 4 == 1 && kk / 4 < kLoads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // The block's one synchronisation point.  Before it: own loads of block b+1 have landed
+        // (younger: block b+2's loads and block b-2's write-out) and own reads of this block's
+        // slot have returned.  After it: block b+1 is complete in LDS, and this block's slot is
+        // free for block b+3.
+        wait_vmem_and_lds<kLoads + kStores>();
+        wg_barrier();
+        store_block(b - 1, b > 0);  // staged by all waves before the barrier
+        issue_block(b + 3);
+        // second part: the window is refilled with the next block's first fragments
+#pragma unroll
+        for (int kk = KSUB - kWin; kk < KSUB; ++kk) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
+            af[kk % kWin] = read_frag(nxt, kk + kWin - KSUB);
+        }
+        // one operand read behind every MFMA, the global->LDS loads spread between them
+#pragma unroll
+        for (int kk = 0; kk < kWin; ++kk) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+            if (kk < kLoads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
         }
         __builtin_amdgcn_sched_barrier(0);
         // stage the block's results for the coalesced write-out after the next barrier
@@ -263,7 +285,7 @@ __global__ __launch_bounds__(256) void conv2d_wreg_kernel(const uint16_t *__rest
     if (nblocks > 0) {
         wait_vmem_and_lds<0>();
         wg_barrier();
-        store_block(nblocks - 1);
+        store_block(nblocks - 1, true);
     }
     wait_vmem_and_lds<0>();
 }
@@ -380,7 +402,7 @@ extern "C" perf_status perf_conv2d(const void *x, const void *w, void *y, int64_
                          N * H * W * C < (int64_t(1) << 30) && K * R * S * C < (int64_t(1) << 30) &&
                          ((N * P * Q + 127) / 128) * ((K + 127) / 128) <= kMaxGridX;
     // filter shapes with a weights-in-registers instance
-    if (mfma_ok && R == 3 && S == 3 && C == 64 && K == 128)
+    if (mfma_ok && R == 3 && S == 3 && C == 64 && K == 128 && Q >= 32 && N * P * Q * K < (int64_t(1) << 29))
         return y_dt == PERF_F32 ? launch_conv_wreg<3, 3, 64, float>(x, w, y, g, st)
                                 : launch_conv_wreg<3, 3, 64, uint16_t>(x, w, y, g, st);
     if (mfma_ok)
