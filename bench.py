@@ -124,7 +124,7 @@ def build_workloads(torch, perf):
     d3 = c3.make()
     a3, b3 = rotated(G.dev(d3["a_bf16"]), 4), rotated(G.dev(d3["b_bf16"]), 4)
     o3 = torch.empty((4, c3.M, c3.N), dtype=torch.float32, device="cuda")
-    wls.append(Workload("gemm_4096x4096x4096_bf16", "gemm_mfma_kernel<4,4,f32>", "mfma", c3.flops(),
+    wls.append(Workload("gemm_4096x4096x4096_bf16", "gemm_mfma_kernel<4,4,2,2,f32>", "mfma", c3.flops(),
                         lambda i: perf.perf_gemm(a3[i % 4].data_ptr(), b3[i % 4].data_ptr(), o3[i % 4].data_ptr(),
                                                  c3.M, c3.N, c3.K, ROW, c3.K, COL, c3.K, c3.N, 1, 0, 0, 0, 1.0,
                                                  BF16, F32, st()), 4))
@@ -137,7 +137,7 @@ def build_workloads(torch, perf):
     p4 = torch.empty_like(s4)
     S, D = c4.seq, c4.d
     qk_bytes = 2 * c4.batch * S * D * 2 + c4.batch * S * S * 4
-    wls.append(Workload("attn_scores_qk_512x(512x512x64)", "gemm_mfma_kernel<4,4,f32>", "hbm", qk_bytes,
+    wls.append(Workload("attn_scores_qk_512x(512x512x64)", "gemm_mfma_kernel<4,4,2,2,f32>", "hbm", qk_bytes,
                         lambda i: perf.perf_gemm(q4.data_ptr(), k4.data_ptr(), s4.data_ptr(), S, S, D, ROW, D, COL, D,
                                                  S, c4.batch, S * D, S * D, S * S, c4.alpha, BF16, F32, st()),
                         1, "28 flop/byte: bound by the 512 MiB fp32 score store, not by MFMA"))
@@ -151,7 +151,7 @@ def build_workloads(torch, perf):
     x5 = rotated(G.dev(d5["x_bf16"]), 16)
     w5 = G.dev(d5["w_bf16"])
     y5 = torch.empty((16, c5.N, c5.P, c5.Q, c5.K), dtype=torch.int16, device="cuda")
-    wls.append(Workload("conv2d_32x56x56x64_k128_3x3_bf16", "conv2d_mfma_kernel<bf16>", "mfma", c5.flops(),
+    wls.append(Workload("conv2d_32x56x56x64_k128_3x3_bf16", "conv2d_wreg_kernel<3,3,64,bf16>", "mfma", c5.flops(),
                         lambda i: perf.perf_conv2d(x5[i % 16].data_ptr(), w5.data_ptr(), y5[i % 16].data_ptr(), c5.N,
                                                    c5.H, c5.W, c5.C, c5.K, c5.R, c5.S, 1, 1, 1, 1, BF16, BF16, st()),
                         16))
