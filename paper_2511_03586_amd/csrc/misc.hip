@@ -42,7 +42,7 @@ extern "C" perf_status perf_copy(const void *src, void *dst, int64_t bytes, perf
     const int64_t nvec = vec ? bytes / 16 : 0;
     if (nvec > 0) {
         int64_t blocks = (nvec + 256 * kCopyUnroll - 1) / (256 * kCopyUnroll);
-        if (blocks > 256 * 32) blocks = 256 * 32;
+        if (blocks > 256 * 1024) blocks = 256 * 1024;  // one pass per workgroup measured faster than a long grid-stride loop
         hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const uint4_t *)src, (uint4_t *)dst,
                            nvec);
     }
