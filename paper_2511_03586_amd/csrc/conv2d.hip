@@ -91,6 +91,22 @@ __global__ __launch_bounds__(64 * WM * WN) void conv2d_mfma_kernel(const uint16_
 }
 
 // ---- weights-in-registers kernel ---------------------------------------------------
+// Stage one accumulator (32 channels x 32 pixels, weights as the MFMA row operand) for the
+// row-wise write-out: element group a of a lane is 4 consecutive channels of its pixel.
+template <typename CT>
+__device__ __forceinline__ void stage_acc(const float16_t &acc, char *stg)
+{
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        if constexpr (sizeof(CT) == 4) {
+            *reinterpret_cast<float4_t *>(stg + 8 * a * 4) = float4_t{acc[4 * a], acc[4 * a + 1], acc[4 * a + 2], acc[4 * a + 3]};
+        } else {
+            *reinterpret_cast<uint2_t *>(stg + 8 * a * 2) =
+                uint2_t{pack_bf16(acc[4 * a], acc[4 * a + 1]), pack_bf16(acc[4 * a + 2], acc[4 * a + 3])};
+        }
+    }
+}
+
 // For filters small enough that a wavefront can keep its share of them in registers
 // (here: 128 output channels, 4 waves x 32 channels, R*S*C = 576 -> 36 operand fragments
 // = 144 VGPRs per lane), the contraction is turned around: the weights never move after
@@ -127,7 +143,7 @@ __global__ __launch_bounds__(256) void conv2d_wreg_kernel(const uint16_t *__rest
     constexpr int kRowLanes = KOUT * (int)sizeof(CT) / 16;  // lanes per pixel row of 16-byte pieces
     constexpr int kStores = 8 * kRowLanes / 64;             // store instructions per wave per block (8 rows per wave)
     static_assert(C % 32 == 0 && (NSUB * 2) % 4 == 0, "sub-tiles must divide among the four waves");
-    static_assert(kLoads + kStores < 64, "vmcnt is a 6-bit counter");
+    static_assert(kLoads + 2 * kStores < 64, "vmcnt is a 6-bit counter");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -152,8 +168,8 @@ __global__ __launch_bounds__(256) void conv2d_wreg_kernel(const uint16_t *__rest
     const uint32_t chunk_l = load_chunk(row_l, lane) * 16;
     // All offsets are 32-bit: the host admits this kernel only for tensors below 2 GiB, and
     // an offset is used only when its tap lies inside the image (then it is the true one).
-    auto issue_block = [&](int b) {
-        char *slot = smem + (b % kSlots) * kSlot;
+    uint32_t voff_l[kLoads];  // per-lane offsets of the next block to fetch (out of range: zeros)
+    auto prep_block = [&]() {
         const int ih0 = p_l * g.sh - g.ph, iw0 = q_l * g.sw - g.pw;
         const uint32_t pix = (uint32_t)(((n_l * g.H + ih0) * g.W + iw0) * C) * 2u + chunk_l;
         const bool live = m_l < end;
@@ -164,8 +180,7 @@ __global__ __launch_bounds__(256) void conv2d_wreg_kernel(const uint16_t *__rest
             const int r = tap / S, sft = tap % S;
             const uint32_t tap_off = (uint32_t)((r * g.W + sft) * C + cb * 32) * 2u;  // scalar
             const bool inside = live && (unsigned)(ih0 + r) < (unsigned)g.H && (unsigned)(iw0 + sft) < (unsigned)g.W;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void *)(slot + sub * 2048 + half * 1024),
-                                                     16, inside ? pix + tap_off : kOutOfRange, 0, 0, 0);
+            voff_l[t] = inside ? pix + tap_off : kOutOfRange;
         }
         // advance this lane's pixel by one block (32 pixels): Q >= 32 (checked by the host),
         // so the column wraps at most once; written as selects to keep the loop body free of
@@ -178,6 +193,22 @@ __global__ __launch_bounds__(256) void conv2d_wreg_kernel(const uint16_t *__rest
         const bool wrap_p = p_l == g.P;
         p_l = wrap_p ? 0 : p_l;
         n_l = wrap_p ? n_l + 1 : n_l;
+    };
+    auto fire_block = [&](int b) {
+        char *slot = smem + (b % kSlots) * kSlot;
+#pragma unroll
+        for (int t = 0; t < kLoads; ++t) {
+            const int sub = (wave >> 1) + 2 * t;
+            // (copied to a local first: with the captured array element as the builtin's argument the
+            // host pass silently drops this kernel's stub and the library no longer loads)
+            const uint32_t vo = voff_l[t];
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void *)(slot + sub * 2048 + half * 1024),
+                                                     16, vo, 0, 0, 0);
+        }
+    };
+    auto issue_block = [&](int b) {
+        prep_block();
+        fire_block(b);
     };
 
     // operand reads: fragment kk of a block lives in sub-tile kk / (2*... ) -- tap-major, then 16-channel group
@@ -229,60 +260,66 @@ __global__ __launch_bounds__(256) void conv2d_wreg_kernel(const uint16_t *__rest
             __builtin_amdgcn_raw_buffer_store_b128(v, yr, (enable && m < end) ? off : kOutOfRange, 0, 2 /* nt */);
         }
     };
-    for (int b = 0; b < nblocks; ++b) {
-        const char *cur = smem + (b % kSlots) * kSlot;
-        const char *nxt = smem + ((b + 1) % kSlots) * kSlot;
-        float16_t acc;
+    // One block.  `acc` collects block b; `prev` holds block b-1's finished results.
+    //   first 24 MFMAs (window refilled from this block's slot), and in their shadow: block
+    //     b-1's results go to the LDS staging buffer, block b-2 is written out from the other
+    //     staging buffer, and the offsets of block b+3 are computed;
+    //   the block's one synchronisation point.  Before it: own loads of block b+1 have landed
+    //     (younger: block b+2's loads and the write-outs of blocks b-3 and b-2) and own reads of
+    //     this block's slot have returned.  After it: block b+1 is complete in LDS, this block's
+    //     slot is free for block b+3, and block b-1's staged results are visible;
+    //   last 12 MFMAs (window refilled with the next block's first fragments) with the loads of
+    //     block b+3 between them.
+    float16_t accs[2];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-        // first part: the window is refilled from this block's own slot
+    for (int e = 0; e < 16; ++e) accs[1][e] = 0.f;
+    for (int b0 = 0; b0 < nblocks; b0 += 2) {
 #pragma unroll
-        for (int kk = 0; kk < KSUB - kWin; ++kk) {
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
-            af[kk % kWin] = read_frag(cur, kk + kWin);
-        }
+        for (int h = 0; h < 2; ++h) {
+            const int b = b0 + h;
+            if (b >= nblocks) break;
+            float16_t &acc = accs[h];
+            const float16_t &prev = accs[h ^ 1];
+            const char *cur = smem + (b % kSlots) * kSlot;
+            const char *nxt = smem + ((b + 1) % kSlots) * kSlot;
 #pragma unroll
-        for (int kk = 0; kk < KSUB - kWin; ++kk) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // The block's one synchronisation point.  Before it: own loads of block b+1 have landed
-        // (younger: block b+2's loads and block b-2's write-out) and own reads of this block's
-        // slot have returned.  After it: block b+1 is complete in LDS, and this block's slot is
-        // free for block b+3.
-        wait_vmem_and_lds<kLoads + kStores>();
-        wg_barrier();
-        store_block(b - 1, b > 0);  // staged by all waves before the barrier
-        issue_block(b + 3);
-        // second part: the window is refilled with the next block's first fragments
+            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+            stage_acc<CT>(prev, out_stage + ((b - 1) & 1) * kOutBytes + stage_wr);  // (b == 0: zeros, never written out)
+            store_block(b - 2, b > 1);
+            prep_block();
 #pragma unroll
-        for (int kk = KSUB - kWin; kk < KSUB; ++kk) {
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
-            af[kk % kWin] = read_frag(nxt, kk + kWin - KSUB);
-        }
-        // one operand read behind every MFMA, the global->LDS loads spread between them
-#pragma unroll
-        for (int kk = 0; kk < kWin; ++kk) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
-            if (kk < kLoads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // stage the block's results for the coalesced write-out after the next barrier
-        char *stg = out_stage + (b & 1) * kOutBytes + stage_wr;
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            if constexpr (sizeof(CT) == 4) {
-                *reinterpret_cast<float4_t *>(stg + 8 * a * 4) =
-                    float4_t{acc[4 * a], acc[4 * a + 1], acc[4 * a + 2], acc[4 * a + 3]};
-            } else {
-                *reinterpret_cast<uint2_t *>(stg + 8 * a * 2) =
-                    uint2_t{pack_bf16(acc[4 * a], acc[4 * a + 1]), pack_bf16(acc[4 * a + 2], acc[4 * a + 3])};
+            for (int kk = 0; kk < KSUB - kWin; ++kk) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
+                af[kk % kWin] = read_frag(cur, kk + kWin);
             }
+#pragma unroll
+            for (int kk = 0; kk < KSUB - kWin; ++kk) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            wait_vmem_and_lds<kLoads + 2 * kStores>();
+            wg_barrier();
+            fire_block(b + 3);
+#pragma unroll
+            for (int kk = KSUB - kWin; kk < KSUB; ++kk) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
+                af[kk % kWin] = read_frag(nxt, kk + kWin - KSUB);
+            }
+#pragma unroll
+            for (int kk = 0; kk < kWin; ++kk) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+                if (kk < kLoads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
+    const float16_t acc1 = ((nblocks - 1) & 1) ? accs[1] : accs[0];  // the last block's results
     if (nblocks > 0) {
+        // drain: block nblocks-2 is staged (if it exists), block nblocks-1 is still in registers
+        stage_acc<CT>(acc1, out_stage + ((nblocks - 1) & 1) * kOutBytes + stage_wr);
+        store_block(nblocks - 2, nblocks > 1);
         wait_vmem_and_lds<0>();
         wg_barrier();
         store_block(nblocks - 1, true);
