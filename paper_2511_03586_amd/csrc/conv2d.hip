@@ -172,14 +172,35 @@ __global__ __launch_bounds__(256) void conv2d_wreg_kernel(const uint16_t *__rest
     auto prep_block = [&]() {
         const int ih0 = p_l * g.sh - g.ph, iw0 = q_l * g.sw - g.pw;
         const uint32_t pix = (uint32_t)(((n_l * g.H + ih0) * g.W + iw0) * C) * 2u + chunk_l;
-        const bool live = m_l < end;
+        // row / column validity once per filter row / column (the per-tap combination is then
+        // scalar mask arithmetic, not vector work)
+        bool row_ok[R], col_ok[S];
+#pragma unroll
+        for (int r = 0; r < R; ++r) row_ok[r] = m_l < end && (unsigned)(ih0 + r) < (unsigned)g.H;
+#pragma unroll
+        for (int sft = 0; sft < S; ++sft) col_ok[sft] = (unsigned)(iw0 + sft) < (unsigned)g.W;
 #pragma unroll
         for (int t = 0; t < kLoads; ++t) {
-            const int sub = (wave >> 1) + 2 * t;  // uniform: sub-tile -> filter tap and channel block
-            const int tap = sub / CB, cb = sub % CB;
+            // sub-tile = 2t + wave/2 -> filter tap and channel block.  With two 32-channel blocks
+            // per tap (CB == 2) the tap is t and the channel block wave/2, so r and s are
+            // compile-time; otherwise they are uniform run-time values.
+            int tap, cb;
+            if constexpr (CB == 2) {
+                tap = t;
+                cb = wave >> 1;
+            } else {
+                const int sub = (wave >> 1) + 2 * t;
+                tap = sub / CB;
+                cb = sub % CB;
+            }
             const int r = tap / S, sft = tap % S;
             const uint32_t tap_off = (uint32_t)((r * g.W + sft) * C + cb * 32) * 2u;  // scalar
-            const bool inside = live && (unsigned)(ih0 + r) < (unsigned)g.H && (unsigned)(iw0 + sft) < (unsigned)g.W;
+            bool inside;
+            if constexpr (CB == 2) {
+                inside = row_ok[r] && col_ok[sft];
+            } else {
+                inside = m_l < end && (unsigned)(ih0 + r) < (unsigned)g.H && (unsigned)(iw0 + sft) < (unsigned)g.W;
+            }
             voff_l[t] = inside ? pix + tap_off : kOutOfRange;
         }
         // advance this lane's pixel by one block (32 pixels): Q >= 32 (checked by the host),
@@ -224,20 +245,45 @@ __global__ __launch_bounds__(256) void conv2d_wreg_kernel(const uint16_t *__rest
         return *reinterpret_cast<const bf16x8_t *>(slot + sub * 2048 + ((kk & 1) ? frag_hi : frag_lo));
     };
 
+    // Weights of this wave's 32 channels -> registers.  Fragment kk covers K indices
+    // kk*16 .. +15; a lane holds channel lane%32 and the 8 K values starting at 8*(lane/32).
+    // Read straight from memory that pattern touches 32 different rows per instruction and
+    // is bound by address processing, so the wave's 36 KiB (contiguous in memory) first go
+    // to a private LDS region with fully coalesced global->LDS loads and are picked up from
+    // there.  Each row (72 chunks of 16 bytes) is stored rotated by row/2 chunks, which
+    // spreads the 16 rows read by one ds_read_b128 phase over all 16 bank slots.
+    constexpr int kRowChunks = R * S * C / 8;  // 16-byte chunks per weight row
+    constexpr int kWChunks = 32 * kRowChunks;  // per wave
+    static_assert(kWChunks % 64 == 0, "whole wave loads");
+    bf16x8_t wf[KSUB];
+    {
+        char *wreg = smem + wave * (kWChunks * 16);
+        const rsrc_t wr = make_rsrc(w + (int64_t)wave * 32 * (R * S * C), (uint32_t)(kWChunks * 16));
+#pragma unroll
+        for (int i = 0; i < kWChunks / 64; ++i) {
+            const int L = i * 64 + lane;  // LDS chunk this lane fills
+            const int r = L / kRowChunks, cp = L - r * kRowChunks;
+            int c = cp - (r >> 1);
+            c = c < 0 ? c + kRowChunks : c;
+            const uint32_t vo = (uint32_t)(r * kRowChunks + c) * 16u;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (__attribute__((address_space(3))) void *)(wreg + i * 1024), 16, vo,
+                                                     0, 0, 0);
+        }
+        wait_vmem<0>();
+        const int row = lane & 31;
+#pragma unroll
+        for (int kk = 0; kk < KSUB; ++kk) {
+            int cp = 2 * kk + (lane >> 5) + (row >> 1);
+            cp = cp >= kRowChunks ? cp - kRowChunks : cp;
+            wf[kk] = *reinterpret_cast<const bf16x8_t *>(wreg + (row * kRowChunks + cp) * 16);
+        }
+        wait_vmem_and_lds<0>();
+        wg_barrier();  // every wave has its weights: LDS is free for the activation ring
+    }
     issue_block(0);
     issue_block(1);
     issue_block(2);
-    // weights of this wave's 32 channels, fetched behind the first activation blocks so the two
-    // latencies overlap: fragment kk covers K indices kk*16 .. +15, a lane holds channel
-    // lane%32 and the 8 K values starting at 8*(lane/32)
-    bf16x8_t wf[KSUB];
-    {
-        const uint16_t *wl = w + (int64_t)(wave * 32 + (lane & 31)) * (R * S * C) + 8 * (lane >> 5);
-#pragma unroll
-        for (int kk = 0; kk < KSUB; ++kk) wf[kk] = *reinterpret_cast<const bf16x8_t *>(wl + kk * 16);
-    }
-    static_assert(kSlots * kLoads + KSUB < 64, "prologue loads must fit the vmcnt counter");
-    wait_vmem<KSUB + 2 * kLoads>();  // own part of block 0 has landed (loads complete in order)
+    wait_vmem<2 * kLoads>();  // own part of block 0 has landed (loads complete in order)
     wg_barrier();
 #pragma unroll
     for (int kk = 0; kk < kWin; ++kk) af[kk] = read_frag(smem, kk);
@@ -380,7 +426,9 @@ static perf_status launch_conv_mfma(const void *x, const void *w, void *y, const
 template <int R, int S, int C, typename CT>
 static perf_status launch_conv_wreg(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
 {
-    constexpr int kLds = 3 * (R * S * (C / 32)) * 2048 + 2 * 32 * (128 * (int)sizeof(CT) + 16);
+    constexpr int kRing = 3 * (R * S * (C / 32)) * 2048 + 2 * 32 * (128 * (int)sizeof(CT) + 16);
+    constexpr int kWeights = 128 * R * S * C * 2;  // prologue staging of all weights
+    constexpr int kLds = kRing > kWeights ? kRing : kWeights;
     const int64_t Mtot = (int64_t)g.N * g.P * g.Q;
     int grid = 256;  // one persistent workgroup per CU
     if ((Mtot + 31) / 32 < grid) grid = (int)((Mtot + 31) / 32);
