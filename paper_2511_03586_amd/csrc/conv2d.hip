@@ -111,266 +111,284 @@ __device__ __forceinline__ void stage_acc(const float16_t &acc, char *stg)
 // (here: 128 output channels, 4 waves x 32 channels, R*S*C = 576 -> 36 operand fragments
 // = 144 VGPRs per lane), the contraction is turned around: the weights never move after
 // the prologue, and the activations stream through LDS once per 32-pixel block.
-//   * one persistent workgroup per CU owns a contiguous range of output pixels;
-//   * per block of 32 pixels the four waves together fetch the 32 x 576 im2col slice into
-//     an LDS ring slot (global -> LDS, zero padding by buffer range check), as R*S*C/32
-//     swizzled sub-tiles of 32 pixels x 32 channels;
-//   * every wave reads the whole slice (one ds_read_b128 per MFMA) and multiplies it with
-//     its own 32 channels: 36 MFMAs chained on a single accumulator, fed from a window of
-//     12 operand registers that is refilled as soon as each MFMA has consumed its slot;
-//   * one barrier per block (two thirds into its MFMAs, when the window moves on to the
-//     next block's slot); LDS holds 3 blocks, loads run up to three blocks ahead.
+// One persistent workgroup of 8 waves per CU owns a contiguous range of output pixels; the
+// waves are specialised, and a SIMD hosts one of each kind:
+//   * waves 0-3 ("MFMA waves") hold the weights of 32 output channels each.  Per block
+//     they read the whole 32 x 576 im2col slice from an LDS ring slot (one ds_read_b128
+//     per MFMA, through a rolling window of 9 operand registers) and chain 36 MFMAs on one
+//     accumulator; the previous block's results are converted and staged in LDS in the
+//     shadow of the first MFMAs.  Nothing else is in their instruction stream.
+//   * waves 4-7 ("memory waves") compute the im2col offsets, fetch each block's slice
+//     global -> LDS three blocks ahead (zero padding by the buffer range check, as R*S*C/32
+//     swizzled sub-tiles of 32 pixels x 32 channels), and write staged results out as
+//     whole pixel rows, 16 bytes per lane.
+//   * one workgroup barrier per block, three quarters into its MFMAs, when the operand
+//     window moves on to the next block's slot.
 // The MFMA takes the weights as its row operand, so a lane ends up with 4 consecutive
-// output channels of one pixel; the block's results are staged in LDS and written out
-// after the next barrier as whole pixel rows, 16 bytes per lane.
+// output channels of one pixel.
 template <int R, int S, int C, typename CT>
-__global__ __launch_bounds__(256) void conv2d_wreg_kernel(const uint16_t *__restrict__ x,
+__global__ __launch_bounds__(512) void conv2d_wreg_kernel(const uint16_t *__restrict__ x,
                                                           const uint16_t *__restrict__ w, CT *__restrict__ y,
                                                           ConvGeom g, int px_per_wg)
 {
-    constexpr int KOUT = 128;               // 4 waves x 32 channels
+    constexpr int KOUT = 128;               // 4 MFMA waves x 32 channels
     constexpr int KSUB = R * S * C / 16;    // MFMA k-substeps per pixel block
     constexpr int CB = C / 32;              // 32-channel sub-tiles per filter tap
     constexpr int NSUB = R * S * CB;        // LDS sub-tiles per block, 2 KiB each
     constexpr int kSlot = NSUB * 2048;
     constexpr int kSlots = 3;
-    constexpr int kLoads = NSUB * 2 / 4;    // direct-to-LDS loads per wave per block (1 KiB each)
+    constexpr int kLoads = NSUB * 2 / 4;    // direct-to-LDS loads per memory wave per block (1 KiB each)
     // output staging: a block's 32 x 128 results go through LDS so that global stores write
     // whole pixel rows (16 bytes per lane); the row pitch is padded by 16 bytes against bank
     // conflicts of the column-wise writes
     constexpr int kOutPitch = KOUT * (int)sizeof(CT) + 16;
     constexpr int kOutBytes = 32 * kOutPitch;
     constexpr int kRowLanes = KOUT * (int)sizeof(CT) / 16;  // lanes per pixel row of 16-byte pieces
-    constexpr int kStores = 8 * kRowLanes / 64;             // store instructions per wave per block (8 rows per wave)
-    static_assert(C % 32 == 0 && (NSUB * 2) % 4 == 0, "sub-tiles must divide among the four waves");
+    constexpr int kStores = 8 * kRowLanes / 64;             // store instructions per memory wave per block (8 rows each)
+    constexpr int kWin = 9;                                 // operand window of the MFMA waves
+    static_assert(CB == 2, "two 32-channel sub-tiles per filter tap");
+    static_assert((NSUB * 2) % 4 == 0, "sub-tiles must divide among the four memory waves");
+    static_assert(KSUB % kWin == 0 && KSUB % 2 == 0, "window and weight halves must divide the fragment count");
     static_assert(kLoads + 2 * kStores < 64, "vmcnt is a 6-bit counter");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
+    char *const out_stage = smem + kSlots * kSlot;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int Mtot = g.N * g.P * g.Q;
     const int start = blockIdx.x * px_per_wg, end = min(start + px_per_wg, Mtot);
     const int nblocks = (end - start + 31) / 32;
+    // Both kinds of wave execute exactly 2 + nblocks workgroup barriers.
 
-    // activation loads: a wave fills half `wave % 2` (16 pixels) of sub-tiles wave/2, wave/2 + 2, ...
-    // lane -> pixel row half*16 + lane/4 of the block, chunk position lane%4
-    const rsrc_t xr = make_rsrc(x, (uint32_t)((int64_t)g.N * g.H * g.W * g.C * 2));
-    const int half = wave & 1, row_l = half * 16 + (lane >> 2);
-    int n_l, p_l, q_l;  // pixel start + row_l of block 0 as (image, output row, output column)
-    {
-        const int m = start + row_l;
-        n_l = m / (g.P * g.Q);
-        const int pq = m - n_l * (g.P * g.Q);
-        p_l = pq / g.Q;
-        q_l = pq - p_l * g.Q;
-    }
-    int m_l = start + row_l;
-    const uint32_t chunk_l = load_chunk(row_l, lane) * 16;
-    // All offsets are 32-bit: the host admits this kernel only for tensors below 2 GiB, and
-    // an offset is used only when its tap lies inside the image (then it is the true one).
-    uint32_t voff_l[kLoads];  // per-lane offsets of the next block to fetch (out of range: zeros)
-    auto prep_block = [&]() {
-        const int ih0 = p_l * g.sh - g.ph, iw0 = q_l * g.sw - g.pw;
-        const uint32_t pix = (uint32_t)(((n_l * g.H + ih0) * g.W + iw0) * C) * 2u + chunk_l;
-        // row / column validity once per filter row / column (the per-tap combination is then
-        // scalar mask arithmetic, not vector work)
-        bool row_ok[R], col_ok[S];
+    if (wave < 4) {
+        // ------------------------------ MFMA waves ------------------------------
+        __builtin_amdgcn_s_setprio(2);
+        // Weights of this wave's 32 channels -> registers.  Fragment kk covers K indices
+        // kk*16 .. +15; a lane holds channel lane%32 and the 8 K values starting at 8*(lane/32).
+        // Read straight from memory that pattern touches 32 different rows per instruction, so
+        // the wave's 36 KiB go through a private LDS region with coalesced global->LDS loads,
+        // in two halves of 288 K values (the region overlaps ring slot 2 and the output
+        // staging, which are not in use before the first barrier; slots 0 and 1 are being
+        // filled by the memory waves meanwhile).  A row's 36 chunks of 16 bytes are stored
+        // rotated by row/4 chunks, which spreads the 16 rows read by one ds_read_b128 phase
+        // over all 16 bank slots.
+        constexpr int kHalfChunks = R * S * C / 16;  // 16-byte chunks per weight row and half (36)
+        constexpr int kWLoads = 32 * kHalfChunks / 64;  // wave loads per half (18)
+        static_assert((32 * kHalfChunks) % 64 == 0, "whole wave loads");
+        bf16x8_t wf[KSUB];
+        {
+            char *wreg = smem + 2 * kSlot + wave * (32 * kHalfChunks * 16);
+            const rsrc_t wr = make_rsrc(w + (int64_t)wave * 32 * (R * S * C), (uint32_t)(32 * R * S * C * 2));
+            // LDS chunk L = i*64 + lane of the region holds row L / 36 at stored position L % 36
+            uint32_t wvo[kWLoads];
+            int row = lane >= kHalfChunks ? 1 : 0, cp = lane - row * kHalfChunks;
 #pragma unroll
-        for (int r = 0; r < R; ++r) row_ok[r] = m_l < end && (unsigned)(ih0 + r) < (unsigned)g.H;
-#pragma unroll
-        for (int sft = 0; sft < S; ++sft) col_ok[sft] = (unsigned)(iw0 + sft) < (unsigned)g.W;
-#pragma unroll
-        for (int t = 0; t < kLoads; ++t) {
-            // sub-tile = 2t + wave/2 -> filter tap and channel block.  With two 32-channel blocks
-            // per tap (CB == 2) the tap is t and the channel block wave/2, so r and s are
-            // compile-time; otherwise they are uniform run-time values.
-            int tap, cb;
-            if constexpr (CB == 2) {
-                tap = t;
-                cb = wave >> 1;
-            } else {
-                const int sub = (wave >> 1) + 2 * t;
-                tap = sub / CB;
-                cb = sub % CB;
+            for (int i = 0; i < kWLoads; ++i) {
+                int c = cp - (row >> 2);
+                c = c < 0 ? c + kHalfChunks : c;
+                wvo[i] = (uint32_t)(row * (2 * kHalfChunks) + c) * 16u;
+                cp += 64 - kHalfChunks;
+                ++row;
+                if (cp >= kHalfChunks) {
+                    cp -= kHalfChunks;
+                    ++row;
+                }
             }
-            const int r = tap / S, sft = tap % S;
-            const uint32_t tap_off = (uint32_t)((r * g.W + sft) * C + cb * 32) * 2u;  // scalar
-            bool inside;
-            if constexpr (CB == 2) {
-                inside = row_ok[r] && col_ok[sft];
-            } else {
-                inside = m_l < end && (unsigned)(ih0 + r) < (unsigned)g.H && (unsigned)(iw0 + sft) < (unsigned)g.W;
-            }
-            voff_l[t] = inside ? pix + tap_off : kOutOfRange;
-        }
-        // advance this lane's pixel by one block (32 pixels): Q >= 32 (checked by the host),
-        // so the column wraps at most once; written as selects to keep the loop body free of
-        // branches (the instruction interleaving below works inside one basic block only)
-        m_l += 32;
-        q_l += 32;
-        const bool wrap_q = q_l >= g.Q;
-        q_l = wrap_q ? q_l - g.Q : q_l;
-        p_l = wrap_q ? p_l + 1 : p_l;
-        const bool wrap_p = p_l == g.P;
-        p_l = wrap_p ? 0 : p_l;
-        n_l = wrap_p ? n_l + 1 : n_l;
-    };
-    auto fire_block = [&](int b) {
-        char *slot = smem + (b % kSlots) * kSlot;
+            const int frow = lane & 31;
 #pragma unroll
-        for (int t = 0; t < kLoads; ++t) {
-            const int sub = (wave >> 1) + 2 * t;
-            // (copied to a local first: with the captured array element as the builtin's argument the
-            // host pass silently drops this kernel's stub and the library no longer loads)
-            const uint32_t vo = voff_l[t];
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void *)(slot + sub * 2048 + half * 1024),
-                                                     16, vo, 0, 0, 0);
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int i = 0; i < kWLoads; ++i) {
+                    const uint32_t vo = wvo[i];
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (__attribute__((address_space(3))) void *)(wreg + i * 1024),
+                                                             16, vo, h * (kHalfChunks * 16), 0, 0);
+                }
+                wait_vmem<0>();
+#pragma unroll
+                for (int kk = 0; kk < KSUB / 2; ++kk) {
+                    int p = 2 * kk + (lane >> 5) + (frow >> 2);
+                    p = p >= kHalfChunks ? p - kHalfChunks : p;
+                    wf[h * (KSUB / 2) + kk] = *reinterpret_cast<const bf16x8_t *>(wreg + (frow * kHalfChunks + p) * 16);
+                }
+                wait_vmem_and_lds<0>();  // the region is rewritten by the next half / released at the barrier
+            }
         }
-    };
-    auto issue_block = [&](int b) {
-        prep_block();
-        fire_block(b);
-    };
+        const int frag_lo = frag_offset(lane & 31, lane >> 5);        // k-substep 0 of a sub-tile
+        const int frag_hi = frag_offset(lane & 31, 2 + (lane >> 5));  // k-substep 1
+        // fragment kk of a block: sub-tile kk/2 (32 channels = 2 k-substeps; sub-tiles are stored
+        // tap-major), read relative to the two per-lane addresses of the block's slot so that
+        // the sub-tile offset fits the instruction's immediate field
+        typedef const __attribute__((address_space(3))) char lds_char_t;
+        typedef const __attribute__((address_space(3))) bf16x8_t lds_frag_t;
+        lds_char_t *const lds0 = (lds_char_t *)smem;
+        auto read_frag = [&](uint32_t slot_lo, uint32_t slot_hi, int kk) {
+            return *(lds_frag_t *)(lds0 + ((kk & 1) ? slot_hi : slot_lo) + (kk / 2) * 2048);
+        };
+        // staging position: lane holds channels wave*32 + 8a + 4*(lane/32) + 0..3 of pixel lane%32
+        const int stage_wr = (lane & 31) * kOutPitch + (wave * 32 + 4 * (lane >> 5)) * (int)sizeof(CT);
 
-    // operand reads: fragment kk of a block lives in sub-tile kk / (2*... ) -- tap-major, then 16-channel group
-    const int frag_lo = frag_offset(lane & 31, lane >> 5);        // k-substep 0 of a sub-tile
-    const int frag_hi = frag_offset(lane & 31, 2 + (lane >> 5));  // k-substep 1
-    // operand window: MFMA kk uses slot kk % kWin, which is refilled at once with the fragment
-    // kWin positions further down the stream (this block's, or the next block's first ones)
-    constexpr int kWin = 12;
-    static_assert(KSUB % kWin == 0, "window must divide the fragment count");
-    bf16x8_t af[kWin];
-    auto read_frag = [&](const char *slot, int kk) {
-        const int sub = kk / 2;  // 32 channels per sub-tile = 2 k-substeps; sub-tiles are stored tap-major
-        return *reinterpret_cast<const bf16x8_t *>(slot + sub * 2048 + ((kk & 1) ? frag_hi : frag_lo));
-    };
+        wg_barrier();  // block 0 is complete in slot 0 (and every wave is done with the weight region)
+        bf16x8_t af[kWin];
+#pragma unroll
+        for (int kk = 0; kk < kWin; ++kk) af[kk] = read_frag((uint32_t)frag_lo, (uint32_t)frag_hi, kk);
+        float16_t accs[2];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) accs[0][e] = accs[1][e] = 0.f;
 
-    // Weights of this wave's 32 channels -> registers.  Fragment kk covers K indices
-    // kk*16 .. +15; a lane holds channel lane%32 and the 8 K values starting at 8*(lane/32).
-    // Read straight from memory that pattern touches 32 different rows per instruction and
-    // is bound by address processing, so the wave's 36 KiB (contiguous in memory) first go
-    // to a private LDS region with fully coalesced global->LDS loads and are picked up from
-    // there.  Each row (72 chunks of 16 bytes) is stored rotated by row/2 chunks, which
-    // spreads the 16 rows read by one ds_read_b128 phase over all 16 bank slots.
-    constexpr int kRowChunks = R * S * C / 8;  // 16-byte chunks per weight row
-    constexpr int kWChunks = 32 * kRowChunks;  // per wave
-    static_assert(kWChunks % 64 == 0, "whole wave loads");
-    bf16x8_t wf[KSUB];
-    {
-        char *wreg = smem + wave * (kWChunks * 16);
-        const rsrc_t wr = make_rsrc(w + (int64_t)wave * 32 * (R * S * C), (uint32_t)(kWChunks * 16));
+        // One block: `acc` collects block b, `prev` holds block b-1's results (zeros for b = 0,
+        // staged but never written out).  In the shadow of the first MFMAs `prev` is converted
+        // and staged, then cleared for block b+1.  Before the barrier every read of this
+        // block's slot has returned; after it block b+1 is complete in LDS.
+        for (int b0 = 0; b0 < nblocks; b0 += 2) {
 #pragma unroll
-        for (int i = 0; i < kWChunks / 64; ++i) {
-            const int L = i * 64 + lane;  // LDS chunk this lane fills
-            const int r = L / kRowChunks, cp = L - r * kRowChunks;
-            int c = cp - (r >> 1);
-            c = c < 0 ? c + kRowChunks : c;
-            const uint32_t vo = (uint32_t)(r * kRowChunks + c) * 16u;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (__attribute__((address_space(3))) void *)(wreg + i * 1024), 16, vo,
-                                                     0, 0, 0);
-        }
-        wait_vmem<0>();
-        const int row = lane & 31;
+            for (int h = 0; h < 2; ++h) {
+                const int b = b0 + h;
+                if (b >= nblocks) break;
+                float16_t &acc = accs[h];
+                float16_t &prev = accs[h ^ 1];
+                const uint32_t cur = (uint32_t)(b % kSlots) * kSlot, nxt = (uint32_t)((b + 1) % kSlots) * kSlot;
+                uint32_t cur_lo = cur + frag_lo, cur_hi = cur + frag_hi;
+                uint32_t nxt_lo = nxt + frag_lo, nxt_hi = nxt + frag_hi;
+                // opaque to the optimiser: folded with the sub-tile offsets they turn into one address
+                // register per read, which does not fit the register budget of two waves per SIMD
+                asm volatile("" : "+v"(cur_lo), "+v"(cur_hi), "+v"(nxt_lo), "+v"(nxt_hi));
+                char *stg = out_stage + ((b - 1) & 1) * kOutBytes + stage_wr;
 #pragma unroll
-        for (int kk = 0; kk < KSUB; ++kk) {
-            int cp = 2 * kk + (lane >> 5) + (row >> 1);
-            cp = cp >= kRowChunks ? cp - kRowChunks : cp;
-            wf[kk] = *reinterpret_cast<const bf16x8_t *>(wreg + (row * kRowChunks + cp) * 16);
-        }
-        wait_vmem_and_lds<0>();
-        wg_barrier();  // every wave has its weights: LDS is free for the activation ring
-    }
-    issue_block(0);
-    issue_block(1);
-    issue_block(2);
-    wait_vmem<2 * kLoads>();  // own part of block 0 has landed (loads complete in order)
-    wg_barrier();
+                for (int kk = 0; kk < KSUB - kWin; ++kk) {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
+                    af[kk % kWin] = read_frag(cur_lo, cur_hi, kk + kWin);
+                    if (kk >= 1 && kk < 5) {
+                        const int a = kk - 1;
+                        if constexpr (sizeof(CT) == 4) {
+                            *reinterpret_cast<float4_t *>(stg + 8 * a * 4) =
+                                float4_t{prev[4 * a], prev[4 * a + 1], prev[4 * a + 2], prev[4 * a + 3]};
+                        } else {
+                            *reinterpret_cast<uint2_t *>(stg + 8 * a * 2) =
+                                uint2_t{pack_bf16(prev[4 * a], prev[4 * a + 1]), pack_bf16(prev[4 * a + 2], prev[4 * a + 3])};
+                        }
+                    }
+                    if (kk >= 6 && kk < 10) {
 #pragma unroll
-    for (int kk = 0; kk < kWin; ++kk) af[kk] = read_frag(smem, kk);
-
-    // output: lane holds channels wave*32 + 8a + 4*(lane/32) + 0..3 of pixel lane%32
-    char *const out_stage = smem + kSlots * kSlot;
-    const int stage_wr = (lane & 31) * kOutPitch + (wave * 32 + 4 * (lane >> 5)) * (int)sizeof(CT);
-    // write-out of a staged block: this wave stores pixel rows wave*8 .. wave*8+7 through a
-    // buffer resource; rows past the range (or a disabled call) get an out-of-range offset and
-    // are dropped by the hardware, so there is no branch
-    const rsrc_t yr = make_rsrc(y, (uint32_t)((int64_t)Mtot * KOUT * sizeof(CT)));
-    auto store_block = [&](int b, bool enable) {
-        const char *stg = out_stage + (b & 1) * kOutBytes;
+                        for (int e = 0; e < 4; ++e) prev[4 * (kk - 6) + e] = 0.f;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                wait_vmem_and_lds<0>();
+                wg_barrier();
 #pragma unroll
-        for (int t = 0; t < kStores; ++t) {
-            const int row = wave * 8 + t * (64 / kRowLanes) + lane / kRowLanes;
-            const int m = start + b * 32 + row;
-            const uint4_t v = *reinterpret_cast<const uint4_t *>(stg + row * kOutPitch + (lane % kRowLanes) * 16);
-            const uint32_t off = (uint32_t)m * (uint32_t)(KOUT * sizeof(CT)) + (lane % kRowLanes) * 16;
-            __builtin_amdgcn_raw_buffer_store_b128(v, yr, (enable && m < end) ? off : kOutOfRange, 0, 2 /* nt */);
-        }
-    };
-    // One block.  `acc` collects block b; `prev` holds block b-1's finished results.
-    //   first 24 MFMAs (window refilled from this block's slot), and in their shadow: block
-    //     b-1's results go to the LDS staging buffer, block b-2 is written out from the other
-    //     staging buffer, and the offsets of block b+3 are computed;
-    //   the block's one synchronisation point.  Before it: own loads of block b+1 have landed
-    //     (younger: block b+2's loads and the write-outs of blocks b-3 and b-2) and own reads of
-    //     this block's slot have returned.  After it: block b+1 is complete in LDS, this block's
-    //     slot is free for block b+3, and block b-1's staged results are visible;
-    //   last 12 MFMAs (window refilled with the next block's first fragments) with the loads of
-    //     block b+3 between them.
-    float16_t accs[2];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) accs[1][e] = 0.f;
-    for (int b0 = 0; b0 < nblocks; b0 += 2) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int b = b0 + h;
-            if (b >= nblocks) break;
-            float16_t &acc = accs[h];
-            const float16_t &prev = accs[h ^ 1];
-            const char *cur = smem + (b % kSlots) * kSlot;
-            const char *nxt = smem + ((b + 1) % kSlots) * kSlot;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-            stage_acc<CT>(prev, out_stage + ((b - 1) & 1) * kOutBytes + stage_wr);  // (b == 0: zeros, never written out)
-            store_block(b - 2, b > 1);
-            prep_block();
-#pragma unroll
-            for (int kk = 0; kk < KSUB - kWin; ++kk) {
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
-                af[kk % kWin] = read_frag(cur, kk + kWin);
+                for (int kk = KSUB - kWin; kk < KSUB; ++kk) {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
+                    af[kk % kWin] = read_frag(nxt_lo, nxt_hi, kk + kWin - KSUB);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-#pragma unroll
-            for (int kk = 0; kk < KSUB - kWin; ++kk) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            wait_vmem_and_lds<kLoads + 2 * kStores>();
-            wg_barrier();
-            fire_block(b + 3);
-#pragma unroll
-            for (int kk = KSUB - kWin; kk < KSUB; ++kk) {
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
-                af[kk % kWin] = read_frag(nxt, kk + kWin - KSUB);
-            }
-#pragma unroll
-            for (int kk = 0; kk < kWin; ++kk) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
-                if (kk < kLoads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
-            }
-            __builtin_amdgcn_sched_barrier(0);
         }
-    }
-    const float16_t acc1 = ((nblocks - 1) & 1) ? accs[1] : accs[0];  // the last block's results
-    if (nblocks > 0) {
-        // drain: block nblocks-2 is staged (if it exists), block nblocks-1 is still in registers
-        stage_acc<CT>(acc1, out_stage + ((nblocks - 1) & 1) * kOutBytes + stage_wr);
-        store_block(nblocks - 2, nblocks > 1);
+        // the last block's results
+        const float16_t last = ((nblocks - 1) & 1) ? accs[1] : accs[0];
+        stage_acc<CT>(last, out_stage + ((nblocks - 1) & 1) * kOutBytes + stage_wr);
         wait_vmem_and_lds<0>();
         wg_barrier();
-        store_block(nblocks - 1, true);
+    } else {
+        // ------------------------------ memory waves ------------------------------
+        const int mw = wave - 4;
+        // activation loads: a wave fills half `mw % 2` (16 pixels) of sub-tiles mw/2, mw/2 + 2, ...
+        // lane -> pixel row half*16 + lane/4 of the block, chunk position lane%4
+        const rsrc_t xr = make_rsrc(x, (uint32_t)((int64_t)g.N * g.H * g.W * g.C * 2));
+        const int half = mw & 1, row_l = half * 16 + (lane >> 2);
+        int n_l, p_l, q_l;  // pixel start + row_l of block 0 as (image, output row, output column)
+        {
+            const int m = start + row_l;
+            n_l = m / (g.P * g.Q);
+            const int pq = m - n_l * (g.P * g.Q);
+            p_l = pq / g.Q;
+            q_l = pq - p_l * g.Q;
+        }
+        int m_l = start + row_l;
+        const uint32_t chunk_l = load_chunk(row_l, lane) * 16;
+        // All offsets are 32-bit: the host admits this kernel only for tensors below 2 GiB, and
+        // an offset is used only when its tap lies inside the image (then it is the true one).
+        uint32_t voff_l[kLoads];  // per-lane offsets of the next block to fetch (out of range: zeros)
+        auto prep_block = [&]() {
+            const int ih0 = p_l * g.sh - g.ph, iw0 = q_l * g.sw - g.pw;
+            const uint32_t pix = (uint32_t)(((n_l * g.H + ih0) * g.W + iw0) * C) * 2u + chunk_l;
+            // row / column validity once per filter row / column
+            bool row_ok[R], col_ok[S];
+#pragma unroll
+            for (int r = 0; r < R; ++r) row_ok[r] = m_l < end && (unsigned)(ih0 + r) < (unsigned)g.H;
+#pragma unroll
+            for (int sft = 0; sft < S; ++sft) col_ok[sft] = (unsigned)(iw0 + sft) < (unsigned)g.W;
+#pragma unroll
+            for (int t = 0; t < kLoads; ++t) {
+                // sub-tile 2t + mw/2 = filter tap t, channel block mw/2
+                const int r = t / S, sft = t % S;
+                const uint32_t tap_off = (uint32_t)((r * g.W + sft) * C + (mw >> 1) * 32) * 2u;  // scalar
+                voff_l[t] = (row_ok[r] && col_ok[sft]) ? pix + tap_off : kOutOfRange;
+            }
+            // advance this lane's pixel by one block (32 pixels): Q >= 32 (checked by the host),
+            // so the column wraps at most once
+            m_l += 32;
+            q_l += 32;
+            const bool wrap_q = q_l >= g.Q;
+            q_l = wrap_q ? q_l - g.Q : q_l;
+            p_l = wrap_q ? p_l + 1 : p_l;
+            const bool wrap_p = p_l == g.P;
+            p_l = wrap_p ? 0 : p_l;
+            n_l = wrap_p ? n_l + 1 : n_l;
+        };
+        auto fire_block = [&](int b) {
+            char *slot = smem + (b % kSlots) * kSlot;
+#pragma unroll
+            for (int t = 0; t < kLoads; ++t) {
+                const int sub = (mw >> 1) + 2 * t;
+                // (copied to a local first: with the captured array element as the builtin's argument the
+                // host pass silently drops this kernel's stub and the library no longer loads)
+                const uint32_t vo = voff_l[t];
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    xr, (__attribute__((address_space(3))) void *)(slot + sub * 2048 + half * 1024), 16, vo, 0, 0, 0);
+            }
+        };
+        // write-out of a staged block: this wave stores pixel rows mw*8 .. mw*8+7 through a
+        // buffer resource; rows past the range (or a disabled call) get an out-of-range offset
+        // and are dropped by the hardware, so every call issues the same number of stores and
+        // the vmcnt arithmetic below is uniform
+        const rsrc_t yr = make_rsrc(y, (uint32_t)((int64_t)Mtot * KOUT * sizeof(CT)));
+        auto store_block = [&](int b, bool enable) {
+            const char *stg = out_stage + (b & 1) * kOutBytes;
+#pragma unroll
+            for (int t = 0; t < kStores; ++t) {
+                const int row = mw * 8 + t * (64 / kRowLanes) + lane / kRowLanes;
+                const int m = start + b * 32 + row;
+                const uint4_t v = *reinterpret_cast<const uint4_t *>(stg + row * kOutPitch + (lane % kRowLanes) * 16);
+                const uint32_t off = (uint32_t)m * (uint32_t)(KOUT * sizeof(CT)) + (lane % kRowLanes) * 16;
+                __builtin_amdgcn_raw_buffer_store_b128(v, yr, (enable && m < end) ? off : kOutOfRange, 0, 2 /* nt */);
+            }
+        };
+        // Memory operations complete in order, so "block j has landed" is a bound on the number
+        // of younger operations.  Steady-state issue order:  ... L(b+1) S(b-3) L(b+2) S(b-2) | barrier b
+        // (L = a block's kLoads loads, S = a block's kStores stores); the prologue issues disabled
+        // stores so that the same bound holds from the first block on.
+        prep_block();
+        fire_block(0);
+        prep_block();
+        fire_block(1);
+        store_block(0, false);
+        prep_block();
+        wait_vmem<kLoads + kStores>();  // block 0 has landed
+        wg_barrier();                   // MFMA waves are done with the weight region (slot 2, staging)
+        fire_block(2);
+        store_block(0, false);
+        prep_block();
+        for (int b = 0; b < nblocks; ++b) {
+            wait_vmem_and_lds<kLoads + 2 * kStores>();  // own part of block b+1 has landed; staging reads are back
+            wg_barrier();  // block b+1 complete, slot of block b free, block b-1 staged
+            fire_block(b + 3);
+            store_block(b - 1, b > 0);
+            prep_block();
+        }
+        wg_barrier();  // the last block is staged
+        store_block(nblocks - 1, nblocks > 0);
+        wait_vmem_and_lds<0>();
     }
-    wait_vmem_and_lds<0>();
 }
 
 template <typename T> __device__ __forceinline__ float load_xw(const T *p);
@@ -426,9 +444,11 @@ static perf_status launch_conv_mfma(const void *x, const void *w, void *y, const
 template <int R, int S, int C, typename CT>
 static perf_status launch_conv_wreg(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
 {
-    constexpr int kRing = 3 * (R * S * (C / 32)) * 2048 + 2 * 32 * (128 * (int)sizeof(CT) + 16);
-    constexpr int kWeights = 128 * R * S * C * 2;  // prologue staging of all weights
+    constexpr int kSlot = (R * S * (C / 32)) * 2048;
+    constexpr int kRing = 3 * kSlot + 2 * 32 * (128 * (int)sizeof(CT) + 16);
+    constexpr int kWeights = 2 * kSlot + 128 * R * S * C;  // prologue: half of the weights behind ring slots 0 and 1
     constexpr int kLds = kRing > kWeights ? kRing : kWeights;
+    static_assert(kLds <= 160 * 1024, "LDS of one CU");
     const int64_t Mtot = (int64_t)g.N * g.P * g.Q;
     int grid = 256;  // one persistent workgroup per CU
     if ((Mtot + 31) / 32 < grid) grid = (int)((Mtot + 31) / 32);
@@ -441,7 +461,7 @@ static perf_status launch_conv_wreg(const void *x, const void *w, void *y, const
             return PERF_ERR_LAUNCH;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), kLds, st, (const uint16_t *)x, (const uint16_t *)w, (CT *)y,
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), kLds, st, (const uint16_t *)x, (const uint16_t *)w, (CT *)y,
                        g, px_per_wg);
     return launch_status();
 }

@@ -105,9 +105,9 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const XT *__
     const int64_t nwaves = (int64_t)gridDim.x * kLnWaves;
     const float inv_cols = 1.0f / (float)cols;
 
-    for (int64_t r = wave; r < rows; r += nwaves) {
+    uint4_t raw[NC];
+    auto load_row = [&](int64_t r) {
         const XT *xr = x + r * ldx;
-        uint4_t raw[NC];
 #pragma unroll
         for (int j = 0; j < NC; ++j) {
             const int c = (j * 64 + lane) * E;
@@ -116,6 +116,9 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const XT *__
             else
                 raw[j] = uint4_t{0u, 0u, 0u, 0u};
         }
+    };
+    if (wave < rows) load_row(wave);
+    for (int64_t r = wave; r < rows; r += nwaves) {
         // Pass 1 (registers): provisional mean from the plain sum.
         float v[NC][E];
         float s = 0.f;
@@ -125,6 +128,8 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const XT *__
 #pragma unroll
             for (int e = 0; e < E; ++e) s += v[j][e];  // padding chunks hold zeros
         }
+        // the raw registers are free again: the next row's loads fly during this row's arithmetic
+        if (r + nwaves < rows) load_row(r + nwaves);
         const float mean0 = wave_allreduce(s, OpSum{}) * inv_cols;
         // Pass 2 (registers): shift by the provisional mean, then first and second moments
         // of the shifted data.  The shifted values are small, so neither moment cancels, and
@@ -167,6 +172,9 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_rows_kernel(const XT *__
                 }
                 store_chunk<YT, E>(yr + ch * E, o);
             }
+            // keeps the LDS reads of gamma / beta chunk by chunk; hoisted together they
+            // double the register count and halve the occupancy
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
