@@ -178,6 +178,20 @@ def measure_copy_ceiling(torch, perf, moved_bytes=2 << 30, iters=20):
     return 2.0 * n * iters / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
+def measure_mfma_ceiling(torch, perf, iters=2000, reps=5):
+    """Measured matrix-core ceiling: the library's register-only bf16 MFMA loop (TFLOP/s)."""
+    sink = torch.zeros(perf.MFMA_PROBE_SINK_FLOATS, dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    perf.perf_mfma_probe(sink.data_ptr(), iters, st)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        perf.perf_mfma_probe(sink.data_ptr(), iters, st)
+    e1.record()
+    torch.cuda.synchronize()
+    return perf.MFMA_PROBE_FLOP_PER_ITER * iters * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
 def cpu_baseline(wl_rooflines):
     """Time the CPU oracle (as it stands) on a bounded sample of every workload."""
     import oracle
@@ -185,34 +199,41 @@ def cpu_baseline(wl_rooflines):
     threads = oracle.max_threads()
     res = {}
 
-    def timed(fn):
+    def timed(fn, min_seconds=2.5):
+        """Average seconds per call over as many calls as fill `min_seconds` (about 15 s in all)."""
         t0 = time.perf_counter()
-        fn()
-        return time.perf_counter() - t0
+        calls = 0
+        while True:
+            fn()
+            calls += 1
+            dt = time.perf_counter() - t0
+            if dt >= min_seconds:
+                return dt / calls
 
-    x = configs.SoftmaxWorkload(rows=8192, cols=1024).make()["x"].astype(np.float64)
-    res["softmax_131072x1024"] = ("hbm", 8 * x.size / timed(lambda: oracle.softmax(x)) / 1e9, "8192 of 131072 rows")
-    d = configs.LayerNormWorkload(rows=2048).make()
+    x = configs.SoftmaxWorkload(rows=16384, cols=1024).make()["x"].astype(np.float64)
+    res["softmax_131072x1024"] = ("hbm", 8 * x.size / timed(lambda: oracle.softmax(x)) / 1e9, "16384 of 131072 rows")
+    d = configs.LayerNormWorkload(rows=4096).make()
     xw = oracle.widen(d["x_bf16"], True)
     res["layernorm_8192x4096_bf16"] = ("hbm", 4 * xw.size / timed(lambda: oracle.layernorm(xw, d["gamma"], d["beta"], 1e-5)) / 1e9,
-                                       "2048 of 8192 rows")
+                                       "4096 of 8192 rows")
     d = configs.CONFIG3.make()
-    a, b = oracle.widen(d["a_bf16"][:256], True), oracle.widen(d["b_bf16"], True)
-    res["gemm_4096x4096x4096_bf16"] = ("mfma", 2 * 256 * 4096 * 4096 / timed(lambda: oracle.gemm(a, b, 256, 4096, 4096, b_col=True)) / 1e12,
-                                       "256 of 4096 rows of C")
-    c4 = configs.AttnScoreWorkload(batch=16)
+    a, b = oracle.widen(d["a_bf16"][:1024], True), oracle.widen(d["b_bf16"], True)
+    res["gemm_4096x4096x4096_bf16"] = ("mfma", 2 * 1024 * 4096 * 4096 / timed(lambda: oracle.gemm(a, b, 1024, 4096, 4096, b_col=True)) / 1e12,
+                                       "1024 of 4096 rows of C")
+    c4 = configs.AttnScoreWorkload(batch=32)
     d = c4.make()
     q, k = oracle.widen(d["q_bf16"], True), oracle.widen(d["k_bf16"], True)
     sc = {}
-    t = timed(lambda: sc.setdefault("s", oracle.gemm(q, k, 512, 512, 64, b_col=True, alpha=0.125, batch=16)))
-    res["attn_scores_qk_512x(512x512x64)"] = ("hbm", (2 * q.size * 2 + 4 * 16 * 512 * 512) / t / 1e9, "16 of 512 matrices")
+    sc["s"] = oracle.gemm(q, k, 512, 512, 64, b_col=True, alpha=0.125, batch=32)
+    t = timed(lambda: oracle.gemm(q, k, 512, 512, 64, b_col=True, alpha=0.125, batch=32))
+    res["attn_scores_qk_512x(512x512x64)"] = ("hbm", (2 * q.size * 2 + 4 * 32 * 512 * 512) / t / 1e9, "32 of 512 matrices")
     t = timed(lambda: oracle.softmax(sc["s"].reshape(-1, 512)))
-    res["attn_softmax_262144x512"] = ("hbm", 8 * 16 * 512 * 512 / t / 1e9, "8192 of 262144 rows")
-    c5 = configs.ConvWorkload(N=2)
+    res["attn_softmax_262144x512"] = ("hbm", 8 * 32 * 512 * 512 / t / 1e9, "16384 of 262144 rows")
+    c5 = configs.ConvWorkload(N=8)
     d = c5.make()
     xx, ww = oracle.widen(d["x_bf16"], True), oracle.widen(d["w_bf16"], True)
     res["conv2d_32x56x56x64_k128_3x3_bf16"] = ("mfma", c5.flops() / timed(lambda: oracle.conv2d(xx, ww, (1, 1), (1, 1))) / 1e12,
-                                               "2 of 32 images")
+                                               "8 of 32 images")
     fracs, per = [], {}
     for name, (bound, ach, sample) in res.items():
         peak = HBM_PEAK_GBS if bound == "hbm" else MFMA_BF16_PEAK_TFLOPS
@@ -221,7 +242,8 @@ def cpu_baseline(wl_rooflines):
     geo = math.exp(sum(math.log(f) for f in fracs) / len(fracs)) * 100.0
     return {"value": float(f"{geo:.4g}"), "unit": "% of MI355X roofline (geomean over the same workloads)",
             "cores": threads, "kind": "oracle",
-            "sample": "; ".join(f"{k}: {v['sample']}" for k, v in per.items()), "per_workload": per}
+            "sample": "each oracle call repeated for 2.5 s and averaged; "
+                      + "; ".join(f"{k}: {v['sample']}" for k, v in per.items()), "per_workload": per}
 
 
 def main():
@@ -266,6 +288,7 @@ def main():
     ms_per_step = sum(w.ms for w in wls)
 
     copy_gbs = measure_copy_ceiling(torch, perf)
+    mfma_tflops = measure_mfma_ceiling(torch, perf)
     copy_same = {w.name: measure_copy_ceiling(torch, perf, moved_bytes=w.unit_work, iters=50)
                  for w in wls if w.bound == "hbm" and w.unit_work < (1 << 29)}
 
@@ -282,6 +305,7 @@ def main():
         entry = {"workload": w.name, "us": round(w.ms * 1e3, 2), "buffer_sets": w.nsets, "roofline": r}
         if w.bound == "mfma":
             entry["tflops"] = r["achieved"]
+            entry["frac_of_measured_mfma_loop"] = round(r["achieved"] / mfma_tflops, 4)
         else:
             entry["gbs"] = r["achieved"]
             entry["frac_of_measured_copy"] = round(r["achieved"] / copy_gbs, 4)
@@ -312,6 +336,7 @@ def main():
                                "512x(512x512x64) QK^T/8 + softmax, conv 32x56x56x64->128 3x3 bf16)"},
         "roofline": roof,
         "copy_ceiling_gbs": round(copy_gbs, 1),
+        "mfma_loop_ceiling_tflops": round(mfma_tflops, 1),
         "workloads": per,
     }
     if not args.no_cpu_baseline:

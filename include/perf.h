@@ -114,6 +114,14 @@ perf_status perf_conv2d(const void *x, const void *w, void *y, int64_t N, int64_
  * of the paper's operators.  Errors: NULL, SHAPE (bytes < 0), LAUNCH. */
 perf_status perf_copy(const void *src, void *dst, int64_t bytes, perf_stream stream);
 
+/* Register-only bf16 MFMA loop, the measured matrix-core ceiling printed beside the GEMM and
+ * convolution figures (not one of the paper's operators): 4096 wavefronts (1024 workgroups
+ * of 256 threads) each issue iters * 32 v_mfma_f32_32x32x16_bf16 on 16 independent
+ * accumulators, i.e. 4096 * iters * 32 * 32768 flop per call, with no memory access inside
+ * the loop.  `sink` (device, at least 4096 floats, written once per wavefront) keeps the
+ * result live.  Errors: NULL, SHAPE (iters < 1 or > 2^24), ALIGN, LAUNCH. */
+perf_status perf_mfma_probe(float *sink, int64_t iters, perf_stream stream);
+
 /* Human-readable name of a status code; static storage, never freed. */
 const char *perf_status_string(perf_status s);
 

@@ -30,6 +30,7 @@ SIGNATURES = {
                          _i64, _i64, _i64, _i64, _f32, _int, _int, _ptr]),
     "perf_conv2d": (_int, [_ptr, _ptr, _ptr] + [_i64] * 11 + [_int, _int, _ptr]),
     "perf_copy": (_int, [_ptr, _ptr, _i64, _ptr]),
+    "perf_mfma_probe": (_int, [_ptr, _i64, _ptr]),
     "perf_status_string": (ctypes.c_char_p, [_int]),
     "perf_version": (_int, []),
 }
@@ -99,3 +100,11 @@ def perf_conv2d(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, 
 
 def perf_copy(src, dst, nbytes, stream=None, check=True) -> int:
     return _check("perf_copy", lib().perf_copy(src, dst, nbytes, stream), check)
+
+
+MFMA_PROBE_SINK_FLOATS = 4096
+MFMA_PROBE_FLOP_PER_ITER = 4096 * 32 * 32768
+
+
+def perf_mfma_probe(sink, iters, stream=None, check=True) -> int:
+    return _check("perf_mfma_probe", lib().perf_mfma_probe(sink, iters, stream), check)

@@ -1,4 +1,5 @@
-// Status strings, version, and the streaming copy used as the measured HBM ceiling.
+// Status strings, version, and the two measured ceilings the benchmark prints beside its
+// figures: a streaming copy (HBM) and a register-only MFMA loop (matrix cores).
 #include "device_utils.h"
 #include "host_utils.h"
 
@@ -29,7 +30,54 @@ __global__ __launch_bounds__(64) void copy_tail_kernel(const unsigned char *__re
     for (int64_t i = threadIdx.x; i < n; i += 64) dst[i] = src[i];
 }
 
+// Register-only bf16 MFMA loop: 16 independent 32x32 accumulators per wave (the GEMM's
+// 4x4 wave tile), two MFMAs per accumulator and iteration issued back to back as in the
+// GEMM main loop, operands constant.  No memory traffic inside the loop, so its rate is
+// what the matrix cores sustain at the clock the power management allows.
+constexpr int kProbeAcc = 16;
+constexpr int kProbeWorkgroups = 256 * 4;
+
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ sink, int64_t iters)
+{
+    const int lane = threadIdx.x & 63;
+    bf16x8_t a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        a[e] = (__bf16)(float)((lane + e) & 3);
+        b[e] = (__bf16)(float)((lane ^ e) & 1);
+    }
+    float16_t acc[kProbeAcc];
+#pragma unroll
+    for (int i = 0; i < kProbeAcc; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < kProbeAcc; ++i) {
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[i], 0, 0, 0);
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < kProbeAcc; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s += acc[i][e];
+    if (lane == 0) sink[blockIdx.x * 4 + (threadIdx.x >> 6)] = s;
+}
+
 }  // namespace perf
+
+extern "C" perf_status perf_mfma_probe(float *sink, int64_t iters, perf_stream stream)
+{
+    using namespace perf;
+    if (!sink) return PERF_ERR_NULL;
+    if (iters < 1 || iters > (int64_t(1) << 24)) return PERF_ERR_SHAPE;
+    if (!aligned(sink, 4)) return PERF_ERR_ALIGN;
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(kProbeWorkgroups), dim3(256), 0, static_cast<hipStream_t>(stream), sink,
+                       iters);
+    return launch_status();
+}
 
 extern "C" perf_status perf_copy(const void *src, void *dst, int64_t bytes, perf_stream stream)
 {

@@ -105,3 +105,10 @@ def test_copy_argument_errors():
     assert perf.perf_copy(None, FAKE, 16, check=False) == perf.PERF_ERR_NULL
     assert perf.perf_copy(FAKE, FAKE + 64, -1, check=False) == perf.PERF_ERR_SHAPE
     assert perf.perf_copy(FAKE, FAKE + 64, 0, check=False) == perf.PERF_OK    # nothing to do, no launch
+
+
+def test_mfma_probe_argument_errors():
+    assert perf.perf_mfma_probe(None, 1, check=False) == perf.PERF_ERR_NULL
+    assert perf.perf_mfma_probe(FAKE, 0, check=False) == perf.PERF_ERR_SHAPE
+    assert perf.perf_mfma_probe(FAKE, (1 << 24) + 1, check=False) == perf.PERF_ERR_SHAPE
+    assert perf.perf_mfma_probe(FAKE + 2, 1, check=False) == perf.PERF_ERR_ALIGN
