@@ -2,7 +2,8 @@
 // Section 4.3 of the paper):  C_b = alpha * A_b * B_b, fp32 accumulation.
 //
 //  * gemm_mfma_kernel: bf16 operands, A row-major and B column-major (both K-contiguous),
-//    K a multiple of 32.  256x256 (or 128x128) workgroup tile, see mfma_tile.h.
+//    K a multiple of 32.  256x256 (or 128x128) workgroup tile; the K-step-64 loop of
+//    mfma_tile.h when K is a multiple of 64, else its K-step-32 loop.
 //  * gemm_general_kernel: any layout / dtype / size; 64x64 tile of fp32 FMAs.
 #include "mfma_tile.h"
 #include "host_utils.h"
@@ -27,7 +28,7 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
     tn = within / rows_in_band;
 }
 
-template <int TM, int TN, int WM, int WN, bool PINGPONG, typename CT>
+template <int TM, int TN, int WM, int WN, bool K64, typename CT>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t *__restrict__ A,
                                                                  const uint16_t *__restrict__ B, CT *__restrict__ C,
                                                                  int M, int N, int K, int64_t lda, int64_t ldb,
@@ -52,17 +53,22 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t 
         const uint16_t *Bb = B + (int64_t)bz * strideB;
         CT *Cb = C + (int64_t)bz * strideC;
 
-        RowMajorSrc<Shape::kLoadsA, NW> src_a(Ab + (int64_t)m0 * lda, min(BM, M - m0), lda, ktiles, wave, lane);
-        RowMajorSrc<Shape::kLoadsB, NW> src_b(Bb + (int64_t)n0 * ldb, min(BN, N - n0), ldb, ktiles, wave, lane);
-
-        WaveTile<TM, TN> t;
-        t.clear();
         const int a_row0 = wm * 32 * TM, b_row0 = wn * 32 * TN;
-        if constexpr (PINGPONG)
-            mfma_mainloop_pingpong<TM, TN, WM, WN>(t, smem, ktiles, wave, lane, a_row0, b_row0, src_a, src_b);
-        else
+        if constexpr (K64) {
+            RowMajorSrc64<BM / (8 * NW), NW> src_a(Ab + (int64_t)m0 * lda, min(BM, M - m0), lda, K / 64, wave, lane);
+            RowMajorSrc64<BN / (8 * NW), NW> src_b(Bb + (int64_t)n0 * ldb, min(BN, N - n0), ldb, K / 64, wave, lane);
+            WaveTile16<2 * TM, 2 * TN> t;
+            t.clear();
+            mfma_mainloop_k64<TM, TN, WM, WN>(t, smem, K / 64, wave, lane, a_row0, b_row0, src_a, src_b);
+            store_tile16<2 * TM, 2 * TN, CT>(t, Cb, ldc, M, N, m0 + a_row0, n0 + b_row0, alpha, lane);
+        } else {
+            RowMajorSrc<Shape::kLoadsA, NW> src_a(Ab + (int64_t)m0 * lda, min(BM, M - m0), lda, ktiles, wave, lane);
+            RowMajorSrc<Shape::kLoadsB, NW> src_b(Bb + (int64_t)n0 * ldb, min(BN, N - n0), ldb, ktiles, wave, lane);
+            WaveTile<TM, TN> t;
+            t.clear();
             mfma_mainloop<TM, TN, WM, WN>(t, smem, ktiles, wave, lane, a_row0, b_row0, src_a, src_b);
-        store_tile<TM, TN, CT>(t, Cb, ldc, M, N, m0 + a_row0, n0 + b_row0, alpha, lane);
+            store_tile<TM, TN, CT>(t, Cb, ldc, M, N, m0 + a_row0, n0 + b_row0, alpha, lane);
+        }
     }
 }
 
@@ -133,14 +139,14 @@ struct GemmArgs {
     hipStream_t st;
 };
 
-template <int TM, int TN, int WM, int WN, bool PINGPONG, typename CT>
+template <int TM, int TN, int WM, int WN, bool K64, typename CT>
 static perf_status launch_mfma(const GemmArgs &g)
 {
     using Shape = TileShape<TM, TN, WM, WN>;
     constexpr int BM = Shape::BM, BN = Shape::BN;
     const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
     const size_t lds = Shape::kLdsBytes;
-    auto kern = gemm_mfma_kernel<TM, TN, WM, WN, PINGPONG, CT>;
+    auto kern = gemm_mfma_kernel<TM, TN, WM, WN, K64, CT>;
     static bool attr_done = false;  // raising the dynamic-LDS cap is a per-function, idempotent setting
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -206,8 +212,15 @@ extern "C" perf_status perf_gemm(const void *A, const void *B, void *C, int64_t 
     if (mfma_ok) {
         // the 256x256 tile needs enough tiles to occupy the 256 CUs; otherwise 128x128
         const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * batch;
-        if (big_tiles >= 256)
+        // the K-step-64 loop pays off in the main loop; short reductions are bound by the C
+        // store, which the other loop's epilogue (two full 128-byte row segments per store
+        // instruction, no lane exchange) does faster (measured on 512 x (512x512x64))
+        const bool k64 = K % 64 == 0 && K >= 512;
+        if (big_tiles >= 256) {
+            if (k64) return c_dt == PERF_F32 ? launch_mfma<4, 4, 2, 2, true, float>(g) : launch_mfma<4, 4, 2, 2, true, uint16_t>(g);
             return c_dt == PERF_F32 ? launch_mfma<4, 4, 2, 2, false, float>(g) : launch_mfma<4, 4, 2, 2, false, uint16_t>(g);
+        }
+        if (k64) return c_dt == PERF_F32 ? launch_mfma<2, 2, 2, 2, true, float>(g) : launch_mfma<2, 2, 2, 2, true, uint16_t>(g);
         return c_dt == PERF_F32 ? launch_mfma<2, 2, 2, 2, false, float>(g) : launch_mfma<2, 2, 2, 2, false, uint16_t>(g);
     }
     if (ab_dt == PERF_BF16)

@@ -62,6 +62,22 @@ def test_alpha_bf16_output_batched_and_padded_ld():
     P.assert_contraction_close(c, ref, s, 64)
 
 
+def test_k64_loop_tails_alpha_bf16_batched_and_odd_ldc():
+    # K a multiple of 64 and >= 512 selects the K-step-64 loop (16x16x32 MFMAs, lane-exchange epilogue)
+    _check(configs.GemmWorkload(M=300, N=200, K=576))                          # 128x128 tiles, ragged, odd step count
+    _check(configs.GemmWorkload(M=256, N=384, K=512), alpha=0.125)             # full tiles, vector epilogue, alpha
+    _check(configs.GemmWorkload(M=256, N=256, K=512), c_bf16=True)             # bf16 vector epilogue
+    _check(configs.GemmWorkload(M=130, N=70, K=512), alpha=-2.0, batch=3, c_bf16=True)
+    _check(configs.GemmWorkload(M=512, N=512, K=512), batch=64)                # 256 tiles of 256x256: the large-tile kernel
+    _check(configs.GemmWorkload(M=2048 + 40, N=2048 - 24, K=640))              # large-tile kernel with ragged edges
+    wl = configs.GemmWorkload(M=256, N=256, K=512)
+    d = wl.make()
+    c = G.run_gemm(d["a_bf16"], d["b_bf16"], 256, 256, 512, ldc=258)[0]        # ldc not a multiple of 4: scalar epilogue
+    ad, bd = oracle.widen(d["a_bf16"], True), oracle.widen(d["b_bf16"], True)
+    ref = oracle.gemm(ad, bd, 256, 256, 512, b_col=True)
+    P.assert_contraction_close(c, ref, oracle.gemm_absdot(ad, bd, 256, 256, 512, b_col=True), 512)
+
+
 @pytest.mark.parametrize("a_col,b_col", [(False, False), (True, False), (True, True), (False, True)])
 @pytest.mark.parametrize("M,N,K", [(5, 7, 3), (65, 63, 17), (100, 130, 65)])
 def test_general_kernel_layouts_exact_integers(a_col, b_col, M, N, K):
