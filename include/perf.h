@@ -108,6 +108,25 @@ perf_status perf_conv2d(const void *x, const void *w, void *y, int64_t N, int64_
                         int64_t stride_w, int64_t pad_h, int64_t pad_w, perf_dtype xw_dt,
                         perf_dtype y_dt, perf_stream stream);
 
+/* Batched score GEMM with the row softmax fused into it (the "bmm" followed by "softmax"
+ * pair of the operator table, Section 4.3, joined as the paper's fusion moves join a
+ * producer with its consumer, Sections 2.2 and 3.1):
+ *     P_b = softmax_rows(alpha * A_b * B_b^T),   b = 0 .. batch-1,
+ * i.e. perf_gemm with A row-major (M x K, ld lda) and B column-major (N rows of K, ld ldb)
+ * followed by perf_softmax (scale 1) on every row of the M x N result, with the same
+ * arithmetic (fp32 accumulation, fp32 softmax) and the same max convention.
+ *   A, B     device, bf16 or f32 (ab_dt);  P  device, M x N, row stride ldp, f32 or bf16
+ * For bf16 operands with K = 64 or 128, N <= 512 and 16-byte aligned rows the scores never
+ * reach memory (one kernel; its exponential is exp2 of a plain fp32 product, relative error
+ * about 2^-24 times the exponent); other legal cases run the two operators one
+ * after the other through P, which then must be f32 (bf16 P: UNSUPPORTED).
+ * Errors: NULL, SHAPE (dimension < 1, ld too small, negative stride, batches overlapping in
+ * P, alpha not finite), DTYPE, ALIGN, UNSUPPORTED, LAUNCH. */
+perf_status perf_gemm_softmax(const void *A, const void *B, void *P, int64_t M, int64_t N,
+                              int64_t K, int64_t lda, int64_t ldb, int64_t ldp, int64_t batch,
+                              int64_t strideA, int64_t strideB, int64_t strideP, float alpha,
+                              perf_dtype ab_dt, perf_dtype p_dt, perf_stream stream);
+
 /* Plain device-to-device streaming copy of `bytes` bytes (dst and src must not overlap).
  * It is the measured HBM ceiling the benchmark prints beside each bandwidth figure and
  * the known-size kernel against which profiler byte counters are scaled; it is not one

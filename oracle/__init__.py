@@ -111,6 +111,15 @@ def gemm(a, b, M, N, K, a_col=False, b_col=False, alpha=1.0, batch=1, lda=None, 
     return c[0] if batch == 1 else c
 
 
+def gemm_softmax(a, b, M, N, K, alpha=1.0, batch=1):
+    """P[b] = softmax_rows(alpha * A[b] @ B[b]^T): the "bmm" then "softmax" pair of the operator
+    table (Section 4.3 of the paper) as the plain composition of the two definitions above.
+    A is row-major [M,K], B holds N rows of K (column-major K x N), batches densely packed.
+    Returns float64 [batch, M, N]."""
+    s = gemm(a, b, M, N, K, a_col=False, b_col=True, alpha=alpha, batch=batch)
+    return softmax(np.ascontiguousarray(s).reshape(batch * M, N), 1.0).reshape(batch, M, N)
+
+
 def gemm_absdot(a, b, M, N, K, a_col=False, b_col=False):
     a, b = widen(a).ravel(), widen(b).ravel()
     lda = M if a_col else K

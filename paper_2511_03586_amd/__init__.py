@@ -29,6 +29,8 @@ SIGNATURES = {
     "perf_gemm": (_int, [_ptr, _ptr, _ptr, _i64, _i64, _i64, _int, _i64, _int, _i64, _i64,
                          _i64, _i64, _i64, _i64, _f32, _int, _int, _ptr]),
     "perf_conv2d": (_int, [_ptr, _ptr, _ptr] + [_i64] * 11 + [_int, _int, _ptr]),
+    "perf_gemm_softmax": (_int, [_ptr, _ptr, _ptr, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _f32,
+                                 _int, _int, _ptr]),
     "perf_copy": (_int, [_ptr, _ptr, _i64, _ptr]),
     "perf_mfma_probe": (_int, [_ptr, _i64, _ptr]),
     "perf_status_string": (ctypes.c_char_p, [_int]),
@@ -89,6 +91,13 @@ def perf_gemm(A, B, C, M, N, K, la, lda, lb, ldb, ldc, batch=1, strideA=0, strid
     return _check("perf_gemm",
                   lib().perf_gemm(A, B, C, M, N, K, la, lda, lb, ldb, ldc, batch, strideA, strideB, strideC,
                                   alpha, ab_dt, c_dt, stream), check)
+
+
+def perf_gemm_softmax(A, B, P, M, N, K, lda, ldb, ldp, batch=1, strideA=0, strideB=0, strideP=0, alpha=1.0,
+                      ab_dt=PERF_BF16, p_dt=PERF_F32, stream=None, check=True) -> int:
+    return _check("perf_gemm_softmax",
+                  lib().perf_gemm_softmax(A, B, P, M, N, K, lda, ldb, ldp, batch, strideA, strideB, strideP,
+                                          alpha, ab_dt, p_dt, stream), check)
 
 
 def perf_conv2d(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, xw_dt=PERF_BF16,

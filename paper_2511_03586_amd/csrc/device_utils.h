@@ -88,4 +88,17 @@ __device__ __forceinline__ float wave_allreduce(float v, Op op)
     return v;
 }
 
+// All-reduce over each half of the wave (lanes 0-31 and 32-63 separately).
+template <typename Op>
+__device__ __forceinline__ float half_allreduce(float v, Op op)
+{
+    v = op(v, dpp_move<0xB1>(v));   // quad_perm [1,0,3,2]
+    v = op(v, dpp_move<0x4E>(v));   // quad_perm [2,3,0,1]
+    v = op(v, dpp_move<0x141>(v));  // row_half_mirror
+    v = op(v, dpp_move<0x140>(v));  // row_mirror
+    float a, b;
+    swap16(v, a, b);
+    return op(a, b);
+}
+
 }  // namespace perf

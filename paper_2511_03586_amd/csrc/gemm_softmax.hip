@@ -1,0 +1,201 @@
+// Attention-score GEMM with the row softmax as its epilogue, for gfx950:
+//     P_b = softmax_rows(alpha * A_b * B_b^T)
+// (the "bmm" and "softmax" rows of the operator table, Section 4.3 of the paper, joined the
+// way the paper's fusion moves join producer and consumer scopes, Sections 2.2 and 3.1: the
+// score matrix never goes to memory, so the traffic is the operands plus one write of P).
+//
+//  * gemm_softmax_kernel: bf16 operands, both K-contiguous, N <= 512, K = 64 or 128.  A
+//    workgroup of 4 waves owns 64 rows x all N columns of one matrix; each wave 16 rows x N
+//    as up to 32 accumulators of 16x16 (128 registers), computed with B as the MFMA's row
+//    operand, so that a lane holds 4 consecutive columns per accumulator and all of a
+//    lane's values belong to ONE row: the row reductions are in-lane plus two lane
+//    exchanges, and the write-out is 16 bytes per lane in whole 128-byte segments.  The
+//    operand strip and all of B go to LDS once (global->LDS loads, the swizzled 128-byte
+//    rows of mfma_tile.h).  With K = 64 two workgroups fit a CU (72 KiB of LDS, <= 256
+//    registers), so one's exponentials overlap the other's loads and stores.
+//  * any other legal case: perf_gemm into P followed by perf_softmax in place.
+#include "mfma_tile.h"
+#include "softmax_math.h"
+#include "host_utils.h"
+
+namespace perf {
+
+// T16N: 16-column accumulators per wave (N <= 16 * T16N); MASK: N < 16 * T16N.
+template <int T16N, bool MASK, typename PT>
+__global__ __launch_bounds__(256, 2) void gemm_softmax_kernel(const uint16_t *__restrict__ A,
+                                                              const uint16_t *__restrict__ B, PT *__restrict__ P,
+                                                              int M, int N, int K, int64_t lda, int64_t ldb,
+                                                              int64_t ldp, int64_t strideA, int64_t strideB,
+                                                              int64_t strideP, float sign, float c)
+{
+    constexpr int NW = 4, BM = 64, BN = 16 * T16N;
+    constexpr int LA = BM / (8 * NW);                    // wave loads per K-step of 64: A strip
+    constexpr int LB = (BN + 8 * NW - 1) / (8 * NW);     // ... and B (the last one may be partly unused)
+    constexpr int kRowsB = LB * 8 * NW;
+    constexpr int kStepBytes = (BM + kRowsB) * kRowBytes64;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: LDS addresses stay scalar
+    const int m0 = blockIdx.x * BM;
+    const int ksteps = K / 64;
+    const uint16_t *Ab = A + (int64_t)blockIdx.y * strideA;
+    const uint16_t *Bb = B + (int64_t)blockIdx.y * strideB;
+    PT *Pb = P + (int64_t)blockIdx.y * strideP;
+
+    RowMajorSrc64<LA, NW> src_a(Ab + (int64_t)m0 * lda, min(BM, M - m0), lda, ksteps, wave, lane);
+    RowMajorSrc64<LB, NW> src_b(Bb, min(kRowsB, N), ldb, ksteps, wave, lane);
+    for (int ks = 0; ks < ksteps; ++ks) {
+        char *step = smem + ks * kStepBytes;
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            const uint32_t vo = src_a.voff[i], so = src_a.soff;
+            issue_load_to(src_a.rsrc, vo, so, step + (i * NW + wave) * 8 * kRowBytes64);
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            const uint32_t vo = src_b.voff[i], so = src_b.soff;
+            issue_load_to(src_b.rsrc, vo, so, step + BM * kRowBytes64 + (i * NW + wave) * 8 * kRowBytes64);
+        }
+        src_a.advance();
+        src_b.advance();
+    }
+    wait_vmem<0>();
+    wg_barrier();
+
+    // acc[j] element e: row m0 + 16*wave + lane%16, column 16 j + 4 (lane/16) + e
+    WaveTile16<1, T16N> t;
+    t.clear();
+    for (int ks = 0; ks < ksteps; ++ks) {
+        const char *step = smem + ks * kStepBytes;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int chunk = 4 * half + (lane >> 4);
+            const bf16x8_t a = *reinterpret_cast<const bf16x8_t *>(step + frag_offset64(wave * 16 + (lane & 15), chunk));
+#pragma unroll
+            for (int j = 0; j < T16N; ++j) {
+                const bf16x8_t b = *reinterpret_cast<const bf16x8_t *>(step + BM * kRowBytes64 +
+                                                                        frag_offset64(j * 16 + (lane & 15), chunk));
+                t.acc[0][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, a, t.acc[0][j], 0, 0, 0);
+            }
+        }
+    }
+
+    // Row softmax.  All of a lane's values belong to row lane%16; lanes l, l^16, l^32, l^48
+    // share it.  exp(|alpha| * (v - m)) is evaluated as exp2 of a plain product: its relative
+    // error is ~2^-24 times the exponent, i.e. below 4e-6 for every result above 2^-100, and
+    // smaller results are below the floor under which only the absolute error is specified.
+    float m = -FLT_MAX;
+#pragma unroll
+    for (int j = 0; j < T16N; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float v = t.acc[0][j][e] * sign;
+            if (MASK) v = (16 * j + 4 * (lane >> 4) + e < N) ? v : -FLT_MAX;
+            t.acc[0][j][e] = v;
+            m = __builtin_fmaxf(m, v);
+        }
+    {
+        float a, b;
+        swap16(m, a, b);
+        m = __builtin_fmaxf(a, b);
+        swap32(m, a, b);
+        m = __builtin_fmaxf(a, b);
+    }
+    float z = 0.f;
+#pragma unroll
+    for (int j = 0; j < T16N; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float p = __builtin_amdgcn_exp2f((t.acc[0][j][e] - m) * c);
+            if (MASK) p = (16 * j + 4 * (lane >> 4) + e < N) ? p : 0.f;  // (c == 0 would give masked columns weight 1)
+            t.acc[0][j][e] = p;
+            z += p;
+        }
+    {
+        float a, b;
+        swap16(z, a, b);
+        z = a + b;
+        swap32(z, a, b);
+        z = a + b;
+    }
+    store_tile16<1, T16N, PT>(t, Pb, ldp, M, N, m0 + wave * 16, 0, 1.0f / z, lane);
+}
+
+template <int T16N, bool MASK, typename PT>
+static perf_status launch_fused(const void *A, const void *B, void *P, int64_t M, int64_t N, int64_t K, int64_t lda,
+                                int64_t ldb, int64_t ldp, int64_t batch, int64_t strideA, int64_t strideB,
+                                int64_t strideP, float alpha, hipStream_t st)
+{
+    constexpr int kRowsB = (16 * T16N + 31) / 32 * 32;
+    const size_t lds = (size_t)(K / 64) * (64 + kRowsB) * kRowBytes64;
+    auto kern = gemm_softmax_kernel<T16N, MASK, PT>;
+    static size_t lds_set = 0;  // the dynamic-LDS cap is a per-function setting; raise it when a larger K comes along
+    if (lds > lds_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return PERF_ERR_LAUNCH;
+        lds_set = lds;
+    }
+    const float sign = alpha < 0.f ? -1.f : 1.f;
+    const float c = (float)(std::fabs((double)alpha) * 1.4426950408889634074);  // |alpha| log2(e)
+    const unsigned gx = (unsigned)((M + 63) / 64);
+    for (int64_t b0 = 0; b0 < batch; b0 += kMaxGridYZ) {
+        const unsigned gy = (unsigned)(batch - b0 < kMaxGridYZ ? batch - b0 : kMaxGridYZ);
+        hipLaunchKernelGGL(kern, dim3(gx, gy), dim3(256), lds, st, (const uint16_t *)A + b0 * strideA,
+                           (const uint16_t *)B + b0 * strideB, (PT *)P + b0 * strideP, (int)M, (int)N, (int)K, lda, ldb,
+                           ldp, strideA, strideB, strideP, sign, c);
+    }
+    return launch_status();
+}
+
+}  // namespace perf
+
+extern "C" perf_status perf_gemm_softmax(const void *A, const void *B, void *P, int64_t M, int64_t N, int64_t K,
+                                         int64_t lda, int64_t ldb, int64_t ldp, int64_t batch, int64_t strideA,
+                                         int64_t strideB, int64_t strideP, float alpha, perf_dtype ab_dt,
+                                         perf_dtype p_dt, perf_stream stream)
+{
+    using namespace perf;
+    if (!A || !B || !P) return PERF_ERR_NULL;
+    if (!dtype_ok(ab_dt) || !dtype_ok(p_dt)) return PERF_ERR_DTYPE;
+    if (M < 1 || N < 1 || K < 1 || batch < 1) return PERF_ERR_SHAPE;
+    if (lda < K || ldb < K || ldp < N) return PERF_ERR_SHAPE;
+    if (strideA < 0 || strideB < 0 || strideP < 0 || !std::isfinite(alpha)) return PERF_ERR_SHAPE;
+    if (batch > 1 && strideP < (M - 1) * ldp + N) return PERF_ERR_SHAPE;
+    const int64_t kLim = INT64_MAX / 8;
+    if (M > kLim / lda || N > kLim / ldb || M > kLim / ldp) return PERF_ERR_SHAPE;
+    if (batch > 1 && (strideA > kLim / batch || strideB > kLim / batch || strideP > kLim / batch)) return PERF_ERR_SHAPE;
+    if (!aligned(A, dtype_size(ab_dt)) || !aligned(B, dtype_size(ab_dt)) || !aligned(P, dtype_size(p_dt)))
+        return PERF_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    const bool fused = ab_dt == PERF_BF16 && (K == 64 || K == 128) && N <= 512 && lda % 8 == 0 && ldb % 8 == 0 &&
+                       strideA % 8 == 0 && strideB % 8 == 0 && aligned(A, 16) && aligned(B, 16) && lda <= (1 << 21) &&
+                       ldb <= (1 << 21) && M <= (1 << 30) && (M + 63) / 64 <= kMaxGridX;
+    if (fused) {
+#define PERF_FUSED(T, MASK)                                                                                              \
+    (p_dt == PERF_F32                                                                                                    \
+         ? launch_fused<T, MASK, float>(A, B, P, M, N, K, lda, ldb, ldp, batch, strideA, strideB, strideP, alpha, st)    \
+         : launch_fused<T, MASK, uint16_t>(A, B, P, M, N, K, lda, ldb, ldp, batch, strideA, strideB, strideP, alpha, st))
+        if (N == 512) return PERF_FUSED(32, false);
+        if (N > 256) return PERF_FUSED(32, true);
+        if (N == 256) return PERF_FUSED(16, false);
+        if (N > 128) return PERF_FUSED(16, true);
+        if (N == 128) return PERF_FUSED(8, false);
+        if (N > 64) return PERF_FUSED(8, true);
+        return PERF_FUSED(4, true);
+#undef PERF_FUSED
+    }
+    // Unfused: scores into P, then the row softmax in place (fp32 P only).
+    if (p_dt != PERF_F32) return PERF_ERR_UNSUPPORTED;
+    perf_status s = perf_gemm(A, B, P, M, N, K, PERF_ROW_MAJOR, lda, PERF_COL_MAJOR, ldb, ldp, batch, strideA, strideB,
+                              strideP, alpha, ab_dt, PERF_F32, stream);
+    if (s != PERF_OK) return s;
+    if (batch == 1 || strideP == M * ldp) return perf_softmax(P, P, batch * M, N, ldp, ldp, PERF_F32, PERF_F32, 1.0f, stream);
+    for (int64_t b = 0; b < batch; ++b) {
+        s = perf_softmax((float *)P + b * strideP, (float *)P + b * strideP, M, N, ldp, ldp, PERF_F32, PERF_F32, 1.0f, stream);
+        if (s != PERF_OK) return s;
+    }
+    return PERF_OK;
+}

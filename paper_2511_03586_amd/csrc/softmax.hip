@@ -11,40 +11,10 @@
 //  * softmax_block_kernel: general fallback, one 256-thread workgroup per row, any
 //    length or alignment; a streaming (max, sum) pair per thread is merged through LDS,
 //    and the row is kept in LDS when it fits so HBM is still read once.
-#include <cfloat>
-#include "device_utils.h"
+#include "softmax_math.h"
 #include "host_utils.h"
 
 namespace perf {
-
-// exp(s * t) for t <= 0 as exp2 of a compensated product: p = t*c_hi rounded, the
-// rounding residual and the low part of the constant are applied as a first-order
-// correction, so the relative error stays near 2^-23 for any exponent magnitude.
-// Results below 2^-160 (far under the smallest fp32 subnormal) are returned as 0.
-__device__ __forceinline__ float exp_scaled(float t, float c_hi, float c_lo)
-{
-    t = __builtin_fmaxf(t, -FLT_MAX);  // -inf * 0 would be NaN when scale == 0
-    float p = t * c_hi;
-    float r = __builtin_fmaf(t, c_hi, -p) + t * c_lo;
-    float e = __builtin_amdgcn_exp2f(p);
-    float v = __builtin_fmaf(e, r * 0.69314718056f, e);
-    return p < -160.f ? 0.f : v;       // also discards the NaN residual of an overflowed p
-}
-
-struct ExpConst {
-    float sign, c_hi, c_lo;
-};
-
-static ExpConst make_exp_const(float scale)
-{
-    // |scale| * log2(e) split into an fp32 head and tail.
-    double c = std::fabs((double)scale) * 1.4426950408889634074;
-    ExpConst k;
-    k.sign = scale < 0.f ? -1.f : 1.f;
-    k.c_hi = (float)c;
-    k.c_lo = (float)(c - (double)k.c_hi);
-    return k;
-}
 
 template <int NV, int RPW>
 __global__ __launch_bounds__(256) void softmax_rows_kernel(const float *__restrict__ x, float *__restrict__ y,

@@ -96,6 +96,21 @@ def run_gemm(a, b, M, N, K, a_col=False, b_col=True, alpha=1.0, batch=1, ab_bf16
     return c[:, :, :N].copy()
 
 
+def run_gemm_softmax(a, b, M, N, K, alpha=1.0, batch=1, ab_bf16=True, p_bf16=False, lda=None, ldb=None, ldp=None):
+    """a: [batch] x M rows of lda, b: [batch] x N rows of ldb (storage arrays). Returns P [batch, M, N]."""
+    lda, ldb, ldp = lda or K, ldb or K, ldp or N
+    sa, sb, sp = M * lda, N * ldb, M * ldp
+    ad, bd = dev(np.ascontiguousarray(a).ravel()), dev(np.ascontiguousarray(b).ravel())
+    assert ad.numel() >= batch * sa and bd.numel() >= batch * sb
+    pd = torch.zeros(batch * sp, dtype=torch.int16 if p_bf16 else torch.float32, device="cuda")
+    perf.perf_gemm_softmax(ad.data_ptr(), bd.data_ptr(), pd.data_ptr(), M, N, K, lda, ldb, ldp, batch, sa, sb, sp,
+                           alpha, dt(ab_bf16), dt(p_bf16), stream())
+    torch.cuda.synchronize()
+    p = host(pd, p_bf16).reshape(batch, M, ldp)
+    assert np.all(p[:, :, N:] == 0), "kernel wrote into the row padding of P"
+    return p[:, :, :N].copy()
+
+
 def run_conv2d(x, w, stride=(1, 1), pad=(0, 0), xw_bf16=True, y_bf16=True):
     N, H, W, C = x.shape
     K, R, S, _ = w.shape

@@ -112,3 +112,20 @@ def test_mfma_probe_argument_errors():
     assert perf.perf_mfma_probe(FAKE, 0, check=False) == perf.PERF_ERR_SHAPE
     assert perf.perf_mfma_probe(FAKE, (1 << 24) + 1, check=False) == perf.PERF_ERR_SHAPE
     assert perf.perf_mfma_probe(FAKE + 2, 1, check=False) == perf.PERF_ERR_ALIGN
+
+
+def test_gemm_softmax_argument_errors():
+    def f(A=FAKE, B=FAKE + 4096, P=FAKE + 8192, M=8, N=8, K=32, lda=32, ldb=32, ldp=8, batch=1, sa=0, sb=0, sp=0,
+          alpha=1.0, ab=perf.PERF_BF16, pd=perf.PERF_F32):
+        return perf.perf_gemm_softmax(A, B, P, M, N, K, lda, ldb, ldp, batch, sa, sb, sp, alpha, ab, pd, check=False)
+    assert f(A=None) == perf.PERF_ERR_NULL
+    assert f(P=None) == perf.PERF_ERR_NULL
+    assert f(M=0) == perf.PERF_ERR_SHAPE
+    assert f(lda=31) == perf.PERF_ERR_SHAPE
+    assert f(ldp=7) == perf.PERF_ERR_SHAPE
+    assert f(batch=2, sp=63) == perf.PERF_ERR_SHAPE          # batches would overlap in P
+    assert f(sa=-1) == perf.PERF_ERR_SHAPE
+    assert f(alpha=float("inf")) == perf.PERF_ERR_SHAPE
+    assert f(ab=7) == perf.PERF_ERR_DTYPE
+    assert f(A=FAKE + 1) == perf.PERF_ERR_ALIGN
+    assert f(K=33, lda=33, ldb=33, pd=perf.PERF_BF16) == perf.PERF_ERR_UNSUPPORTED   # two-operator path needs f32 P

@@ -1,0 +1,121 @@
+"""GPU parity: perf_gemm_softmax (fused kernel and the two-operator path) against the CPU oracle.
+Tolerance: the softmax of scores S has relative error |dS| + O(2^-23), and the fp32-accumulated
+bf16 scores obey |dS| <= K 2^-24 |alpha| sum_k |a||b| whatever the summation order; the gate is
+1e-5 (the bar for fp32 reductions) plus that bound, entries below 1e-30 by absolute error."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import configs, rng
+from tests import gpu_helpers as G
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(M, N, K, batch, seed=0, sigma=1.0):
+    q = rng.normal(rng.tensor_seed(4, 0, seed), (batch, M, K), 0.0, sigma)
+    k = rng.normal(rng.tensor_seed(4, 1, seed), (batch, N, K), 0.0, sigma)
+    return rng.f32_to_bf16_bits(q), rng.f32_to_bf16_bits(k)
+
+
+def _tol(ad, bd, M, N, K, alpha, batch):
+    worst = 0.0
+    for i in range(batch):
+        s = oracle.gemm_absdot(ad.reshape(batch, -1)[i], bd.reshape(batch, -1)[i], M, N, K, b_col=True)
+        worst = max(worst, float(s.max()))
+    return 1e-5 + K * 2.0 ** -24 * abs(alpha) * worst
+
+
+def _check(M, N, K, alpha=0.125, batch=1, p_bf16=False, seed=0, **kw):
+    a, b = _inputs(M, N, K, batch, seed)
+    p = G.run_gemm_softmax(a, b, M, N, K, alpha=alpha, batch=batch, p_bf16=p_bf16, **kw)
+    ad, bd = oracle.widen(a, True), oracle.widen(b, True)
+    ref = oracle.gemm_softmax(ad, bd, M, N, K, alpha=float(np.float32(alpha)), batch=batch)
+    tol = _tol(ad, bd, M, N, K, float(np.float32(alpha)), batch)
+    if p_bf16:
+        got = P.bf16_to_f64(p)
+        assert np.max(np.abs(got - ref) / np.maximum(ref, 2.0 ** -20)) <= 2.0 ** -8 + tol
+    else:
+        P.assert_softmax_close(p.reshape(-1, N), ref.reshape(-1, N), tol=tol)
+        np.testing.assert_allclose(p.astype(np.float64).sum(-1), 1.0, atol=1e-5)
+    return p, ref
+
+
+@pytest.mark.parametrize("M,N,K", [
+    (128, 512, 64), (512, 512, 64), (300, 500, 64), (1, 1, 32), (37, 64, 32), (129, 65, 96),
+    (256, 128, 128), (200, 256, 128), (64, 257, 64), (5, 33, 32),
+])
+def test_fused_kernel_shapes_tails_and_masks(M, N, K):
+    _check(M, N, K)
+
+
+def test_fused_alpha_signs_batches_bf16_output_and_padded_ld():
+    _check(160, 512, 64, alpha=-0.125)
+    _check(160, 192, 64, alpha=0.0)          # all scores equal: every probability 1/N
+    _check(130, 70, 64, alpha=0.5, batch=5)
+    _check(256, 512, 64, p_bf16=True)
+    _check(100, 300, 64, p_bf16=True, batch=2)
+    M, N, K = 96, 80, 64
+    a, b = _inputs(M, N, K, 1, seed=3)
+    ap = np.zeros((M, 72), np.uint16); ap[:, :K] = a[0]
+    bp = np.zeros((N, 88), np.uint16); bp[:, :K] = b[0]
+    p = G.run_gemm_softmax(ap, bp, M, N, K, alpha=0.125, lda=72, ldb=88, ldp=84)
+    ref = oracle.gemm_softmax(oracle.widen(a, True), oracle.widen(b, True), M, N, K, alpha=0.125)
+    P.assert_softmax_close(p.reshape(-1, N), ref.reshape(-1, N), tol=2e-5)
+
+
+def test_argmax_matches_scores():
+    M, N, K = 256, 512, 64
+    a, b = _inputs(M, N, K, 1, seed=7)
+    p = G.run_gemm_softmax(a, b, M, N, K, alpha=0.125)[0]
+    s = oracle.gemm(oracle.widen(a, True), oracle.widen(b, True), M, N, K, b_col=True, alpha=0.125)
+    # the probabilities are monotone in the fp32 scores, which differ from the exact ones by
+    # accumulation rounding: accept any column whose exact score is within that rounding of the best
+    am = p.argmax(1)
+    best = s.max(1)
+    assert np.all(best - s[np.arange(M), am] <= 64 * 2.0 ** -24 * 64.0)
+
+
+@pytest.mark.parametrize("M,N,K,batch", [(64, 1024, 64, 1), (100, 300, 256, 2), (33, 40, 48, 1), (70, 600, 64, 3)])
+def test_two_operator_path(M, N, K, batch):
+    # N > 512, K > 128 or K not a multiple of 32: scores through P, softmax in place
+    _check(M, N, K, batch=batch)
+
+
+def test_fp32_operands_take_the_two_operator_path():
+    g = np.random.default_rng(2)
+    M, N, K = 50, 60, 20
+    a = g.standard_normal((M, K)).astype(np.float32)
+    b = g.standard_normal((N, K)).astype(np.float32)
+    p = G.run_gemm_softmax(a, b, M, N, K, alpha=0.3, ab_bf16=False)[0]
+    ref = oracle.gemm_softmax(a.astype(np.float64), b.astype(np.float64), M, N, K, alpha=float(np.float32(0.3)))[0]
+    P.assert_softmax_close(p, ref, tol=2e-5)
+
+
+def test_config4_full_size_sampled_batches_and_row_sums():
+    import torch
+    import paper_2511_03586_amd as perf
+    wl = configs.CONFIG4
+    d = wl.make()
+    q, k = G.dev(d["q_bf16"].ravel()), G.dev(d["k_bf16"].ravel())
+    S, D, B = wl.seq, wl.d, wl.batch
+    p = torch.zeros(B * S * S, dtype=torch.float32, device="cuda")
+    perf.perf_gemm_softmax(q.data_ptr(), k.data_ptr(), p.data_ptr(), S, S, D, D, D, S, B, S * D, S * D, S * S,
+                           wl.alpha, perf.PERF_BF16, perf.PERF_F32, G.stream())
+    torch.cuda.synchronize()
+    sums = p.view(B * S, S).sum(1)
+    assert float((sums - 1).abs().max()) <= 1e-5
+    ph = p.view(B, S, S)
+    for bi in (0, 1, 255, 511):
+        ad, bd = oracle.widen(d["q_bf16"][bi], True), oracle.widen(d["k_bf16"][bi], True)
+        ref = oracle.gemm_softmax(ad, bd, S, S, D, alpha=wl.alpha)[0]
+        tol = _tol(ad, bd, S, S, D, wl.alpha, 1)
+        P.assert_softmax_close(ph[bi].cpu().numpy(), ref, tol=tol)
+
+
+def test_deterministic():
+    a, b = _inputs(256, 512, 64, 2, seed=9)
+    p1 = G.run_gemm_softmax(a, b, 256, 512, 64, alpha=0.125, batch=2)
+    p2 = G.run_gemm_softmax(a, b, 256, 512, 64, alpha=0.125, batch=2)
+    assert np.array_equal(p1, p2)
