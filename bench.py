@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--only", default="", help="comma-separated workload names (profiling aid)")
+    ap.add_argument("--no-paper-shapes", action="store_true", help="skip the second workload (the paper's table shapes)")
     return ap.parse_args()
 
 
@@ -163,6 +164,69 @@ def build_workloads(torch, perf):
                                                    c5.H, c5.W, c5.C, c5.K, c5.R, c5.S, 1, 1, 1, 1, BF16, BF16, st()),
                         16))
     keep = (x1, y1, xl, yl, x2, y2, g2, b2, a3, b3, o3, q4, k4, s4, p4, x5, w5, y5)
+    return wls, keep
+
+
+def build_paper_workloads(torch, perf):
+    """The paper's own table shapes (Section 4.3) for the operator kinds built here: a second
+    workload, listed under `paper_shapes` and not averaged into `value`."""
+    from workloads import configs, rng
+    st = lambda: torch.cuda.current_stream().cuda_stream
+    F32, BF16, ROW, COL = perf.PERF_F32, perf.PERF_BF16, perf.PERF_ROW_MAJOR, perf.PERF_COL_MAJOR
+    wls, keep = [], []
+
+    def sets(t, n):
+        out = torch.empty((n,) + tuple(t.shape), dtype=t.dtype, device="cuda")
+        for i in range(n):
+            out[i] = torch.roll(t, shifts=i, dims=0)
+        keep.append(out)
+        return out
+
+    ps = configs.PAPER_SOFTMAX
+    xs = sets(G.dev(ps.make()["x"]), 8)
+    ys = torch.empty_like(xs); keep.append(ys)
+    wls.append(Workload("paper_softmax_24576x512_f32", "softmax_rows_kernel", "hbm", ps.bytes_moved(),
+                        lambda i: perf.perf_softmax(xs[i % 8].data_ptr(), ys[i % 8].data_ptr(), ps.rows, ps.cols,
+                                                    ps.cols, ps.cols, F32, F32, 1.0, st()), 8))
+    for tag, wl, n in (("paper_layernorm_16384x1024_f32", configs.PAPER_LAYERNORM_1, 4),
+                       ("paper_layernorm_4096x4096_f32", configs.PAPER_LAYERNORM_2, 4)):
+        d = wl.make()
+        x = sets(G.dev(rng.bf16_bits_to_f32(d["x_bf16"])), n)
+        y = torch.empty_like(x); keep.append(y)
+        g, b = G.dev(d["gamma"]), G.dev(d["beta"]); keep.extend([g, b])
+        wls.append(Workload(tag, "layernorm_rows_kernel<f32,f32,f32>", "hbm", 8 * wl.rows * wl.cols,
+                            lambda i, x=x, y=y, g=g, b=b, wl=wl, n=n: perf.perf_layernorm(
+                                x[i % n].data_ptr(), g.data_ptr(), b.data_ptr(), y[i % n].data_ptr(), None, None,
+                                wl.rows, wl.cols, wl.cols, wl.cols, wl.eps, F32, F32, F32, st()), n))
+    pm = configs.PAPER_MATMUL
+    d = pm.make()
+    am, bm = sets(G.dev(d["a_bf16"]), 16), sets(G.dev(d["b_bf16"]), 16)
+    cm = torch.empty((16, pm.M, pm.N), dtype=torch.float32, device="cuda"); keep.append(cm)
+    wls.append(Workload("paper_matmul_768x1024x1024_bf16", "gemm_mfma_kernel<2,2,2,2>", "mfma", pm.flops(),
+                        lambda i: perf.perf_gemm(am[i % 16].data_ptr(), bm[i % 16].data_ptr(), cm[i % 16].data_ptr(),
+                                                 pm.M, pm.N, pm.K, ROW, pm.K, COL, pm.K, pm.N, 1, 0, 0, 0, 1.0, BF16,
+                                                 F32, st()), 16, "96 tiles of 128x128 on 256 CUs"))
+    pb, nb = configs.PAPER_BMM, configs.PAPER_BMM_BATCH
+    d = pb.make()
+    ab = sets(G.dev(d["a_bf16"]).repeat(nb, 1, 1), 4)
+    bb = sets(G.dev(d["b_bf16"]).repeat(nb, 1, 1), 4)
+    cb = torch.empty((4, nb, pb.M, pb.N), dtype=torch.float32, device="cuda"); keep.append(cb)
+    wls.append(Workload("paper_bmm_192x256x128x256_bf16", "gemm_mfma_kernel<2,2,2,2>", "mfma", nb * pb.flops(),
+                        lambda i: perf.perf_gemm(ab[i % 4].data_ptr(), bb[i % 4].data_ptr(), cb[i % 4].data_ptr(),
+                                                 pb.M, pb.N, pb.K, ROW, pb.K, COL, pb.K, pb.N, nb, pb.M * pb.K,
+                                                 pb.N * pb.K, pb.M * pb.N, 1.0, BF16, F32, st()), 4,
+                        "64 flop/byte: bound by the fp32 C store"))
+    for tag, wl, kern, note in (("paper_conv_8x64x64x56x56x3_bf16", configs.PAPER_CONV_2, "conv2d_mfma_kernel<2,2,2,2>", ""),
+                                ("paper_conv_8x10x3x512x512x5_bf16", configs.PAPER_CONV_1, "conv2d_direct_kernel",
+                                 "3 input channels: no MFMA instance, one thread per output")):
+        d = wl.make()
+        x = sets(G.dev(d["x_bf16"]), 8)
+        w = G.dev(d["w_bf16"]); keep.append(w)
+        y = torch.empty((8, wl.N, wl.P, wl.Q, wl.K), dtype=torch.int16, device="cuda"); keep.append(y)
+        wls.append(Workload(tag, kern, "mfma", wl.flops(),
+                            lambda i, x=x, w=w, y=y, wl=wl: perf.perf_conv2d(
+                                x[i % 8].data_ptr(), w.data_ptr(), y[i % 8].data_ptr(), wl.N, wl.H, wl.W, wl.C, wl.K,
+                                wl.R, wl.S, wl.stride, wl.stride, wl.pad, wl.pad, BF16, BF16, st()), 8, note))
     return wls, keep
 
 
@@ -347,6 +411,30 @@ def main():
         "mfma_loop_ceiling_tflops": round(mfma_tflops, 1),
         "workloads": per,
     }
+    if not args.no_paper_shapes and not args.only:
+        del keep
+        torch.cuda.empty_cache()
+        pw, pkeep = build_paper_workloads(torch, perf)
+        for s_ in range(args.warmup):
+            for w in pw:
+                w.launch(s_)
+        evs = []
+        for w in pw:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for s_ in range(K):
+                w.launch(args.warmup + s_)
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        plist = []
+        for w, (e0, e1) in zip(pw, evs):
+            w.ms = e0.elapsed_time(e1) / K
+            entry = {"workload": w.name, "us": round(w.ms * 1e3, 2), "buffer_sets": w.nsets, "roofline": w.roofline()}
+            if w.note:
+                entry["note"] = w.note
+            plist.append(entry)
+        out["paper_shapes"] = plist
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(per)
     print(json.dumps(out))

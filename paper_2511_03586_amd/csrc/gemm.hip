@@ -2,7 +2,7 @@
 // Section 4.3 of the paper):  C_b = alpha * A_b * B_b, fp32 accumulation.
 //
 //  * gemm_mfma_kernel: bf16 operands, A row-major and B column-major (both K-contiguous),
-//    K a multiple of 32.  256x256 (or 128x128) workgroup tile; the K-step-64 loop of
+//    K a multiple of 32.  256x256, 128x128 or 64x64 workgroup tile; the K-step-64 loop of
 //    mfma_tile.h when K is a multiple of 64, else its K-step-32 loop.
 //  * gemm_general_kernel: any layout / dtype / size; 64x64 tile of fp32 FMAs.
 #include "mfma_tile.h"
@@ -208,9 +208,9 @@ extern "C" perf_status perf_gemm(const void *A, const void *B, void *C, int64_t 
     const bool mfma_ok = ab_dt == PERF_BF16 && la == PERF_ROW_MAJOR && lb == PERF_COL_MAJOR && K % kBK == 0 &&
                          lda % 8 == 0 && ldb % 8 == 0 && strideA % 8 == 0 && strideB % 8 == 0 && aligned(A, 16) &&
                          aligned(B, 16) && lda <= (1 << 21) && ldb <= (1 << 21) && M <= (1 << 30) && N <= (1 << 30) && K <= (1 << 30) &&
-                         ((M + 127) / 128) * ((N + 127) / 128) <= kMaxGridX;
+                         ((M + 63) / 64) * ((N + 63) / 64) <= kMaxGridX;
     if (mfma_ok) {
-        // the 256x256 tile needs enough tiles to occupy the 256 CUs; otherwise 128x128
+        // the 256x256 tile needs enough tiles to occupy the 256 CUs; otherwise 128x128 or 64x64
         const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * batch;
         // the K-step-64 loop pays off in the main loop; short reductions are bound by the C
         // store, which the other loop's epilogue (two full 128-byte row segments per store
@@ -220,8 +220,14 @@ extern "C" perf_status perf_gemm(const void *A, const void *B, void *C, int64_t 
             if (k64) return c_dt == PERF_F32 ? launch_mfma<4, 4, 2, 2, true, float>(g) : launch_mfma<4, 4, 2, 2, true, uint16_t>(g);
             return c_dt == PERF_F32 ? launch_mfma<4, 4, 2, 2, false, float>(g) : launch_mfma<4, 4, 2, 2, false, uint16_t>(g);
         }
-        if (k64) return c_dt == PERF_F32 ? launch_mfma<2, 2, 2, 2, true, float>(g) : launch_mfma<2, 2, 2, 2, true, uint16_t>(g);
-        return c_dt == PERF_F32 ? launch_mfma<2, 2, 2, 2, false, float>(g) : launch_mfma<2, 2, 2, 2, false, uint16_t>(g);
+        // small problems: 64x64 tiles when 128x128 tiles would leave most of the 256 CUs idle
+        const int64_t mid_tiles = ((M + 127) / 128) * ((N + 127) / 128) * batch;
+        if (mid_tiles >= 192) {
+            if (k64) return c_dt == PERF_F32 ? launch_mfma<2, 2, 2, 2, true, float>(g) : launch_mfma<2, 2, 2, 2, true, uint16_t>(g);
+            return c_dt == PERF_F32 ? launch_mfma<2, 2, 2, 2, false, float>(g) : launch_mfma<2, 2, 2, 2, false, uint16_t>(g);
+        }
+        if (k64) return c_dt == PERF_F32 ? launch_mfma<1, 1, 2, 2, true, float>(g) : launch_mfma<1, 1, 2, 2, true, uint16_t>(g);
+        return c_dt == PERF_F32 ? launch_mfma<1, 1, 2, 2, false, float>(g) : launch_mfma<1, 1, 2, 2, false, uint16_t>(g);
     }
     if (ab_dt == PERF_BF16)
         return c_dt == PERF_F32 ? launch_general<uint16_t, float>(g) : launch_general<uint16_t, uint16_t>(g);

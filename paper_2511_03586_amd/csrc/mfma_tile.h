@@ -376,7 +376,6 @@ __device__ __forceinline__ void mfma_mainloop_k64(WaveTile16<2 * TM, 2 * TN> &t,
     constexpr int kMfmas = T16M * T16N;
     static_assert(2 * kStageBytes64 <= Shape::kLdsBytes, "the two stages fit the LDS the launch provides");
     static_assert(2 * kLoads < 64, "two steps of loads must fit the vmcnt counter");
-    static_assert(T16M + T16N + kLoads <= kMfmas, "at most one memory instruction per MFMA");
     bf16x8_t fa[2][T16M], fb[2][T16N];  // [buffer][tile]: operands of one half-step
 
     // per-lane LDS byte offsets of the fragments of K half `half` (tile rows of 16, chunk = 4*half + lane/16)

@@ -62,6 +62,12 @@ def test_alpha_bf16_output_batched_and_padded_ld():
     P.assert_contraction_close(c, ref, s, 64)
 
 
+def test_mid_tile_kernels():
+    # 128x128 tiles are chosen between 192 such tiles and 256 tiles of 256x256; smaller problems get 64x64 tiles
+    _check(configs.GemmWorkload(M=1792, N=1800, K=64))      # K-step-32 loop, 128x128 tiles, ragged N
+    _check(configs.GemmWorkload(M=1792, N=1792, K=512))     # K-step-64 loop, 128x128 tiles
+
+
 def test_k64_loop_tails_alpha_bf16_batched_and_odd_ldc():
     # K a multiple of 64 and >= 512 selects the K-step-64 loop (16x16x32 MFMAs, lane-exchange epilogue)
     _check(configs.GemmWorkload(M=300, N=200, K=576))                          # 128x128 tiles, ragged, odd step count

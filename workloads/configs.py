@@ -119,3 +119,18 @@ CONFIG2 = LayerNormWorkload()
 CONFIG3 = GemmWorkload()
 CONFIG4 = AttnScoreWorkload()
 CONFIG5 = ConvWorkload()
+
+
+# Shapes of the paper's own operator table (Section 4.3) for the four operator kinds built
+# here, with this module's recipes (same distributions and seeds, config numbers 11..17).
+# The table gives extents only; the readings used: layernorm / softmax rows x cols (fp32);
+# matmul 768x1024x1024 = M x K x N; bmm 192x256x128x256 = batch x M x K x N; conv
+# N x K_out x C_in x H x W x filter, stride 1, "same" zero padding.
+PAPER_SOFTMAX = SoftmaxWorkload(rows=24576, cols=512, config=11)
+PAPER_LAYERNORM_1 = LayerNormWorkload(rows=16384, cols=1024, config=12)
+PAPER_LAYERNORM_2 = LayerNormWorkload(rows=4096, cols=4096, config=13)
+PAPER_MATMUL = GemmWorkload(M=768, N=1024, K=1024, config=14)
+PAPER_BMM_BATCH = 192
+PAPER_BMM = GemmWorkload(M=256, N=256, K=128, config=15)          # per matrix; PAPER_BMM_BATCH of them
+PAPER_CONV_1 = ConvWorkload(N=8, H=512, W=512, C=3, K=10, R=5, S=5, pad=2, config=16)
+PAPER_CONV_2 = ConvWorkload(N=8, H=56, W=56, C=64, K=64, R=3, S=3, pad=1, config=17)
