@@ -31,6 +31,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published (2.5 PFLOP/s)
+VALU_F32_PEAK_TFLOPS = 157.3    # MI355X fp32 vector, published
 
 
 def parse():
@@ -57,6 +58,8 @@ class Workload:
         sec = self.ms * 1e-3
         if self.bound == "hbm":
             ach, peak, unit = self.unit_work / sec / 1e9, HBM_PEAK_GBS, "GB/s"
+        elif self.bound == "alu":   # fp32 vector FMAs
+            ach, peak, unit = self.unit_work / sec / 1e12, VALU_F32_PEAK_TFLOPS, "TFLOP/s"
         else:
             ach, peak, unit = self.unit_work / sec / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
         return {"kernel": self.kernel, "bound": self.bound, "achieved": round(ach, 2), "peak": peak,
@@ -217,13 +220,13 @@ def build_paper_workloads(torch, perf):
                                                  pb.N * pb.K, pb.M * pb.N, 1.0, BF16, F32, st()), 4,
                         "64 flop/byte: bound by the fp32 C store"))
     for tag, wl, kern, note in (("paper_conv_8x64x64x56x56x3_bf16", configs.PAPER_CONV_2, "conv2d_mfma_kernel<2,2,2,2>", ""),
-                                ("paper_conv_8x10x3x512x512x5_bf16", configs.PAPER_CONV_1, "conv2d_direct_kernel",
-                                 "3 input channels: no MFMA instance, one thread per output")):
+                                ("paper_conv_8x10x3x512x512x5_bf16", configs.PAPER_CONV_1, "conv2d_smallc_kernel<12>",
+                                 "3 input channels: no MFMA K-step; fp32 vector FMAs, priced against the vector peak")):
         d = wl.make()
         x = sets(G.dev(d["x_bf16"]), 8)
         w = G.dev(d["w_bf16"]); keep.append(w)
         y = torch.empty((8, wl.N, wl.P, wl.Q, wl.K), dtype=torch.int16, device="cuda"); keep.append(y)
-        wls.append(Workload(tag, kern, "mfma", wl.flops(),
+        wls.append(Workload(tag, kern, "alu" if wl.C < 32 else "mfma", wl.flops(),
                             lambda i, x=x, w=w, y=y, wl=wl: perf.perf_conv2d(
                                 x[i % 8].data_ptr(), w.data_ptr(), y[i % 8].data_ptr(), wl.N, wl.H, wl.W, wl.C, wl.K,
                                 wl.R, wl.S, wl.stride, wl.stride, wl.pad, wl.pad, BF16, BF16, st()), 8, note))

@@ -11,6 +11,9 @@
 //
 //  * conv2d_wreg_kernel: bf16, 3x3 filter, 64 -> 128 channels: weights held in registers.
 //  * conv2d_mfma_kernel: bf16, C a multiple of 32; main loop shared with the GEMM.
+//  * conv2d_smallc_kernel: few input channels (no 32-wide K-step for the matrix cores, e.g.
+//    the 3-channel 5x5 first layer of the paper's "conv 1"): one thread per output pixel
+//    and block of KB output channels, weights broadcast from LDS, fp32 FMAs.
 //  * conv2d_direct_kernel: any other legal case; one thread per output element.
 #include "mfma_tile.h"
 #include "host_utils.h"
@@ -420,6 +423,50 @@ __global__ __launch_bounds__(256) void conv2d_direct_kernel(const T *__restrict_
     }
 }
 
+// Direct convolution for small C: thread = (output pixel, block of KB output channels).
+// Each input value is loaded once per thread and multiplied into KB accumulators; the
+// block's weights sit in LDS as fp32 [R*S*C][KB], and since every lane reads the same
+// address the reads are broadcasts (16 bytes = 4 channels per instruction).
+template <int KB, typename T, typename CT>
+__global__ __launch_bounds__(256) void conv2d_smallc_kernel(const T *__restrict__ x, const T *__restrict__ w,
+                                                            CT *__restrict__ y, ConvGeom g, int64_t npix)
+{
+    extern __shared__ __attribute__((aligned(16))) float wl[];
+    const int taps = g.R * g.S * g.C;
+    const int k0 = blockIdx.y * KB;
+    for (int i = threadIdx.x; i < taps * KB; i += 256) {
+        const int t = i / KB, k = k0 + i % KB;
+        wl[i] = k < g.K ? load_xw<T>(w + (int64_t)k * taps + t) : 0.f;
+    }
+    __syncthreads();
+    for (int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x; m < npix; m += (int64_t)gridDim.x * 256) {
+        const int q = (int)(m % g.Q), p = (int)((m / g.Q) % g.P);
+        const int64_t n = m / ((int64_t)g.P * g.Q);
+        float acc[KB];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) acc[kb] = 0.f;
+        for (int r = 0; r < g.R; ++r) {
+            const int ih = p * g.sh - g.ph + r;
+            if (ih < 0 || ih >= g.H) continue;
+            for (int sft = 0; sft < g.S; ++sft) {
+                const int iw = q * g.sw - g.pw + sft;
+                if (iw < 0 || iw >= g.W) continue;
+                const T *xp = x + ((n * g.H + ih) * g.W + iw) * g.C;
+                const float *wp = wl + (r * g.S + sft) * g.C * KB;
+                for (int c = 0; c < g.C; ++c) {
+                    const float xv = load_xw<T>(xp + c);
+#pragma unroll
+                    for (int kb = 0; kb < KB; ++kb) acc[kb] = __builtin_fmaf(xv, wp[c * KB + kb], acc[kb]);
+                }
+            }
+        }
+        CT *yp = y + m * g.K + k0;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+            if (k0 + kb < g.K) store_c<CT>(yp + kb, acc[kb]);
+    }
+}
+
 template <int TM, int TN, int WM, int WN, typename CT>
 static perf_status launch_conv_mfma(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
 {
@@ -464,6 +511,30 @@ static perf_status launch_conv_wreg(const void *x, const void *w, void *y, const
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(512), kLds, st, (const uint16_t *)x, (const uint16_t *)w, (CT *)y,
                        g, px_per_wg);
     return launch_status();
+}
+
+constexpr int kSmallcLdsBytes = 48 * 1024;
+
+template <int KB, typename T, typename CT>
+static perf_status launch_conv_smallc(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
+{
+    const int64_t npix = (int64_t)g.N * g.P * g.Q;
+    int64_t blocks = (npix + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    const unsigned gy = (unsigned)((g.K + KB - 1) / KB);
+    const size_t lds = (size_t)g.R * g.S * g.C * KB * sizeof(float);
+    hipLaunchKernelGGL((conv2d_smallc_kernel<KB, T, CT>), dim3((unsigned)blocks, gy), dim3(256), lds, st, (const T *)x,
+                       (const T *)w, (CT *)y, g, npix);
+    return launch_status();
+}
+
+template <typename T, typename CT>
+static perf_status dispatch_conv_smallc(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
+{
+    if (g.K <= 4) return launch_conv_smallc<4, T, CT>(x, w, y, g, st);
+    if (g.K <= 8) return launch_conv_smallc<8, T, CT>(x, w, y, g, st);
+    if (g.K <= 12) return launch_conv_smallc<12, T, CT>(x, w, y, g, st);
+    return launch_conv_smallc<16, T, CT>(x, w, y, g, st);
 }
 
 template <typename T, typename CT>
@@ -513,6 +584,14 @@ extern "C" perf_status perf_conv2d(const void *x, const void *w, void *y, int64_
     if (mfma_ok)
         return y_dt == PERF_F32 ? launch_conv_mfma<2, 2, 2, 2, float>(x, w, y, g, st)
                                 : launch_conv_mfma<2, 2, 2, 2, uint16_t>(x, w, y, g, st);
+    // few input channels: channel-blocked direct kernel, if a 16-channel block of weights fits its LDS budget
+    if (C < 32 && R * S * C * 16 * 4 <= kSmallcLdsBytes && (K + 15) / 16 <= kMaxGridYZ) {
+        if (xw_dt == PERF_BF16)
+            return y_dt == PERF_F32 ? dispatch_conv_smallc<uint16_t, float>(x, w, y, g, st)
+                                    : dispatch_conv_smallc<uint16_t, uint16_t>(x, w, y, g, st);
+        return y_dt == PERF_F32 ? dispatch_conv_smallc<float, float>(x, w, y, g, st)
+                                : dispatch_conv_smallc<float, uint16_t>(x, w, y, g, st);
+    }
     if (xw_dt == PERF_BF16)
         return y_dt == PERF_F32 ? launch_conv_direct<uint16_t, float>(x, w, y, g, st)
                                 : launch_conv_direct<uint16_t, uint16_t>(x, w, y, g, st);

@@ -57,6 +57,18 @@ def test_direct_path_shapes(kw):
     _check(configs.ConvWorkload(**kw), y_bf16=False)
 
 
+def test_small_channel_kernel_channel_blocks_and_fp32_operands():
+    # C < 32: channel-blocked direct kernel; K = 37 needs three blocks of 16 with a ragged last one
+    _check(configs.ConvWorkload(N=1, H=8, W=8, C=5, K=37, R=3, S=3, pad=1))
+    _check(configs.ConvWorkload(N=2, H=11, W=6, C=1, K=6, R=3, S=2, pad=1, stride=2), y_bf16=False)
+    g = np.random.default_rng(4)
+    x = g.standard_normal((2, 7, 9, 4)).astype(np.float32)
+    w = g.standard_normal((9, 3, 3, 4)).astype(np.float32)
+    y = G.run_conv2d(x, w, (1, 1), (1, 1), xw_bf16=False, y_bf16=False)
+    ref, ad = oracle.conv2d(x.astype(np.float64), w.astype(np.float64), (1, 1), (1, 1), want_absdot=True)
+    assert np.max(np.abs(y - ref) / np.maximum(ad, 1e-30)) <= 36 * 2.0 ** -23
+
+
 def test_delta_kernels_and_tap_counts_are_exact():
     C = 64
     x = rng.bf16_bits_to_f32(configs.ConvWorkload(N=1, H=5, W=7, C=C, K=C).make()["x_bf16"])
