@@ -41,10 +41,14 @@ def _load():
                                     i64, i64, i64, i64, dbl]
         lib.oracle_gemm_absdot.argtypes = [ptr, ptr, ptr, i64, i64, i64, cint, i64, cint, i64, i64]
         lib.oracle_conv2d.argtypes = [ptr, ptr, ptr, ptr] + [i64] * 11
+        lib.oracle_rmsnorm.argtypes = [ptr, ptr, ptr, ptr, i64, i64, dbl]
+        lib.oracle_reduce_mean.argtypes = [ptr, ptr, i64, i64, cint]
+        lib.oracle_eltwise.argtypes = [cint, ptr, ptr, ptr, i64]
         lib.oracle_round_f32.argtypes = [ptr, ptr, i64]
         lib.oracle_round_bf16.argtypes = [ptr, ptr, i64]
         for f in ("oracle_set_threads", "oracle_softmax", "oracle_layernorm", "oracle_gemm",
-                  "oracle_gemm_absdot", "oracle_conv2d", "oracle_round_f32", "oracle_round_bf16"):
+                  "oracle_gemm_absdot", "oracle_conv2d", "oracle_round_f32", "oracle_round_bf16",
+                  "oracle_rmsnorm", "oracle_reduce_mean", "oracle_eltwise"):
             getattr(lib, f).restype = None
         _lib = lib
     return _lib
@@ -92,6 +96,39 @@ def layernorm(x, gamma, beta, eps: float):
     _load().oracle_layernorm(_p(x), _p(gamma), _p(beta), _p(y), _p(mean), _p(rstd),
                              rows, cols, cols, cols, float(eps))
     return y, mean, rstd
+
+
+def rmsnorm(x, gamma, eps: float):
+    """Returns (y, rrms), float64; x is 2-D, gamma 1-D of length cols."""
+    x, gamma = widen(x), widen(gamma)
+    rows, cols = x.shape
+    assert gamma.shape == (cols,)
+    y = np.empty_like(x)
+    r = np.empty(rows, dtype=np.float64)
+    _load().oracle_rmsnorm(_p(x), _p(gamma), _p(y), _p(r), rows, cols, float(eps))
+    return y, r
+
+
+def reduce_mean(x, axis: int):
+    """Mean of a 2-D float64 array along ``axis`` (0 or 1)."""
+    x = widen(x)
+    rows, cols = x.shape
+    y = np.empty(rows if axis == 1 else cols, dtype=np.float64)
+    _load().oracle_reduce_mean(_p(x), _p(y), rows, cols, int(axis))
+    return y
+
+
+ELTWISE_ADD, ELTWISE_MUL, ELTWISE_RELU = 0, 1, 2
+
+
+def eltwise(op: int, a, b=None):
+    """Element-wise add / mul / relu of float64 arrays (b unused for relu)."""
+    a = widen(a)
+    b = widen(b) if b is not None else a
+    assert a.shape == b.shape
+    y = np.empty_like(a)
+    _load().oracle_eltwise(int(op), _p(a.ravel()), _p(b.ravel()), _p(y.reshape(-1)), a.size)
+    return y
 
 
 def gemm(a, b, M, N, K, a_col=False, b_col=False, alpha=1.0, batch=1, lda=None, ldb=None):

@@ -1,6 +1,8 @@
 /*
  * CPU oracle for the operator hot path: row softmax, LayerNorm, (batched) GEMM and
- * 2-D convolution, written out as their plain definitions in double precision.
+ * 2-D convolution, and for the streaming operators added next to them (RMS norm, mean
+ * along an axis, add / mul / relu), written out as their plain definitions in double
+ * precision.
  *
  * THIS IS TEST INFRASTRUCTURE, NOT A PRODUCT PATH.  Only the tests, the smoke check
  * and the benchmark's cpu_baseline leg may call it.  It shares no code with the HIP
@@ -170,6 +172,51 @@ void oracle_conv2d(const double *x, const double *w, double *y, double *absdot,
                     y[((n * P + p) * Q + q) * K + k] = acc;
                     if (absdot) absdot[((n * P + p) * Q + q) * K + k] = aacc;
                 }
+}
+
+/* RMS normalisation over the last dimension ("rmsnorm" row of the operator table, Section
+ * 4.3; standard definition):  r_i = 1/sqrt(mean_j x_ij^2 + eps),  y_ij = x_ij * r_i * gamma_j.
+ * rrms (nullable) receives r_i. */
+void oracle_rmsnorm(const double *x, const double *gamma, double *y, double *rrms, int64_t rows, int64_t cols,
+                    double eps)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        const double *xr = x + i * cols;
+        double ss = 0.0;
+        for (int64_t j = 0; j < cols; ++j) ss += xr[j] * xr[j];
+        const double r = 1.0 / sqrt(ss / (double)cols + eps);
+        for (int64_t j = 0; j < cols; ++j) y[i * cols + j] = xr[j] * r * gamma[j];
+        if (rrms) rrms[i] = r;
+    }
+}
+
+/* Mean along one axis of a rows x cols matrix ("reducemean" row of the operator table):
+ * axis 1: y_i = (1/cols) sum_j x_ij (length rows); axis 0: y_j = (1/rows) sum_i x_ij (length cols). */
+void oracle_reduce_mean(const double *x, double *y, int64_t rows, int64_t cols, int axis)
+{
+    if (axis == 1) {
+#pragma omp parallel for schedule(static)
+        for (int64_t i = 0; i < rows; ++i) {
+            double s = 0.0;
+            for (int64_t j = 0; j < cols; ++j) s += x[i * cols + j];
+            y[i] = s / (double)cols;
+        }
+    } else {
+#pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < cols; ++j) {
+            double s = 0.0;
+            for (int64_t i = 0; i < rows; ++i) s += x[i * cols + j];
+            y[j] = s / (double)rows;
+        }
+    }
+}
+
+/* Element-wise operators of the table ("add", "mul", "relu"): op 0: a+b, 1: a*b, 2: max(a,0). */
+void oracle_eltwise(int op, const double *a, const double *b, double *y, int64_t n)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) y[i] = op == 0 ? a[i] + b[i] : op == 1 ? a[i] * b[i] : (a[i] > 0.0 ? a[i] : 0.0);
 }
 
 /* One rounding of a double to fp32 (round-to-nearest-even: the C conversion under the
