@@ -230,6 +230,40 @@ def build_paper_workloads(torch, perf):
                             lambda i, x=x, w=w, y=y, wl=wl: perf.perf_conv2d(
                                 x[i % 8].data_ptr(), w.data_ptr(), y[i % 8].data_ptr(), wl.N, wl.H, wl.W, wl.C, wl.K,
                                 wl.R, wl.S, wl.stride, wl.stride, wl.pad, wl.pad, BF16, BF16, st()), 8, note))
+    # streaming operators of the table: rmsnorm 3072x4096, reducemean 4096x4096 (either axis), add 3072x4096,
+    # mul 6x14336, relu 4096x4096; fp32, entries N(1, var 3) like the LayerNorm recipe
+    def normal_f32(cfg, shape):
+        return G.dev(rng.normal(rng.tensor_seed(cfg, 0), shape, 1.0, 3.0))
+    xr = sets(normal_f32(18, (3072, 4096)), 8)
+    yr = torch.empty_like(xr); keep.append(yr)
+    gr = G.dev(rng.uniform(rng.tensor_seed(18, 1), (4096,), 0.5, 1.5)); keep.append(gr)
+    wls.append(Workload("paper_rmsnorm_3072x4096_f32", "rmsnorm_rows_kernel<f32,f32,f32,16>", "hbm", 8 * 3072 * 4096,
+                        lambda i: perf.perf_rmsnorm(xr[i % 8].data_ptr(), gr.data_ptr(), yr[i % 8].data_ptr(), None, 3072,
+                                                    4096, 4096, 4096, 1e-5, F32, F32, F32, st()), 8))
+    xm = sets(normal_f32(19, (4096, 4096)), 8)
+    ym = torch.empty((8, 4096), dtype=torch.float32, device="cuda"); keep.append(ym)
+    wls.append(Workload("paper_reducemean_4096x4096_f32_axis1", "rowmean_kernel<f32>", "hbm", 4 * 4096 * 4096,
+                        lambda i: perf.perf_reduce_mean(xm[i % 8].data_ptr(), ym[i % 8].data_ptr(), 4096, 4096, 4096, 1,
+                                                        F32, F32, st()), 8))
+    wls.append(Workload("paper_reducemean_4096x4096_f32_axis0", "colmean_kernel<f32>", "hbm", 4 * 4096 * 4096,
+                        lambda i: perf.perf_reduce_mean(xm[i % 8].data_ptr(), ym[i % 8].data_ptr(), 4096, 4096, 4096, 0,
+                                                        F32, F32, st()), 8,
+                        "one workgroup per 16 columns (64-byte row segments), no workspace, no atomics"))
+    ya = torch.empty_like(xr); keep.append(ya)
+    n_add = 3072 * 4096
+    wls.append(Workload("paper_add_3072x4096_f32", "eltwise_kernel<add,f32>", "hbm", 12 * n_add,
+                        lambda i: perf.perf_eltwise(perf.PERF_ADD, xr[i % 8].data_ptr(), xr[(i + 3) % 8].data_ptr(),
+                                                    ya[i % 8].data_ptr(), n_add, F32, st()), 8))
+    xs6 = sets(normal_f32(20, (6, 14336)), 64)
+    ys6 = torch.empty_like(xs6); keep.append(ys6)
+    wls.append(Workload("paper_mul_6x14336_f32", "eltwise_kernel<mul,f32>", "hbm", 12 * 6 * 14336,
+                        lambda i: perf.perf_eltwise(perf.PERF_MUL, xs6[i % 64].data_ptr(), xs6[(i + 7) % 64].data_ptr(),
+                                                    ys6[i % 64].data_ptr(), 6 * 14336, F32, st()), 64,
+                        "1 MB per launch: launch-latency bound"))
+    yl = torch.empty_like(xm); keep.append(yl)
+    wls.append(Workload("paper_relu_4096x4096_f32", "eltwise_kernel<relu,f32>", "hbm", 8 * 4096 * 4096,
+                        lambda i: perf.perf_eltwise(perf.PERF_RELU, xm[i % 8].data_ptr(), None, yl[i % 8].data_ptr(),
+                                                    4096 * 4096, F32, st()), 8))
     return wls, keep
 
 

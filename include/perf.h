@@ -127,6 +127,33 @@ perf_status perf_gemm_softmax(const void *A, const void *B, void *P, int64_t M, 
                               int64_t strideA, int64_t strideB, int64_t strideP, float alpha,
                               perf_dtype ab_dt, perf_dtype p_dt, perf_stream stream);
 
+/* RMS normalisation over the last dimension ("rmsnorm" row of the operator table, Section
+ * 4.3).  For each row:  r = 1/sqrt(mean_j x[j]^2 + eps);  y[j] = x[j] * r * gamma[j].
+ * Arithmetic is fp32; the result is rounded once to y_dt.
+ *   x, y       device, rows x cols, row stride ldx / ldy; dtypes f32 or bf16
+ *   gamma      device, length cols, dtype param_dt;  rrms_out  device fp32[rows] or NULL: receives r
+ * y == x exactly is allowed.  Errors as perf_layernorm. */
+perf_status perf_rmsnorm(const void *x, const void *gamma, void *y, float *rrms_out, int64_t rows,
+                         int64_t cols, int64_t ldx, int64_t ldy, float eps, perf_dtype x_dt,
+                         perf_dtype param_dt, perf_dtype y_dt, perf_stream stream);
+
+/* Mean along one axis of a rows x cols matrix ("reducemean" row of the operator table; the
+ * table does not say which axis, both are provided): axis 1: y[i] = mean_j x[i][j] (rows
+ * results); axis 0: y[j] = mean_i x[i][j] (cols results).  fp32 accumulation in a fixed order.
+ *   x  device, row stride ldx, f32 or bf16;  y  device, contiguous, f32 or bf16
+ * Errors: NULL, SHAPE (dimension < 1, ldx < cols, axis not 0 or 1), DTYPE, ALIGN, LAUNCH. */
+perf_status perf_reduce_mean(const void *x, void *y, int64_t rows, int64_t cols, int64_t ldx, int axis,
+                             perf_dtype x_dt, perf_dtype y_dt, perf_stream stream);
+
+/* Element-wise operators of the table ("add", "mul", "relu") on n contiguous elements:
+ * y = a + b, a * b, or max(a, 0) (b ignored, may be NULL).  One dtype for all operands;
+ * fp32 arithmetic, one rounding to dt.  y may equal a or b exactly.
+ * Errors: NULL, SHAPE (n < 0), DTYPE, ALIGN, UNSUPPORTED (op out of range; misaligned buffers
+ * of more than 2^26 elements), LAUNCH. */
+typedef enum { PERF_ADD = 0, PERF_MUL = 1, PERF_RELU = 2 } perf_eltwise_op;
+perf_status perf_eltwise(perf_eltwise_op op, const void *a, const void *b, void *y, int64_t n,
+                         perf_dtype dt, perf_stream stream);
+
 /* Plain device-to-device streaming copy of `bytes` bytes (dst and src must not overlap).
  * It is the measured HBM ceiling the benchmark prints beside each bandwidth figure and
  * the known-size kernel against which profiler byte counters are scaled; it is not one

@@ -31,6 +31,9 @@ SIGNATURES = {
     "perf_conv2d": (_int, [_ptr, _ptr, _ptr] + [_i64] * 11 + [_int, _int, _ptr]),
     "perf_gemm_softmax": (_int, [_ptr, _ptr, _ptr, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _f32,
                                  _int, _int, _ptr]),
+    "perf_rmsnorm": (_int, [_ptr, _ptr, _ptr, _ptr, _i64, _i64, _i64, _i64, _f32, _int, _int, _int, _ptr]),
+    "perf_reduce_mean": (_int, [_ptr, _ptr, _i64, _i64, _i64, _int, _int, _int, _ptr]),
+    "perf_eltwise": (_int, [_int, _ptr, _ptr, _ptr, _i64, _int, _ptr]),
     "perf_copy": (_int, [_ptr, _ptr, _i64, _ptr]),
     "perf_mfma_probe": (_int, [_ptr, _i64, _ptr]),
     "perf_status_string": (ctypes.c_char_p, [_int]),
@@ -105,6 +108,24 @@ def perf_conv2d(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, 
     return _check("perf_conv2d",
                   lib().perf_conv2d(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w,
                                     xw_dt, y_dt, stream), check)
+
+
+PERF_ADD, PERF_MUL, PERF_RELU = 0, 1, 2
+
+
+def perf_rmsnorm(x, gamma, y, rrms_out, rows, cols, ldx, ldy, eps, x_dt=PERF_BF16, param_dt=PERF_F32,
+                 y_dt=PERF_BF16, stream=None, check=True) -> int:
+    return _check("perf_rmsnorm",
+                  lib().perf_rmsnorm(x, gamma, y, rrms_out, rows, cols, ldx, ldy, eps, x_dt, param_dt, y_dt, stream),
+                  check)
+
+
+def perf_reduce_mean(x, y, rows, cols, ldx, axis, x_dt=PERF_F32, y_dt=PERF_F32, stream=None, check=True) -> int:
+    return _check("perf_reduce_mean", lib().perf_reduce_mean(x, y, rows, cols, ldx, axis, x_dt, y_dt, stream), check)
+
+
+def perf_eltwise(op, a, b, y, n, dt=PERF_F32, stream=None, check=True) -> int:
+    return _check("perf_eltwise", lib().perf_eltwise(op, a, b, y, n, dt, stream), check)
 
 
 def perf_copy(src, dst, nbytes, stream=None, check=True) -> int:

@@ -1,0 +1,429 @@
+// Streaming operators of the paper's operator table (Section 4.3) beyond softmax and
+// LayerNorm: RMS normalisation ("rmsnorm"), the mean along an axis ("reducemean") and the
+// element-wise "add" / "mul" / "relu".  All are bound by HBM; each reads its input once with
+// 16-byte accesses and writes once.  No atomics, no workspace.
+//
+//  * rmsnorm_rows_kernel: a wavefront owns a row (as in LayerNorm): one load of the row into
+//    registers, sum of squares by a DPP / permlane butterfly, scale, 16-byte stores; gamma is
+//    staged once per workgroup in LDS.  rmsnorm_block_kernel: general fallback.
+//  * rowmean_kernel: a wavefront per row, any length.
+//  * colmean_kernel: a workgroup owns 4 chunks of 16 bytes of every row (64 contiguous
+//    bytes per row); 64 row lanes stride over the rows and are combined through LDS.
+//  * eltwise_kernel: one pass, four 16-byte vectors per thread.
+#include "row_io.h"
+#include "host_utils.h"
+
+namespace perf {
+
+// ---- RMS norm ------------------------------------------------------------------------
+constexpr int kRmsThreads = 256;
+constexpr int kRmsWaves = kRmsThreads / 64;
+
+// NC: 16-byte chunks of the row held per lane (cols <= NC * 64 * E).
+template <typename XT, typename PT, typename YT, int NC>
+__global__ __launch_bounds__(kRmsThreads) void rmsnorm_rows_kernel(const XT *__restrict__ x, const PT *__restrict__ gamma,
+                                                                   YT *__restrict__ y, float *__restrict__ rrms_out,
+                                                                   int64_t rows, int cols, int64_t ldx, int64_t ldy,
+                                                                   float eps)
+{
+    constexpr int E = Elem<XT>::kPerChunk;
+    constexpr int NCH = NC * 64;
+    // gamma as fp32 in planes of 4 floats per chunk: plane q of chunk c holds elements c*E + 4q .. +3
+    extern __shared__ float4_t lds[];
+    for (int i = threadIdx.x; i < (E / 4) * NCH; i += kRmsThreads) {
+        const int q = i / NCH, c = i % NCH;
+        const int col = c * E + 4 * q;
+        float4_t g = {0.f, 0.f, 0.f, 0.f};
+        if (col < cols) {  // cols is a multiple of E
+#pragma unroll
+            for (int e = 0; e < 4; ++e) g[e] = Elem<PT>::load1(gamma + col + e);
+        }
+        lds[i] = g;
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * kRmsWaves + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * kRmsWaves;
+    const float inv_cols = 1.0f / (float)cols;
+
+    uint4_t raw[NC];
+    auto load_row = [&](int64_t r) {
+        const XT *xr = x + r * ldx;
+#pragma unroll
+        for (int j = 0; j < NC; ++j) {
+            const int c = (j * 64 + lane) * E;
+            raw[j] = c < cols ? __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xr + c)) : uint4_t{0u, 0u, 0u, 0u};
+        }
+    };
+    if (wave < rows) load_row(wave);
+    for (int64_t r = wave; r < rows; r += nwaves) {
+        float v[NC][E];
+        float ss = 0.f;
+#pragma unroll
+        for (int j = 0; j < NC; ++j) {
+            Elem<XT>::unpack(raw[j], v[j]);
+#pragma unroll
+            for (int e = 0; e < E; ++e) ss = __builtin_fmaf(v[j][e], v[j][e], ss);  // padding chunks hold zeros
+        }
+        if (r + nwaves < rows) load_row(r + nwaves);  // next row's loads fly during this row's arithmetic
+        ss = wave_allreduce(ss, OpSum{});
+        const float rr = 1.0f / __builtin_sqrtf(ss * inv_cols + eps);
+        if (lane == 0 && rrms_out) rrms_out[r] = rr;
+        YT *yr = y + r * ldy;
+#pragma unroll
+        for (int j = 0; j < NC; ++j) {
+            const int ch = j * 64 + lane;
+            if (ch * E < cols) {
+                float o[E];
+#pragma unroll
+                for (int q = 0; q < E / 4; ++q) {
+                    const float4_t g = lds[q * NCH + ch];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[4 * q + e] = v[j][4 * q + e] * rr * g[e];
+                }
+                store_chunk<YT, E>(yr + ch * E, o);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keeps the gamma reads chunk by chunk (register count)
+        }
+    }
+}
+
+__device__ __forceinline__ float block_sum_256(float v, float *red)
+{
+    v = wave_allreduce(v, OpSum{});
+    __syncthreads();  // red may still be read from the previous use
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// General fallback: one workgroup per row, scalar accesses, two passes.
+template <typename XT, typename PT, typename YT>
+__global__ __launch_bounds__(256) void rmsnorm_block_kernel(const XT *__restrict__ x, const PT *__restrict__ gamma,
+                                                            YT *__restrict__ y, float *__restrict__ rrms_out,
+                                                            int64_t rows, int64_t cols, int64_t ldx, int64_t ldy,
+                                                            float eps)
+{
+    __shared__ float red[4];
+    for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
+        const XT *xr = x + r * ldx;
+        float ss = 0.f;
+        for (int64_t c = threadIdx.x; c < cols; c += 256) {
+            const float v = Elem<XT>::load1(xr + c);
+            ss = __builtin_fmaf(v, v, ss);
+        }
+        const float rr = 1.0f / __builtin_sqrtf(block_sum_256(ss, red) / (float)cols + eps);
+        if (threadIdx.x == 0 && rrms_out) rrms_out[r] = rr;
+        for (int64_t c = threadIdx.x; c < cols; c += 256)
+            Elem<YT>::store1(y + r * ldy + c, Elem<XT>::load1(xr + c) * rr * Elem<PT>::load1(gamma + c));
+    }
+}
+
+struct RmsArgs {
+    const void *x, *gamma;
+    void *y;
+    float *rrms;
+    int64_t rows, cols, ldx, ldy;
+    float eps;
+    hipStream_t st;
+};
+
+template <typename XT, typename PT, typename YT, int NC>
+static void launch_rms_nc(const RmsArgs &a)
+{
+    constexpr int E = Elem<XT>::kPerChunk;
+    const size_t lds_bytes = (size_t)(E / 4) * NC * 64 * sizeof(float4_t);
+    int64_t blocks = (a.rows + kRmsWaves - 1) / kRmsWaves;
+    if (blocks > 512) blocks = 512;  // two workgroups per CU; waves then loop over rows
+    hipLaunchKernelGGL((rmsnorm_rows_kernel<XT, PT, YT, NC>), dim3((unsigned)blocks), dim3(kRmsThreads), lds_bytes, a.st,
+                       (const XT *)a.x, (const PT *)a.gamma, (YT *)a.y, a.rrms, a.rows, (int)a.cols, a.ldx, a.ldy, a.eps);
+}
+
+template <typename XT, typename PT, typename YT>
+static void launch_rms_typed(const RmsArgs &a, bool vec_ok)
+{
+    constexpr int E = Elem<XT>::kPerChunk;
+    const int64_t chunks = (a.cols + 64 * E - 1) / (64 * E);
+    if (vec_ok && chunks <= 16) {
+        if (chunks <= 2) launch_rms_nc<XT, PT, YT, 2>(a);
+        else if (chunks <= 8) launch_rms_nc<XT, PT, YT, 8>(a);
+        else launch_rms_nc<XT, PT, YT, 16>(a);
+    } else {
+        const int64_t blocks = a.rows < 65536 ? a.rows : 65536;
+        hipLaunchKernelGGL((rmsnorm_block_kernel<XT, PT, YT>), dim3((unsigned)blocks), dim3(256), 0, a.st,
+                           (const XT *)a.x, (const PT *)a.gamma, (YT *)a.y, a.rrms, a.rows, a.cols, a.ldx, a.ldy, a.eps);
+    }
+}
+
+template <typename XT, typename PT>
+static void launch_rms_y(const RmsArgs &a, bool vec_ok, int y_dt)
+{
+    if (y_dt == PERF_F32) launch_rms_typed<XT, PT, float>(a, vec_ok);
+    else launch_rms_typed<XT, PT, uint16_t>(a, vec_ok);
+}
+
+template <typename XT>
+static void launch_rms_p(const RmsArgs &a, bool vec_ok, int p_dt, int y_dt)
+{
+    if (p_dt == PERF_F32) launch_rms_y<XT, float>(a, vec_ok, y_dt);
+    else launch_rms_y<XT, uint16_t>(a, vec_ok, y_dt);
+}
+
+// ---- means ---------------------------------------------------------------------------
+// Mean of every row: a wavefront per row; 16-byte loads when VEC (cols, ldx and x suitably
+// aligned), else element loads.
+template <typename XT, typename YT, bool VEC>
+__global__ __launch_bounds__(256) void rowmean_kernel(const XT *__restrict__ x, YT *__restrict__ y, int64_t rows,
+                                                      int64_t cols, int64_t ldx)
+{
+    constexpr int E = Elem<XT>::kPerChunk;
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t r = wave; r < rows; r += nwaves) {
+        const XT *xr = x + r * ldx;
+        float s0 = 0.f, s1 = 0.f;
+        if (VEC) {
+            const int64_t nch = cols / E;
+            int64_t c = lane;
+            for (; c + 64 < nch; c += 128) {  // two independent loads in flight per lane
+                const uint4_t r0 = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xr) + c);
+                const uint4_t r1 = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xr) + c + 64);
+                float v0[E], v1[E];
+                Elem<XT>::unpack(r0, v0);
+                Elem<XT>::unpack(r1, v1);
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    s0 += v0[e];
+                    s1 += v1[e];
+                }
+            }
+            if (c < nch) {
+                float v0[E];
+                Elem<XT>::unpack(__builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xr) + c), v0);
+#pragma unroll
+                for (int e = 0; e < E; ++e) s0 += v0[e];
+            }
+        } else {
+            for (int64_t c = lane; c < cols; c += 64) s0 += Elem<XT>::load1(xr + c);
+        }
+        const float s = wave_allreduce(s0 + s1, OpSum{});
+        if (lane == 0) Elem<YT>::store1(y + r, s / (float)cols);
+    }
+}
+
+// Mean of every column, 16-byte path: thread = (row lane tid/4, chunk tid%4); a workgroup
+// owns the 4*E columns starting at blockIdx.x * 4 * E.
+template <typename XT, typename YT>
+__global__ __launch_bounds__(256) void colmean_kernel(const XT *__restrict__ x, YT *__restrict__ y, int64_t rows,
+                                                      int64_t cols, int64_t ldx)
+{
+    constexpr int E = Elem<XT>::kPerChunk;
+    constexpr int kUnroll = 16;  // 16 x 16 bytes in flight per thread: 64 KiB per workgroup
+    __shared__ float part[64][4 * E + 1];
+    const int cl = threadIdx.x & 3, rl = threadIdx.x >> 2;
+    const int64_t col0 = ((int64_t)blockIdx.x * 4 + cl) * E;
+    float acc[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[e] = 0.f;
+    if (col0 < cols) {  // cols is a multiple of E
+        const XT *xc = x + col0;
+        int64_t r = rl;
+        for (; r + 64 * (kUnroll - 1) < rows; r += 64 * kUnroll) {
+            uint4_t raw[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                raw[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xc + (r + 64 * u) * ldx));
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                float v[E];
+                Elem<XT>::unpack(raw[u], v);
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc[e] += v[e];
+            }
+        }
+        for (; r < rows; r += 64) {
+            float v[E];
+            Elem<XT>::unpack(__builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xc + r * ldx)), v);
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[e] += v[e];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < E; ++e) part[rl][cl * E + e] = acc[e];
+    __syncthreads();
+    if (threadIdx.x < 4 * E) {
+        const int64_t col = (int64_t)blockIdx.x * 4 * E + threadIdx.x;
+        if (col < cols) {
+            float s = 0.f;
+            for (int i = 0; i < 64; ++i) s += part[i][threadIdx.x];
+            Elem<YT>::store1(y + col, s / (float)rows);
+        }
+    }
+}
+
+// Mean of every column, element path: a thread per column.
+template <typename XT, typename YT>
+__global__ __launch_bounds__(256) void colmean_scalar_kernel(const XT *__restrict__ x, YT *__restrict__ y, int64_t rows,
+                                                             int64_t cols, int64_t ldx)
+{
+    const int64_t col = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (col >= cols) return;
+    float s = 0.f;
+    for (int64_t r = 0; r < rows; ++r) s += Elem<XT>::load1(x + r * ldx + col);
+    Elem<YT>::store1(y + col, s / (float)rows);
+}
+
+template <typename XT, typename YT>
+static void launch_mean(const void *x, void *y, int64_t rows, int64_t cols, int64_t ldx, int axis, hipStream_t st)
+{
+    constexpr int E = Elem<XT>::kPerChunk;
+    const bool vec = cols % E == 0 && ldx % E == 0 && aligned(x, 16);
+    if (axis == 1) {
+        int64_t blocks = (rows + 3) / 4;
+        if (blocks > 256 * 64) blocks = 256 * 64;
+        auto kern = vec ? rowmean_kernel<XT, YT, true> : rowmean_kernel<XT, YT, false>;
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, st, (const XT *)x, (YT *)y, rows, cols, ldx);
+    } else if (vec) {
+        hipLaunchKernelGGL((colmean_kernel<XT, YT>), dim3((unsigned)((cols + 4 * E - 1) / (4 * E))), dim3(256), 0, st,
+                           (const XT *)x, (YT *)y, rows, cols, ldx);
+    } else {
+        hipLaunchKernelGGL((colmean_scalar_kernel<XT, YT>), dim3((unsigned)((cols + 255) / 256)), dim3(256), 0, st,
+                           (const XT *)x, (YT *)y, rows, cols, ldx);
+    }
+}
+
+// ---- element-wise --------------------------------------------------------------------
+template <int OP> __device__ __forceinline__ float apply_op(float a, float b)
+{
+    if (OP == PERF_ADD) return a + b;
+    if (OP == PERF_MUL) return a * b;
+    return __builtin_fmaxf(a, 0.f) + 0.f;  // relu; "+ 0" turns a -0 into +0
+}
+
+constexpr int kEltUnroll = 4;
+
+template <int OP, typename T>
+__global__ __launch_bounds__(256) void eltwise_kernel(const T *__restrict__ a, const T *__restrict__ b, T *__restrict__ y,
+                                                      int64_t nvec)
+{
+    constexpr int E = Elem<T>::kPerChunk;
+    const int64_t base = (int64_t)blockIdx.x * 256 * kEltUnroll + threadIdx.x;
+    uint4_t ra[kEltUnroll], rb[kEltUnroll];
+#pragma unroll
+    for (int u = 0; u < kEltUnroll; ++u) {
+        const int64_t i = base + u * 256;
+        if (i < nvec) {
+            ra[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(a) + i);
+            if (OP != PERF_RELU) rb[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(b) + i);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kEltUnroll; ++u) {
+        const int64_t i = base + u * 256;
+        if (i < nvec) {
+            float va[E], vb[E], o[E];
+            Elem<T>::unpack(ra[u], va);
+            if (OP != PERF_RELU) Elem<T>::unpack(rb[u], vb);
+#pragma unroll
+            for (int e = 0; e < E; ++e) o[e] = apply_op<OP>(va[e], OP != PERF_RELU ? vb[e] : 0.f);
+            store_chunk<T, E>(y + i * E, o);
+        }
+    }
+}
+
+template <int OP, typename T>
+__global__ __launch_bounds__(64) void eltwise_tail_kernel(const T *__restrict__ a, const T *__restrict__ b, T *__restrict__ y,
+                                                          int64_t n)
+{
+    for (int64_t i = threadIdx.x; i < n; i += 64)
+        Elem<T>::store1(y + i, apply_op<OP>(Elem<T>::load1(a + i), OP != PERF_RELU ? Elem<T>::load1(b + i) : 0.f));
+}
+
+template <int OP, typename T>
+static perf_status launch_eltwise(const void *a, const void *b, void *y, int64_t n, hipStream_t st)
+{
+    constexpr int E = Elem<T>::kPerChunk;
+    const bool vec = aligned(a, 16) && aligned(y, 16) && (OP == PERF_RELU || aligned(b, 16));
+    const int64_t nvec = vec ? n / E : 0;
+    if (nvec > 0) {
+        const int64_t blocks = (nvec + 256 * kEltUnroll - 1) / (256 * kEltUnroll);
+        if (blocks > kMaxGridX) return PERF_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL((eltwise_kernel<OP, T>), dim3((unsigned)blocks), dim3(256), 0, st, (const T *)a, (const T *)b,
+                           (T *)y, nvec);
+    }
+    const int64_t done = nvec * E;
+    if (done < n) {
+        if (n - done > (int64_t(1) << 20) * 64) return PERF_ERR_UNSUPPORTED;  // unaligned bulk: not a streaming case
+        hipLaunchKernelGGL((eltwise_tail_kernel<OP, T>), dim3(1), dim3(64), 0, st, (const T *)a + done,
+                           OP != PERF_RELU ? (const T *)b + done : (const T *)a, (T *)y + done, n - done);
+    }
+    return launch_status();
+}
+
+template <typename T>
+static perf_status dispatch_eltwise(int op, const void *a, const void *b, void *y, int64_t n, hipStream_t st)
+{
+    if (op == PERF_ADD) return launch_eltwise<PERF_ADD, T>(a, b, y, n, st);
+    if (op == PERF_MUL) return launch_eltwise<PERF_MUL, T>(a, b, y, n, st);
+    return launch_eltwise<PERF_RELU, T>(a, b, y, n, st);
+}
+
+}  // namespace perf
+
+extern "C" perf_status perf_rmsnorm(const void *x, const void *gamma, void *y, float *rrms_out, int64_t rows,
+                                    int64_t cols, int64_t ldx, int64_t ldy, float eps, perf_dtype x_dt,
+                                    perf_dtype param_dt, perf_dtype y_dt, perf_stream stream)
+{
+    using namespace perf;
+    if (!x || !gamma || !y) return PERF_ERR_NULL;
+    if (!dtype_ok(x_dt) || !dtype_ok(param_dt) || !dtype_ok(y_dt)) return PERF_ERR_DTYPE;
+    if (rows < 1 || cols < 1 || ldx < cols || ldy < cols || !(eps >= 0.f) || !std::isfinite(eps)) return PERF_ERR_SHAPE;
+    if (rows > (INT64_MAX / 4) / ldx || rows > (INT64_MAX / 4) / ldy) return PERF_ERR_SHAPE;
+    if (!aligned(x, dtype_size(x_dt)) || !aligned(y, dtype_size(y_dt)) || !aligned(gamma, dtype_size(param_dt)) ||
+        (rrms_out && !aligned(rrms_out, 4)))
+        return PERF_ERR_ALIGN;
+    const int64_t ex = 16 / dtype_size(x_dt);
+    const bool vec_ok = cols % ex == 0 && ldx % ex == 0 && aligned(x, 16) && aligned(y, 16) &&
+                        (ldy * dtype_size(y_dt)) % 16 == 0;
+    RmsArgs a{x, gamma, y, rrms_out, rows, cols, ldx, ldy, eps, static_cast<hipStream_t>(stream)};
+    if (x_dt == PERF_F32) launch_rms_p<float>(a, vec_ok, param_dt, y_dt);
+    else launch_rms_p<uint16_t>(a, vec_ok, param_dt, y_dt);
+    return launch_status();
+}
+
+extern "C" perf_status perf_reduce_mean(const void *x, void *y, int64_t rows, int64_t cols, int64_t ldx, int axis,
+                                        perf_dtype x_dt, perf_dtype y_dt, perf_stream stream)
+{
+    using namespace perf;
+    if (!x || !y) return PERF_ERR_NULL;
+    if (!dtype_ok(x_dt) || !dtype_ok(y_dt)) return PERF_ERR_DTYPE;
+    if (rows < 1 || cols < 1 || ldx < cols || (axis != 0 && axis != 1)) return PERF_ERR_SHAPE;
+    if (rows > (INT64_MAX / 4) / ldx || cols > (int64_t)kMaxGridX * 16) return PERF_ERR_SHAPE;
+    if (!aligned(x, dtype_size(x_dt)) || !aligned(y, dtype_size(y_dt))) return PERF_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (x_dt == PERF_F32) {
+        if (y_dt == PERF_F32) launch_mean<float, float>(x, y, rows, cols, ldx, axis, st);
+        else launch_mean<float, uint16_t>(x, y, rows, cols, ldx, axis, st);
+    } else {
+        if (y_dt == PERF_F32) launch_mean<uint16_t, float>(x, y, rows, cols, ldx, axis, st);
+        else launch_mean<uint16_t, uint16_t>(x, y, rows, cols, ldx, axis, st);
+    }
+    return launch_status();
+}
+
+extern "C" perf_status perf_eltwise(perf_eltwise_op op, const void *a, const void *b, void *y, int64_t n, perf_dtype dt,
+                                    perf_stream stream)
+{
+    using namespace perf;
+    if (op != PERF_ADD && op != PERF_MUL && op != PERF_RELU) return PERF_ERR_UNSUPPORTED;
+    if (!a || !y || (op != PERF_RELU && !b)) return PERF_ERR_NULL;
+    if (!dtype_ok(dt)) return PERF_ERR_DTYPE;
+    if (n < 0) return PERF_ERR_SHAPE;
+    if (!aligned(a, dtype_size(dt)) || !aligned(y, dtype_size(dt)) || (op != PERF_RELU && !aligned(b, dtype_size(dt))))
+        return PERF_ERR_ALIGN;
+    if (n == 0) return PERF_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return dt == PERF_F32 ? dispatch_eltwise<float>(op, a, b, y, n, st) : dispatch_eltwise<uint16_t>(op, a, b, y, n, st);
+}

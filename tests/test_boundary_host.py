@@ -129,3 +129,32 @@ def test_gemm_softmax_argument_errors():
     assert f(ab=7) == perf.PERF_ERR_DTYPE
     assert f(A=FAKE + 1) == perf.PERF_ERR_ALIGN
     assert f(K=33, lda=33, ldb=33, pd=perf.PERF_BF16) == perf.PERF_ERR_UNSUPPORTED   # two-operator path needs f32 P
+
+
+def test_streaming_ops_argument_errors():
+    r = lambda **k: perf.perf_rmsnorm(**{**dict(x=FAKE, gamma=FAKE + 4096, y=FAKE + 8192, rrms_out=None, rows=4, cols=8,
+                                                 ldx=8, ldy=8, eps=1e-5, check=False), **k})
+    assert r(x=None) == perf.PERF_ERR_NULL
+    assert r(gamma=None) == perf.PERF_ERR_NULL
+    assert r(cols=0) == perf.PERF_ERR_SHAPE
+    assert r(ldy=7) == perf.PERF_ERR_SHAPE
+    assert r(eps=-1.0) == perf.PERF_ERR_SHAPE
+    assert r(x_dt=5) == perf.PERF_ERR_DTYPE
+    assert r(x=FAKE + 1) == perf.PERF_ERR_ALIGN
+    assert r(rrms_out=FAKE + 2) == perf.PERF_ERR_ALIGN
+    m = lambda **k: perf.perf_reduce_mean(**{**dict(x=FAKE, y=FAKE + 4096, rows=4, cols=8, ldx=8, axis=1, check=False), **k})
+    assert m(y=None) == perf.PERF_ERR_NULL
+    assert m(rows=0) == perf.PERF_ERR_SHAPE
+    assert m(ldx=7) == perf.PERF_ERR_SHAPE
+    assert m(axis=2) == perf.PERF_ERR_SHAPE
+    assert m(y_dt=3) == perf.PERF_ERR_DTYPE
+    assert m(x=FAKE + 2) == perf.PERF_ERR_ALIGN
+    e = lambda **k: perf.perf_eltwise(**{**dict(op=perf.PERF_ADD, a=FAKE, b=FAKE + 4096, y=FAKE + 8192, n=16, check=False), **k})
+    assert e(a=None) == perf.PERF_ERR_NULL
+    assert e(b=None) == perf.PERF_ERR_NULL
+    assert e(op=perf.PERF_RELU, b=None, n=0) == perf.PERF_OK        # relu needs no b; nothing to do, no launch
+    assert e(op=7) == perf.PERF_ERR_UNSUPPORTED
+    assert e(n=-1) == perf.PERF_ERR_SHAPE
+    assert e(dt=4) == perf.PERF_ERR_DTYPE
+    assert e(y=FAKE + 2) == perf.PERF_ERR_ALIGN
+    assert e(n=0) == perf.PERF_OK
