@@ -154,6 +154,28 @@ typedef enum { PERF_ADD = 0, PERF_MUL = 1, PERF_RELU = 2 } perf_eltwise_op;
 perf_status perf_eltwise(perf_eltwise_op op, const void *a, const void *b, void *y, int64_t n,
                          perf_dtype dt, perf_stream stream);
 
+/* The same operators with the kernel variant chosen by the caller instead of by the
+ * library's shape rules: the knob a timing-driven search turns (the paper's search scores a
+ * candidate by the measured runtime of the code it emits, Section 3.2, after validating its
+ * output against the untransformed program, Section 3.1; tune.py beside the Python binding
+ * does that over these variants).  Arguments, results and errors are those of perf_gemm /
+ * perf_conv2d; a variant that cannot run the problem returns UNSUPPORTED.
+ *   perf_gemm_variant:  tile = 64, 128 or 256 (workgroup tile edge), kstep = 32 or 64
+ *     (main loop; K must be a multiple of it); only the bf16 row-major x column-major case
+ *     that the MFMA kernels cover has variants.
+ *   perf_conv2d_variant: variant 1 = weights in registers (3x3, 64 -> 128 channels, bf16),
+ *     2 = implicit GEMM on the shared main loop (bf16, C a multiple of 32), 3 = channel-blocked
+ *     direct kernel, 4 = one thread per output. */
+perf_status perf_gemm_variant(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K,
+                              perf_layout la, int64_t lda, perf_layout lb, int64_t ldb, int64_t ldc,
+                              int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC,
+                              float alpha, perf_dtype ab_dt, perf_dtype c_dt, int tile, int kstep,
+                              perf_stream stream);
+perf_status perf_conv2d_variant(const void *x, const void *w, void *y, int64_t N, int64_t H, int64_t W,
+                                int64_t C, int64_t K, int64_t R, int64_t S, int64_t stride_h,
+                                int64_t stride_w, int64_t pad_h, int64_t pad_w, perf_dtype xw_dt,
+                                perf_dtype y_dt, int variant, perf_stream stream);
+
 /* Plain device-to-device streaming copy of `bytes` bytes (dst and src must not overlap).
  * It is the measured HBM ceiling the benchmark prints beside each bandwidth figure and
  * the known-size kernel against which profiler byte counters are scaled; it is not one

@@ -34,6 +34,9 @@ SIGNATURES = {
     "perf_rmsnorm": (_int, [_ptr, _ptr, _ptr, _ptr, _i64, _i64, _i64, _i64, _f32, _int, _int, _int, _ptr]),
     "perf_reduce_mean": (_int, [_ptr, _ptr, _i64, _i64, _i64, _int, _int, _int, _ptr]),
     "perf_eltwise": (_int, [_int, _ptr, _ptr, _ptr, _i64, _int, _ptr]),
+    "perf_gemm_variant": (_int, [_ptr, _ptr, _ptr, _i64, _i64, _i64, _int, _i64, _int, _i64, _i64, _i64, _i64, _i64, _i64,
+                                 _f32, _int, _int, _int, _int, _ptr]),
+    "perf_conv2d_variant": (_int, [_ptr, _ptr, _ptr] + [_i64] * 11 + [_int, _int, _int, _ptr]),
     "perf_copy": (_int, [_ptr, _ptr, _i64, _ptr]),
     "perf_mfma_probe": (_int, [_ptr, _i64, _ptr]),
     "perf_status_string": (ctypes.c_char_p, [_int]),
@@ -108,6 +111,23 @@ def perf_conv2d(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, 
     return _check("perf_conv2d",
                   lib().perf_conv2d(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w,
                                     xw_dt, y_dt, stream), check)
+
+
+def perf_gemm_variant(A, B, C, M, N, K, la, lda, lb, ldb, ldc, batch, strideA, strideB, strideC, alpha, ab_dt, c_dt,
+                      tile, kstep, stream=None, check=True) -> int:
+    return _check("perf_gemm_variant",
+                  lib().perf_gemm_variant(A, B, C, M, N, K, la, lda, lb, ldb, ldc, batch, strideA, strideB, strideC,
+                                          alpha, ab_dt, c_dt, tile, kstep, stream), check)
+
+
+CONV_WREG, CONV_MFMA, CONV_SMALLC, CONV_DIRECT = 1, 2, 3, 4
+
+
+def perf_conv2d_variant(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, xw_dt, y_dt, variant,
+                        stream=None, check=True) -> int:
+    return _check("perf_conv2d_variant",
+                  lib().perf_conv2d_variant(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, xw_dt, y_dt,
+                                            variant, stream), check)
 
 
 PERF_ADD, PERF_MUL, PERF_RELU = 0, 1, 2

@@ -550,11 +550,15 @@ static perf_status launch_conv_direct(const void *x, const void *w, void *y, con
 
 }  // namespace perf
 
-extern "C" perf_status perf_conv2d(const void *x, const void *w, void *y, int64_t N, int64_t H, int64_t W, int64_t C,
-                                   int64_t K, int64_t R, int64_t S, int64_t stride_h, int64_t stride_w, int64_t pad_h,
-                                   int64_t pad_w, perf_dtype xw_dt, perf_dtype y_dt, perf_stream stream)
+namespace perf {
+
+enum ConvVariant { kConvAuto = 0, kConvWreg = 1, kConvMfma = 2, kConvSmallC = 3, kConvDirect = 4 };
+
+// variant: kConvAuto = chosen here from the shape; otherwise the caller's choice (perf_conv2d_variant).
+static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N, int64_t H, int64_t W, int64_t C,
+                               int64_t K, int64_t R, int64_t S, int64_t stride_h, int64_t stride_w, int64_t pad_h,
+                               int64_t pad_w, perf_dtype xw_dt, perf_dtype y_dt, perf_stream stream, int variant)
 {
-    using namespace perf;
     if (!x || !w || !y) return PERF_ERR_NULL;
     if (!dtype_ok(xw_dt) || !dtype_ok(y_dt)) return PERF_ERR_DTYPE;
     if (N < 1 || H < 1 || W < 1 || C < 1 || K < 1 || R < 1 || S < 1) return PERF_ERR_SHAPE;
@@ -578,14 +582,26 @@ extern "C" perf_status perf_conv2d(const void *x, const void *w, void *y, int64_
                          N * H * W * C < (int64_t(1) << 30) && K * R * S * C < (int64_t(1) << 30) &&
                          ((N * P * Q + 127) / 128) * ((K + 127) / 128) <= kMaxGridX;
     // filter shapes with a weights-in-registers instance
-    if (mfma_ok && R == 3 && S == 3 && C == 64 && K == 128 && Q >= 32 && N * P * Q * K < (int64_t(1) << 29))
+    const bool wreg_ok = mfma_ok && R == 3 && S == 3 && C == 64 && K == 128 && Q >= 32 && N * P * Q * K < (int64_t(1) << 29);
+    // few input channels: channel-blocked direct kernel, if a 16-channel block of weights fits its LDS budget
+    const bool smallc_ok = R * S * C * 16 * 4 <= kSmallcLdsBytes && (K + 15) / 16 <= kMaxGridYZ;
+    if (variant == kConvAuto)
+        // (the channel-blocked kernel has one thread per pixel: below ~64 workgroups of pixels the
+        // thread-per-output kernel has more parallelism and measured faster)
+        variant = wreg_ok ? kConvWreg
+                  : mfma_ok ? kConvMfma
+                  : (C < 32 && smallc_ok && N * P * Q >= 16384) ? kConvSmallC
+                                                                : kConvDirect;
+    else if ((variant == kConvWreg && !wreg_ok) || (variant == kConvMfma && !mfma_ok) ||
+             (variant == kConvSmallC && !smallc_ok) || variant < kConvWreg || variant > kConvDirect)
+        return PERF_ERR_UNSUPPORTED;
+    if (variant == kConvWreg)
         return y_dt == PERF_F32 ? launch_conv_wreg<3, 3, 64, float>(x, w, y, g, st)
                                 : launch_conv_wreg<3, 3, 64, uint16_t>(x, w, y, g, st);
-    if (mfma_ok)
+    if (variant == kConvMfma)
         return y_dt == PERF_F32 ? launch_conv_mfma<2, 2, 2, 2, float>(x, w, y, g, st)
                                 : launch_conv_mfma<2, 2, 2, 2, uint16_t>(x, w, y, g, st);
-    // few input channels: channel-blocked direct kernel, if a 16-channel block of weights fits its LDS budget
-    if (C < 32 && R * S * C * 16 * 4 <= kSmallcLdsBytes && (K + 15) / 16 <= kMaxGridYZ) {
+    if (variant == kConvSmallC) {
         if (xw_dt == PERF_BF16)
             return y_dt == PERF_F32 ? dispatch_conv_smallc<uint16_t, float>(x, w, y, g, st)
                                     : dispatch_conv_smallc<uint16_t, uint16_t>(x, w, y, g, st);
@@ -597,4 +613,23 @@ extern "C" perf_status perf_conv2d(const void *x, const void *w, void *y, int64_
                                 : launch_conv_direct<uint16_t, uint16_t>(x, w, y, g, st);
     return y_dt == PERF_F32 ? launch_conv_direct<float, float>(x, w, y, g, st)
                             : launch_conv_direct<float, uint16_t>(x, w, y, g, st);
+}
+
+}  // namespace perf
+
+extern "C" perf_status perf_conv2d(const void *x, const void *w, void *y, int64_t N, int64_t H, int64_t W, int64_t C,
+                                   int64_t K, int64_t R, int64_t S, int64_t stride_h, int64_t stride_w, int64_t pad_h,
+                                   int64_t pad_w, perf_dtype xw_dt, perf_dtype y_dt, perf_stream stream)
+{
+    return perf::conv2d_impl(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, xw_dt, y_dt, stream,
+                             perf::kConvAuto);
+}
+
+extern "C" perf_status perf_conv2d_variant(const void *x, const void *w, void *y, int64_t N, int64_t H, int64_t W,
+                                           int64_t C, int64_t K, int64_t R, int64_t S, int64_t stride_h,
+                                           int64_t stride_w, int64_t pad_h, int64_t pad_w, perf_dtype xw_dt,
+                                           perf_dtype y_dt, int variant, perf_stream stream)
+{
+    if (variant == perf::kConvAuto) return PERF_ERR_UNSUPPORTED;
+    return perf::conv2d_impl(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, xw_dt, y_dt, stream, variant);
 }

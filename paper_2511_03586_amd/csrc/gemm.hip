@@ -181,12 +181,22 @@ static perf_status launch_general(const GemmArgs &g)
 
 }  // namespace perf
 
-extern "C" perf_status perf_gemm(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K,
-                                 perf_layout la, int64_t lda, perf_layout lb, int64_t ldb, int64_t ldc, int64_t batch,
-                                 int64_t strideA, int64_t strideB, int64_t strideC, float alpha, perf_dtype ab_dt,
-                                 perf_dtype c_dt, perf_stream stream)
+namespace perf {
+
+template <int TM, int TN, int WM, int WN>
+static perf_status launch_mfma_rt(const GemmArgs &g, bool k64, bool c_f32)
 {
-    using namespace perf;
+    if (k64) return c_f32 ? launch_mfma<TM, TN, WM, WN, true, float>(g) : launch_mfma<TM, TN, WM, WN, true, uint16_t>(g);
+    return c_f32 ? launch_mfma<TM, TN, WM, WN, false, float>(g) : launch_mfma<TM, TN, WM, WN, false, uint16_t>(g);
+}
+
+// tile / kstep: 0 = chosen here from the shape; otherwise the caller's choice (perf_gemm_variant).
+static perf_status gemm_impl(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K, perf_layout la,
+                             int64_t lda, perf_layout lb, int64_t ldb, int64_t ldc, int64_t batch, int64_t strideA,
+                             int64_t strideB, int64_t strideC, float alpha, perf_dtype ab_dt, perf_dtype c_dt,
+                             perf_stream stream, int tile, int kstep)
+{
+    // (argument checks first: they run for every variant)
     if (!A || !B || !C) return PERF_ERR_NULL;
     if (!dtype_ok(ab_dt) || !dtype_ok(c_dt)) return PERF_ERR_DTYPE;
     if (!layout_ok(la) || !layout_ok(lb)) return PERF_ERR_LAYOUT;
@@ -209,27 +219,49 @@ extern "C" perf_status perf_gemm(const void *A, const void *B, void *C, int64_t 
                          lda % 8 == 0 && ldb % 8 == 0 && strideA % 8 == 0 && strideB % 8 == 0 && aligned(A, 16) &&
                          aligned(B, 16) && lda <= (1 << 21) && ldb <= (1 << 21) && M <= (1 << 30) && N <= (1 << 30) && K <= (1 << 30) &&
                          ((M + 63) / 64) * ((N + 63) / 64) <= kMaxGridX;
+    if (tile != 0 || kstep != 0) {  // the caller's variant: only the MFMA kernels have variants
+        if (!mfma_ok || (tile != 64 && tile != 128 && tile != 256) || (kstep != 32 && kstep != 64) || K % kstep != 0)
+            return PERF_ERR_UNSUPPORTED;
+    }
     if (mfma_ok) {
-        // the 256x256 tile needs enough tiles to occupy the 256 CUs; otherwise 128x128 or 64x64
-        const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * batch;
-        // the K-step-64 loop pays off in the main loop; short reductions are bound by the C
-        // store, which the other loop's epilogue (two full 128-byte row segments per store
-        // instruction, no lane exchange) does faster (measured on 512 x (512x512x64))
-        const bool k64 = K % 64 == 0 && K >= 512;
-        if (big_tiles >= 256) {
-            if (k64) return c_dt == PERF_F32 ? launch_mfma<4, 4, 2, 2, true, float>(g) : launch_mfma<4, 4, 2, 2, true, uint16_t>(g);
-            return c_dt == PERF_F32 ? launch_mfma<4, 4, 2, 2, false, float>(g) : launch_mfma<4, 4, 2, 2, false, uint16_t>(g);
+        if (tile == 0) {
+            // the 256x256 tile needs enough tiles to occupy the 256 CUs; otherwise 128x128, or 64x64
+            // when 128x128 tiles would leave most of the CUs idle
+            const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * batch;
+            const int64_t mid_tiles = ((M + 127) / 128) * ((N + 127) / 128) * batch;
+            tile = big_tiles >= 256 ? 256 : mid_tiles >= 192 ? 128 : 64;
+            // the K-step-64 loop pays off in the main loop; short reductions are bound by the C
+            // store, which the other loop's epilogue (two full 128-byte row segments per store
+            // instruction, no lane exchange) does faster (measured on 512 x (512x512x64))
+            kstep = (K % 64 == 0 && K >= 512) ? 64 : 32;
         }
-        // small problems: 64x64 tiles when 128x128 tiles would leave most of the 256 CUs idle
-        const int64_t mid_tiles = ((M + 127) / 128) * ((N + 127) / 128) * batch;
-        if (mid_tiles >= 192) {
-            if (k64) return c_dt == PERF_F32 ? launch_mfma<2, 2, 2, 2, true, float>(g) : launch_mfma<2, 2, 2, 2, true, uint16_t>(g);
-            return c_dt == PERF_F32 ? launch_mfma<2, 2, 2, 2, false, float>(g) : launch_mfma<2, 2, 2, 2, false, uint16_t>(g);
-        }
-        if (k64) return c_dt == PERF_F32 ? launch_mfma<1, 1, 2, 2, true, float>(g) : launch_mfma<1, 1, 2, 2, true, uint16_t>(g);
-        return c_dt == PERF_F32 ? launch_mfma<1, 1, 2, 2, false, float>(g) : launch_mfma<1, 1, 2, 2, false, uint16_t>(g);
+        const bool k64 = kstep == 64, c_f32 = c_dt == PERF_F32;
+        if (tile == 256) return launch_mfma_rt<4, 4, 2, 2>(g, k64, c_f32);
+        if (tile == 128) return launch_mfma_rt<2, 2, 2, 2>(g, k64, c_f32);
+        return launch_mfma_rt<1, 1, 2, 2>(g, k64, c_f32);
     }
     if (ab_dt == PERF_BF16)
         return c_dt == PERF_F32 ? launch_general<uint16_t, float>(g) : launch_general<uint16_t, uint16_t>(g);
     return launch_general<float, float>(g);
+}
+
+}  // namespace perf
+
+extern "C" perf_status perf_gemm(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K,
+                                 perf_layout la, int64_t lda, perf_layout lb, int64_t ldb, int64_t ldc, int64_t batch,
+                                 int64_t strideA, int64_t strideB, int64_t strideC, float alpha, perf_dtype ab_dt,
+                                 perf_dtype c_dt, perf_stream stream)
+{
+    return perf::gemm_impl(A, B, C, M, N, K, la, lda, lb, ldb, ldc, batch, strideA, strideB, strideC, alpha, ab_dt, c_dt,
+                           stream, 0, 0);
+}
+
+extern "C" perf_status perf_gemm_variant(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K,
+                                         perf_layout la, int64_t lda, perf_layout lb, int64_t ldb, int64_t ldc,
+                                         int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC, float alpha,
+                                         perf_dtype ab_dt, perf_dtype c_dt, int tile, int kstep, perf_stream stream)
+{
+    if (tile == 0 || kstep == 0) return PERF_ERR_UNSUPPORTED;
+    return perf::gemm_impl(A, B, C, M, N, K, la, lda, lb, ldb, ldc, batch, strideA, strideB, strideC, alpha, ab_dt, c_dt,
+                           stream, tile, kstep);
 }

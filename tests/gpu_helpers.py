@@ -111,14 +111,18 @@ def run_gemm_softmax(a, b, M, N, K, alpha=1.0, batch=1, ab_bf16=True, p_bf16=Fal
     return p[:, :, :N].copy()
 
 
-def run_conv2d(x, w, stride=(1, 1), pad=(0, 0), xw_bf16=True, y_bf16=True):
+def run_conv2d(x, w, stride=(1, 1), pad=(0, 0), xw_bf16=True, y_bf16=True, variant=0):
     N, H, W, C = x.shape
     K, R, S, _ = w.shape
     P = (H + 2 * pad[0] - R) // stride[0] + 1
     Q = (W + 2 * pad[1] - S) // stride[1] + 1
     xd, wd = dev(x), dev(w)
     yd = torch.zeros(N * P * Q * K, dtype=torch.int16 if y_bf16 else torch.float32, device="cuda")
-    perf.perf_conv2d(xd.data_ptr(), wd.data_ptr(), yd.data_ptr(), N, H, W, C, K, R, S, stride[0], stride[1],
-                     pad[0], pad[1], dt(xw_bf16), dt(y_bf16), stream())
+    if variant:
+        perf.perf_conv2d_variant(xd.data_ptr(), wd.data_ptr(), yd.data_ptr(), N, H, W, C, K, R, S, stride[0], stride[1],
+                                 pad[0], pad[1], dt(xw_bf16), dt(y_bf16), variant, stream())
+    else:
+        perf.perf_conv2d(xd.data_ptr(), wd.data_ptr(), yd.data_ptr(), N, H, W, C, K, R, S, stride[0], stride[1],
+                         pad[0], pad[1], dt(xw_bf16), dt(y_bf16), stream())
     torch.cuda.synchronize()
     return host(yd, y_bf16).reshape(N, P, Q, K)

@@ -158,3 +158,27 @@ def test_streaming_ops_argument_errors():
     assert e(dt=4) == perf.PERF_ERR_DTYPE
     assert e(y=FAKE + 2) == perf.PERF_ERR_ALIGN
     assert e(n=0) == perf.PERF_OK
+
+
+def test_variant_entry_points_refuse_without_touching_the_device():
+    g = perf.perf_gemm_variant(FAKE, FAKE + 4096, FAKE + 8192, 64, 64, 64, perf.PERF_ROW_MAJOR, 64, perf.PERF_COL_MAJOR,
+                               64, 64, 1, 0, 0, 0, 1.0, perf.PERF_BF16, perf.PERF_F32, 0, 32, check=False)
+    assert g == perf.PERF_ERR_UNSUPPORTED                       # tile 0 is "library's choice": not a variant
+    g = perf.perf_gemm_variant(FAKE, FAKE + 4096, FAKE + 8192, 64, 64, 64, perf.PERF_ROW_MAJOR, 64, perf.PERF_COL_MAJOR,
+                               64, 64, 1, 0, 0, 0, 1.0, perf.PERF_BF16, perf.PERF_F32, 96, 32, check=False)
+    assert g == perf.PERF_ERR_UNSUPPORTED
+    g = perf.perf_gemm_variant(FAKE, FAKE + 4096, FAKE + 8192, 64, 64, 64, perf.PERF_ROW_MAJOR, 64, perf.PERF_ROW_MAJOR,
+                               64, 64, 1, 0, 0, 0, 1.0, perf.PERF_BF16, perf.PERF_F32, 128, 32, check=False)
+    assert g == perf.PERF_ERR_UNSUPPORTED                       # row-major B has no MFMA variant
+    g = perf.perf_gemm_variant(None, FAKE, FAKE, 64, 64, 64, perf.PERF_ROW_MAJOR, 64, perf.PERF_COL_MAJOR,
+                               64, 64, 1, 0, 0, 0, 1.0, perf.PERF_BF16, perf.PERF_F32, 128, 32, check=False)
+    assert g == perf.PERF_ERR_NULL
+    c = perf.perf_conv2d_variant(FAKE, FAKE + 4096, FAKE + 8192, 1, 8, 8, 3, 4, 3, 3, 1, 1, 1, 1, perf.PERF_BF16,
+                                 perf.PERF_BF16, perf.CONV_WREG, check=False)
+    assert c == perf.PERF_ERR_UNSUPPORTED
+    c = perf.perf_conv2d_variant(FAKE, FAKE + 4096, FAKE + 8192, 1, 8, 8, 3, 4, 3, 3, 1, 1, 1, 1, perf.PERF_BF16,
+                                 perf.PERF_BF16, 9, check=False)
+    assert c == perf.PERF_ERR_UNSUPPORTED
+    c = perf.perf_conv2d_variant(FAKE, FAKE + 4096, FAKE + 8192, 1, 8, 8, 3, 4, 3, 3, 0, 1, 1, 1, perf.PERF_BF16,
+                                 perf.PERF_BF16, perf.CONV_DIRECT, check=False)
+    assert c == perf.PERF_ERR_SHAPE

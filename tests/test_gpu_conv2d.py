@@ -16,11 +16,11 @@ def _bits(a):
     return rng.f32_to_bf16_bits(np.asarray(a, dtype=np.float32))
 
 
-def _check(wl, y_bf16=True, stride=None, pad=None):
+def _check(wl, y_bf16=True, stride=None, pad=None, variant=0):
     d = wl.make()
     stride = stride or (wl.stride, wl.stride)
     pad = pad or (wl.pad, wl.pad)
-    y = G.run_conv2d(d["x_bf16"], d["w_bf16"], stride, pad, y_bf16=y_bf16)
+    y = G.run_conv2d(d["x_bf16"], d["w_bf16"], stride, pad, y_bf16=y_bf16, variant=variant)
     ref, ad = oracle.conv2d(oracle.widen(d["x_bf16"], True), oracle.widen(d["w_bf16"], True), stride, pad,
                             want_absdot=True)
     yg = P.bf16_to_f64(y) if y_bf16 else y
@@ -58,13 +58,15 @@ def test_direct_path_shapes(kw):
 
 
 def test_small_channel_kernel_channel_blocks_and_fp32_operands():
-    # C < 32: channel-blocked direct kernel; K = 37 needs three blocks of 16 with a ragged last one
-    _check(configs.ConvWorkload(N=1, H=8, W=8, C=5, K=37, R=3, S=3, pad=1))
-    _check(configs.ConvWorkload(N=2, H=11, W=6, C=1, K=6, R=3, S=2, pad=1, stride=2), y_bf16=False)
+    # C < 32 and at least 16384 output pixels: channel-blocked direct kernel; K = 37 needs three
+    # blocks of 16 with a ragged last one
+    _check(configs.ConvWorkload(N=1, H=130, W=128, C=5, K=37, R=3, S=3, pad=1))
+    _check(configs.ConvWorkload(N=2, H=11, W=6, C=1, K=6, R=3, S=2, pad=1, stride=2), y_bf16=False, variant=3)
+    _check(configs.ConvWorkload(N=2, H=9, W=9, C=3, K=10, R=5, S=5, pad=2), variant=3)
     g = np.random.default_rng(4)
     x = g.standard_normal((2, 7, 9, 4)).astype(np.float32)
     w = g.standard_normal((9, 3, 3, 4)).astype(np.float32)
-    y = G.run_conv2d(x, w, (1, 1), (1, 1), xw_bf16=False, y_bf16=False)
+    y = G.run_conv2d(x, w, (1, 1), (1, 1), xw_bf16=False, y_bf16=False, variant=3)
     ref, ad = oracle.conv2d(x.astype(np.float64), w.astype(np.float64), (1, 1), (1, 1), want_absdot=True)
     assert np.max(np.abs(y - ref) / np.maximum(ad, 1e-30)) <= 36 * 2.0 ** -23
 
