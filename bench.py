@@ -372,25 +372,26 @@ def main():
         wls = [w for w in wls if w.name in names]
     torch.cuda.synchronize()
 
-    for s in range(args.warmup):
-        for w in wls:
-            w.launch(s)
-    torch.cuda.synchronize()
-
-    # timed region: K steps; each workload's K launches are bracketed by HIP events on the
-    # launch stream, so the per-kernel durations and the step time come from the same runs
+    # Per workload: W untimed warm-up launches, then exactly K timed launches bracketed by HIP
+    # events on the launch stream (a kernel's warm-up directly precedes its timed launches, so a
+    # 20 us kernel is not timed in the clock state the previous workload left behind).
+    # `wall_ms` is the host clock around all timed launches only.
     K = args.steps
-    t0 = time.perf_counter()
     events = []
+    wall_ms = 0.0
     for w in wls:
+        for s in range(args.warmup):
+            w.launch(s)
+        torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
         e0.record()
         for s in range(K):
             w.launch(args.warmup + s)
         e1.record()
+        torch.cuda.synchronize()
+        wall_ms += (time.perf_counter() - t0) * 1e3
         events.append((e0, e1))
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
     for w, (e0, e1) in zip(wls, events):
         w.ms = e0.elapsed_time(e1) / K
     ms_per_step = sum(w.ms for w in wls)
@@ -452,11 +453,10 @@ def main():
         del keep
         torch.cuda.empty_cache()
         pw, pkeep = build_paper_workloads(torch, perf)
-        for s_ in range(args.warmup):
-            for w in pw:
-                w.launch(s_)
         evs = []
         for w in pw:
+            for s_ in range(args.warmup):
+                w.launch(s_)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for s_ in range(K):

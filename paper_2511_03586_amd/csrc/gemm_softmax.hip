@@ -26,7 +26,8 @@ __global__ __launch_bounds__(256, 2) void gemm_softmax_kernel(const uint16_t *__
                                                               const uint16_t *__restrict__ B, PT *__restrict__ P,
                                                               int M, int N, int K, int64_t lda, int64_t ldb,
                                                               int64_t ldp, int64_t strideA, int64_t strideB,
-                                                              int64_t strideP, float sign, float c)
+                                                              int64_t strideP, float sign, float c, int strips,
+                                                              int xcd_remap)
 {
     constexpr int NW = 4, BM = 64, BN = 16 * T16N;
     constexpr int LA = BM / (8 * NW);                    // wave loads per K-step of 64: A strip
@@ -37,11 +38,23 @@ __global__ __launch_bounds__(256, 2) void gemm_softmax_kernel(const uint16_t *__
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: LDS addresses stay scalar
-    const int m0 = blockIdx.x * BM;
+    // Workgroup id -> (row strip, matrix).  Ids are dealt round-robin to the 8 XCDs, each with
+    // a private L2; with the remap all strips of one matrix run on one XCD, so B is fetched
+    // over the fabric once per matrix instead of once per strip.
+    int strip, bz;
+    if (xcd_remap) {
+        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+        strip = j % strips;
+        bz = (j / strips) * 8 + xcd;
+    } else {
+        strip = blockIdx.x % strips;
+        bz = blockIdx.x / strips;
+    }
+    const int m0 = strip * BM;
     const int ksteps = K / 64;
-    const uint16_t *Ab = A + (int64_t)blockIdx.y * strideA;
-    const uint16_t *Bb = B + (int64_t)blockIdx.y * strideB;
-    PT *Pb = P + (int64_t)blockIdx.y * strideP;
+    const uint16_t *Ab = A + (int64_t)bz * strideA;
+    const uint16_t *Bb = B + (int64_t)bz * strideB;
+    PT *Pb = P + (int64_t)bz * strideP;
 
     RowMajorSrc64<LA, NW> src_a(Ab + (int64_t)m0 * lda, min(BM, M - m0), lda, ksteps, wave, lane);
     RowMajorSrc64<LB, NW> src_b(Bb, min(kRowsB, N), ldb, ksteps, wave, lane);
@@ -139,12 +152,15 @@ static perf_status launch_fused(const void *A, const void *B, void *P, int64_t M
     }
     const float sign = alpha < 0.f ? -1.f : 1.f;
     const float c = (float)(std::fabs((double)alpha) * 1.4426950408889634074);  // |alpha| log2(e)
-    const unsigned gx = (unsigned)((M + 63) / 64);
-    for (int64_t b0 = 0; b0 < batch; b0 += kMaxGridYZ) {
-        const unsigned gy = (unsigned)(batch - b0 < kMaxGridYZ ? batch - b0 : kMaxGridYZ);
-        hipLaunchKernelGGL(kern, dim3(gx, gy), dim3(256), lds, st, (const uint16_t *)A + b0 * strideA,
+    const int64_t strips = (M + 63) / 64;
+    // one-dimensional grid of strips x matrices, in chunks that keep the grid below its limit
+    const int64_t per_launch = (kMaxGridX / strips) / 8 * 8;
+    if (per_launch < 8) return PERF_ERR_UNSUPPORTED;
+    for (int64_t b0 = 0; b0 < batch; b0 += per_launch) {
+        const int64_t nb = batch - b0 < per_launch ? batch - b0 : per_launch;
+        hipLaunchKernelGGL(kern, dim3((unsigned)(strips * nb)), dim3(256), lds, st, (const uint16_t *)A + b0 * strideA,
                            (const uint16_t *)B + b0 * strideB, (PT *)P + b0 * strideP, (int)M, (int)N, (int)K, lda, ldb,
-                           ldp, strideA, strideB, strideP, sign, c);
+                           ldp, strideA, strideB, strideP, sign, c, (int)strips, nb % 8 == 0 ? 1 : 0);
     }
     return launch_status();
 }
@@ -172,7 +188,7 @@ extern "C" perf_status perf_gemm_softmax(const void *A, const void *B, void *P, 
 
     const bool fused = ab_dt == PERF_BF16 && (K == 64 || K == 128) && N <= 512 && lda % 8 == 0 && ldb % 8 == 0 &&
                        strideA % 8 == 0 && strideB % 8 == 0 && aligned(A, 16) && aligned(B, 16) && lda <= (1 << 21) &&
-                       ldb <= (1 << 21) && M <= (1 << 30) && (M + 63) / 64 <= kMaxGridX;
+                       ldb <= (1 << 21) && M <= (1 << 24);
     if (fused) {
 #define PERF_FUSED(T, MASK)                                                                                              \
     (p_dt == PERF_F32                                                                                                    \
