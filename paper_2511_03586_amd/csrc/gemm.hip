@@ -42,13 +42,24 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: LDS addresses stay scalar
     const int wm = wave / WN, wn = wave % WN;
+    // Batches of small matrices (fewer than 8 tiles each): workgroups are dealt round-robin to
+    // the 8 XCDs in linear grid order, so the tiles of one matrix would land on different
+    // XCDs and its operands would cross the fabric once per tile.  Remap so that a matrix
+    // stays on one XCD (needs a multiple of 8 matrices in the launch).
+    int bid = blockIdx.x, bz = blockIdx.y;
+    const int tiles = tiles_m * tiles_n;
+    if (tiles < 8 && gridDim.y % 8 == 0) {
+        const unsigned id = blockIdx.x + (unsigned)tiles * blockIdx.y;
+        const unsigned xcd = id & 7, j = id >> 3;
+        bid = (int)(j % (unsigned)tiles);
+        bz = (int)((j / (unsigned)tiles) * 8 + xcd);
+    }
     int tm, tn;
-    tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
+    tile_of_block(bid, tiles_m, tiles_n, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const int ktiles = K / kBK;
 
     {
-        const int bz = blockIdx.y;
         const uint16_t *Ab = A + (int64_t)bz * strideA;
         const uint16_t *Bb = B + (int64_t)bz * strideB;
         CT *Cb = C + (int64_t)bz * strideC;
