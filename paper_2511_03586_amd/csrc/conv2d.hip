@@ -159,7 +159,10 @@ __global__ __launch_bounds__(512) void conv2d_wreg_kernel(const uint16_t *__rest
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int Mtot = g.N * g.P * g.Q;
-    const int start = blockIdx.x * px_per_wg, end = min(start + px_per_wg, Mtot);
+    // workgroup ids are dealt round-robin to the 8 XCDs: give each XCD a contiguous run of pixel
+    // ranges, so that neighbouring ranges (which share halo rows of the input) share an L2
+    const int wg = gridDim.x % 8 == 0 ? (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
+    const int start = wg * px_per_wg, end = min(start + px_per_wg, Mtot);
     const int nblocks = (end - start + 31) / 32;
     // Both kinds of wave execute exactly 2 + nblocks workgroup barriers.
 
