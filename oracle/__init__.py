@@ -43,12 +43,13 @@ def _load():
         lib.oracle_conv2d.argtypes = [ptr, ptr, ptr, ptr] + [i64] * 11
         lib.oracle_rmsnorm.argtypes = [ptr, ptr, ptr, ptr, i64, i64, dbl]
         lib.oracle_reduce_mean.argtypes = [ptr, ptr, i64, i64, cint]
+        lib.oracle_batchnorm.argtypes = [ptr, ptr, ptr, ptr, ptr, ptr, i64, i64, i64, dbl]
         lib.oracle_eltwise.argtypes = [cint, ptr, ptr, ptr, i64]
         lib.oracle_round_f32.argtypes = [ptr, ptr, i64]
         lib.oracle_round_bf16.argtypes = [ptr, ptr, i64]
         for f in ("oracle_set_threads", "oracle_softmax", "oracle_layernorm", "oracle_gemm",
                   "oracle_gemm_absdot", "oracle_conv2d", "oracle_round_f32", "oracle_round_bf16",
-                  "oracle_rmsnorm", "oracle_reduce_mean", "oracle_eltwise"):
+                  "oracle_rmsnorm", "oracle_reduce_mean", "oracle_eltwise", "oracle_batchnorm"):
             getattr(lib, f).restype = None
         _lib = lib
     return _lib
@@ -107,6 +108,19 @@ def rmsnorm(x, gamma, eps: float):
     r = np.empty(rows, dtype=np.float64)
     _load().oracle_rmsnorm(_p(x), _p(gamma), _p(y), _p(r), rows, cols, float(eps))
     return y, r
+
+
+def batchnorm(x, gamma, beta, eps: float):
+    """x: [N, C, H, W] (or [N, C, HW]) float64; batch statistics per channel. Returns (y, mean, rstd)."""
+    x, gamma, beta = widen(x), widen(gamma), widen(beta)
+    N, C = x.shape[0], x.shape[1]
+    HW = int(np.prod(x.shape[2:]))
+    assert gamma.shape == (C,) and beta.shape == (C,)
+    y = np.empty_like(x)
+    m = np.empty(C, dtype=np.float64)
+    r = np.empty(C, dtype=np.float64)
+    _load().oracle_batchnorm(_p(x), _p(gamma), _p(beta), _p(y), _p(m), _p(r), N, C, HW, float(eps))
+    return y, m, r
 
 
 def reduce_mean(x, axis: int):

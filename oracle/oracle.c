@@ -191,6 +191,37 @@ void oracle_rmsnorm(const double *x, const double *gamma, double *y, double *rrm
     }
 }
 
+/* Batch normalisation with batch statistics ("batchnorm" rows of the operator table, Section
+ * 4.3; the paper's case study computes the statistics first and then streams, Section 4.3):
+ * x is [N][C][HW]; per channel c over all n and positions: mu_c = mean, var_c = biased variance,
+ * r_c = 1/sqrt(var_c + eps), y = (x - mu_c) * r_c * gamma_c + beta_c.  mean / rstd (nullable)
+ * receive mu_c and r_c.  Two passes per channel, in index order. */
+void oracle_batchnorm(const double *x, const double *gamma, const double *beta, double *y, double *mean,
+                      double *rstd, int64_t N, int64_t C, int64_t HW, double eps)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < C; ++c) {
+        double s = 0.0;
+        for (int64_t n = 0; n < N; ++n)
+            for (int64_t i = 0; i < HW; ++i) s += x[(n * C + c) * HW + i];
+        const double mu = s / (double)(N * HW);
+        double q = 0.0;
+        for (int64_t n = 0; n < N; ++n)
+            for (int64_t i = 0; i < HW; ++i) {
+                const double d = x[(n * C + c) * HW + i] - mu;
+                q += d * d;
+            }
+        const double r = 1.0 / sqrt(q / (double)(N * HW) + eps);
+        for (int64_t n = 0; n < N; ++n)
+            for (int64_t i = 0; i < HW; ++i) {
+                const int64_t o = (n * C + c) * HW + i;
+                y[o] = (x[o] - mu) * r * gamma[c] + beta[c];
+            }
+        if (mean) mean[c] = mu;
+        if (rstd) rstd[c] = r;
+    }
+}
+
 /* Mean along one axis of a rows x cols matrix ("reducemean" row of the operator table):
  * axis 1: y_i = (1/cols) sum_j x_ij (length rows); axis 0: y_j = (1/rows) sum_i x_ij (length cols). */
 void oracle_reduce_mean(const double *x, double *y, int64_t rows, int64_t cols, int axis)

@@ -62,3 +62,37 @@ def test_eltwise_exact_cases():
     r = oracle.eltwise(oracle.ELTWISE_RELU, a)
     np.testing.assert_array_equal(r, [[1.0, 0.0, 0.0, 3.5], [0.0, 7.0, 0.0, 2.0]])
     assert not np.any(np.signbit(r))     # relu(-0.0) and relu(negative) are +0
+
+
+def test_batchnorm_closed_forms_and_invariants():
+    eps = 1e-5
+    g = np.random.default_rng(6)
+    N, C, H, W = 3, 4, 5, 6
+    x = g.standard_normal((N, C, H, W)) * np.array([1.0, 3.0, 0.5, 2.0])[None, :, None, None] + np.array([0.0, 10.0, -4.0, 1e3])[None, :, None, None]
+    gamma, beta = g.uniform(0.5, 1.5, C), g.standard_normal(C)
+    y, m, r = oracle.batchnorm(x, gamma, beta, eps)
+    # numpy second opinion (statistics over N, H, W per channel, biased variance)
+    mu = x.mean(axis=(0, 2, 3)); var = x.var(axis=(0, 2, 3))
+    np.testing.assert_allclose(m, mu, rtol=1e-13)
+    np.testing.assert_allclose(r, 1 / np.sqrt(var + eps), rtol=1e-12)
+    np.testing.assert_allclose(y, (x - mu[None, :, None, None]) / np.sqrt(var + eps)[None, :, None, None] * gamma[None, :, None, None]
+                               + beta[None, :, None, None], rtol=1e-9, atol=1e-12)
+    # pre-affine output: zero mean, variance var/(var+eps) per channel
+    y1, _, _ = oracle.batchnorm(x, np.ones(C), np.zeros(C), eps)
+    np.testing.assert_allclose(y1.mean(axis=(0, 2, 3)), 0.0, atol=1e-10)
+    np.testing.assert_allclose(y1.var(axis=(0, 2, 3)), var / (var + eps), rtol=1e-10)
+    # channels are independent: permuting them permutes the result
+    p = np.array([2, 0, 3, 1])
+    yp, mp, rp = oracle.batchnorm(x[:, p], gamma[p], beta[p], eps)
+    np.testing.assert_array_equal(yp, y[:, p]); np.testing.assert_array_equal(mp, m[p])
+    # constant channel -> beta; two-valued channel +-a -> +-a/sqrt(a^2+eps)*gamma + beta
+    xc = np.full((2, 1, 3, 4), 7.0)
+    yc, mc, _ = oracle.batchnorm(xc, np.array([1.3]), np.array([0.25]), eps)
+    assert np.all(yc == 0.25) and mc[0] == 7.0
+    xa = 2.0 * (-1.0) ** np.arange(24).reshape(2, 1, 3, 4)
+    ya, _, ra = oracle.batchnorm(xa, np.array([1.5]), np.array([-1.0]), eps)
+    np.testing.assert_allclose(ya, xa / np.sqrt(4.0 + eps) * 1.5 - 1.0, rtol=1e-15)
+    # N and HW are pooled: moving data between the batch and spatial axes changes nothing
+    x2 = x.reshape(N, C, H * W)
+    y2, m2, _ = oracle.batchnorm(np.concatenate([x2[:, :, :15], x2[:, :, 15:]], axis=0).reshape(2 * N, C, 15), gamma, beta, eps)
+    np.testing.assert_allclose(m2, m, rtol=1e-13)
