@@ -260,6 +260,22 @@ def build_paper_workloads(torch, perf):
                         lambda i: perf.perf_eltwise(perf.PERF_MUL, xs6[i % 64].data_ptr(), xs6[(i + 7) % 64].data_ptr(),
                                                     ys6[i % 64].data_ptr(), 6 * 14336, F32, st()), 64,
                         "1 MB per launch: launch-latency bound"))
+    # batchnorm 8x64x300x300 and 8x3x2048x2048 (NCHW, fp32): x is read twice (statistics, then the
+    # streaming kernel) and y written once: 12 bytes per element
+    for tag, (bn_n, bn_c, bn_h, bn_w), cfg in (("paper_batchnorm_8x64x300x300_f32", (8, 64, 300, 300), 21),
+                                             ("paper_batchnorm_8x3x2048x2048_f32", (8, 3, 2048, 2048), 22)):
+        xb = sets(normal_f32(cfg, (bn_n, bn_c, bn_h * bn_w)), 2)
+        yb = torch.empty_like(xb); keep.append(yb)
+        gb = G.dev(rng.uniform(rng.tensor_seed(cfg, 1), (bn_c,), 0.5, 1.5)); keep.append(gb)
+        bb2 = G.dev(rng.normal(rng.tensor_seed(cfg, 2), (bn_c,), 0.0, 0.1)); keep.append(bb2)
+        wsb = torch.empty(perf.perf_batchnorm_workspace_bytes(bn_n, bn_c, bn_h, bn_w) // 4, dtype=torch.float32,
+                          device="cuda"); keep.append(wsb)
+        wls.append(Workload(tag, "bn_partial_kernel + bn_finalize_kernel + bn_apply_kernel", "hbm",
+                            12 * bn_n * bn_c * bn_h * bn_w,
+                            lambda i, xb=xb, yb=yb, gb=gb, bb2=bb2, wsb=wsb, d=(bn_n, bn_c, bn_h, bn_w): perf.perf_batchnorm(
+                                xb[i % 2].data_ptr(), gb.data_ptr(), bb2.data_ptr(), yb[i % 2].data_ptr(), None, None,
+                                wsb.data_ptr(), d[0], d[1], d[2], d[3], 1e-5, F32, F32, F32, st()), 2,
+                            "three launches; priced at two reads + one write of the tensor"))
     yl = torch.empty_like(xm); keep.append(yl)
     wls.append(Workload("paper_relu_4096x4096_f32", "eltwise_kernel<relu,f32>", "hbm", 8 * 4096 * 4096,
                         lambda i: perf.perf_eltwise(perf.PERF_RELU, xm[i % 8].data_ptr(), None, yl[i % 8].data_ptr(),

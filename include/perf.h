@@ -10,7 +10,8 @@
  *
  * Conventions shared by every entry point
  *  - All data pointers are DEVICE pointers (HBM), owned by the caller.  The library
- *    allocates no device memory and keeps no state between calls.
+ *    allocates no device memory and keeps no state between calls (the one operator that
+ *    needs scratch memory, perf_batchnorm, takes it from the caller).
  *  - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL = the default
  *    stream) and return without synchronising.  Buffers must stay alive and unmodified
  *    until the stream has run the enqueued kernels.
@@ -136,6 +137,26 @@ perf_status perf_gemm_softmax(const void *A, const void *B, void *P, int64_t M, 
 perf_status perf_rmsnorm(const void *x, const void *gamma, void *y, float *rrms_out, int64_t rows,
                          int64_t cols, int64_t ldx, int64_t ldy, float eps, perf_dtype x_dt,
                          perf_dtype param_dt, perf_dtype y_dt, perf_stream stream);
+
+/* Batch normalisation with batch statistics ("batchnorm" rows of the operator table, Section
+ * 4.3; statistics first, then a streaming kernel, as in the paper's case study).  x and y are
+ * N x C x H x W, contiguous.  Per channel c, over all n, h, w:
+ *     mu = mean x;  var = biased variance;  r = 1/sqrt(var + eps);
+ *     y = (x - mu) * r * gamma[c] + beta[c].
+ * fp32 statistics (segment statistics merged in double), result rounded once to y_dt.
+ *   gamma, beta         device, length C, dtype param_dt
+ *   mean_out, rstd_out  device fp32[C] or NULL
+ *   workspace           device, at least perf_batchnorm_workspace_bytes(N, C, H, W) bytes, 4-byte
+ *                       aligned, owned by the caller; its contents are scratch
+ * perf_batchnorm_workspace_bytes returns -1 for a shape perf_batchnorm would reject.
+ * y == x exactly is allowed when the dtypes match.
+ * Errors: NULL, SHAPE (dimension < 1 or > 2^24, N*C > 65535, eps < 0 or not finite), DTYPE, ALIGN,
+ * LAUNCH. */
+int64_t perf_batchnorm_workspace_bytes(int64_t N, int64_t C, int64_t H, int64_t W);
+perf_status perf_batchnorm(const void *x, const void *gamma, const void *beta, void *y, float *mean_out,
+                           float *rstd_out, void *workspace, int64_t N, int64_t C, int64_t H, int64_t W,
+                           float eps, perf_dtype x_dt, perf_dtype param_dt, perf_dtype y_dt,
+                           perf_stream stream);
 
 /* Mean along one axis of a rows x cols matrix ("reducemean" row of the operator table; the
  * table does not say which axis, both are provided): axis 1: y[i] = mean_j x[i][j] (rows

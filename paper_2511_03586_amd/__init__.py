@@ -37,6 +37,9 @@ SIGNATURES = {
     "perf_gemm_variant": (_int, [_ptr, _ptr, _ptr, _i64, _i64, _i64, _int, _i64, _int, _i64, _i64, _i64, _i64, _i64, _i64,
                                  _f32, _int, _int, _int, _int, _ptr]),
     "perf_conv2d_variant": (_int, [_ptr, _ptr, _ptr] + [_i64] * 11 + [_int, _int, _int, _ptr]),
+    "perf_batchnorm_workspace_bytes": (_i64, [_i64, _i64, _i64, _i64]),
+    "perf_batchnorm": (_int, [_ptr, _ptr, _ptr, _ptr, _ptr, _ptr, _ptr, _i64, _i64, _i64, _i64, _f32, _int, _int, _int,
+                              _ptr]),
     "perf_copy": (_int, [_ptr, _ptr, _i64, _ptr]),
     "perf_mfma_probe": (_int, [_ptr, _i64, _ptr]),
     "perf_status_string": (ctypes.c_char_p, [_int]),
@@ -146,6 +149,17 @@ def perf_reduce_mean(x, y, rows, cols, ldx, axis, x_dt=PERF_F32, y_dt=PERF_F32, 
 
 def perf_eltwise(op, a, b, y, n, dt=PERF_F32, stream=None, check=True) -> int:
     return _check("perf_eltwise", lib().perf_eltwise(op, a, b, y, n, dt, stream), check)
+
+
+def perf_batchnorm_workspace_bytes(N, C, H, W) -> int:
+    return int(lib().perf_batchnorm_workspace_bytes(N, C, H, W))
+
+
+def perf_batchnorm(x, gamma, beta, y, mean_out, rstd_out, workspace, N, C, H, W, eps, x_dt=PERF_F32,
+                   param_dt=PERF_F32, y_dt=PERF_F32, stream=None, check=True) -> int:
+    return _check("perf_batchnorm",
+                  lib().perf_batchnorm(x, gamma, beta, y, mean_out, rstd_out, workspace, N, C, H, W, eps, x_dt,
+                                       param_dt, y_dt, stream), check)
 
 
 def perf_copy(src, dst, nbytes, stream=None, check=True) -> int:

@@ -14,7 +14,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libperf.so")
-SOURCES = ["misc.hip", "softmax.hip", "layernorm.hip", "gemm.hip", "gemm_softmax.hip", "conv2d.hip", "streaming.hip"]
+SOURCES = ["misc.hip", "softmax.hip", "layernorm.hip", "gemm.hip", "gemm_softmax.hip", "conv2d.hip", "streaming.hip", "batchnorm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          # keep the compiler from forming packed-fp32 VALU ops
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -182,3 +182,21 @@ def test_variant_entry_points_refuse_without_touching_the_device():
     c = perf.perf_conv2d_variant(FAKE, FAKE + 4096, FAKE + 8192, 1, 8, 8, 3, 4, 3, 3, 0, 1, 1, 1, perf.PERF_BF16,
                                  perf.PERF_BF16, perf.CONV_DIRECT, check=False)
     assert c == perf.PERF_ERR_SHAPE
+
+
+def test_batchnorm_argument_errors_and_workspace_size():
+    f = lambda **k: perf.perf_batchnorm(**{**dict(x=FAKE, gamma=FAKE + 4096, beta=FAKE + 8192, y=FAKE + 12288,
+                                                  mean_out=None, rstd_out=None, workspace=FAKE + 16384, N=2, C=3, H=4, W=5,
+                                                  eps=1e-5, check=False), **k})
+    for k in ("x", "gamma", "beta", "y", "workspace"):
+        assert f(**{k: None}) == perf.PERF_ERR_NULL
+    assert f(N=0) == perf.PERF_ERR_SHAPE and f(W=0) == perf.PERF_ERR_SHAPE
+    assert f(N=4096, C=4096) == perf.PERF_ERR_SHAPE            # N*C planes ride on one grid dimension
+    assert f(eps=float("nan")) == perf.PERF_ERR_SHAPE
+    assert f(y_dt=6) == perf.PERF_ERR_DTYPE
+    assert f(workspace=FAKE + 2) == perf.PERF_ERR_ALIGN
+    assert f(x=FAKE + 1) == perf.PERF_ERR_ALIGN
+    # 3 floats per segment of 16384 elements per plane, plus scale and mean per channel
+    assert perf.perf_batchnorm_workspace_bytes(8, 64, 300, 300) == 4 * (3 * 64 * 8 * 6 + 2 * 64)
+    assert perf.perf_batchnorm_workspace_bytes(1, 1, 1, 1) == 4 * (3 + 2)
+    assert perf.perf_batchnorm_workspace_bytes(0, 1, 1, 1) == -1
