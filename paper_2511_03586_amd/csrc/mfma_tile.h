@@ -356,13 +356,17 @@ __device__ __forceinline__ void mfma16(float4_t &acc, const bf16x8_t &a, const b
 
 // K loop over `ksteps` steps of 64.  LDS: two stages of (BM + BN) rows x 128 bytes.
 // Schedule of step p (stage p%2 holds it), in two halves of 32 K:
-//   half 0: MFMAs on K 0..31 (fragments read during the previous half); read the fragments
-//           of K 32..63 from the same stage;
-//   wait: own loads of step p+1 have landed, own reads of stage p are back; barrier;
-//   half 1: MFMAs on K 32..63; read the first fragments of step p+1 from the other stage;
-//           load step p+2 into stage p%2.
-// Memory instructions are spread evenly between the MFMAs; the order is fixed by hand
-// (scheduling fences), since the MFMAs are opaque to the scheduler.  The operands are
+//   half 0: MFMAs on K 0..31 (fragments read during the previous half); in its first quarter
+//           the fragments of K 32..63 are read from the same stage; at 3/8 a barrier (every
+//           wave is done reading stage p), after which step p+2 starts loading into stage p;
+//   between the halves: own loads of step p+1 have landed; barrier;
+//   half 1: MFMAs on K 32..63; in its first quarter the first fragments of step p+1 are read
+//           from the other stage; the rest of step p+2's loads.
+// The loads of a step are thus spread over 5/8 of a half and a whole half instead of being
+// issued by all four waves in one half: the texture path takes 64 bytes per clock, and a
+// wave whose load cannot issue cannot issue the MFMAs behind it either (measured: 11 % fewer
+// cycles on 4096^3).  The order is fixed by hand (scheduling fences), since the MFMAs are
+// opaque to the scheduler.  The operands are
 // swapped (B rows as the MFMA's row operand), so a lane ends up with 4 consecutive n of one m.
 template <int TM, int TN, int WM, int WN, typename SrcA, typename SrcB>
 __device__ __forceinline__ void mfma_mainloop_k64(WaveTile16<2 * TM, 2 * TN> &t, char *smem, int ksteps, int wave,
@@ -393,23 +397,43 @@ __device__ __forceinline__ void mfma_mainloop_k64(WaveTile16<2 * TM, 2 * TN> &t,
         }
     };
     // MFMAs of one half-step from fragment buffer BUF; between them: the reads of the next
-    // half-step's fragments (stage rstage, K half RHALF) into the other buffer and, if LOADS,
-    // one step of global->LDS loads into lstage.
-    auto half_step = [&](auto buf_c, auto rhalf_c, auto loads_c, const char *rstage, char *lstage) {
+    // half-step's fragments (stage rstage, K half RHALF) into the other buffer, the first
+    // (half 0) or second (half 1) part of one step of global->LDS loads into lstage, and in
+    // half 0 the barrier in front of those loads.
+    // positions, in MFMAs of a half-step: reads before MFMA floor(g * kQ4 / kR), barrier of half
+    // 0 before MFMA kQB, its kLa loads spread over [kQB, kMfmas), half 1's kLb loads over the half
+    constexpr int kR = T16M + T16N, kQ4 = kMfmas / 4 > 0 ? kMfmas / 4 : 1, kQB = (3 * kMfmas) / 8;
+    constexpr int kLa = kLoads / 2, kLb = kLoads - kLa, kSpan = kMfmas - kQB;
+    auto half_step = [&](auto buf_c, auto rhalf_c, auto second_c, const char *rstage, char *lstage) {
         constexpr int BUF = decltype(buf_c)::value, RHALF = decltype(rhalf_c)::value;
-        constexpr int kMem = T16M + T16N + (decltype(loads_c)::value ? kLoads : 0);
+        constexpr bool SECOND = decltype(second_c)::value;
 #pragma unroll
         for (int q = 0; q < kMfmas; ++q) {
-            // memory instruction g goes in front of MFMA floor(g * kMfmas / kMem)
 #pragma unroll
-            for (int g = (q * kMem + kMfmas - 1) / kMfmas; g < ((q + 1) * kMem + kMfmas - 1) / kMfmas; ++g) {
+            for (int g = (q < kQ4 ? (q * kR + kQ4 - 1) / kQ4 : kR); g < (q < kQ4 ? ((q + 1) * kR + kQ4 - 1) / kQ4 : kR); ++g) {
                 if (g < T16M)
                     fa[BUF ^ 1][g] = *reinterpret_cast<const bf16x8_t *>(rstage + frag_a(g, RHALF));
-                else if (g < T16M + T16N)
-                    fb[BUF ^ 1][g - T16M] = *reinterpret_cast<const bf16x8_t *>(rstage + frag_b(g - T16M, RHALF));
                 else
-                    issue_one(lstage, g - T16M - T16N);
+                    fb[BUF ^ 1][g - T16M] = *reinterpret_cast<const bf16x8_t *>(rstage + frag_b(g - T16M, RHALF));
                 __builtin_amdgcn_sched_barrier(0);
+            }
+            if (!SECOND && q == kQB) {
+                wait_vmem_and_lds<kLoads>();  // own reads of this stage are back (the loads of step p+1 may still fly)
+                wg_barrier();
+            }
+            if (!SECOND) {
+#pragma unroll
+                for (int i = (q >= kQB ? ((q - kQB) * kLa + kSpan - 1) / kSpan : kLa);
+                     i < (q >= kQB ? ((q - kQB + 1) * kLa + kSpan - 1) / kSpan : kLa); ++i) {
+                    issue_one(lstage, i);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+#pragma unroll
+                for (int i = (q * kLb + kMfmas - 1) / kMfmas; i < ((q + 1) * kLb + kMfmas - 1) / kMfmas; ++i) {
+                    issue_one(lstage, kLa + i);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
             mfma16(t.acc[q / T16N][q % T16N], fb[BUF][q % T16N], fa[BUF][q / T16N]);
             __builtin_amdgcn_sched_barrier(0);
@@ -434,11 +458,11 @@ __device__ __forceinline__ void mfma_mainloop_k64(WaveTile16<2 * TM, 2 * TN> &t,
 
     for (int p = 0; p < ksteps; ++p) {
         char *cur = smem + (p & 1) * kStageBytes64, *nxt = smem + ((p + 1) & 1) * kStageBytes64;
-        wait_vmem_and_lds<kLoads>();  // the fragments of half 0 are back
+        wait_vmem_and_lds<kLoads>();  // the fragments of half 0 are back (loads of step p+1 may still fly)
         half_step(c0{}, c1{}, std::false_type{}, cur, cur);
-        wait_vmem_and_lds<0>();  // own loads of step p+1 have landed, own reads of stage p are back
+        wait_vmem_and_lds<kLa>();  // own loads of step p+1 have landed (only this half's loads of step p+2 are younger)
         wg_barrier();
-        half_step(c1{}, c0{}, std::true_type{}, nxt, cur);  // step p+2 goes into the stage of step p
+        half_step(c1{}, c0{}, std::true_type{}, nxt, cur);
         src_a.advance();
         src_b.advance();
     }
