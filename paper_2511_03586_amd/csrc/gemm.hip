@@ -71,7 +71,17 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t 
             WaveTile16<2 * TM, 2 * TN> t;
             t.clear();
             mfma_mainloop_k64<TM, TN, WM, WN>(t, smem, K / 64, wave, lane, a_row0, b_row0, src_a, src_b);
-            store_tile16<2 * TM, 2 * TN, CT>(t, Cb, ldc, M, N, m0 + a_row0, n0 + b_row0, alpha, lane);
+            if constexpr (sizeof(CT) == 2) {
+                // bf16 C: through LDS, so that the stores are 16 bytes per lane in whole rows
+                wg_barrier();  // every wave has left the main loop and its loads have landed: LDS is free
+                constexpr int kWaveStage = (32 * TM) * (64 * TN);
+                static_assert(NW * kWaveStage <= Shape::kLdsBytes, "the staged tiles fit the main loop's LDS");
+                if (!store_tile16_bf16<2 * TM, 2 * TN>(t, Cb, ldc, M, N, m0 + a_row0, n0 + b_row0, alpha, lane,
+                                                      smem + wave * kWaveStage))
+                    store_tile16<2 * TM, 2 * TN, CT>(t, Cb, ldc, M, N, m0 + a_row0, n0 + b_row0, alpha, lane);
+            } else {
+                store_tile16<2 * TM, 2 * TN, CT>(t, Cb, ldc, M, N, m0 + a_row0, n0 + b_row0, alpha, lane);
+            }
         } else {
             RowMajorSrc<Shape::kLoadsA, NW> src_a(Ab + (int64_t)m0 * lda, min(BM, M - m0), lda, ktiles, wave, lane);
             RowMajorSrc<Shape::kLoadsB, NW> src_b(Bb + (int64_t)n0 * ldb, min(BN, N - n0), ldb, ktiles, wave, lane);

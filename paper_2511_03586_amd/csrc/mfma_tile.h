@@ -522,4 +522,41 @@ __device__ __forceinline__ void store_tile16(const WaveTile16<T16M, T16N> &t, CT
     }
 }
 
+// bf16 variant of the full-tile write-out: the wave's tile is packed to bf16 and staged in a
+// private LDS region (rows of 32*T16N bytes, 16-byte chunks XOR-swizzled by the row so that
+// neither the column-wise writes nor the row-wise reads conflict), then written as 16 bytes
+// per lane, whole rows of the tile per group of 2*T16N lanes.  `stage` must not be in use by
+// any other wave (the caller puts a barrier between the main loop and this).
+// Returns false (nothing written) when the tile is not full or C is not 16-byte aligned.
+template <int T16M, int T16N>
+__device__ __forceinline__ bool store_tile16_bf16(const WaveTile16<T16M, T16N> &t, uint16_t *C, int64_t ldc, int M, int N,
+                                                  int row0, int col0, float alpha, int lane, char *stage)
+{
+    constexpr int kRowBytes = 32 * T16N, kChunks = 2 * T16N, kMask = (kChunks < 16 ? kChunks : 16) - 1;
+    static_assert((kChunks & (kChunks - 1)) == 0 && 64 % kChunks == 0, "power-of-two chunks per row");
+    if (!(ldc % 8 == 0 && (reinterpret_cast<uintptr_t>(C) & 15) == 0 && row0 + 16 * T16M <= M && col0 + 16 * T16N <= N))
+        return false;
+    const int m16 = lane & 15, q = lane >> 4;
+#pragma unroll
+    for (int i = 0; i < T16M; ++i) {
+        const int row = 16 * i + m16;
+#pragma unroll
+        for (int j = 0; j < T16N; ++j) {
+            const float4_t v = t.acc[i][j] * alpha;
+            const int chunk = (2 * j + (q >> 1)) ^ (row & kMask);  // 8 bf16 per chunk: columns 16 j + 8 (q/2) ..
+            *reinterpret_cast<uint2_t *>(stage + row * kRowBytes + chunk * 16 + (q & 1) * 8) =
+                uint2_t{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        }
+    }
+    // (same wave wrote and reads: the LDS operations of a wave complete in order)
+    constexpr int kRowsPerInstr = 64 / kChunks;
+#pragma unroll
+    for (int r0 = 0; r0 < 16 * T16M; r0 += kRowsPerInstr) {
+        const int row = r0 + lane / kChunks, c = lane % kChunks;
+        const uint4_t v = *reinterpret_cast<const uint4_t *>(stage + row * kRowBytes + ((c ^ (row & kMask)) * 16));
+        __builtin_nontemporal_store(v, reinterpret_cast<uint4_t *>(C + (int64_t)(row0 + row) * ldc + col0 + c * 8));
+    }
+    return true;
+}
+
 }  // namespace perf
