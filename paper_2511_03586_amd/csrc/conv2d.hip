@@ -151,7 +151,7 @@ __global__ __launch_bounds__(512) void conv2d_wreg_kernel(const uint16_t *__rest
     constexpr int kWin = 9;                                 // operand window of the MFMA waves
     static_assert(CB == 2, "two 32-channel sub-tiles per filter tap");
     static_assert((NSUB * 2) % 4 == 0, "sub-tiles must divide among the four memory waves");
-    static_assert(KSUB % kWin == 0 && KSUB % 2 == 0, "window and weight halves must divide the fragment count");
+    static_assert(KSUB % kWin == 0 && KSUB % 4 == 0, "window and weight quarters must divide the fragment count");
     static_assert(kLoads + 2 * kStores < 64, "vmcnt is a 6-bit counter");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     char *const out_stage = smem + kSlots * kSlot;
@@ -173,51 +173,60 @@ __global__ __launch_bounds__(512) void conv2d_wreg_kernel(const uint16_t *__rest
         // kk*16 .. +15; a lane holds channel lane%32 and the 8 K values starting at 8*(lane/32).
         // Read straight from memory that pattern touches 32 different rows per instruction, so
         // the wave's 36 KiB go through a private LDS region with coalesced global->LDS loads,
-        // in two halves of 288 K values (the region overlaps ring slot 2 and the output
-        // staging, which are not in use before the first barrier; slots 0 and 1 are being
-        // filled by the memory waves meanwhile).  A row's 36 chunks of 16 bytes are stored
-        // rotated by row/4 chunks, which spreads the 16 rows read by one ds_read_b128 phase
-        // over all 16 bank slots.
-        constexpr int kHalfChunks = R * S * C / 16;  // 16-byte chunks per weight row and half (36)
-        constexpr int kWLoads = 32 * kHalfChunks / 64;  // wave loads per half (18)
-        static_assert((32 * kHalfChunks) % 64 == 0, "whole wave loads");
+        // in four quarters of 144 K values through two sub-regions, so that two quarters are
+        // always in flight while a third is read into registers (the region overlaps ring
+        // slot 2 and the output staging, which are not in use before the first barrier; slots
+        // 0 and 1 are being filled by the memory waves meanwhile).  A row's 18 chunks of
+        // 16 bytes are stored rotated by row/8 chunks, which spreads the 16 rows read by one
+        // ds_read_b128 phase over all 16 bank slots (row pitch 18 chunks = 2 slots).
+        constexpr int kQC = R * S * C / 32;       // 16-byte chunks per weight row and quarter (18)
+        constexpr int kQLoads = 32 * kQC / 64;    // wave loads per quarter (9)
+        constexpr int kQBytes = 32 * kQC * 16;
+        static_assert((32 * kQC) % 64 == 0 && KSUB % 4 == 0 && R * S * C == 32 * kQC, "whole wave loads per quarter");
         bf16x8_t wf[KSUB];
         {
-            char *wreg = smem + 2 * kSlot + wave * (32 * kHalfChunks * 16);
+            char *wreg = smem + 2 * kSlot + wave * (2 * kQBytes);
             const rsrc_t wr = make_rsrc(w + (int64_t)wave * 32 * (R * S * C), (uint32_t)(32 * R * S * C * 2));
-            // LDS chunk L = i*64 + lane of the region holds row L / 36 at stored position L % 36
-            uint32_t wvo[kWLoads];
-            int row = lane >= kHalfChunks ? 1 : 0, cp = lane - row * kHalfChunks;
+            uint32_t wvo[kQLoads];
 #pragma unroll
-            for (int i = 0; i < kWLoads; ++i) {
-                int c = cp - (row >> 2);
-                c = c < 0 ? c + kHalfChunks : c;
-                wvo[i] = (uint32_t)(row * (2 * kHalfChunks) + c) * 16u;
-                cp += 64 - kHalfChunks;
-                ++row;
-                if (cp >= kHalfChunks) {
-                    cp -= kHalfChunks;
-                    ++row;
-                }
+            for (int i = 0; i < kQLoads; ++i) {
+                const int L = i * 64 + lane, row = L / kQC;
+                int c = L % kQC - (row >> 3);
+                c = c < 0 ? c + kQC : c;
+                wvo[i] = (uint32_t)(row * (4 * kQC) + c) * 16u;
             }
             const int frow = lane & 31;
+            auto issue_q = [&](int q, int sub) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-#pragma unroll
-                for (int i = 0; i < kWLoads; ++i) {
+                for (int i = 0; i < kQLoads; ++i) {
                     const uint32_t vo = wvo[i];
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (__attribute__((address_space(3))) void *)(wreg + i * 1024),
-                                                             16, vo, h * (kHalfChunks * 16), 0, 0);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (__attribute__((address_space(3))) void *)(wreg + sub * kQBytes + i * 1024),
+                                                             16, vo, q * (kQC * 16), 0, 0);
                 }
-                wait_vmem<0>();
+            };
+            auto read_q = [&](int q, int sub) {
 #pragma unroll
-                for (int kk = 0; kk < KSUB / 2; ++kk) {
-                    int p = 2 * kk + (lane >> 5) + (frow >> 2);
-                    p = p >= kHalfChunks ? p - kHalfChunks : p;
-                    wf[h * (KSUB / 2) + kk] = *reinterpret_cast<const bf16x8_t *>(wreg + (frow * kHalfChunks + p) * 16);
+                for (int kk = 0; kk < KSUB / 4; ++kk) {
+                    int p = 2 * kk + (lane >> 5) + (frow >> 3);
+                    p = p >= kQC ? p - kQC : p;
+                    wf[q * (KSUB / 4) + kk] = *reinterpret_cast<const bf16x8_t *>(wreg + sub * kQBytes + (frow * kQC + p) * 16);
                 }
-                wait_vmem_and_lds<0>();  // the region is rewritten by the next half / released at the barrier
-            }
+            };
+            issue_q(0, 0);
+            issue_q(1, 1);
+            wait_vmem<kQLoads>();
+            read_q(0, 0);
+            wait_vmem_and_lds<kQLoads>();
+            issue_q(2, 0);
+            wait_vmem<kQLoads>();
+            read_q(1, 1);
+            wait_vmem_and_lds<kQLoads>();
+            issue_q(3, 1);
+            wait_vmem<kQLoads>();
+            read_q(2, 0);
+            wait_vmem<0>();
+            read_q(3, 1);
+            wait_vmem_and_lds<0>();
         }
         const int frag_lo = frag_offset(lane & 31, lane >> 5);        // k-substep 0 of a sub-tile
         const int frag_hi = frag_offset(lane & 31, 2 + (lane >> 5));  // k-substep 1
@@ -496,7 +505,7 @@ static perf_status launch_conv_wreg(const void *x, const void *w, void *y, const
 {
     constexpr int kSlot = (R * S * (C / 32)) * 2048;
     constexpr int kRing = 3 * kSlot + 2 * 32 * (128 * (int)sizeof(CT) + 16);
-    constexpr int kWeights = 2 * kSlot + 128 * R * S * C;  // prologue: half of the weights behind ring slots 0 and 1
+    constexpr int kWeights = 2 * kSlot + 128 * R * S * C;  // prologue: two quarters of the weights behind ring slots 0 and 1
     constexpr int kLds = kRing > kWeights ? kRing : kWeights;
     static_assert(kLds <= 160 * 1024, "LDS of one CU");
     const int64_t Mtot = (int64_t)g.N * g.P * g.Q;
