@@ -7,8 +7,9 @@
 //    registers, sum of squares by a DPP / permlane butterfly, scale, 16-byte stores; gamma is
 //    staged once per workgroup in LDS.  rmsnorm_block_kernel: general fallback.
 //  * rowmean_kernel: a wavefront per row, any length.
-//  * colmean_kernel: a workgroup owns 4 chunks of 16 bytes of every row (64 contiguous
-//    bytes per row); 64 row lanes stride over the rows and are combined through LDS.
+//  * colmean_kernel: a workgroup owns 4 or 8 chunks of 16 bytes of every row (64 or 128
+//    contiguous bytes per row); 64 or 32 row lanes stride over the rows and are combined
+//    through LDS; workgroups that share 128-byte lines are placed on the same XCD.
 //  * eltwise_kernel: one pass, four 16-byte vectors per thread.
 #include "row_io.h"
 #include "host_utils.h"
@@ -213,28 +214,35 @@ __global__ __launch_bounds__(256) void rowmean_kernel(const XT *__restrict__ x, 
     }
 }
 
-// Mean of every column, 16-byte path: thread = (row lane tid/4, chunk tid%4); a workgroup
-// owns the 4*E columns starting at blockIdx.x * 4 * E.
-template <typename XT, typename YT>
+// Mean of every column, 16-byte path: thread = (row lane tid/CW, chunk tid%CW); a workgroup
+// owns CW chunks of 16 bytes (CW * E columns) of every row.  With CW = 8 and 16-byte elements
+// groups of 4 the workgroup reads whole 128-byte lines; with CW = 4 two neighbouring
+// workgroups share each line, and the group index is remapped so that they run on the same
+// XCD (workgroup ids are dealt round-robin to the 8 XCDs, whose L2s are private: without the
+// remap both XCDs fetch the line from memory).
+template <typename XT, typename YT, int CW>
 __global__ __launch_bounds__(256) void colmean_kernel(const XT *__restrict__ x, YT *__restrict__ y, int64_t rows,
                                                       int64_t cols, int64_t ldx)
 {
     constexpr int E = Elem<XT>::kPerChunk;
+    constexpr int kRowLanes = 256 / CW;
     constexpr int kUnroll = 16;  // 16 x 16 bytes in flight per thread: 64 KiB per workgroup
-    __shared__ float part[64][4 * E + 1];
-    const int cl = threadIdx.x & 3, rl = threadIdx.x >> 2;
-    const int64_t col0 = ((int64_t)blockIdx.x * 4 + cl) * E;
+    __shared__ float part[kRowLanes][CW * E + 1];
+    const int64_t group = gridDim.x % 8 == 0 ? (int64_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)
+                                             : (int64_t)blockIdx.x;
+    const int cl = threadIdx.x % CW, rl = threadIdx.x / CW;
+    const int64_t col0 = (group * CW + cl) * E;
     float acc[E];
 #pragma unroll
     for (int e = 0; e < E; ++e) acc[e] = 0.f;
     if (col0 < cols) {  // cols is a multiple of E
         const XT *xc = x + col0;
         int64_t r = rl;
-        for (; r + 64 * (kUnroll - 1) < rows; r += 64 * kUnroll) {
+        for (; r + kRowLanes * (kUnroll - 1) < rows; r += kRowLanes * kUnroll) {
             uint4_t raw[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)
-                raw[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xc + (r + 64 * u) * ldx));
+                raw[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xc + (r + kRowLanes * u) * ldx));
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 float v[E];
@@ -243,7 +251,7 @@ __global__ __launch_bounds__(256) void colmean_kernel(const XT *__restrict__ x, 
                 for (int e = 0; e < E; ++e) acc[e] += v[e];
             }
         }
-        for (; r < rows; r += 64) {
+        for (; r < rows; r += kRowLanes) {
             float v[E];
             Elem<XT>::unpack(__builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xc + r * ldx)), v);
 #pragma unroll
@@ -253,11 +261,11 @@ __global__ __launch_bounds__(256) void colmean_kernel(const XT *__restrict__ x, 
 #pragma unroll
     for (int e = 0; e < E; ++e) part[rl][cl * E + e] = acc[e];
     __syncthreads();
-    if (threadIdx.x < 4 * E) {
-        const int64_t col = (int64_t)blockIdx.x * 4 * E + threadIdx.x;
+    if (threadIdx.x < CW * E) {
+        const int64_t col = group * CW * E + threadIdx.x;
         if (col < cols) {
             float s = 0.f;
-            for (int i = 0; i < 64; ++i) s += part[i][threadIdx.x];
+            for (int i = 0; i < kRowLanes; ++i) s += part[i][threadIdx.x];
             Elem<YT>::store1(y + col, s / (float)rows);
         }
     }
@@ -286,8 +294,14 @@ static void launch_mean(const void *x, void *y, int64_t rows, int64_t cols, int6
         auto kern = vec ? rowmean_kernel<XT, YT, true> : rowmean_kernel<XT, YT, false>;
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, st, (const XT *)x, (YT *)y, rows, cols, ldx);
     } else if (vec) {
-        hipLaunchKernelGGL((colmean_kernel<XT, YT>), dim3((unsigned)((cols + 4 * E - 1) / (4 * E))), dim3(256), 0, st,
-                           (const XT *)x, (YT *)y, rows, cols, ldx);
+        // whole 128-byte lines per workgroup when that still gives every CU a workgroup
+        constexpr int kWide = 8;
+        if ((cols + kWide * E - 1) / (kWide * E) >= 256)
+            hipLaunchKernelGGL((colmean_kernel<XT, YT, kWide>), dim3((unsigned)((cols + kWide * E - 1) / (kWide * E))),
+                               dim3(256), 0, st, (const XT *)x, (YT *)y, rows, cols, ldx);
+        else
+            hipLaunchKernelGGL((colmean_kernel<XT, YT, 4>), dim3((unsigned)((cols + 4 * E - 1) / (4 * E))), dim3(256), 0,
+                               st, (const XT *)x, (YT *)y, rows, cols, ldx);
     } else {
         hipLaunchKernelGGL((colmean_scalar_kernel<XT, YT>), dim3((unsigned)((cols + 255) / 256)), dim3(256), 0, st,
                            (const XT *)x, (YT *)y, rows, cols, ldx);
