@@ -252,6 +252,13 @@ def build_paper_workloads(torch, perf):
                         lambda i: perf.perf_reduce_mean(xm[i % 8].data_ptr(), ym[i % 8].data_ptr(), 4096, 4096, 4096, 0,
                                                         F32, F32, st()), 8,
                         "one workgroup per 16 columns (64-byte row segments), no workspace, no atomics"))
+    wsm = torch.empty(max(4, perf.perf_reduce_mean_workspace_bytes(4096, 4096, 0, F32)) // 4, dtype=torch.float32,
+                      device="cuda"); keep.append(wsm)
+    wls.append(Workload("paper_reducemean_4096x4096_f32_axis0_workspace", "colsum_partial_kernel<f32> + colsum_final_kernel",
+                        "hbm", 4 * 4096 * 4096,
+                        lambda i: perf.perf_reduce_mean_ws(xm[i % 8].data_ptr(), ym[i % 8].data_ptr(), wsm.data_ptr(), 4096,
+                                                           4096, 4096, 0, F32, F32, st()), 8,
+                        "two launches through a 2 MiB caller-supplied workspace: row ranges of 1 KiB-wide column blocks"))
     ya = torch.empty_like(xr); keep.append(ya)
     n_add = 3072 * 4096
     wls.append(Workload("paper_add_3072x4096_f32", "eltwise_kernel<add,f32>", "hbm", 12 * n_add,

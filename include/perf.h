@@ -166,6 +166,21 @@ perf_status perf_batchnorm(const void *x, const void *gamma, const void *beta, v
 perf_status perf_reduce_mean(const void *x, void *y, int64_t rows, int64_t cols, int64_t ldx, int axis,
                              perf_dtype x_dt, perf_dtype y_dt, perf_stream stream);
 
+/* The same operator with a caller-supplied workspace.  For axis 0 (16-byte-aligned x, cols and
+ * ldx multiples of 16 bytes) the rows are split among workgroups that each sum a 1 KiB-wide
+ * column block, and the partial sums are merged in a fixed order by a second kernel: the grid
+ * no longer depends on the number of columns and memory is read in long runs.  Every other
+ * case is perf_reduce_mean itself.
+ *   workspace  device, at least perf_reduce_mean_workspace_bytes(rows, cols, axis, x_dt) bytes,
+ *              4-byte aligned, owned by the caller, contents are scratch; may be NULL when
+ *              that size is 0 (axis 1, or cols not a multiple of 16 bytes)
+ * perf_reduce_mean_workspace_bytes returns -1 for arguments perf_reduce_mean_ws would reject.
+ * Errors: as perf_reduce_mean; NULL / ALIGN also for a missing or misaligned workspace. */
+int64_t perf_reduce_mean_workspace_bytes(int64_t rows, int64_t cols, int axis, perf_dtype x_dt);
+perf_status perf_reduce_mean_ws(const void *x, void *y, void *workspace, int64_t rows, int64_t cols,
+                                int64_t ldx, int axis, perf_dtype x_dt, perf_dtype y_dt,
+                                perf_stream stream);
+
 /* Element-wise operators of the table ("add", "mul", "relu") on n contiguous elements:
  * y = a + b, a * b, or max(a, 0) (b ignored, may be NULL).  One dtype for all operands;
  * fp32 arithmetic, one rounding to dt.  y may equal a or b exactly.

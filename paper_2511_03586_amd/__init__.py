@@ -33,6 +33,8 @@ SIGNATURES = {
                                  _int, _int, _ptr]),
     "perf_rmsnorm": (_int, [_ptr, _ptr, _ptr, _ptr, _i64, _i64, _i64, _i64, _f32, _int, _int, _int, _ptr]),
     "perf_reduce_mean": (_int, [_ptr, _ptr, _i64, _i64, _i64, _int, _int, _int, _ptr]),
+    "perf_reduce_mean_workspace_bytes": (_i64, [_i64, _i64, _int, _int]),
+    "perf_reduce_mean_ws": (_int, [_ptr, _ptr, _ptr, _i64, _i64, _i64, _int, _int, _int, _ptr]),
     "perf_eltwise": (_int, [_int, _ptr, _ptr, _ptr, _i64, _int, _ptr]),
     "perf_gemm_variant": (_int, [_ptr, _ptr, _ptr, _i64, _i64, _i64, _int, _i64, _int, _i64, _i64, _i64, _i64, _i64, _i64,
                                  _f32, _int, _int, _int, _int, _ptr]),
@@ -145,6 +147,16 @@ def perf_rmsnorm(x, gamma, y, rrms_out, rows, cols, ldx, ldy, eps, x_dt=PERF_BF1
 
 def perf_reduce_mean(x, y, rows, cols, ldx, axis, x_dt=PERF_F32, y_dt=PERF_F32, stream=None, check=True) -> int:
     return _check("perf_reduce_mean", lib().perf_reduce_mean(x, y, rows, cols, ldx, axis, x_dt, y_dt, stream), check)
+
+
+def perf_reduce_mean_workspace_bytes(rows, cols, axis, x_dt=PERF_F32) -> int:
+    return int(lib().perf_reduce_mean_workspace_bytes(rows, cols, axis, x_dt))
+
+
+def perf_reduce_mean_ws(x, y, workspace, rows, cols, ldx, axis, x_dt=PERF_F32, y_dt=PERF_F32, stream=None,
+                        check=True) -> int:
+    return _check("perf_reduce_mean_ws",
+                  lib().perf_reduce_mean_ws(x, y, workspace, rows, cols, ldx, axis, x_dt, y_dt, stream), check)
 
 
 def perf_eltwise(op, a, b, y, n, dt=PERF_F32, stream=None, check=True) -> int:

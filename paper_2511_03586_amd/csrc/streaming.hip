@@ -308,6 +308,121 @@ static void launch_mean(const void *x, void *y, int64_t rows, int64_t cols, int6
     }
 }
 
+// ---- column mean in two stages (caller-supplied workspace) ----------------------------
+// Stage 1: workgroup (cb, sp) sums rows [sp * rows_per, (sp+1) * rows_per) of the 64 chunks
+// of 16 bytes starting at chunk cb * 64: a wave reads 1 KiB of one row per instruction, so
+// the memory sees long contiguous runs instead of one cache line per row, and the grid is
+// as large as the row split makes it, whatever the number of columns.  Stage 2 adds the
+// partial sums of a column in split order.  Both orders are fixed: results are reproducible.
+constexpr int kColsumTargetGroups = 2048;  // workgroups aimed for in stage 1
+constexpr int kColsumMinRows = 32;         // rows per workgroup at least (8 per wave)
+constexpr int kColsumUnroll = 8;
+
+struct ColsumPlan {
+    int64_t col_blocks, splits, rows_per;
+};
+static ColsumPlan colsum_plan(int64_t rows, int64_t cols, int E)
+{
+    ColsumPlan p;
+    p.col_blocks = (cols + 64 * E - 1) / (64 * E);
+    int64_t splits = (kColsumTargetGroups + p.col_blocks - 1) / p.col_blocks;
+    const int64_t max_splits = (rows + kColsumMinRows - 1) / kColsumMinRows;
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    p.rows_per = ((rows + splits - 1) / splits + 3) / 4 * 4;
+    p.splits = (rows + p.rows_per - 1) / p.rows_per;
+    return p;
+}
+
+template <typename XT>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const XT *__restrict__ x, float *__restrict__ ws,
+                                                             int64_t rows, int64_t cols, int64_t ldx, int64_t rows_per)
+{
+    constexpr int E = Elem<XT>::kPerChunk;
+    __shared__ float part[4][64 * E];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t col0 = ((int64_t)blockIdx.x * 64 + lane) * E;
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per;
+    const int64_t r1 = r0 + rows_per < rows ? r0 + rows_per : rows;
+    float acc[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[e] = 0.f;
+    if (col0 < cols) {  // cols is a multiple of E
+        const XT *xc = x + col0;
+        int64_t r = r0 + wave;
+        for (; r + 4 * (kColsumUnroll - 1) < r1; r += 4 * kColsumUnroll) {
+            uint4_t raw[kColsumUnroll];
+#pragma unroll
+            for (int u = 0; u < kColsumUnroll; ++u)
+                raw[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xc + (r + 4 * u) * ldx));
+#pragma unroll
+            for (int u = 0; u < kColsumUnroll; ++u) {
+                float v[E];
+                Elem<XT>::unpack(raw[u], v);
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc[e] += v[e];
+            }
+        }
+        for (; r < r1; r += 4) {
+            float v[E];
+            Elem<XT>::unpack(__builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xc + r * ldx)), v);
+#pragma unroll
+            for (int e = 0; e < E; ++e) acc[e] += v[e];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < E; ++e) part[wave][e * 64 + lane] = acc[e];
+    __syncthreads();
+    for (int i = threadIdx.x; i < 64 * E; i += 256) {
+        const int e = i / 64, l = i % 64;
+        const int64_t col = ((int64_t)blockIdx.x * 64 + l) * E + e;
+        if (col < cols) ws[(int64_t)blockIdx.y * cols + col] = (part[0][i] + part[1][i]) + (part[2][i] + part[3][i]);
+    }
+}
+
+// Stage 2 (1024 threads): thread = (column tid%32 of the block, split lane tid/32): a row of 32 lanes reads
+// one 128-byte line of a split's partial sums; a lane has 8 independent loads in flight
+// (splits sl, sl+32, .. in batches of 8); the 32 split lanes are combined through LDS in
+// lane order.
+template <typename YT>
+__global__ __launch_bounds__(1024) void colsum_final_kernel(const float *__restrict__ ws, YT *__restrict__ y,
+                                                           int64_t rows, int64_t cols, int64_t splits)
+{
+    constexpr int kLanes = 32, kBatch = 8;
+    __shared__ float part[kLanes][32 + 1];
+    const int cl = threadIdx.x & 31, sl = threadIdx.x >> 5;
+    const int64_t col = (int64_t)blockIdx.x * 32 + cl;
+    float s = 0.f;
+    if (col < cols) {
+        for (int64_t sp = sl; sp < splits; sp += kLanes * kBatch) {
+            float v[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) v[u] = sp + u * kLanes < splits ? ws[(sp + u * kLanes) * cols + col] : 0.f;
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) s += v[u];
+        }
+    }
+    part[sl][cl] = s;
+    __syncthreads();
+    if (sl == 0 && col < cols) {
+        float t = 0.f;
+#pragma unroll
+        for (int i = 0; i < kLanes; ++i) t += part[i][cl];
+        Elem<YT>::store1(y + col, t / (float)rows);
+    }
+}
+
+template <typename XT, typename YT>
+static void launch_colmean_ws(const void *x, void *y, float *ws, int64_t rows, int64_t cols, int64_t ldx, hipStream_t st)
+{
+    constexpr int E = Elem<XT>::kPerChunk;
+    const ColsumPlan p = colsum_plan(rows, cols, E);
+    hipLaunchKernelGGL((colsum_partial_kernel<XT>), dim3((unsigned)p.col_blocks, (unsigned)p.splits), dim3(256), 0, st,
+                       (const XT *)x, ws, rows, cols, ldx, p.rows_per);
+    hipLaunchKernelGGL((colsum_final_kernel<YT>), dim3((unsigned)((cols + 31) / 32)), dim3(1024), 0, st, (const float *)ws,
+                       (YT *)y, rows, cols, p.splits);
+}
+
 // ---- element-wise --------------------------------------------------------------------
 template <int OP> __device__ __forceinline__ float apply_op(float a, float b)
 {
@@ -423,6 +538,47 @@ extern "C" perf_status perf_reduce_mean(const void *x, void *y, int64_t rows, in
     } else {
         if (y_dt == PERF_F32) launch_mean<uint16_t, float>(x, y, rows, cols, ldx, axis, st);
         else launch_mean<uint16_t, uint16_t>(x, y, rows, cols, ldx, axis, st);
+    }
+    return launch_status();
+}
+
+extern "C" int64_t perf_reduce_mean_workspace_bytes(int64_t rows, int64_t cols, int axis, perf_dtype x_dt)
+{
+    using namespace perf;
+    if (!dtype_ok(x_dt) || rows < 1 || cols < 1 || (axis != 0 && axis != 1)) return -1;
+    if (cols > (int64_t)kMaxGridX * 16) return -1;
+    const int E = x_dt == PERF_F32 ? 4 : 8;
+    if (axis == 1 || cols % E != 0) return 0;
+    const ColsumPlan p = colsum_plan(rows, cols, E);
+    if (p.splits > 65535) return -1;
+    return p.splits * cols * (int64_t)sizeof(float);
+}
+
+extern "C" perf_status perf_reduce_mean_ws(const void *x, void *y, void *workspace, int64_t rows, int64_t cols,
+                                           int64_t ldx, int axis, perf_dtype x_dt, perf_dtype y_dt, perf_stream stream)
+{
+    using namespace perf;
+    if (!x || !y) return PERF_ERR_NULL;
+    if (!dtype_ok(x_dt) || !dtype_ok(y_dt)) return PERF_ERR_DTYPE;
+    if (rows < 1 || cols < 1 || ldx < cols || (axis != 0 && axis != 1)) return PERF_ERR_SHAPE;
+    const int64_t need = perf_reduce_mean_workspace_bytes(rows, cols, axis, x_dt);
+    if (need < 0) return PERF_ERR_SHAPE;
+    if (need > 0 && !workspace) return PERF_ERR_NULL;
+    if (need > 0 && !aligned(workspace, 4)) return PERF_ERR_ALIGN;
+    const int E = x_dt == PERF_F32 ? 4 : 8;
+    // the two-stage path needs 16-byte accesses; everything else is the plain entry point's work
+    if (need == 0 || ldx % E != 0 || !aligned(x, 16))
+        return perf_reduce_mean(x, y, rows, cols, ldx, axis, x_dt, y_dt, stream);
+    if (rows > (INT64_MAX / 4) / ldx) return PERF_ERR_SHAPE;
+    if (!aligned(y, dtype_size(y_dt))) return PERF_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *ws = static_cast<float *>(workspace);
+    if (x_dt == PERF_F32) {
+        if (y_dt == PERF_F32) launch_colmean_ws<float, float>(x, y, ws, rows, cols, ldx, st);
+        else launch_colmean_ws<float, uint16_t>(x, y, ws, rows, cols, ldx, st);
+    } else {
+        if (y_dt == PERF_F32) launch_colmean_ws<uint16_t, float>(x, y, ws, rows, cols, ldx, st);
+        else launch_colmean_ws<uint16_t, uint16_t>(x, y, ws, rows, cols, ldx, st);
     }
     return launch_status();
 }

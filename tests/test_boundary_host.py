@@ -149,6 +149,24 @@ def test_streaming_ops_argument_errors():
     assert m(axis=2) == perf.PERF_ERR_SHAPE
     assert m(y_dt=3) == perf.PERF_ERR_DTYPE
     assert m(x=FAKE + 2) == perf.PERF_ERR_ALIGN
+    mw = lambda **k: perf.perf_reduce_mean_ws(**{**dict(x=FAKE, y=FAKE + 4096, workspace=FAKE + 8192, rows=64, cols=8, ldx=8,
+                                                        axis=0, check=False), **k})
+    assert perf.perf_reduce_mean_workspace_bytes(64, 8, 0) == 2 * 8 * 4         # two row ranges of 32 rows
+    assert perf.perf_reduce_mean_workspace_bytes(4096, 4096, 0) == 128 * 4096 * 4
+    assert perf.perf_reduce_mean_workspace_bytes(4096, 4096, 0, perf.PERF_BF16) == 128 * 4096 * 4
+    assert perf.perf_reduce_mean_workspace_bytes(64, 8, 1) == 0                 # axis 1 needs none
+    assert perf.perf_reduce_mean_workspace_bytes(64, 7, 0) == 0                 # not whole 16-byte chunks: plain path
+    assert perf.perf_reduce_mean_workspace_bytes(0, 8, 0) == -1
+    assert perf.perf_reduce_mean_workspace_bytes(8, 8, 2) == -1
+    assert perf.perf_reduce_mean_workspace_bytes(8, 8, 0, 7) == -1
+    assert mw(x=None) == perf.PERF_ERR_NULL
+    assert mw(workspace=None) == perf.PERF_ERR_NULL
+    assert mw(workspace=FAKE + 8194) == perf.PERF_ERR_ALIGN
+    assert mw(rows=0) == perf.PERF_ERR_SHAPE
+    assert mw(ldx=7) == perf.PERF_ERR_SHAPE
+    assert mw(axis=3) == perf.PERF_ERR_SHAPE
+    assert mw(x_dt=9) == perf.PERF_ERR_DTYPE
+    assert mw(x=FAKE + 2) == perf.PERF_ERR_ALIGN                                # falls to the plain path, which rejects it
     e = lambda **k: perf.perf_eltwise(**{**dict(op=perf.PERF_ADD, a=FAKE, b=FAKE + 4096, y=FAKE + 8192, n=16, check=False), **k})
     assert e(a=None) == perf.PERF_ERR_NULL
     assert e(b=None) == perf.PERF_ERR_NULL

@@ -79,15 +79,25 @@ def test_rmsnorm_closed_forms_on_gpu():
     np.testing.assert_allclose(y, np.sign(x), rtol=2e-7)
 
 
-def _run_mean(x, axis, x_bf16, y_bf16, ldx=None):
+def _run_mean(x, axis, x_bf16, y_bf16, ldx=None, ws=False):
     rows, cols = x.shape
     ldx = ldx or cols
     xb = np.zeros((rows, ldx), dtype=x.dtype); xb[:, :cols] = x
     xd = G.dev(xb.ravel())
     n = rows if axis == 1 else cols
     yd = torch.zeros(n, dtype=torch.int16 if y_bf16 else torch.float32, device="cuda")
-    perf.perf_reduce_mean(xd.data_ptr(), yd.data_ptr(), rows, cols, ldx, axis, G.dt(x_bf16), G.dt(y_bf16), G.stream())
-    torch.cuda.synchronize()
+    if ws:
+        nbytes = perf.perf_reduce_mean_workspace_bytes(rows, cols, axis, G.dt(x_bf16))
+        assert nbytes >= 0
+        # scratch with junk in it, a guard word behind it
+        wd = torch.full((nbytes // 4 + 1,), float("nan"), dtype=torch.float32, device="cuda")
+        perf.perf_reduce_mean_ws(xd.data_ptr(), yd.data_ptr(), wd.data_ptr() if nbytes else None, rows, cols, ldx, axis,
+                                 G.dt(x_bf16), G.dt(y_bf16), G.stream())
+        torch.cuda.synchronize()
+        assert bool(torch.isnan(wd[-1]))  # nothing written past the stated size
+    else:
+        perf.perf_reduce_mean(xd.data_ptr(), yd.data_ptr(), rows, cols, ldx, axis, G.dt(x_bf16), G.dt(y_bf16), G.stream())
+        torch.cuda.synchronize()
     return G.host(yd, y_bf16)
 
 
@@ -100,6 +110,34 @@ def test_reduce_mean_fp32(rows, cols, axis):
     ref = oracle.reduce_mean(x.astype(np.float64), axis)
     floor = np.sqrt(np.mean(x.astype(np.float64) ** 2))
     assert np.max(np.abs(y - ref) / np.maximum(np.abs(ref), floor)) <= 1e-5
+
+
+@pytest.mark.parametrize("rows,cols", [(4096, 4096), (100, 1000), (1, 4), (3, 8), (257, 96), (64, 20000), (5000, 32),
+                                       (16384, 1024), (70, 33), (33, 260)])
+@pytest.mark.parametrize("axis", [0, 1])
+def test_reduce_mean_with_workspace_fp32(rows, cols, axis):
+    g = np.random.default_rng(rows + cols + axis)
+    x = (g.standard_normal((rows, cols)) * 2 + 0.5).astype(np.float32)
+    y = _run_mean(x, axis, False, False, ws=True)
+    ref = oracle.reduce_mean(x.astype(np.float64), axis)
+    floor = np.sqrt(np.mean(x.astype(np.float64) ** 2))
+    assert np.max(np.abs(y - ref) / np.maximum(np.abs(ref), floor)) <= 1e-5
+
+
+def test_reduce_mean_with_workspace_bf16_padded_exact_and_reproducible():
+    g = np.random.default_rng(4)
+    x = (g.standard_normal((300, 264)) + 1).astype(np.float32)
+    xb = _bf16(x)
+    y = _run_mean(xb, 0, True, True, ldx=272, ws=True)
+    ref = oracle.reduce_mean(oracle.widen(xb, True), 0)
+    assert np.all(np.abs(P.bf16_to_f64(y) - ref) <= 2.0 ** -8 * np.maximum(np.abs(ref), 2.0 ** -7) + 1e-5)
+    y32 = _run_mean(xb, 0, True, False, ldx=272, ws=True)
+    assert np.max(np.abs(y32 - ref)) <= 1e-5 * 1.5
+    xi = g.integers(-8, 9, (1024, 512)).astype(np.float32)        # sums exact in fp32, count a power of two
+    np.testing.assert_array_equal(_run_mean(xi, 0, False, False, ws=True),
+                                  oracle.reduce_mean(xi.astype(np.float64), 0).astype(np.float32))
+    xr = (g.standard_normal((2048, 768)) * 3).astype(np.float32)  # fixed summation order: bit-identical reruns
+    np.testing.assert_array_equal(_run_mean(xr, 0, False, False, ws=True), _run_mean(xr, 0, False, False, ws=True))
 
 
 def test_reduce_mean_bf16_padded_and_exact_integers():
