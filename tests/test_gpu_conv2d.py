@@ -41,6 +41,16 @@ def test_mfma_path_shapes(kw):
     _check(configs.ConvWorkload(**kw))
 
 
+@pytest.mark.parametrize("kw", [dict(N=2), dict(N=1, H=12, W=40), dict(N=3, H=33, W=35), dict(N=1, H=40, W=70, stride=2),
+                                dict(N=5, pad=0), dict(N=1, H=3, W=32)])
+@pytest.mark.parametrize("y_bf16", [True, False])
+def test_weights_in_registers_kernel(kw, y_bf16):
+    # ragged last blocks, odd and even block counts per workgroup, fewer workgroups than CUs,
+    # stride 2, no padding
+    import paper_2511_03586_amd as perf
+    _check(configs.ConvWorkload(**kw), y_bf16=y_bf16, variant=perf.CONV_WREG)
+
+
 def test_mfma_rectangular_filter_and_mixed_stride_pad():
     wl = configs.ConvWorkload(N=2, H=9, W=14, C=64, K=48, R=1, S=3)
     _check(wl, pad=(0, 1))
