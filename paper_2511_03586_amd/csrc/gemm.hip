@@ -28,15 +28,16 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
     tn = within / rows_in_band;
 }
 
-template <int TM, int TN, int WM, int WN, bool K64, typename CT>
+template <int TM, int TN, int WM, int WN, bool K64, typename CT, int NS = kStages>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t *__restrict__ A,
                                                                  const uint16_t *__restrict__ B, CT *__restrict__ C,
                                                                  int M, int N, int K, int64_t lda, int64_t ldb,
                                                                  int64_t ldc, int64_t strideA, int64_t strideB,
                                                                  int64_t strideC, float alpha, int tiles_m, int tiles_n)
 {
-    using Shape = TileShape<TM, TN, WM, WN>;
+    using Shape = TileShape<TM, TN, WM, WN, NS>;
     constexpr int BM = Shape::BM, BN = Shape::BN, NW = Shape::kWaves;
+    static_assert(!K64 || NS == kStages, "the ring depth is a parameter of the K-step-32 loop only");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t 
             RowMajorSrc<Shape::kLoadsB, NW> src_b(Bb + (int64_t)n0 * ldb, min(BN, N - n0), ldb, ktiles, wave, lane);
             WaveTile<TM, TN> t;
             t.clear();
-            mfma_mainloop<TM, TN, WM, WN>(t, smem, ktiles, wave, lane, a_row0, b_row0, src_a, src_b);
+            mfma_mainloop<TM, TN, WM, WN, NS>(t, smem, ktiles, wave, lane, a_row0, b_row0, src_a, src_b);
             store_tile<TM, TN, CT>(t, Cb, ldc, M, N, m0 + a_row0, n0 + b_row0, alpha, lane);
         }
     }
@@ -160,14 +161,14 @@ struct GemmArgs {
     hipStream_t st;
 };
 
-template <int TM, int TN, int WM, int WN, bool K64, typename CT>
+template <int TM, int TN, int WM, int WN, bool K64, typename CT, int NS = kStages>
 static perf_status launch_mfma(const GemmArgs &g)
 {
-    using Shape = TileShape<TM, TN, WM, WN>;
+    using Shape = TileShape<TM, TN, WM, WN, NS>;
     constexpr int BM = Shape::BM, BN = Shape::BN;
     const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
     const size_t lds = Shape::kLdsBytes;
-    auto kern = gemm_mfma_kernel<TM, TN, WM, WN, K64, CT>;
+    auto kern = gemm_mfma_kernel<TM, TN, WM, WN, K64, CT, NS>;
     static bool attr_done = false;  // raising the dynamic-LDS cap is a per-function, idempotent setting
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -211,6 +212,8 @@ static perf_status launch_mfma_rt(const GemmArgs &g, bool k64, bool c_f32)
     return c_f32 ? launch_mfma<TM, TN, WM, WN, false, float>(g) : launch_mfma<TM, TN, WM, WN, false, uint16_t>(g);
 }
 
+constexpr int kDeepRing = 33;  // `kstep` code of the K-step-32 loop with the deep ring
+
 // tile / kstep: 0 = chosen here from the shape; otherwise the caller's choice (perf_gemm_variant).
 static perf_status gemm_impl(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K, perf_layout la,
                              int64_t lda, perf_layout lb, int64_t ldb, int64_t ldc, int64_t batch, int64_t strideA,
@@ -241,7 +244,8 @@ static perf_status gemm_impl(const void *A, const void *B, void *C, int64_t M, i
                          aligned(B, 16) && lda <= (1 << 21) && ldb <= (1 << 21) && M <= (1 << 30) && N <= (1 << 30) && K <= (1 << 30) &&
                          ((M + 63) / 64) * ((N + 63) / 64) <= kMaxGridX;
     if (tile != 0 || kstep != 0) {  // the caller's variant: only the MFMA kernels have variants
-        if (!mfma_ok || (tile != 64 && tile != 128 && tile != 256) || (kstep != 32 && kstep != 64) || K % kstep != 0)
+        if (!mfma_ok || (tile != 64 && tile != 128 && tile != 256) || (kstep != 32 && kstep != 64 && kstep != kDeepRing) ||
+            (kstep == 64 && K % 64 != 0) || (kstep == kDeepRing && tile == 256))
             return PERF_ERR_UNSUPPORTED;
     }
     if (mfma_ok) {
@@ -251,12 +255,24 @@ static perf_status gemm_impl(const void *A, const void *B, void *C, int64_t M, i
             const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256) * batch;
             const int64_t mid_tiles = ((M + 127) / 128) * ((N + 127) / 128) * batch;
             tile = big_tiles >= 256 ? 256 : mid_tiles >= 192 ? 128 : 64;
-            // the K-step-64 loop pays off in the main loop; short reductions are bound by the C
-            // store, which the other loop's epilogue (two full 128-byte row segments per store
-            // instruction, no lane exchange) does faster (measured on 512 x (512x512x64))
-            kstep = (K % 64 == 0 && K >= 512) ? 64 : 32;
+            // the K-step-64 loop pays off for the 256x256 tile with a long reduction; short
+            // reductions are bound by the C store, which the other loop's epilogue (two full
+            // 128-byte row segments per store instruction, no lane exchange) does faster (measured
+            // on 512 x (512x512x64)), and the smaller tiles measured faster on the K-step-32 loop on
+            // every shape tried.  When a single round of 64x64 tiles has a long reduction, the deep
+            // ring keeps 15 K-steps in flight (1024x1024x4096: 23.9 -> 20.2 us); it takes all the LDS,
+            // so it loses as soon as a CU should hold more than one workgroup.
+            const int64_t small_tiles = ((M + 63) / 64) * ((N + 63) / 64) * batch;
+            kstep = (tile == 256 && K % 64 == 0 && K >= 512) ? 64
+                    : (tile == 64 && small_tiles <= 256 && K >= 2048) ? kDeepRing
+                                                                      : 32;
         }
         const bool k64 = kstep == 64, c_f32 = c_dt == PERF_F32;
+        if (kstep == kDeepRing) {  // K-step 32, ring as deep as the LDS allows: 128 KiB either way
+            if (tile == 128)
+                return c_f32 ? launch_mfma<2, 2, 2, 2, false, float, 8>(g) : launch_mfma<2, 2, 2, 2, false, uint16_t, 8>(g);
+            return c_f32 ? launch_mfma<1, 1, 2, 2, false, float, 16>(g) : launch_mfma<1, 1, 2, 2, false, uint16_t, 16>(g);
+        }
         if (tile == 256) return launch_mfma_rt<4, 4, 2, 2>(g, k64, c_f32);
         if (tile == 128) return launch_mfma_rt<2, 2, 2, 2>(g, k64, c_f32);
         return launch_mfma_rt<1, 1, 2, 2>(g, k64, c_f32);

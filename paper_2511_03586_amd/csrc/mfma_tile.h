@@ -7,7 +7,8 @@
 //
 // Two loops share the machinery (direct global->LDS loads into an XOR-swizzled ring, partial
 // vmcnt waits, bare barriers, MFMAs interleaved one by one with the memory instructions):
-//   * mfma_mainloop: K-step 32 (64-byte LDS rows, ring of 4 stages, one barrier per step),
+//   * mfma_mainloop: K-step 32 (64-byte LDS rows, ring of NS stages (4, or as many as fit the
+//     LDS for small tiles whose short steps cannot hide the memory latency), one barrier per step),
 //     v_mfma_f32_32x32x16_bf16.  Any K that is a multiple of 32; the sources are objects, so
 //     the implicit-GEMM convolution plugs its gathered operand in here.
 //   * mfma_mainloop_k64: K-step 64 (128-byte LDS rows = whole cache lines per request, two
@@ -117,14 +118,14 @@ __device__ __forceinline__ void read_frags(bf16x8_t (&a)[TM], bf16x8_t (&b)[TN],
 }
 
 // Geometry of a workgroup tile.
-template <int TM, int TN, int WM, int WN>
+template <int TM, int TN, int WM, int WN, int NS = kStages>
 struct TileShape {
     static constexpr int kWaves = WM * WN;
     static constexpr int kThreads = 64 * kWaves;
     static constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     static constexpr int kLoadsA = BM / (16 * kWaves), kLoadsB = BN / (16 * kWaves);  // per lane per K-step
     static constexpr int kStageBytes = (BM + BN) * kRowBytes;
-    static constexpr int kLdsBytes = kStages * kStageBytes;
+    static constexpr int kLdsBytes = NS * kStageBytes;  // NS = depth of the K-step-32 loop's ring
     static_assert(BM % (16 * kWaves) == 0 && BN % (16 * kWaves) == 0, "stage rows must divide among the waves");
 };
 
@@ -175,7 +176,7 @@ __device__ __forceinline__ void mma_kstep(WaveTile<TM, TN> &t, const bf16x8_t (&
 //   order: a buffer resource `rsrc`, voffset(i) = per-lane byte offset of the 16-byte chunk
 //   fetched by load i (0 .. kLoadsA-1 / kLoadsB-1) of the current step, soffset() = uniform
 //   byte offset of the current step, advance() = go to the next step.  The loop advances up
-//   to 3 steps past the last one: a source must then keep naming readable (or out-of-range)
+//   to NS-1 steps past the last one: a source must then keep naming readable (or out-of-range)
 //   bytes; that data lands in a free stage and is never used, which keeps the number of
 //   loads in flight, and so the vmcnt waits, uniform.
 //   a_row0 / b_row0: first tile row of this wave's operands.  `wave` must be uniform.
@@ -183,22 +184,23 @@ __device__ __forceinline__ void mma_kstep(WaveTile<TM, TN> &t, const bf16x8_t (&
 // Schedule of step kt (operand registers F[kt&1] were filled during step kt-1):
 //   wait until this wave's loads of step kt+1 have landed and its reads of stage kt are back;
 //   barrier (now stage kt+1 is complete and stage kt is free for every wave);
-//   read stage kt+1 into F[(kt+1)&1], refill stage kt with step kt+4, and run the MFMAs of
+//   read stage kt+1 into F[(kt+1)&1], refill stage kt with step kt+NS, and run the MFMAs of
 //   step kt, the three instruction kinds interleaved.
-template <int TM, int TN, int WM, int WN, typename SrcA, typename SrcB>
+template <int TM, int TN, int WM, int WN, int NS = kStages, typename SrcA, typename SrcB>
 __device__ __forceinline__ void mfma_mainloop(WaveTile<TM, TN> &t, char *smem, int ktiles, int wave, int lane,
                                               int a_row0, int b_row0, SrcA &src_a, SrcB &src_b)
 {
-    using Shape = TileShape<TM, TN, WM, WN>;
+    using Shape = TileShape<TM, TN, WM, WN, NS>;
     constexpr int BM = Shape::BM;
     constexpr int kStageBytes = Shape::kStageBytes;
     constexpr int LA = Shape::kLoadsA, kLoads = Shape::kLoadsA + Shape::kLoadsB;
-    static_assert(3 * kLoads < 64, "three K-steps of loads must fit the vmcnt counter");
+    static_assert(NS >= 3 && (NS & (NS - 1)) == 0, "ring depth: a power of two");
+    static_assert((NS - 1) * kLoads < 64, "the loads in flight must fit the vmcnt counter");
     bf16x8_t fa[2][2][TM], fb[2][2][TN];  // [buffer][k-substep][tile]
 
     // loads of the sources' current K-step into ring slot kt % kStages; called with kt = 0, 1, 2, ...
     auto issue = [&](int kt) {
-        char *stage = smem + (kt % kStages) * kStageBytes;
+        char *stage = smem + (kt % NS) * kStageBytes;
 #pragma unroll
         for (int i = 0; i < kLoads; ++i) {
             if (i < LA)
@@ -211,15 +213,15 @@ __device__ __forceinline__ void mfma_mainloop(WaveTile<TM, TN> &t, char *smem, i
         src_b.advance();
     };
     auto read_step = [&](int kt, int buf) {
-        const char *stage = smem + (kt % kStages) * kStageBytes;
+        const char *stage = smem + (kt % NS) * kStageBytes;
         read_frags<TM, TN>(fa[buf][0], fb[buf][0], stage, stage + BM * kRowBytes, a_row0, b_row0, 0, lane);
         read_frags<TM, TN>(fa[buf][1], fb[buf][1], stage, stage + BM * kRowBytes, a_row0, b_row0, 1, lane);
     };
     auto step = [&](int kt, int buf) {
-        wait_vmem_and_lds<2 * kLoads>();
+        wait_vmem_and_lds<(NS - 2) * kLoads>();
         wg_barrier();
         read_step(kt + 1, buf ^ 1);
-        issue(kt + 4);
+        issue(kt + NS);
         mma_kstep<TM, TN>(t, fa[buf], fb[buf]);
         // interleave: one LDS read or one buffer load behind each of the first MFMAs
 #pragma unroll
@@ -235,11 +237,9 @@ __device__ __forceinline__ void mfma_mainloop(WaveTile<TM, TN> &t, char *smem, i
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    issue(0);
-    issue(1);
-    issue(2);
-    issue(3);
-    wait_vmem<3 * kLoads>();  // step 0 has landed
+#pragma unroll
+    for (int i = 0; i < NS; ++i) issue(i);
+    wait_vmem<(NS - 1) * kLoads>();  // step 0 has landed
     wg_barrier();
     read_step(0, 0);
 

@@ -74,7 +74,7 @@ def run_layernorm(x, gamma, beta, eps, x_bf16, p_bf16, y_bf16, want_stats=True, 
 
 
 def run_gemm(a, b, M, N, K, a_col=False, b_col=True, alpha=1.0, batch=1, ab_bf16=True, c_bf16=False,
-             lda=None, ldb=None, ldc=None):
+             lda=None, ldb=None, ldc=None, tile=0, kstep=0):
     """a, b: storage arrays (uint16 bits or float32), densely packed per batch with the
     given leading dimensions. Returns C as [batch, M, N] (uint16 bits if c_bf16)."""
     lda = lda or (M if a_col else K)
@@ -86,10 +86,14 @@ def run_gemm(a, b, M, N, K, a_col=False, b_col=True, alpha=1.0, batch=1, ab_bf16
     ad, bd = dev(np.ascontiguousarray(a).ravel()), dev(np.ascontiguousarray(b).ravel())
     assert ad.numel() >= batch * sa and bd.numel() >= batch * sb
     cd = torch.zeros(batch * sc, dtype=torch.int16 if c_bf16 else torch.float32, device="cuda")
-    perf.perf_gemm(ad.data_ptr(), bd.data_ptr(), cd.data_ptr(), M, N, K,
-                   perf.PERF_COL_MAJOR if a_col else perf.PERF_ROW_MAJOR, lda,
-                   perf.PERF_COL_MAJOR if b_col else perf.PERF_ROW_MAJOR, ldb, ldc,
-                   batch, sa, sb, sc, alpha, dt(ab_bf16), dt(c_bf16), stream())
+    la = perf.PERF_COL_MAJOR if a_col else perf.PERF_ROW_MAJOR
+    lb = perf.PERF_COL_MAJOR if b_col else perf.PERF_ROW_MAJOR
+    if tile or kstep:  # a named kernel variant instead of the library's own choice
+        perf.perf_gemm_variant(ad.data_ptr(), bd.data_ptr(), cd.data_ptr(), M, N, K, la, lda, lb, ldb, ldc,
+                               batch, sa, sb, sc, alpha, dt(ab_bf16), dt(c_bf16), tile, kstep, stream())
+    else:
+        perf.perf_gemm(ad.data_ptr(), bd.data_ptr(), cd.data_ptr(), M, N, K, la, lda, lb, ldb, ldc,
+                       batch, sa, sb, sc, alpha, dt(ab_bf16), dt(c_bf16), stream())
     torch.cuda.synchronize()
     c = host(cd, c_bf16).reshape(batch, M, ldc)
     assert np.all(c[:, :, N:] == 0), "kernel wrote into the row padding of C"

@@ -65,23 +65,39 @@ def test_alpha_bf16_output_batched_and_padded_ld():
 def test_mid_tile_kernels():
     # 128x128 tiles are chosen between 192 such tiles and 256 tiles of 256x256; smaller problems get 64x64 tiles
     _check(configs.GemmWorkload(M=1792, N=1800, K=64))      # K-step-32 loop, 128x128 tiles, ragged N
-    _check(configs.GemmWorkload(M=1792, N=1792, K=512))     # K-step-64 loop, 128x128 tiles
+    _check(configs.GemmWorkload(M=1792, N=1792, K=512))     # 128x128 tiles, long reduction
+    _check(configs.GemmWorkload(M=1792, N=1792, K=512), tile=128, kstep=64)
 
 
 def test_k64_loop_tails_alpha_bf16_batched_and_odd_ldc():
-    # K a multiple of 64 and >= 512 selects the K-step-64 loop (16x16x32 MFMAs, lane-exchange epilogue)
-    _check(configs.GemmWorkload(M=300, N=200, K=576))                          # 128x128 tiles, ragged, odd step count
-    _check(configs.GemmWorkload(M=256, N=384, K=512), alpha=0.125)             # full tiles, vector epilogue, alpha
-    _check(configs.GemmWorkload(M=256, N=256, K=512), c_bf16=True)             # bf16 vector epilogue
-    _check(configs.GemmWorkload(M=130, N=70, K=512), alpha=-2.0, batch=3, c_bf16=True)
+    # the K-step-64 loop (16x16x32 MFMAs, lane-exchange epilogue, bf16 C staged through LDS); the
+    # library picks it for 256x256 tiles with K a multiple of 64 and >= 512, the smaller tiles are named
+    _check(configs.GemmWorkload(M=300, N=200, K=576), tile=128, kstep=64)      # ragged, odd step count
+    _check(configs.GemmWorkload(M=256, N=384, K=512), alpha=0.125, tile=128, kstep=64)  # full tiles, vector epilogue, alpha
+    _check(configs.GemmWorkload(M=256, N=256, K=512), c_bf16=True, tile=128, kstep=64)  # bf16 epilogue through LDS
+    _check(configs.GemmWorkload(M=256, N=256, K=512), c_bf16=True, tile=64, kstep=64)
+    _check(configs.GemmWorkload(M=512, N=256, K=128), c_bf16=True, tile=256, kstep=64)
+    _check(configs.GemmWorkload(M=130, N=70, K=512), alpha=-2.0, batch=3, c_bf16=True, tile=128, kstep=64)
+    _check(configs.GemmWorkload(M=130, N=70, K=512), alpha=-2.0, batch=3, c_bf16=True, tile=64, kstep=64)
     _check(configs.GemmWorkload(M=512, N=512, K=512), batch=64)                # 256 tiles of 256x256: the large-tile kernel
+    _check(configs.GemmWorkload(M=512, N=512, K=512), batch=64, c_bf16=True)
     _check(configs.GemmWorkload(M=2048 + 40, N=2048 - 24, K=640))              # large-tile kernel with ragged edges
     wl = configs.GemmWorkload(M=256, N=256, K=512)
     d = wl.make()
-    c = G.run_gemm(d["a_bf16"], d["b_bf16"], 256, 256, 512, ldc=258)[0]        # ldc not a multiple of 4: scalar epilogue
+    c = G.run_gemm(d["a_bf16"], d["b_bf16"], 256, 256, 512, ldc=258, tile=128, kstep=64)[0]  # ldc not a multiple of 4: scalar epilogue
     ad, bd = oracle.widen(d["a_bf16"], True), oracle.widen(d["b_bf16"], True)
     ref = oracle.gemm(ad, bd, 256, 256, 512, b_col=True)
     P.assert_contraction_close(c, ref, oracle.gemm_absdot(ad, bd, 256, 256, 512, b_col=True), 512)
+
+
+def test_deep_ring_loop():
+    # K-step-32 loop with the ring filling the LDS (16 stages of a 64x64 tile, 8 of a 128x128 one):
+    # reductions shorter than, equal to and longer than the ring, ragged tiles, batches, bf16 C
+    for tile in (64, 128):
+        _check(configs.GemmWorkload(M=100, N=70, K=64), tile=tile, kstep=33)
+        _check(configs.GemmWorkload(M=192, N=130, K=512), tile=tile, kstep=33, alpha=0.5)
+        _check(configs.GemmWorkload(M=130, N=260, K=1056), tile=tile, kstep=33, batch=2, c_bf16=True)
+    _check(configs.GemmWorkload(M=512, N=512, K=2048))      # one round of 64x64 tiles, long reduction: the library's own choice
 
 
 @pytest.mark.parametrize("a_col,b_col", [(False, False), (True, False), (True, True), (False, True)])
