@@ -131,7 +131,7 @@ def build_workloads(torch, perf):
     d3 = c3.make()
     a3, b3 = rotated(G.dev(d3["a_bf16"]), 4), rotated(G.dev(d3["b_bf16"]), 4)
     o3 = torch.empty((4, c3.M, c3.N), dtype=torch.float32, device="cuda")
-    wls.append(Workload("gemm_4096x4096x4096_bf16", "gemm_mfma_kernel<4,4,2,2,f32>", "mfma", c3.flops(),
+    wls.append(Workload("gemm_4096x4096x4096_bf16", "gemm_mfma_kernel<4,4,2,2,K64,f32>", "mfma", c3.flops(),
                         lambda i: perf.perf_gemm(a3[i % 4].data_ptr(), b3[i % 4].data_ptr(), o3[i % 4].data_ptr(),
                                                  c3.M, c3.N, c3.K, ROW, c3.K, COL, c3.K, c3.N, 1, 0, 0, 0, 1.0,
                                                  BF16, F32, st()), 4))
@@ -144,7 +144,7 @@ def build_workloads(torch, perf):
     p4 = torch.empty_like(s4)
     S, D = c4.seq, c4.d
     qk_bytes = 2 * c4.batch * S * D * 2 + c4.batch * S * S * 4
-    wls.append(Workload("attn_scores_qk_512x(512x512x64)", "gemm_mfma_kernel<4,4,2,2,f32>", "hbm", qk_bytes,
+    wls.append(Workload("attn_scores_qk_512x(512x512x64)", "gemm_mfma_kernel<4,4,2,2,K32,f32>", "hbm", qk_bytes,
                         lambda i: perf.perf_gemm(q4.data_ptr(), k4.data_ptr(), s4.data_ptr(), S, S, D, ROW, D, COL, D,
                                                  S, c4.batch, S * D, S * D, S * S, c4.alpha, BF16, F32, st()),
                         1, "28 flop/byte: bound by the 512 MiB fp32 score store, not by MFMA"))
@@ -154,7 +154,7 @@ def build_workloads(torch, perf):
 
     # -- config 4, fused (an addition, not averaged into `value`): scores and softmax in one kernel,
     #    algorithmic traffic = Q + K + one write of P
-    wls.append(Workload("attn_scores_softmax_fused_512x(512x512x64)", "gemm_softmax_kernel<16,f32>", "hbm", qk_bytes,
+    wls.append(Workload("attn_scores_softmax_fused_512x(512x512x64)", "gemm_softmax_kernel<32,nomask,f32>", "hbm", qk_bytes,
                         lambda i: perf.perf_gemm_softmax(q4.data_ptr(), k4.data_ptr(), p4.data_ptr(), S, S, D, D, D, S,
                                                          c4.batch, S * D, S * D, S * S, c4.alpha, BF16, F32, st()),
                         1, "replaces the two launches above (278 us); listed, not averaged into `value`"))
@@ -208,16 +208,16 @@ def build_paper_workloads(torch, perf):
     d = pm.make()
     am, bm = sets(G.dev(d["a_bf16"]), 16), sets(G.dev(d["b_bf16"]), 16)
     cm = torch.empty((16, pm.M, pm.N), dtype=torch.float32, device="cuda"); keep.append(cm)
-    wls.append(Workload("paper_matmul_768x1024x1024_bf16", "gemm_mfma_kernel<2,2,2,2>", "mfma", pm.flops(),
+    wls.append(Workload("paper_matmul_768x1024x1024_bf16", "gemm_mfma_kernel<1,1,2,2,K32,f32>", "mfma", pm.flops(),
                         lambda i: perf.perf_gemm(am[i % 16].data_ptr(), bm[i % 16].data_ptr(), cm[i % 16].data_ptr(),
                                                  pm.M, pm.N, pm.K, ROW, pm.K, COL, pm.K, pm.N, 1, 0, 0, 0, 1.0, BF16,
-                                                 F32, st()), 16, "96 tiles of 128x128 on 256 CUs"))
+                                                 F32, st()), 16, "192 tiles of 64x64 on 256 CUs; launch and per-step synchronisation dominate"))
     pb, nb = configs.PAPER_BMM, configs.PAPER_BMM_BATCH
     d = pb.make()
     ab = sets(G.dev(d["a_bf16"]).repeat(nb, 1, 1), 4)
     bb = sets(G.dev(d["b_bf16"]).repeat(nb, 1, 1), 4)
     cb = torch.empty((4, nb, pb.M, pb.N), dtype=torch.float32, device="cuda"); keep.append(cb)
-    wls.append(Workload("paper_bmm_192x256x128x256_bf16", "gemm_mfma_kernel<2,2,2,2>", "mfma", nb * pb.flops(),
+    wls.append(Workload("paper_bmm_192x256x128x256_bf16", "gemm_mfma_kernel<2,2,2,2,K32,f32>", "mfma", nb * pb.flops(),
                         lambda i: perf.perf_gemm(ab[i % 4].data_ptr(), bb[i % 4].data_ptr(), cb[i % 4].data_ptr(),
                                                  pb.M, pb.N, pb.K, ROW, pb.K, COL, pb.K, pb.N, nb, pb.M * pb.K,
                                                  pb.N * pb.K, pb.M * pb.N, 1.0, BF16, F32, st()), 4,
