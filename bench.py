@@ -509,6 +509,7 @@ def main():
         for w, (e0, e1) in zip(pw, evs):
             w.ms = e0.elapsed_time(e1) / K
             entry = {"workload": w.name, "us": round(w.ms * 1e3, 2), "buffer_sets": w.nsets, "roofline": w.roofline()}
+            entry["roofline"]["traffic"] = traffic.get(w.name)
             if w.note:
                 entry["note"] = w.note
             plist.append(entry)
