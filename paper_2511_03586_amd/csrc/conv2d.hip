@@ -11,9 +11,10 @@
 //
 //  * conv2d_wreg_kernel: bf16, 3x3 filter, 64 -> 128 channels: weights held in registers.
 //  * conv2d_mfma_kernel: bf16, C a multiple of 32; main loop shared with the GEMM.
-//  * conv2d_smallc_kernel: few input channels (no 32-wide K-step for the matrix cores, e.g.
-//    the 3-channel 5x5 first layer of the paper's "conv 1"): one thread per output pixel
-//    and block of KB output channels, weights broadcast from LDS, fp32 FMAs.
+//  * conv2d_rowmfma_kernel: few input channels with S*C <= 16 (e.g. the 3-channel 5x5 first
+//    layer of the paper's "conv 1"): one filter row per 16-wide MFMA K-step, stride 1.
+//  * conv2d_smallc_kernel: other few-channel cases: one thread per output pixel and block of
+//    KB output channels, weights broadcast from LDS, fp32 FMAs.
 //  * conv2d_direct_kernel: any other legal case; one thread per output element.
 #include "mfma_tile.h"
 #include "host_utils.h"
@@ -479,6 +480,101 @@ __global__ __launch_bounds__(256) void conv2d_smallc_kernel(const T *__restrict_
     }
 }
 
+// ---- few input channels on the matrix cores: one filter row per MFMA -----------------
+// With S*C <= 16 the S*C values one pixel needs from one filter row are contiguous in an NHWC
+// image row (columns q - pad .. q - pad + S - 1, all channels), so a filter row is a single
+// K = 16 step of v_mfma_f32_16x16x16_bf16 (K padded with zero weights): 16 pixels x 16
+// output channels take R MFMAs instead of R*S*C*16 vector FMAs per lane group.
+// A workgroup of 4 waves owns a tile of 32 output rows x 64 columns of one image (stride 1)
+// and one block of 16 output channels.  The 32 + R - 1 input rows of the tile are staged
+// once in LDS (aligned dword loads, zero outside the image).  Wave g takes columns
+// 16g .. 16g+15 and walks down the staged rows: the operand fragment of input row i (a lane's
+// 4 values are 8 contiguous bytes at a 2-byte-aligned position: four 16-bit LDS reads) feeds
+// the R output rows i-R+1 .. i, whose accumulators form a ring of R; the row that has just
+// received its last filter row is stored and its accumulator cleared.
+// The weights are the MFMA's row operand, so a lane ends up with 4 consecutive output
+// channels of one pixel.
+typedef short short4_t __attribute__((ext_vector_type(4)));
+
+template <int R, int S, int C, typename CT>
+__global__ __launch_bounds__(256) void conv2d_rowmfma_kernel(const uint16_t *__restrict__ x,
+                                                             const uint16_t *__restrict__ w, CT *__restrict__ y,
+                                                             ConvGeom g, int tiles_w, int tiles_h)
+{
+    constexpr int TH = 32, TW = 64;
+    constexpr int kRows = TH + R - 1;
+    // elements per staged row: the last pixel's 16 values plus the odd-start element, even
+    constexpr int kPitch = ((TW - 1) * C + 16 + 1 + 1) & ~1;
+    static_assert(S * C <= 16 && R <= 8, "one filter row per K = 16 step");
+    __shared__ uint32_t stage32[kRows * (kPitch / 2)];
+    const uint16_t *stage = reinterpret_cast<const uint16_t *>(stage32);
+
+    const int tid = threadIdx.x, lane = tid & 63, grp = tid >> 6;
+    const int tw = blockIdx.x % tiles_w, th = (blockIdx.x / tiles_w) % tiles_h, n = blockIdx.x / (tiles_w * tiles_h);
+    const int cb = blockIdx.y;
+    const int p0 = th * TH, col0 = tw * TW;
+    const int row_elems = g.W * C;                       // even (checked by the host)
+    const int e0 = (col0 - g.pw) * C, es = e0 & ~1;      // first element the tile needs; staged from the even one below
+    const int delta = e0 - es;
+    const uint16_t *ximg = x + (int64_t)n * g.H * row_elems;
+    for (int idx = tid; idx < kRows * (kPitch / 2); idx += 256) {
+        const int i = idx / (kPitch / 2), d = idx - i * (kPitch / 2);
+        const int ih = p0 - g.ph + i, e = es + 2 * d;
+        uint32_t v = 0;
+        if ((unsigned)ih < (unsigned)g.H && e >= 0 && e < row_elems)  // e and row_elems even: a pair is inside or outside
+            v = *reinterpret_cast<const uint32_t *>(ximg + (int64_t)ih * row_elems + e);
+        stage32[idx] = v;
+    }
+    // weights of this lane's output channel: filter row r, values 4*kg .. 4*kg+3 of its S*C (zero beyond)
+    const int px = lane & 15, kg = lane >> 4;
+    const int ch_w = cb * 16 + px;
+    short4_t wf[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k = 4 * kg + j;
+            wf[r][j] = (k < S * C && ch_w < g.K) ? (short)w[((int64_t)ch_w * R + r) * (S * C) + k] : (short)0;
+        }
+    __syncthreads();
+
+    const int col = col0 + 16 * grp + px;
+    const int lb = (16 * grp + px) * C + 4 * kg + delta;  // element offset of this lane's values in a staged row
+    const int ch0 = cb * 16 + 4 * kg;
+    // two bf16 results per 32-bit store when every pair starts at an even element
+    const bool pair_ok = sizeof(CT) == 2 && g.K % 2 == 0 && (reinterpret_cast<uintptr_t>(y) & 3) == 0;
+    float4_t acc[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[r] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < kRows; ++i) {
+        short4_t bf;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bf[j] = (short)stage[i * kPitch + lb + j];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int pl = i - r;  // output row (within the tile) that takes filter row r from input row i
+            if (pl >= 0 && pl < TH) acc[pl % R] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(wf[r], bf, acc[pl % R], 0, 0, 0);
+        }
+        if (i >= R - 1) {
+            const int pl = i - (R - 1), p = p0 + pl;
+            float4_t &a = acc[pl % R];
+            if (p < g.P && col < g.Q) {
+                CT *yp = y + (((int64_t)n * g.P + p) * g.Q + col) * g.K + ch0;
+                if (pair_ok) {
+                    if (ch0 < g.K) *reinterpret_cast<uint32_t *>(yp) = pack_bf16(a[0], a[1]);
+                    if (ch0 + 2 < g.K) *reinterpret_cast<uint32_t *>(yp + 2) = pack_bf16(a[2], a[3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (ch0 + e < g.K) store_c<CT>(yp + e, a[e]);
+                }
+            }
+            a = float4_t{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+}
+
 template <int TM, int TN, int WM, int WN, typename CT>
 static perf_status launch_conv_mfma(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
 {
@@ -525,6 +621,25 @@ static perf_status launch_conv_wreg(const void *x, const void *w, void *y, const
     return launch_status();
 }
 
+template <int R, int S, int C, typename CT>
+static perf_status launch_conv_rowmfma(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
+{
+    const int tiles_w = (g.Q + 63) / 64, tiles_h = (g.P + 31) / 32;
+    hipLaunchKernelGGL((conv2d_rowmfma_kernel<R, S, C, CT>), dim3((unsigned)((int64_t)g.N * tiles_h * tiles_w), (unsigned)((g.K + 15) / 16)),
+                       dim3(256), 0, st, (const uint16_t *)x, (const uint16_t *)w, (CT *)y, g, tiles_w, tiles_h);
+    return launch_status();
+}
+
+// filter shapes with a filter-row-per-MFMA instance
+template <typename CT>
+static perf_status dispatch_conv_rowmfma(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
+{
+    if (g.R == 5 && g.S == 5 && g.C == 3) return launch_conv_rowmfma<5, 5, 3, CT>(x, w, y, g, st);
+    if (g.R == 3 && g.S == 3 && g.C == 3) return launch_conv_rowmfma<3, 3, 3, CT>(x, w, y, g, st);
+    if (g.R == 3 && g.S == 3 && g.C == 4) return launch_conv_rowmfma<3, 3, 4, CT>(x, w, y, g, st);
+    return PERF_ERR_UNSUPPORTED;
+}
+
 constexpr int kSmallcLdsBytes = 48 * 1024;
 
 template <int KB, typename T, typename CT>
@@ -564,7 +679,7 @@ static perf_status launch_conv_direct(const void *x, const void *w, void *y, con
 
 namespace perf {
 
-enum ConvVariant { kConvAuto = 0, kConvWreg = 1, kConvMfma = 2, kConvSmallC = 3, kConvDirect = 4 };
+enum ConvVariant { kConvAuto = 0, kConvWreg = 1, kConvMfma = 2, kConvSmallC = 3, kConvDirect = 4, kConvRowMfma = 5 };
 
 // variant: kConvAuto = chosen here from the shape; otherwise the caller's choice (perf_conv2d_variant).
 static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N, int64_t H, int64_t W, int64_t C,
@@ -597,16 +712,25 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
     const bool wreg_ok = mfma_ok && R == 3 && S == 3 && C == 64 && K == 128 && Q >= 32 && N * P * Q * K < (int64_t(1) << 29);
     // few input channels: channel-blocked direct kernel, if a 16-channel block of weights fits its LDS budget
     const bool smallc_ok = R * S * C * 16 * 4 <= kSmallcLdsBytes && (K + 15) / 16 <= kMaxGridYZ;
+    // few input channels, one filter row per MFMA K-step: bf16, stride 1, an instantiated filter shape
+    const bool rowmfma_ok = xw_dt == PERF_BF16 && stride_h == 1 && stride_w == 1 && (W * C) % 2 == 0 && aligned(x, 4) &&
+                            ((R == 5 && S == 5 && C == 3) || (R == 3 && S == 3 && (C == 3 || C == 4))) &&
+                            N * H * W * C < (int64_t(1) << 31) && N * ((P + 31) / 32) * ((Q + 63) / 64) <= kMaxGridX &&
+                            (K + 15) / 16 <= kMaxGridYZ;
     if (variant == kConvAuto)
         // (the channel-blocked kernel has one thread per pixel: below ~64 workgroups of pixels the
         // thread-per-output kernel has more parallelism and measured faster)
         variant = wreg_ok ? kConvWreg
                   : mfma_ok ? kConvMfma
+                  : (rowmfma_ok && N * P * Q >= 16384)          ? kConvRowMfma
                   : (C < 32 && smallc_ok && N * P * Q >= 16384) ? kConvSmallC
                                                                 : kConvDirect;
     else if ((variant == kConvWreg && !wreg_ok) || (variant == kConvMfma && !mfma_ok) ||
-             (variant == kConvSmallC && !smallc_ok) || variant < kConvWreg || variant > kConvDirect)
+             (variant == kConvSmallC && !smallc_ok) || (variant == kConvRowMfma && !rowmfma_ok) || variant < kConvWreg ||
+             variant > kConvRowMfma)
         return PERF_ERR_UNSUPPORTED;
+    if (variant == kConvRowMfma)
+        return y_dt == PERF_F32 ? dispatch_conv_rowmfma<float>(x, w, y, g, st) : dispatch_conv_rowmfma<uint16_t>(x, w, y, g, st);
     if (variant == kConvWreg)
         return y_dt == PERF_F32 ? launch_conv_wreg<3, 3, 64, float>(x, w, y, g, st)
                                 : launch_conv_wreg<3, 3, 64, uint16_t>(x, w, y, g, st);

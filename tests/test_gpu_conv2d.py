@@ -67,6 +67,32 @@ def test_direct_path_shapes(kw):
     _check(configs.ConvWorkload(**kw), y_bf16=False)
 
 
+@pytest.mark.parametrize("kw", [
+    dict(N=2, H=40, W=70, C=3, K=10, R=5, S=5, pad=2),      # two row tiles, two column tiles, ragged in both
+    dict(N=1, H=33, W=64, C=3, K=20, R=5, S=5, pad=2),      # two blocks of 16 output channels
+    dict(N=1, H=12, W=16, C=3, K=7, R=3, S=3, pad=1),       # odd channel count: element-wise stores
+    dict(N=2, H=20, W=66, C=4, K=16, R=3, S=3, pad=0),      # 4 channels, no padding
+    dict(N=1, H=9, W=10, C=3, K=10, R=5, S=5, pad=3),       # padding wider than the filter's half width
+    dict(N=1, H=70, W=130, C=3, K=10, R=5, S=5, pad=2),     # three tiles each way
+])
+@pytest.mark.parametrize("y_bf16", [True, False])
+def test_filter_row_per_mfma_kernel(kw, y_bf16):
+    import paper_2511_03586_amd as perf
+    _check(configs.ConvWorkload(**kw), y_bf16=y_bf16, variant=perf.CONV_ROWMFMA)
+
+
+def test_filter_row_per_mfma_kernel_refuses_what_it_cannot_run():
+    import torch
+    import paper_2511_03586_amd as perf
+    buf = torch.zeros(1 << 16, dtype=torch.int16, device="cuda")
+    bad = [dict(C=3, R=5, S=5, W=9), dict(C=3, R=5, S=5, W=10, stride=2), dict(C=5, R=3, S=3, W=10), dict(C=3, R=3, S=5, W=10)]
+    for kw in bad:                                           # W*C odd; stride 2; no instance for these filters
+        c, r, s_, w_, st = kw["C"], kw["R"], kw["S"], kw["W"], kw.get("stride", 1)
+        rc = perf.perf_conv2d_variant(buf.data_ptr(), buf.data_ptr(), buf.data_ptr(), 1, 10, w_, c, 4, r, s_, st, st, 1, 1,
+                                      perf.PERF_BF16, perf.PERF_BF16, perf.CONV_ROWMFMA, G.stream(), check=False)
+        assert rc == perf.PERF_ERR_UNSUPPORTED
+
+
 def test_small_channel_kernel_channel_blocks_and_fp32_operands():
     # C < 32 and at least 16384 output pixels: channel-blocked direct kernel; K = 37 needs three
     # blocks of 16 with a ragged last one

@@ -55,4 +55,5 @@ def test_search_conv_families():
     by = {r["variant"]: r for r in out["results"]}
     assert by[perf.CONV_WREG]["status"] == "unsupported" and by[perf.CONV_MFMA]["status"] == "unsupported"
     assert by[perf.CONV_SMALLC]["status"] == "ok" and by[perf.CONV_DIRECT]["status"] == "ok"
-    assert out["best"]["variant"] == perf.CONV_SMALLC
+    assert by[perf.CONV_ROWMFMA]["status"] == "ok"
+    assert out["best"]["variant"] in (perf.CONV_ROWMFMA, perf.CONV_SMALLC)
