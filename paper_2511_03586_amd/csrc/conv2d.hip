@@ -487,14 +487,17 @@ __global__ __launch_bounds__(256) void conv2d_smallc_kernel(const T *__restrict_
 // output channels take R MFMAs instead of R*S*C*16 vector FMAs per lane group.
 // A workgroup of 4 waves owns a tile of 32 output rows x 64 columns of one image (stride 1)
 // and one block of 16 output channels.  The 32 + R - 1 input rows of the tile are staged
-// once in LDS (aligned dword loads, zero outside the image).  Wave g takes columns
-// 16g .. 16g+15 and walks down the staged rows: the operand fragment of input row i (a lane's
-// 4 values are 8 contiguous bytes at a 2-byte-aligned position: four 16-bit LDS reads) feeds
+// once in LDS (aligned dword loads, zero outside the image), in two copies: as loaded, and
+// shifted down by one element, so that a lane's 4 values (8 contiguous bytes at a
+// 2-byte-aligned position) are two aligned dwords in the copy that matches the parity of its
+// position: one ds_read2_b32 instead of four 16-bit reads.  Wave g takes columns
+// 16g .. 16g+15 and walks down the staged rows: the operand fragment of input row i feeds
 // the R output rows i-R+1 .. i, whose accumulators form a ring of R; the row that has just
 // received its last filter row is stored and its accumulator cleared.
 // The weights are the MFMA's row operand, so a lane ends up with 4 consecutive output
 // channels of one pixel.
 typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
 
 template <int R, int S, int C, typename CT>
 __global__ __launch_bounds__(256) void conv2d_rowmfma_kernel(const uint16_t *__restrict__ x,
@@ -506,8 +509,12 @@ __global__ __launch_bounds__(256) void conv2d_rowmfma_kernel(const uint16_t *__r
     // elements per staged row: the last pixel's 16 values plus the odd-start element, even
     constexpr int kPitch = ((TW - 1) * C + 16 + 1 + 1) & ~1;
     static_assert(S * C <= 16 && R <= 8, "one filter row per K = 16 step");
-    __shared__ uint32_t stage32[kRows * (kPitch / 2)];
-    const uint16_t *stage = reinterpret_cast<const uint16_t *>(stage32);
+    constexpr int kCopy = kRows * (kPitch / 2);  // dwords of one copy
+    __shared__ uint32_t stage32[2 * kCopy];
+    // write-out staging, 16 pixels x up to 16 channels per wave: when all K <= 16 channels of a
+    // pixel belong to this workgroup, the 16 pixels of a wave's row are one contiguous run of
+    // 16*K results in y, written as 16-byte pieces by the first K*sizeof(CT) lanes
+    __shared__ __attribute__((aligned(16))) char out_stage[4][16 * 16 * sizeof(CT)];
 
     const int tid = threadIdx.x, lane = tid & 63, grp = tid >> 6;
     const int tw = blockIdx.x % tiles_w, th = (blockIdx.x / tiles_w) % tiles_h, n = blockIdx.x / (tiles_w * tiles_h);
@@ -517,40 +524,65 @@ __global__ __launch_bounds__(256) void conv2d_rowmfma_kernel(const uint16_t *__r
     const int e0 = (col0 - g.pw) * C, es = e0 & ~1;      // first element the tile needs; staged from the even one below
     const int delta = e0 - es;
     const uint16_t *ximg = x + (int64_t)n * g.H * row_elems;
-    for (int idx = tid; idx < kRows * (kPitch / 2); idx += 256) {
+    // (all loads of a thread first, then the LDS writes: written as one loop the compiler waits
+    // for each load before it issues the next)
+    constexpr int kIters = (kCopy + 255) / 256;
+    uint32_t sv[kIters];
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+        const int idx = tid + it * 256;
         const int i = idx / (kPitch / 2), d = idx - i * (kPitch / 2);
         const int ih = p0 - g.ph + i, e = es + 2 * d;
-        uint32_t v = 0;
-        if ((unsigned)ih < (unsigned)g.H && e >= 0 && e < row_elems)  // e and row_elems even: a pair is inside or outside
-            v = *reinterpret_cast<const uint32_t *>(ximg + (int64_t)ih * row_elems + e);
-        stage32[idx] = v;
+        sv[it] = 0;
+        if (idx < kCopy && (unsigned)ih < (unsigned)g.H && e >= 0 && e < row_elems)  // e, row_elems even: a pair is inside or outside
+            sv[it] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(ximg + (int64_t)ih * row_elems + e));
     }
-    // weights of this lane's output channel: filter row r, values 4*kg .. 4*kg+3 of its S*C (zero beyond)
+#pragma unroll
+    for (int it = 0; it < kIters; ++it)
+        if (tid + it * 256 < kCopy) stage32[tid + it * 256] = sv[it];
+    // weights of the 16 channels, zero-padded to [R][16 channels][16 values], through LDS
+    __shared__ __attribute__((aligned(8))) uint16_t wst[R * 16 * 16];
+    for (int idx = tid; idx < R * 16 * 16; idx += 256) {
+        const int k = idx & 15, ch = cb * 16 + ((idx >> 4) & 15), r = idx >> 8;
+        wst[idx] = (k < S * C && ch < g.K) ? w[((int64_t)ch * R + r) * (S * C) + k] : (uint16_t)0;
+    }
+    __syncthreads();
+    // this lane's output channel (for the MFMA's row operand): values 4*kg .. 4*kg+3 of filter row r
     const int px = lane & 15, kg = lane >> 4;
-    const int ch_w = cb * 16 + px;
     short4_t wf[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+    for (int r = 0; r < R; ++r) wf[r] = *reinterpret_cast<const short4_t *>(wst + (r * 16 + px) * 16 + 4 * kg);
+    // second copy: dword d = elements 2d+1, 2d+2 of the row
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int k = 4 * kg + j;
-            wf[r][j] = (k < S * C && ch_w < g.K) ? (short)w[((int64_t)ch_w * R + r) * (S * C) + k] : (short)0;
-        }
+    for (int it = 0; it < kIters; ++it) {
+        const int idx = tid + it * 256;
+        const int d = idx % (kPitch / 2);
+        const uint32_t hi = (idx < kCopy && d + 1 < kPitch / 2) ? stage32[idx + 1] : 0u;
+        sv[it] = (sv[it] >> 16) | (hi << 16);
+    }
+#pragma unroll
+    for (int it = 0; it < kIters; ++it)
+        if (tid + it * 256 < kCopy) stage32[kCopy + tid + it * 256] = sv[it];
     __syncthreads();
 
     const int col = col0 + 16 * grp + px;
     const int lb = (16 * grp + px) * C + 4 * kg + delta;  // element offset of this lane's values in a staged row
+    const uint32_t *lane_stage = stage32 + (lb & 1) * kCopy + (lb >> 1);
     const int ch0 = cb * 16 + 4 * kg;
-    // two bf16 results per 32-bit store when every pair starts at an even element
-    const bool pair_ok = sizeof(CT) == 2 && g.K % 2 == 0 && (reinterpret_cast<uintptr_t>(y) & 3) == 0;
+    // two results per store when every pair starts at an even element: 32-bit stores of two bf16,
+    // 64-bit stores of two floats
+    const bool pair_ok = g.K % 2 == 0 && (reinterpret_cast<uintptr_t>(y) & (2 * sizeof(CT) - 1)) == 0;
+    const bool run_ok = pair_ok && gridDim.y == 1 && ((int64_t)g.Q * g.K * sizeof(CT)) % 16 == 0 &&
+                        (reinterpret_cast<uintptr_t>(y) & 15) == 0 && col0 + 16 * grp + 15 < g.Q;  // uniform per wave
+    char *const my_out = out_stage[grp];
+    const int run_pieces = g.K * (int)sizeof(CT);  // 16-byte pieces in a wave's run of 16 pixels
     float4_t acc[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) acc[r] = float4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < kRows; ++i) {
-        short4_t bf;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) bf[j] = (short)stage[i * kPitch + lb + j];
+        const uint2_t two = {lane_stage[i * (kPitch / 2)], lane_stage[i * (kPitch / 2) + 1]};
+        const short4_t bf = __builtin_bit_cast(short4_t, two);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int pl = i - r;  // output row (within the tile) that takes filter row r from input row i
@@ -559,11 +591,34 @@ __global__ __launch_bounds__(256) void conv2d_rowmfma_kernel(const uint16_t *__r
         if (i >= R - 1) {
             const int pl = i - (R - 1), p = p0 + pl;
             float4_t &a = acc[pl % R];
-            if (p < g.P && col < g.Q) {
+            if (run_ok) {
+                if (p < g.P) {  // uniform
+                    char *o = my_out + (size_t)(px * g.K + ch0) * sizeof(CT);
+                    if constexpr (sizeof(CT) == 2) {
+                        if (ch0 < g.K) *reinterpret_cast<uint32_t *>(o) = pack_bf16(a[0], a[1]);
+                        if (ch0 + 2 < g.K) *reinterpret_cast<uint32_t *>(o + 4) = pack_bf16(a[2], a[3]);
+                    } else {
+                        if (ch0 < g.K) *reinterpret_cast<float2_t *>(o) = float2_t{a[0], a[1]};
+                        if (ch0 + 2 < g.K) *reinterpret_cast<float2_t *>(o + 8) = float2_t{a[2], a[3]};
+                    }
+                    __builtin_amdgcn_wave_barrier();  // (the wave's LDS operations execute in order)
+                    if (lane < run_pieces) {
+                        const uint4_t v = *reinterpret_cast<const uint4_t *>(my_out + lane * 16);
+                        char *dst = reinterpret_cast<char *>(y + (((int64_t)n * g.P + p) * g.Q + col0 + 16 * grp) * g.K);
+                        *reinterpret_cast<uint4_t *>(dst + lane * 16) = v;
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                }
+            } else if (p < g.P && col < g.Q) {
                 CT *yp = y + (((int64_t)n * g.P + p) * g.Q + col) * g.K + ch0;
                 if (pair_ok) {
-                    if (ch0 < g.K) *reinterpret_cast<uint32_t *>(yp) = pack_bf16(a[0], a[1]);
-                    if (ch0 + 2 < g.K) *reinterpret_cast<uint32_t *>(yp + 2) = pack_bf16(a[2], a[3]);
+                    if constexpr (sizeof(CT) == 2) {
+                        if (ch0 < g.K) *reinterpret_cast<uint32_t *>(yp) = pack_bf16(a[0], a[1]);
+                        if (ch0 + 2 < g.K) *reinterpret_cast<uint32_t *>(yp + 2) = pack_bf16(a[2], a[3]);
+                    } else {
+                        if (ch0 < g.K) *reinterpret_cast<float2_t *>(yp) = float2_t{a[0], a[1]};
+                        if (ch0 + 2 < g.K) *reinterpret_cast<float2_t *>(yp + 2) = float2_t{a[2], a[3]};
+                    }
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
