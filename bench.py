@@ -223,13 +223,16 @@ def build_paper_workloads(torch, perf):
                                                  pb.N * pb.K, pb.M * pb.N, 1.0, BF16, F32, st()), 4,
                         "64 flop/byte: bound by the fp32 C store"))
     for tag, wl, kern, note in (("paper_conv_8x64x64x56x56x3_bf16", configs.PAPER_CONV_2, "conv2d_mfma_kernel<2,2,2,2>", ""),
-                                ("paper_conv_8x10x3x512x512x5_bf16", configs.PAPER_CONV_1, "conv2d_smallc_kernel<12>",
-                                 "3 input channels: no MFMA K-step; fp32 vector FMAs, priced against the vector peak")):
+                                ("paper_conv_8x10x3x512x512x5_bf16", configs.PAPER_CONV_1, "conv2d_rowmfma_kernel<5,5,3,bf16>",
+                                 "3 input channels: one filter row (15 values) per 16-wide MFMA K-step; 3 GFLOP over 52 MiB, "
+                                 "so priced against HBM (input once, output once)")):
         d = wl.make()
         x = sets(G.dev(d["x_bf16"]), 8)
         w = G.dev(d["w_bf16"]); keep.append(w)
         y = torch.empty((8, wl.N, wl.P, wl.Q, wl.K), dtype=torch.int16, device="cuda"); keep.append(y)
-        wls.append(Workload(tag, kern, "alu" if wl.C < 32 else "mfma", wl.flops(),
+        small_c = wl.C < 32
+        nbytes = 2 * (wl.N * wl.H * wl.W * wl.C + wl.K * wl.R * wl.S * wl.C + wl.N * wl.P * wl.Q * wl.K)
+        wls.append(Workload(tag, kern, "hbm" if small_c else "mfma", nbytes if small_c else wl.flops(),
                             lambda i, x=x, w=w, y=y, wl=wl: perf.perf_conv2d(
                                 x[i % 8].data_ptr(), w.data_ptr(), y[i % 8].data_ptr(), wl.N, wl.H, wl.W, wl.C, wl.K,
                                 wl.R, wl.S, wl.stride, wl.stride, wl.pad, wl.pad, BF16, BF16, st()), 8, note))
