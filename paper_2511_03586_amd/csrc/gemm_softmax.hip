@@ -10,9 +10,10 @@
 //    operand, so that a lane holds 4 consecutive columns per accumulator and all of a
 //    lane's values belong to ONE row: the row reductions are in-lane plus two lane
 //    exchanges, and the write-out is 16 bytes per lane in whole 128-byte segments.  The
-//    operand strip and all of B go to LDS once (global->LDS loads, the swizzled 128-byte
-//    rows of mfma_tile.h).  With K = 64 two workgroups fit a CU (72 KiB of LDS, <= 256
-//    registers), so one's exponentials overlap the other's loads and stores.
+//    operand strips and all of B go to LDS (global->LDS loads, the swizzled 128-byte rows
+//    of mfma_tile.h): B once per workgroup, which then walks over several row strips of the
+//    matrix with the next strip's rows in flight.  With K = 64 two workgroups fit a CU
+//    (80 KiB of LDS, <= 256 registers), so one's exponentials overlap the other's stores.
 //  * any other legal case: perf_gemm into P followed by perf_softmax in place.
 #include "mfma_tile.h"
 #include "softmax_math.h"
@@ -21,118 +22,148 @@
 namespace perf {
 
 // T16N: 16-column accumulators per wave (N <= 16 * T16N); MASK: N < 16 * T16N.
+// A workgroup takes `group` consecutive row strips of one matrix: B goes to LDS once per
+// workgroup, and a wave's 16 rows of the next strip are fetched (into the other of two
+// buffers; the rows are the wave's own, so no barrier is involved) while it works on the
+// present one, so its stores follow each other without a load latency in between.
 template <int T16N, bool MASK, typename PT>
 __global__ __launch_bounds__(256, 2) void gemm_softmax_kernel(const uint16_t *__restrict__ A,
                                                               const uint16_t *__restrict__ B, PT *__restrict__ P,
                                                               int M, int N, int K, int64_t lda, int64_t ldb,
                                                               int64_t ldp, int64_t strideA, int64_t strideB,
                                                               int64_t strideP, float sign, float c, int strips,
-                                                              int xcd_remap)
+                                                              int group, int xcd_remap)
 {
     constexpr int NW = 4, BM = 64, BN = 16 * T16N;
-    constexpr int LA = BM / (8 * NW);                    // wave loads per K-step of 64: A strip
-    constexpr int LB = (BN + 8 * NW - 1) / (8 * NW);     // ... and B (the last one may be partly unused)
+    constexpr int LB = (BN + 8 * NW - 1) / (8 * NW);     // wave loads per K-step of 64 for B (the last one may be partly unused)
     constexpr int kRowsB = LB * 8 * NW;
-    constexpr int kStepBytes = (BM + kRowsB) * kRowBytes64;
+    constexpr int kStepB = kRowsB * kRowBytes64, kStepA = BM * kRowBytes64;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: LDS addresses stay scalar
-    // Workgroup id -> (row strip, matrix).  Ids are dealt round-robin to the 8 XCDs, each with
-    // a private L2; with the remap all strips of one matrix run on one XCD, so B is fetched
-    // over the fabric once per matrix instead of once per strip.
-    int strip, bz;
+    // Workgroup id -> (strip group, matrix).  Ids are dealt round-robin to the 8 XCDs, each with
+    // a private L2; with the remap all groups of one matrix run on one XCD, so B is fetched
+    // over the fabric once per matrix.
+    const int groups = (strips + group - 1) / group;
+    int gi, bz;
     if (xcd_remap) {
         const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-        strip = j % strips;
-        bz = (j / strips) * 8 + xcd;
+        gi = j % groups;
+        bz = (j / groups) * 8 + xcd;
     } else {
-        strip = blockIdx.x % strips;
-        bz = blockIdx.x / strips;
+        gi = blockIdx.x % groups;
+        bz = blockIdx.x / groups;
     }
-    const int m0 = strip * BM;
+    const int s0 = gi * group, s1 = min(strips, s0 + group);
     const int ksteps = K / 64;
     const uint16_t *Ab = A + (int64_t)bz * strideA;
     const uint16_t *Bb = B + (int64_t)bz * strideB;
     PT *Pb = P + (int64_t)bz * strideP;
+    char *const smem_a = smem + ksteps * kStepB;  // two buffers of ksteps x 64 rows
 
-    RowMajorSrc64<LA, NW> src_a(Ab + (int64_t)m0 * lda, min(BM, M - m0), lda, ksteps, wave, lane);
-    RowMajorSrc64<LB, NW> src_b(Bb, min(kRowsB, N), ldb, ksteps, wave, lane);
-    for (int ks = 0; ks < ksteps; ++ks) {
-        char *step = smem + ks * kStepBytes;
+    // this wave's 16 rows of strip s -> buffer s & 1 (nothing if the rows lie past M)
+    auto issue_a = [&](int s) {
+        const int row0 = s * BM + wave * 16;
+        if (row0 >= M) return;
+        RowMajorSrc64<2, 1> src(Ab + (int64_t)row0 * lda, min(16, M - row0), lda, ksteps, 0, lane);
+        char *buf = smem_a + (s & 1) * ksteps * kStepA + wave * 16 * kRowBytes64;
+        for (int ks = 0; ks < ksteps; ++ks) {
 #pragma unroll
-        for (int i = 0; i < LA; ++i) {
-            const uint32_t vo = src_a.voff[i], so = src_a.soff;
-            issue_load_to(src_a.rsrc, vo, so, step + (i * NW + wave) * 8 * kRowBytes64);
+            for (int i = 0; i < 2; ++i) {
+                const uint32_t vo = src.voff[i], so = src.soff;
+                issue_load_to(src.rsrc, vo, so, buf + ks * kStepA + i * 8 * kRowBytes64);
+            }
+            src.advance();
         }
+    };
+
+    {
+        RowMajorSrc64<LB, NW> src_b(Bb, min(kRowsB, N), ldb, ksteps, wave, lane);
+        for (int ks = 0; ks < ksteps; ++ks) {
 #pragma unroll
-        for (int i = 0; i < LB; ++i) {
-            const uint32_t vo = src_b.voff[i], so = src_b.soff;
-            issue_load_to(src_b.rsrc, vo, so, step + BM * kRowBytes64 + (i * NW + wave) * 8 * kRowBytes64);
+            for (int i = 0; i < LB; ++i) {
+                const uint32_t vo = src_b.voff[i], so = src_b.soff;
+                issue_load_to(src_b.rsrc, vo, so, smem + ks * kStepB + (i * NW + wave) * 8 * kRowBytes64);
+            }
+            src_b.advance();
         }
-        src_a.advance();
-        src_b.advance();
     }
+    issue_a(s0);
     wait_vmem<0>();
-    wg_barrier();
+    wg_barrier();  // B is complete (and each wave's own rows of the first strip)
 
-    // acc[j] element e: row m0 + 16*wave + lane%16, column 16 j + 4 (lane/16) + e
-    WaveTile16<1, T16N> t;
-    t.clear();
-    for (int ks = 0; ks < ksteps; ++ks) {
-        const char *step = smem + ks * kStepBytes;
+    for (int s = s0; s < s1; ++s) {
+        if (s + 1 < s1) issue_a(s + 1);  // (they have landed before this strip's stores are issued, see below)
+        const int m0 = s * BM;
+        if (m0 + wave * 16 >= M) continue;  // (no barrier inside the loop)
+        const char *abuf = smem_a + (s & 1) * ksteps * kStepA;
+
+        // acc[j] element e: row m0 + 16*wave + lane%16, column 16 j + 4 (lane/16) + e
+        WaveTile16<1, T16N> t;
+        t.clear();
+        for (int ks = 0; ks < ksteps; ++ks) {
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const int chunk = 4 * half + (lane >> 4);
-            const bf16x8_t a = *reinterpret_cast<const bf16x8_t *>(step + frag_offset64(wave * 16 + (lane & 15), chunk));
+            for (int half = 0; half < 2; ++half) {
+                const int chunk = 4 * half + (lane >> 4);
+                const bf16x8_t a =
+                    *reinterpret_cast<const bf16x8_t *>(abuf + ks * kStepA + frag_offset64(wave * 16 + (lane & 15), chunk));
 #pragma unroll
-            for (int j = 0; j < T16N; ++j) {
-                const bf16x8_t b = *reinterpret_cast<const bf16x8_t *>(step + BM * kRowBytes64 +
-                                                                        frag_offset64(j * 16 + (lane & 15), chunk));
-                t.acc[0][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, a, t.acc[0][j], 0, 0, 0);
+                for (int j = 0; j < T16N; ++j) {
+                    const bf16x8_t b = *reinterpret_cast<const bf16x8_t *>(smem + ks * kStepB +
+                                                                            frag_offset64(j * 16 + (lane & 15), chunk));
+                    t.acc[0][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b, a, t.acc[0][j], 0, 0, 0);
+                }
             }
         }
-    }
+        // the reads of this strip's rows are back before the buffer is refilled two strips on
+        // (the compiler waits for them in front of the MFMAs that use them)
 
-    // Row softmax.  All of a lane's values belong to row lane%16; lanes l, l^16, l^32, l^48
-    // share it.  exp(|alpha| * (v - m)) is evaluated as exp2 of a plain product: its relative
-    // error is ~2^-24 times the exponent, i.e. below 4e-6 for every result above 2^-100, and
-    // smaller results are below the floor under which only the absolute error is specified.
-    float m = -FLT_MAX;
+        // Row softmax.  All of a lane's values belong to row lane%16; lanes l, l^16, l^32, l^48
+        // share it.  exp(|alpha| * (v - m)) is evaluated as exp2 of a plain product: its relative
+        // error is ~2^-24 times the exponent, i.e. below 4e-6 for every result above 2^-100, and
+        // smaller results are below the floor under which only the absolute error is specified.
+        float m = -FLT_MAX;
 #pragma unroll
-    for (int j = 0; j < T16N; ++j)
+        for (int j = 0; j < T16N; ++j)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float v = t.acc[0][j][e] * sign;
-            if (MASK) v = (16 * j + 4 * (lane >> 4) + e < N) ? v : -FLT_MAX;
-            t.acc[0][j][e] = v;
-            m = __builtin_fmaxf(m, v);
+            for (int e = 0; e < 4; ++e) {
+                float v = t.acc[0][j][e] * sign;
+                if (MASK) v = (16 * j + 4 * (lane >> 4) + e < N) ? v : -FLT_MAX;
+                t.acc[0][j][e] = v;
+                m = __builtin_fmaxf(m, v);
+            }
+        {
+            float a, b;
+            swap16(m, a, b);
+            m = __builtin_fmaxf(a, b);
+            swap32(m, a, b);
+            m = __builtin_fmaxf(a, b);
         }
-    {
-        float a, b;
-        swap16(m, a, b);
-        m = __builtin_fmaxf(a, b);
-        swap32(m, a, b);
-        m = __builtin_fmaxf(a, b);
-    }
-    float z = 0.f;
+        float z = 0.f;
 #pragma unroll
-    for (int j = 0; j < T16N; ++j)
+        for (int j = 0; j < T16N; ++j)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float p = __builtin_amdgcn_exp2f((t.acc[0][j][e] - m) * c);
-            if (MASK) p = (16 * j + 4 * (lane >> 4) + e < N) ? p : 0.f;  // (c == 0 would give masked columns weight 1)
-            t.acc[0][j][e] = p;
-            z += p;
+            for (int e = 0; e < 4; ++e) {
+                float p = __builtin_amdgcn_exp2f((t.acc[0][j][e] - m) * c);
+                if (MASK) p = (16 * j + 4 * (lane >> 4) + e < N) ? p : 0.f;  // (c == 0 would give masked columns weight 1)
+                t.acc[0][j][e] = p;
+                z += p;
+            }
+        {
+            float a, b;
+            swap16(z, a, b);
+            z = a + b;
+            swap32(z, a, b);
+            z = a + b;
         }
-    {
-        float a, b;
-        swap16(z, a, b);
-        z = a + b;
-        swap32(z, a, b);
-        z = a + b;
+        // The next strip's rows must have landed before they are read: waiting here, where those
+        // loads are a whole strip's arithmetic old, costs least.  It also waits for the previous
+        // strip's stores, i.e. a wave has one strip of stores in flight (32 KiB; 256 KiB per CU),
+        // which is more than the write latency needs.
+        wait_vmem<0>();
+        store_tile16<1, T16N, PT>(t, Pb, ldp, M, N, m0 + wave * 16, 0, 1.0f / z, lane);
     }
-    store_tile16<1, T16N, PT>(t, Pb, ldp, M, N, m0 + wave * 16, 0, 1.0f / z, lane);
 }
 
 template <int T16N, bool MASK, typename PT>
@@ -141,7 +172,7 @@ static perf_status launch_fused(const void *A, const void *B, void *P, int64_t M
                                 int64_t strideP, float alpha, hipStream_t st)
 {
     constexpr int kRowsB = (16 * T16N + 31) / 32 * 32;
-    const size_t lds = (size_t)(K / 64) * (64 + kRowsB) * kRowBytes64;
+    const size_t lds = (size_t)(K / 64) * (2 * 64 + kRowsB) * kRowBytes64;  // B, and two buffers for the row strips
     auto kern = gemm_softmax_kernel<T16N, MASK, PT>;
     static size_t lds_set = 0;  // the dynamic-LDS cap is a per-function setting; raise it when a larger K comes along
     if (lds > lds_set) {
@@ -153,14 +184,18 @@ static perf_status launch_fused(const void *A, const void *B, void *P, int64_t M
     const float sign = alpha < 0.f ? -1.f : 1.f;
     const float c = (float)(std::fabs((double)alpha) * 1.4426950408889634074);  // |alpha| log2(e)
     const int64_t strips = (M + 63) / 64;
-    // one-dimensional grid of strips x matrices, in chunks that keep the grid below its limit
-    const int64_t per_launch = (kMaxGridX / strips) / 8 * 8;
+    // strips per workgroup: as many as still leave two workgroups for every CU
+    int64_t group = strips * batch / 512;
+    group = group < 1 ? 1 : group > strips ? strips : group;
+    const int64_t groups = (strips + group - 1) / group;
+    // one-dimensional grid of strip groups x matrices, in chunks that keep the grid below its limit
+    const int64_t per_launch = (kMaxGridX / groups) / 8 * 8;
     if (per_launch < 8) return PERF_ERR_UNSUPPORTED;
     for (int64_t b0 = 0; b0 < batch; b0 += per_launch) {
         const int64_t nb = batch - b0 < per_launch ? batch - b0 : per_launch;
-        hipLaunchKernelGGL(kern, dim3((unsigned)(strips * nb)), dim3(256), lds, st, (const uint16_t *)A + b0 * strideA,
+        hipLaunchKernelGGL(kern, dim3((unsigned)(groups * nb)), dim3(256), lds, st, (const uint16_t *)A + b0 * strideA,
                            (const uint16_t *)B + b0 * strideB, (PT *)P + b0 * strideP, (int)M, (int)N, (int)K, lda, ldb,
-                           ldp, strideA, strideB, strideP, sign, c, (int)strips, nb % 8 == 0 ? 1 : 0);
+                           ldp, strideA, strideB, strideP, sign, c, (int)strips, (int)group, nb % 8 == 0 ? 1 : 0);
     }
     return launch_status();
 }
