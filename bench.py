@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--reps", type=int, default=5,
+                    help="repetitions of the K timed launches per workload: the first is the step the JSON line's "
+                         "ms_per_step and value come from, all of them give us_median / us_min")
     ap.add_argument("--settle-ms", type=float, default=30.0,
                     help="after the W warm-up launches of a workload, keep launching it untimed until this much "
                          "wall time has passed (the clock needs some milliseconds to settle after a change of load)")
@@ -351,7 +354,8 @@ def cpu_baseline(wl_rooflines):
     res["softmax_131072x1024"] = ("hbm", 8 * x.size / timed(lambda: oracle.softmax(x)) / 1e9, "16384 of 131072 rows")
     d = configs.LayerNormWorkload(rows=4096).make()
     xw = oracle.widen(d["x_bf16"], True)
-    res["layernorm_8192x4096_bf16"] = ("hbm", 4 * xw.size / timed(lambda: oracle.layernorm(xw, d["gamma"], d["beta"], 1e-5)) / 1e9,
+    ln_g, ln_b = d["gamma"], d["beta"]
+    res["layernorm_8192x4096_bf16"] = ("hbm", 4 * xw.size / timed(lambda: oracle.layernorm(xw, ln_g, ln_b, 1e-5)) / 1e9,
                                        "4096 of 8192 rows")
     d = configs.CONFIG3.make()
     a, b = oracle.widen(d["a_bf16"][:1024], True), oracle.widen(d["b_bf16"], True)
@@ -371,15 +375,34 @@ def cpu_baseline(wl_rooflines):
     xx, ww = oracle.widen(d["x_bf16"], True), oracle.widen(d["w_bf16"], True)
     res["conv2d_32x56x56x64_k128_3x3_bf16"] = ("mfma", c5.flops() / timed(lambda: oracle.conv2d(xx, ww, (1, 1), (1, 1))) / 1e12,
                                                "8 of 32 images")
+    # the same on one thread, on samples an eighth of the size (about 1 s each)
+    oracle.set_threads(1)
+    one = {}
+    x1 = x[:2048]
+    one["softmax_131072x1024"] = 8 * x1.size / timed(lambda: oracle.softmax(x1), 0.8) / 1e9
+    xw1 = xw[:512]
+    one["layernorm_8192x4096_bf16"] = 4 * xw1.size / timed(lambda: oracle.layernorm(xw1, ln_g, ln_b, 1e-5), 0.8) / 1e9
+    a1 = a[:128]
+    one["gemm_4096x4096x4096_bf16"] = 2 * 128 * 4096 * 4096 / timed(lambda: oracle.gemm(a1, b, 128, 4096, 4096, b_col=True), 0.8) / 1e12
+    q1, k1 = q[:4], k[:4]
+    t = timed(lambda: oracle.gemm(q1, k1, 512, 512, 64, b_col=True, alpha=0.125, batch=4), 0.8)
+    one["attn_scores_qk_512x(512x512x64)"] = (2 * q1.size * 2 + 4 * 4 * 512 * 512) / t / 1e9
+    s1 = sc["s"].reshape(-1, 512)[:2048]
+    one["attn_softmax_262144x512"] = 8 * s1.size / timed(lambda: oracle.softmax(s1), 0.8) / 1e9
+    xx1 = xx[:1]
+    one["conv2d_32x56x56x64_k128_3x3_bf16"] = (c5.flops() / 8) / timed(lambda: oracle.conv2d(xx1, ww, (1, 1), (1, 1)), 0.8) / 1e12
+    oracle.set_threads(threads)
     fracs, per = [], {}
     for name, (bound, ach, sample) in res.items():
         peak = HBM_PEAK_GBS if bound == "hbm" else MFMA_BF16_PEAK_TFLOPS
         fracs.append(ach / peak)
-        per[name] = {"achieved": float(f"{ach:.4g}"), "unit": "GB/s" if bound == "hbm" else "TFLOP/s", "sample": sample}
+        per[name] = {"achieved": float(f"{ach:.4g}"), "achieved_1_thread": float(f"{one[name]:.4g}"),
+                     "unit": "GB/s" if bound == "hbm" else "TFLOP/s", "sample": sample}
     geo = math.exp(sum(math.log(f) for f in fracs) / len(fracs)) * 100.0
     return {"value": float(f"{geo:.4g}"), "unit": "% of MI355X roofline (geomean over the same workloads)",
             "cores": threads, "kind": "oracle",
-            "sample": "each oracle call repeated for 2.5 s and averaged; "
+            "sample": "each oracle call repeated for 2.5 s and averaged (achieved_1_thread: one thread, an eighth of the "
+                      "sample, 0.8 s); "
                       + "; ".join(f"{k}: {v['sample']}" for k, v in per.items()), "per_workload": per}
 
 
@@ -426,20 +449,42 @@ def main():
                 n += 1
             torch.cuda.synchronize()
 
+    def timed_reps(w):
+        """K timed launches, `reps` times back to back; returns ms per launch of each repetition
+        and the host time around the first."""
+        evs, first_wall = [], 0.0
+        for r in range(max(1, args.reps)):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0 = time.perf_counter()
+            e0.record()
+            for s in range(K):
+                w.launch(args.warmup + r * K + s)
+            e1.record()
+            if r == 0:
+                torch.cuda.synchronize()
+                first_wall = (time.perf_counter() - t0) * 1e3
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        return [e0.elapsed_time(e1) / K for e0, e1 in evs], first_wall
+
     for w in wls:
         warm_up(w)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record()
-        for s in range(K):
-            w.launch(args.warmup + s)
-        e1.record()
-        torch.cuda.synchronize()
-        wall_ms += (time.perf_counter() - t0) * 1e3
-        events.append((e0, e1))
-    for w, (e0, e1) in zip(wls, events):
-        w.ms = e0.elapsed_time(e1) / K
+        w.rep_ms, wall = timed_reps(w)
+        w.ms = w.rep_ms[0]
+        wall_ms += wall
     ms_per_step = sum(w.ms for w in wls)
+
+    # launch floor: the smallest launch the library has (one workgroup copying 16 bytes)
+    tiny = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    for _ in range(20):
+        perf.perf_copy(tiny.data_ptr(), tiny.data_ptr() + 32, 16, torch.cuda.current_stream().cuda_stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(200):
+        perf.perf_copy(tiny.data_ptr(), tiny.data_ptr() + 32, 16, torch.cuda.current_stream().cuda_stream)
+    e1.record()
+    torch.cuda.synchronize()
+    launch_floor_us = e0.elapsed_time(e1) / 200 * 1e3
 
     copy_gbs = measure_copy_ceiling(torch, perf)
     mfma_tflops = measure_mfma_ceiling(torch, perf)
@@ -457,6 +502,10 @@ def main():
         r = w.roofline()
         r["traffic"] = traffic.get(w.name)
         entry = {"workload": w.name, "us": round(w.ms * 1e3, 2), "buffer_sets": w.nsets, "roofline": r}
+        if len(w.rep_ms) > 1:
+            srt = sorted(w.rep_ms)
+            entry["us_median"] = round(srt[len(srt) // 2] * 1e3, 2)
+            entry["us_min"] = round(srt[0] * 1e3, 2)
         if w.bound == "mfma":
             entry["tflops"] = r["achieved"]
             entry["frac_of_measured_mfma_loop"] = round(r["achieved"] / mfma_tflops, 4)
@@ -490,6 +539,7 @@ def main():
                                "(softmax 256x1024 + 131072x1024 companion, LayerNorm 8192x4096 bf16, GEMM 4096^3 bf16, "
                                "512x(512x512x64) QK^T/8 + softmax, conv 32x56x56x64->128 3x3 bf16)"},
         "roofline": roof,
+        "launch_floor_us": round(launch_floor_us, 2),
         "copy_ceiling_gbs": round(copy_gbs, 1),
         "mfma_loop_ceiling_tflops": round(mfma_tflops, 1),
         "workloads": per,
@@ -498,20 +548,17 @@ def main():
         del keep
         torch.cuda.empty_cache()
         pw, pkeep = build_paper_workloads(torch, perf)
-        evs = []
         for w in pw:
             warm_up(w)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for s_ in range(K):
-                w.launch(args.warmup + s_)
-            e1.record()
-            evs.append((e0, e1))
-        torch.cuda.synchronize()
+            w.rep_ms, _ = timed_reps(w)
+            w.ms = w.rep_ms[0]
         plist = []
-        for w, (e0, e1) in zip(pw, evs):
-            w.ms = e0.elapsed_time(e1) / K
+        for w in pw:
             entry = {"workload": w.name, "us": round(w.ms * 1e3, 2), "buffer_sets": w.nsets, "roofline": w.roofline()}
+            if len(w.rep_ms) > 1:
+                srt = sorted(w.rep_ms)
+                entry["us_median"] = round(srt[len(srt) // 2] * 1e3, 2)
+                entry["us_min"] = round(srt[0] * 1e3, 2)
             entry["roofline"]["traffic"] = traffic.get(w.name)
             if w.note:
                 entry["note"] = w.note
