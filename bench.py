@@ -225,7 +225,7 @@ def build_paper_workloads(torch, perf):
                                                  pb.M, pb.N, pb.K, ROW, pb.K, COL, pb.K, pb.N, nb, pb.M * pb.K,
                                                  pb.N * pb.K, pb.M * pb.N, 1.0, BF16, F32, st()), 4,
                         "64 flop/byte: bound by the fp32 C store"))
-    for tag, wl, kern, note in (("paper_conv_8x64x64x56x56x3_bf16", configs.PAPER_CONV_2, "conv2d_mfma_kernel<2,2,2,2>", ""),
+    for tag, wl, kern, note in (("paper_conv_8x64x64x56x56x3_bf16", configs.PAPER_CONV_2, "conv2d_mfma_kernel<1,1,2,2,bf16>", "392 tiles of 64 pixels x 64 channels"),
                                 ("paper_conv_8x10x3x512x512x5_bf16", configs.PAPER_CONV_1, "conv2d_rowmfma_kernel<5,5,3,bf16>",
                                  "3 input channels: one filter row (15 values) per 16-wide MFMA K-step; 3 GFLOP over 52 MiB, "
                                  "so priced against HBM (input once, output once)")):

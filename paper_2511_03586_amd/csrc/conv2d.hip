@@ -762,7 +762,7 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool mfma_ok = xw_dt == PERF_BF16 && C % kBK == 0 && aligned(x, 16) && aligned(w, 16) &&
                          N * H * W * C < (int64_t(1) << 30) && K * R * S * C < (int64_t(1) << 30) &&
-                         ((N * P * Q + 127) / 128) * ((K + 127) / 128) <= kMaxGridX;
+                         ((N * P * Q + 63) / 64) * ((K + 63) / 64) <= kMaxGridX;
     // filter shapes with a weights-in-registers instance
     const bool wreg_ok = mfma_ok && R == 3 && S == 3 && C == 64 && K == 128 && Q >= 32 && N * P * Q * K < (int64_t(1) << 29);
     // few input channels: channel-blocked direct kernel, if a 16-channel block of weights fits its LDS budget
@@ -789,9 +789,22 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
     if (variant == kConvWreg)
         return y_dt == PERF_F32 ? launch_conv_wreg<3, 3, 64, float>(x, w, y, g, st)
                                 : launch_conv_wreg<3, 3, 64, uint16_t>(x, w, y, g, st);
-    if (variant == kConvMfma)
-        return y_dt == PERF_F32 ? launch_conv_mfma<2, 2, 2, 2, float>(x, w, y, g, st)
-                                : launch_conv_mfma<2, 2, 2, 2, uint16_t>(x, w, y, g, st);
+    if (variant == kConvMfma) {
+        // tile: 128 pixels x 128 channels when that gives every CU two workgroups, else 64 pixels;
+        // 64 channels wide when there are no more than 64 (or too few 64 x 128 tiles).  Measured on
+        // 8x56x56x64->64 (11.1 -> 7.8 us), 32x56x56x64->64 (27.7 -> 22.7), 8x28x28x128->256 (16.1 -> 11.8);
+        // 16x56x56x64->256 keeps the large tile (28 us against 35-38).
+        const int64_t Mpix = N * P * Q;
+        bool wide = K > 64;
+        const bool tall = ((Mpix + 127) / 128) * ((K + (wide ? 127 : 63)) / (wide ? 128 : 64)) >= 512;
+        if (!tall && wide && ((Mpix + 63) / 64) * ((K + 127) / 128) < 256) wide = false;
+#define PERF_CONV_MFMA(TM, TN)                                                                       \
+    (y_dt == PERF_F32 ? launch_conv_mfma<TM, TN, 2, 2, float>(x, w, y, g, st)                        \
+                      : launch_conv_mfma<TM, TN, 2, 2, uint16_t>(x, w, y, g, st))
+        if (tall) return wide ? PERF_CONV_MFMA(2, 2) : PERF_CONV_MFMA(2, 1);
+        return wide ? PERF_CONV_MFMA(1, 2) : PERF_CONV_MFMA(1, 1);
+#undef PERF_CONV_MFMA
+    }
     if (variant == kConvSmallC) {
         if (xw_dt == PERF_BF16)
             return y_dt == PERF_F32 ? dispatch_conv_smallc<uint16_t, float>(x, w, y, g, st)

@@ -51,6 +51,17 @@ def test_weights_in_registers_kernel(kw, y_bf16):
     _check(configs.ConvWorkload(**kw), y_bf16=y_bf16, variant=perf.CONV_WREG)
 
 
+@pytest.mark.parametrize("kw,y_bf16", [
+    (dict(N=16, H=56, W=56, C=32, K=256), True),     # 784 tiles of 128 pixels x 128 channels
+    (dict(N=32, H=56, W=56, C=32, K=48), True),      # 784 tiles of 128 x 64, ragged channels
+    (dict(N=4, H=56, W=56, C=32, K=256), False),     # 392 tiles of 64 x 128
+    (dict(N=2, H=56, W=56, C=64, K=64), True),       # 98 tiles of 64 x 64
+])
+def test_mfma_path_tile_shapes(kw, y_bf16):
+    import paper_2511_03586_amd as perf
+    _check(configs.ConvWorkload(**kw), y_bf16=y_bf16, variant=perf.CONV_MFMA)
+
+
 def test_mfma_rectangular_filter_and_mixed_stride_pad():
     wl = configs.ConvWorkload(N=2, H=9, W=14, C=64, K=48, R=1, S=3)
     _check(wl, pad=(0, 1))
