@@ -46,7 +46,9 @@ __global__ __launch_bounds__(256) void bn_partial_kernel(const XT *__restrict__ 
         for (int j = 0; j < kPerThread / E; ++j) {
             const int64_t e0 = ((int64_t)j * 256 + threadIdx.x) * E;
             if (e0 < len) {  // HW is a multiple of E: a chunk is entirely inside or outside
-                Elem<XT>::unpack(__builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xp + e0)), v + j * E);
+                // plain (cacheable) load: what the last-level cache keeps of x is read from there by the
+                // apply kernel (8x64x300x300 fp32: 107 -> 89 us)
+                Elem<XT>::unpack(*reinterpret_cast<const uint4_t *>(xp + e0), v + j * E);
             } else {
 #pragma unroll
                 for (int e = 0; e < E; ++e) v[j * E + e] = 0.f;
