@@ -38,10 +38,17 @@ __global__ __launch_bounds__(256) void bn_partial_kernel(const XT *__restrict__ 
     __shared__ float red[4];
     const int64_t plane = blockIdx.y;  // n*C + c
     const int64_t seg0 = (int64_t)blockIdx.x * kBnSeg;
-    const int64_t len = min((int64_t)kBnSeg, HW - seg0);
+    const bool full = blockIdx.x + 1 < gridDim.x || HW % kBnSeg == 0;  // every segment but a ragged last one
+    const int64_t len = full ? (int64_t)kBnSeg : HW - seg0;
     const XT *xp = x + plane * HW + seg0;
     float v[kPerThread];
-    if (VEC) {
+    if (VEC && full) {
+        // full segment (uniform): straight-line loads, all in flight together; with a bounds
+        // test around each load the compiler waits for the loads two at a time
+#pragma unroll
+        for (int j = 0; j < kPerThread / E; ++j)
+            Elem<XT>::unpack(*reinterpret_cast<const uint4_t *>(xp + ((int64_t)j * 256 + threadIdx.x) * E), v + j * E);
+    } else if (VEC) {
 #pragma unroll
         for (int j = 0; j < kPerThread / E; ++j) {
             const int64_t e0 = ((int64_t)j * 256 + threadIdx.x) * E;
@@ -151,10 +158,26 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const XT *__restrict__ x,
     const int c = (int)(plane % C);
     const float scale = coef[c], mu = coef[C + c], b = Elem<PT>::load1(beta + c);
     const int64_t seg0 = (int64_t)blockIdx.x * kBnSeg;
-    const int64_t len = min((int64_t)kBnSeg, HW - seg0);
+    const bool full = blockIdx.x + 1 < gridDim.x || HW % kBnSeg == 0;  // every segment but a ragged last one
+    const int64_t len = full ? (int64_t)kBnSeg : HW - seg0;
     const XT *xp = x + plane * HW + seg0;
     YT *yp = y + plane * HW + seg0;
-    if (VEC) {
+    if (VEC && full) {
+        // full segment (uniform): straight-line code; with bounds tests the compiler puts a full
+        // wait in front of every store, so each store waits for the one before it
+        uint4_t raw[kPerThread / E];
+#pragma unroll
+        for (int j = 0; j < kPerThread / E; ++j)
+            raw[j] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xp + ((int64_t)j * 256 + threadIdx.x) * E));
+#pragma unroll
+        for (int j = 0; j < kPerThread / E; ++j) {
+            float v[E], o[E];
+            Elem<XT>::unpack(raw[j], v);
+#pragma unroll
+            for (int e = 0; e < E; ++e) o[e] = __builtin_fmaf(v[e] - mu, scale, b);
+            store_chunk<YT, E>(yp + ((int64_t)j * 256 + threadIdx.x) * E, o);
+        }
+    } else if (VEC) {
         uint4_t raw[kPerThread / E];
 #pragma unroll
         for (int j = 0; j < kPerThread / E; ++j) {

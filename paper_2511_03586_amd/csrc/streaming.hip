@@ -438,26 +438,34 @@ __global__ __launch_bounds__(256) void eltwise_kernel(const T *__restrict__ a, c
                                                       int64_t nvec)
 {
     constexpr int E = Elem<T>::kPerChunk;
-    const int64_t base = (int64_t)blockIdx.x * 256 * kEltUnroll + threadIdx.x;
-    uint4_t ra[kEltUnroll], rb[kEltUnroll];
+    const int64_t block0 = (int64_t)blockIdx.x * 256 * kEltUnroll;
+    const int64_t base = block0 + threadIdx.x;
+    const uint4_t *av = reinterpret_cast<const uint4_t *>(a), *bv = reinterpret_cast<const uint4_t *>(b);
+    auto combine = [&](const uint4_t &xa, const uint4_t &xb, int64_t i) {
+        float va[E], vb[E], o[E];
+        Elem<T>::unpack(xa, va);
+        if (OP != PERF_RELU) Elem<T>::unpack(xb, vb);
 #pragma unroll
-    for (int u = 0; u < kEltUnroll; ++u) {
-        const int64_t i = base + u * 256;
-        if (i < nvec) {
-            ra[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(a) + i);
-            if (OP != PERF_RELU) rb[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(b) + i);
+        for (int e = 0; e < E; ++e) o[e] = apply_op<OP>(va[e], OP != PERF_RELU ? vb[e] : 0.f);
+        store_chunk<T, E>(y + i * E, o);
+    };
+    if (block0 + 256 * kEltUnroll <= nvec) {
+        // whole block in range (uniform): straight-line loads, all in flight together.  (With a
+        // bounds test around each load the compiler waits for one load before it issues the next.)
+        uint4_t ra[kEltUnroll], rb[kEltUnroll];
+#pragma unroll
+        for (int u = 0; u < kEltUnroll; ++u) {
+            ra[u] = __builtin_nontemporal_load(av + base + u * 256);
+            rb[u] = OP != PERF_RELU ? __builtin_nontemporal_load(bv + base + u * 256) : uint4_t{0u, 0u, 0u, 0u};
         }
-    }
 #pragma unroll
-    for (int u = 0; u < kEltUnroll; ++u) {
-        const int64_t i = base + u * 256;
-        if (i < nvec) {
-            float va[E], vb[E], o[E];
-            Elem<T>::unpack(ra[u], va);
-            if (OP != PERF_RELU) Elem<T>::unpack(rb[u], vb);
-#pragma unroll
-            for (int e = 0; e < E; ++e) o[e] = apply_op<OP>(va[e], OP != PERF_RELU ? vb[e] : 0.f);
-            store_chunk<T, E>(y + i * E, o);
+        for (int u = 0; u < kEltUnroll; ++u) combine(ra[u], rb[u], base + u * 256);
+    } else {
+        for (int u = 0; u < kEltUnroll; ++u) {
+            const int64_t i = base + u * 256;
+            if (i < nvec)
+                combine(__builtin_nontemporal_load(av + i),
+                        OP != PERF_RELU ? __builtin_nontemporal_load(bv + i) : uint4_t{0u, 0u, 0u, 0u}, i);
         }
     }
 }
