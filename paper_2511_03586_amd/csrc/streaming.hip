@@ -188,7 +188,23 @@ __global__ __launch_bounds__(256) void rowmean_kernel(const XT *__restrict__ x, 
         if (VEC) {
             const int64_t nch = cols / E;
             int64_t c = lane;
-            for (; c + 64 < nch; c += 128) {  // two independent loads in flight per lane
+            constexpr int kU = 8;  // eight independent 16-byte loads in flight per lane (8 KiB per wave)
+            for (; c + 64 * (kU - 1) < nch; c += 64 * kU) {
+                uint4_t raw[kU];
+#pragma unroll
+                for (int u = 0; u < kU; ++u) raw[u] = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xr) + c + 64 * u);
+#pragma unroll
+                for (int u = 0; u < kU; ++u) {
+                    float v[E];
+                    Elem<XT>::unpack(raw[u], v);
+#pragma unroll
+                    for (int e = 0; e < E; ++e) {
+                        if (u & 1) s1 += v[e];
+                        else s0 += v[e];
+                    }
+                }
+            }
+            for (; c + 64 < nch; c += 128) {  // two at a time
                 const uint4_t r0 = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xr) + c);
                 const uint4_t r1 = __builtin_nontemporal_load(reinterpret_cast<const uint4_t *>(xr) + c + 64);
                 float v0[E], v1[E];
