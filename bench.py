@@ -318,15 +318,18 @@ def measure_copy_ceiling(torch, perf, moved_bytes=2 << 30, iters=20):
     return 2.0 * n * iters / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
-def measure_mfma_ceiling(torch, perf, iters=2000, reps=5):
-    """Measured matrix-core ceiling: the library's register-only bf16 MFMA loop (TFLOP/s)."""
+def measure_mfma_ceiling(torch, perf, iters=2000, reps=5, random_operands=False):
+    """Measured matrix-core ceiling: the library's register-only bf16 MFMA loop (TFLOP/s), with
+    constant small-integer operands or with pseudo-random ones that toggle the multipliers."""
     sink = torch.zeros(perf.MFMA_PROBE_SINK_FLOATS, dtype=torch.float32, device="cuda")
     st = torch.cuda.current_stream().cuda_stream
-    perf.perf_mfma_probe(sink.data_ptr(), iters, st)
+    probe = perf.perf_mfma_probe_random if random_operands else perf.perf_mfma_probe
+    for _ in range(3):
+        probe(sink.data_ptr(), iters, st)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
-        perf.perf_mfma_probe(sink.data_ptr(), iters, st)
+        probe(sink.data_ptr(), iters, st)
     e1.record()
     torch.cuda.synchronize()
     return perf.MFMA_PROBE_FLOP_PER_ITER * iters * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
@@ -488,6 +491,7 @@ def main():
 
     copy_gbs = measure_copy_ceiling(torch, perf)
     mfma_tflops = measure_mfma_ceiling(torch, perf)
+    mfma_random_tflops = measure_mfma_ceiling(torch, perf, random_operands=True)
     copy_same = {w.name: measure_copy_ceiling(torch, perf, moved_bytes=w.unit_work, iters=50)
                  for w in wls if w.bound == "hbm" and w.unit_work < (1 << 29)}
 
@@ -509,6 +513,7 @@ def main():
         if w.bound == "mfma":
             entry["tflops"] = r["achieved"]
             entry["frac_of_measured_mfma_loop"] = round(r["achieved"] / mfma_tflops, 4)
+            entry["frac_of_mfma_loop_random_operands"] = round(r["achieved"] / mfma_random_tflops, 4)
         else:
             entry["gbs"] = r["achieved"]
             entry["frac_of_measured_copy"] = round(r["achieved"] / copy_gbs, 4)
@@ -542,6 +547,7 @@ def main():
         "launch_floor_us": round(launch_floor_us, 2),
         "copy_ceiling_gbs": round(copy_gbs, 1),
         "mfma_loop_ceiling_tflops": round(mfma_tflops, 1),
+        "mfma_loop_random_operands_tflops": round(mfma_random_tflops, 1),
         "workloads": per,
     }
     if not args.no_paper_shapes and not args.only:

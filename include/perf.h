@@ -227,6 +227,11 @@ perf_status perf_copy(const void *src, void *dst, int64_t bytes, perf_stream str
  * the loop.  `sink` (device, at least 4096 floats, written once per wavefront) keeps the
  * result live.  Errors: NULL, SHAPE (iters < 1 or > 2^24), ALIGN, LAUNCH. */
 perf_status perf_mfma_probe(float *sink, int64_t iters, perf_stream stream);
+/* The same loop with a different pair of pseudo-random operand registers (values in [-1, 1))
+ * for every accumulator, so that the multipliers toggle as they do in a GEMM on random data: the
+ * clock the power management grants, and so the attainable rate, depends on the operand values.
+ * Arguments and errors as perf_mfma_probe. */
+perf_status perf_mfma_probe_random(float *sink, int64_t iters, perf_stream stream);
 
 /* Human-readable name of a status code; static storage, never freed. */
 const char *perf_status_string(perf_status s);

@@ -44,6 +44,7 @@ SIGNATURES = {
                               _ptr]),
     "perf_copy": (_int, [_ptr, _ptr, _i64, _ptr]),
     "perf_mfma_probe": (_int, [_ptr, _i64, _ptr]),
+    "perf_mfma_probe_random": (_int, [_ptr, _i64, _ptr]),
     "perf_status_string": (ctypes.c_char_p, [_int]),
     "perf_version": (_int, []),
 }
@@ -184,3 +185,7 @@ MFMA_PROBE_FLOP_PER_ITER = 4096 * 32 * 32768
 
 def perf_mfma_probe(sink, iters, stream=None, check=True) -> int:
     return _check("perf_mfma_probe", lib().perf_mfma_probe(sink, iters, stream), check)
+
+
+def perf_mfma_probe_random(sink, iters, stream=None, check=True) -> int:
+    return _check("perf_mfma_probe_random", lib().perf_mfma_probe_random(sink, iters, stream), check)

@@ -37,15 +37,32 @@ __global__ __launch_bounds__(64) void copy_tail_kernel(const unsigned char *__re
 constexpr int kProbeAcc = 16;
 constexpr int kProbeWorkgroups = 256 * 4;
 
+// RANDOM: every accumulator has its own pair of operand registers filled with pseudo-random
+// values in [-1, 1), so consecutive MFMAs see different, fully toggling operands, as in a GEMM
+// on random data; otherwise one pair of small integers for all.  The clock the power management
+// grants depends on that (the same GEMM kernel runs 78 us on zeros and 95-100 us on random data).
+template <bool RANDOM>
 __global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ sink, int64_t iters)
 {
     const int lane = threadIdx.x & 63;
-    bf16x8_t a, b;
+    constexpr int kSets = RANDOM ? kProbeAcc : 1;
+    bf16x8_t as[kSets], bs[kSets];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        a[e] = (__bf16)(float)((lane + e) & 3);
-        b[e] = (__bf16)(float)((lane ^ e) & 1);
-    }
+    for (int i = 0; i < kSets; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if (RANDOM) {
+                uint32_t h = (uint32_t)(threadIdx.x * 131 + i * 17 + e) * 2654435761u;
+                h ^= h >> 15;
+                h *= 2246822519u;
+                h ^= h >> 13;
+                as[i][e] = (__bf16)((float)(h & 0xFFFF) * (1.0f / 32768.0f) - 1.0f);
+                bs[i][e] = (__bf16)((float)(h >> 16) * (1.0f / 32768.0f) - 1.0f);
+            } else {
+                as[i][e] = (__bf16)(float)((lane + e) & 3);
+                bs[i][e] = (__bf16)(float)((lane ^ e) & 1);
+            }
+        }
     float16_t acc[kProbeAcc];
 #pragma unroll
     for (int i = 0; i < kProbeAcc; ++i)
@@ -54,8 +71,8 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ sin
     for (int64_t it = 0; it < iters; ++it) {
 #pragma unroll
         for (int i = 0; i < kProbeAcc; ++i) {
-            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
-            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[i], 0, 0, 0);
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as[i % kSets], bs[i % kSets], acc[i], 0, 0, 0);
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bs[i % kSets], as[i % kSets], acc[i], 0, 0, 0);
         }
     }
     float s = 0.f;
@@ -68,15 +85,25 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ sin
 
 }  // namespace perf
 
-extern "C" perf_status perf_mfma_probe(float *sink, int64_t iters, perf_stream stream)
+static perf_status mfma_probe(float *sink, int64_t iters, bool random, perf_stream stream)
 {
     using namespace perf;
     if (!sink) return PERF_ERR_NULL;
     if (iters < 1 || iters > (int64_t(1) << 24)) return PERF_ERR_SHAPE;
     if (!aligned(sink, 4)) return PERF_ERR_ALIGN;
-    hipLaunchKernelGGL(mfma_probe_kernel, dim3(kProbeWorkgroups), dim3(256), 0, static_cast<hipStream_t>(stream), sink,
-                       iters);
+    auto kern = random ? mfma_probe_kernel<true> : mfma_probe_kernel<false>;
+    hipLaunchKernelGGL(kern, dim3(kProbeWorkgroups), dim3(256), 0, static_cast<hipStream_t>(stream), sink, iters);
     return launch_status();
+}
+
+extern "C" perf_status perf_mfma_probe(float *sink, int64_t iters, perf_stream stream)
+{
+    return mfma_probe(sink, iters, false, stream);
+}
+
+extern "C" perf_status perf_mfma_probe_random(float *sink, int64_t iters, perf_stream stream)
+{
+    return mfma_probe(sink, iters, true, stream);
 }
 
 extern "C" perf_status perf_copy(const void *src, void *dst, int64_t bytes, perf_stream stream)

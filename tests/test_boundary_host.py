@@ -112,6 +112,9 @@ def test_mfma_probe_argument_errors():
     assert perf.perf_mfma_probe(FAKE, 0, check=False) == perf.PERF_ERR_SHAPE
     assert perf.perf_mfma_probe(FAKE, (1 << 24) + 1, check=False) == perf.PERF_ERR_SHAPE
     assert perf.perf_mfma_probe(FAKE + 2, 1, check=False) == perf.PERF_ERR_ALIGN
+    assert perf.perf_mfma_probe_random(None, 1, check=False) == perf.PERF_ERR_NULL
+    assert perf.perf_mfma_probe_random(FAKE, 0, check=False) == perf.PERF_ERR_SHAPE
+    assert perf.perf_mfma_probe_random(FAKE + 2, 1, check=False) == perf.PERF_ERR_ALIGN
 
 
 def test_gemm_softmax_argument_errors():
