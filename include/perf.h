@@ -198,7 +198,8 @@ perf_status perf_eltwise(perf_eltwise_op op, const void *a, const void *b, void 
  * perf_conv2d; a variant that cannot run the problem returns UNSUPPORTED.
  *   perf_gemm_variant:  tile = 64, 128 or 256 (workgroup tile edge); kstep = 32 or 64 (main loop;
  *     K must be a multiple of it), or 33 = the K-step-32 loop with its LDS ring deepened to 128 KiB
- *     (16 stages for tile 64, 8 for tile 128, not for 256); only the bf16 row-major x
+ *     (16 stages for tile 64, 8 for tile 128, not for 256), or 65 = the K-step-64 loop built on
+ *     the 32x32x16 MFMA (tile 256 only, K a multiple of 64); only the bf16 row-major x
  *     column-major case that the MFMA kernels cover has variants.
  *   perf_conv2d_variant: variant 1 = weights in registers (3x3, 64 -> 128 channels, bf16),
  *     2 = implicit GEMM on the shared main loop (bf16, C a multiple of 32), 3 = channel-blocked

@@ -28,7 +28,7 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
     tn = within / rows_in_band;
 }
 
-template <int TM, int TN, int WM, int WN, bool K64, typename CT, int NS = kStages>
+template <int TM, int TN, int WM, int WN, bool K64, typename CT, int NS = kStages, bool MI32 = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t *__restrict__ A,
                                                                  const uint16_t *__restrict__ B, CT *__restrict__ C,
                                                                  int M, int N, int K, int64_t lda, int64_t ldb,
@@ -66,7 +66,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t 
         CT *Cb = C + (int64_t)bz * strideC;
 
         const int a_row0 = wm * 32 * TM, b_row0 = wn * 32 * TN;
-        if constexpr (K64) {
+        if constexpr (K64 && MI32) {
+            RowMajorSrc64<BM / (8 * NW), NW> src_a(Ab + (int64_t)m0 * lda, min(BM, M - m0), lda, K / 64, wave, lane);
+            RowMajorSrc64<BN / (8 * NW), NW> src_b(Bb + (int64_t)n0 * ldb, min(BN, N - n0), ldb, K / 64, wave, lane);
+            WaveTile<TM, TN> t;
+            t.clear();
+            mfma_mainloop_k64_mi32<TM, TN, WM, WN>(t, smem, K / 64, wave, lane, a_row0, b_row0, src_a, src_b);
+            store_tile<TM, TN, CT>(t, Cb, ldc, M, N, m0 + a_row0, n0 + b_row0, alpha, lane);
+        } else if constexpr (K64) {
             RowMajorSrc64<BM / (8 * NW), NW> src_a(Ab + (int64_t)m0 * lda, min(BM, M - m0), lda, K / 64, wave, lane);
             RowMajorSrc64<BN / (8 * NW), NW> src_b(Bb + (int64_t)n0 * ldb, min(BN, N - n0), ldb, K / 64, wave, lane);
             WaveTile16<2 * TM, 2 * TN> t;
@@ -161,14 +168,14 @@ struct GemmArgs {
     hipStream_t st;
 };
 
-template <int TM, int TN, int WM, int WN, bool K64, typename CT, int NS = kStages>
+template <int TM, int TN, int WM, int WN, bool K64, typename CT, int NS = kStages, bool MI32 = false>
 static perf_status launch_mfma(const GemmArgs &g)
 {
     using Shape = TileShape<TM, TN, WM, WN, NS>;
     constexpr int BM = Shape::BM, BN = Shape::BN;
     const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
     const size_t lds = Shape::kLdsBytes;
-    auto kern = gemm_mfma_kernel<TM, TN, WM, WN, K64, CT, NS>;
+    auto kern = gemm_mfma_kernel<TM, TN, WM, WN, K64, CT, NS, MI32>;
     static bool attr_done = false;  // raising the dynamic-LDS cap is a per-function, idempotent setting
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -213,6 +220,7 @@ static perf_status launch_mfma_rt(const GemmArgs &g, bool k64, bool c_f32)
 }
 
 constexpr int kDeepRing = 33;  // `kstep` code of the K-step-32 loop with the deep ring
+constexpr int kK64Mi32 = 65;  // `kstep` code of the K-step-64 loop with 32x32x16 MFMAs (256x256 tile)
 
 // tile / kstep: 0 = chosen here from the shape; otherwise the caller's choice (perf_gemm_variant).
 static perf_status gemm_impl(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K, perf_layout la,
@@ -244,8 +252,10 @@ static perf_status gemm_impl(const void *A, const void *B, void *C, int64_t M, i
                          aligned(B, 16) && lda <= (1 << 21) && ldb <= (1 << 21) && M <= (1 << 30) && N <= (1 << 30) && K <= (1 << 30) &&
                          ((M + 63) / 64) * ((N + 63) / 64) <= kMaxGridX;
     if (tile != 0 || kstep != 0) {  // the caller's variant: only the MFMA kernels have variants
-        if (!mfma_ok || (tile != 64 && tile != 128 && tile != 256) || (kstep != 32 && kstep != 64 && kstep != kDeepRing) ||
-            (kstep == 64 && K % 64 != 0) || (kstep == kDeepRing && tile == 256))
+        if (!mfma_ok || (tile != 64 && tile != 128 && tile != 256) ||
+            (kstep != 32 && kstep != 64 && kstep != kDeepRing && kstep != kK64Mi32) ||
+            ((kstep == 64 || kstep == kK64Mi32) && K % 64 != 0) || (kstep == kDeepRing && tile == 256) ||
+            (kstep == kK64Mi32 && tile != 256))
             return PERF_ERR_UNSUPPORTED;
     }
     if (mfma_ok) {
@@ -268,6 +278,9 @@ static perf_status gemm_impl(const void *A, const void *B, void *C, int64_t M, i
                                                                       : 32;
         }
         const bool k64 = kstep == 64, c_f32 = c_dt == PERF_F32;
+        if (kstep == kK64Mi32)
+            return c_f32 ? launch_mfma<4, 4, 2, 2, true, float, kStages, true>(g)
+                         : launch_mfma<4, 4, 2, 2, true, uint16_t, kStages, true>(g);
         if (kstep == kDeepRing) {  // K-step 32, ring as deep as the LDS allows: 128 KiB either way
             if (tile == 128)
                 return c_f32 ? launch_mfma<2, 2, 2, 2, false, float, 8>(g) : launch_mfma<2, 2, 2, 2, false, uint16_t, 8>(g);

@@ -470,6 +470,120 @@ __device__ __forceinline__ void mfma_mainloop_k64(WaveTile16<2 * TM, 2 * TN> &t,
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // MFMA -> VALU read distance (see mfma16)
 }
 
+// The same loop and schedule with v_mfma_f32_32x32x16_bf16: 32 MFMAs of 32 cycles per half-step
+// instead of 64 of 16, on 32x32 accumulators (the compiler ties those in place, so the plain
+// builtin is used; A is the row operand, results are written by store_tile).  Per MAC the
+// larger instruction reads half as many operand registers, and with random operands a
+// register-only loop of it sustains 1.84 PFLOP/s on the box against 1.47 for 16x16x32: the
+// clock is set by power, and this form needs less of it.
+template <int TM, int TN, int WM, int WN, typename SrcA, typename SrcB>
+__device__ __forceinline__ void mfma_mainloop_k64_mi32(WaveTile<TM, TN> &t, char *smem, int ksteps, int wave,
+                                                       int lane, int a_row0, int b_row0, SrcA &src_a, SrcB &src_b)
+{
+    using Shape = TileShape<TM, TN, WM, WN>;
+    constexpr int BM = Shape::BM, BN = Shape::BN, NW = Shape::kWaves;
+    constexpr int kStageBytes64 = (BM + BN) * kRowBytes64;
+    constexpr int LA = BM / (8 * NW), LB = BN / (8 * NW), kLoads = LA + LB;
+    constexpr int kMfmas = 2 * TM * TN;  // per half-step: two k-substeps of 16 for every 32x32 accumulator
+    static_assert(2 * kStageBytes64 <= Shape::kLdsBytes, "the two stages fit the LDS the launch provides");
+    static_assert(2 * kLoads < 64, "two steps of loads must fit the vmcnt counter");
+    bf16x8_t fa[2][2 * TM], fb[2][2 * TN];  // [buffer][k-substep * tiles + tile]: operands of one half-step
+
+    // per-lane LDS byte offsets of fragment g of K half `half`: k-substep g / tiles of the half
+    // (16 K: chunks 4*half + 2*(g / tiles) + lane/32), tile g % tiles (rows of 32)
+    auto frag_a = [&](int g, int half) {
+        return frag_offset64(a_row0 + (g % TM) * 32 + (lane & 31), 4 * half + 2 * (g / TM) + (lane >> 5));
+    };
+    auto frag_b = [&](int g, int half) {
+        return BM * kRowBytes64 + frag_offset64(b_row0 + (g % TN) * 32 + (lane & 31), 4 * half + 2 * (g / TN) + (lane >> 5));
+    };
+    auto issue_one = [&](char *stage, int i) {
+        if (i < LA) {
+            const uint32_t vo = src_a.voff[i], so = src_a.soff;
+            issue_load_to(src_a.rsrc, vo, so, stage + (i * NW + wave) * 8 * kRowBytes64);
+        } else {
+            const uint32_t vo = src_b.voff[i - LA], so = src_b.soff;
+            issue_load_to(src_b.rsrc, vo, so, stage + BM * kRowBytes64 + ((i - LA) * NW + wave) * 8 * kRowBytes64);
+        }
+    };
+    // MFMAs of one half-step from fragment buffer BUF; between them: the reads of the next
+    // half-step's fragments (stage rstage, K half RHALF) into the other buffer, the first
+    // (half 0) or second (half 1) part of one step of global->LDS loads into lstage, and in
+    // half 0 the barrier in front of those loads.
+    // positions, in MFMAs of a half-step: reads before MFMA floor(g * kQ4 / kR), barrier of half
+    // 0 before MFMA kQB, its kLa loads spread over [kQB, kMfmas), half 1's kLb loads over the half
+    constexpr int kFa = 2 * TM, kFb = 2 * TN;
+    constexpr int kR = kFa + kFb, kQ4 = kMfmas / 4 > 0 ? kMfmas / 4 : 1, kQB = (3 * kMfmas) / 8;
+    constexpr int kLa = kLoads / 2, kLb = kLoads - kLa, kSpan = kMfmas - kQB;
+    auto half_step = [&](auto buf_c, auto rhalf_c, auto second_c, const char *rstage, char *lstage) {
+        constexpr int BUF = decltype(buf_c)::value, RHALF = decltype(rhalf_c)::value;
+        constexpr bool SECOND = decltype(second_c)::value;
+#pragma unroll
+        for (int q = 0; q < kMfmas; ++q) {
+#pragma unroll
+            for (int g = (q < kQ4 ? (q * kR + kQ4 - 1) / kQ4 : kR); g < (q < kQ4 ? ((q + 1) * kR + kQ4 - 1) / kQ4 : kR); ++g) {
+                if (g < kFa)
+                    fa[BUF ^ 1][g] = *reinterpret_cast<const bf16x8_t *>(rstage + frag_a(g, RHALF));
+                else
+                    fb[BUF ^ 1][g - kFa] = *reinterpret_cast<const bf16x8_t *>(rstage + frag_b(g - kFa, RHALF));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (!SECOND && q == kQB) {
+                wait_vmem_and_lds<kLoads>();  // own reads of this stage are back (the loads of step p+1 may still fly)
+                wg_barrier();
+            }
+            if (!SECOND) {
+#pragma unroll
+                for (int i = (q >= kQB ? ((q - kQB) * kLa + kSpan - 1) / kSpan : kLa);
+                     i < (q >= kQB ? ((q - kQB + 1) * kLa + kSpan - 1) / kSpan : kLa); ++i) {
+                    issue_one(lstage, i);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+#pragma unroll
+                for (int i = (q * kLb + kMfmas - 1) / kMfmas; i < ((q + 1) * kLb + kMfmas - 1) / kMfmas; ++i) {
+                    issue_one(lstage, kLa + i);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            {
+                // accumulator (i, j) takes its two k-substeps back to back
+                const int ij = q / 2, ks = q % 2, i = ij / TN, j = ij % TN;
+                t.acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[BUF][ks * TM + i], fb[BUF][ks * TN + j], t.acc[i][j], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    using c0 = std::integral_constant<int, 0>;
+    using c1 = std::integral_constant<int, 1>;
+
+    for (int p = 0; p < 2; ++p) {  // steps 0 and 1 (step 1 may repeat step 0's data; it is then never used)
+        char *stage = smem + p * kStageBytes64;
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) issue_one(stage, i);
+        src_a.advance();
+        src_b.advance();
+    }
+    wait_vmem<kLoads>();  // step 0 has landed
+    wg_barrier();
+#pragma unroll
+    for (int i = 0; i < kFa; ++i) fa[0][i] = *reinterpret_cast<const bf16x8_t *>(smem + frag_a(i, 0));
+#pragma unroll
+    for (int j = 0; j < kFb; ++j) fb[0][j] = *reinterpret_cast<const bf16x8_t *>(smem + frag_b(j, 0));
+
+    for (int p = 0; p < ksteps; ++p) {
+        char *cur = smem + (p & 1) * kStageBytes64, *nxt = smem + ((p + 1) & 1) * kStageBytes64;
+        wait_vmem_and_lds<kLoads>();  // the fragments of half 0 are back (loads of step p+1 may still fly)
+        half_step(c0{}, c1{}, std::false_type{}, cur, cur);
+        wait_vmem_and_lds<kLa>();  // own loads of step p+1 have landed (only this half's loads of step p+2 are younger)
+        wg_barrier();
+        half_step(c1{}, c0{}, std::true_type{}, nxt, cur);
+        src_a.advance();
+        src_b.advance();
+    }
+    wait_vmem_and_lds<0>();  // drain the over-issued loads and reads before LDS is reused or released
+}
+
 // Write a wave's 16x16 accumulators to row-major C: element e of acc[i][j] is
 // m = row0 + 16 i + lane%16, n = col0 + 16 j + 4 (lane/16) + e.  In the full-tile case pairs
 // of column tiles are exchanged between the lanes of rows 0-7 and 8-15 of a 16-lane group

@@ -89,6 +89,15 @@ def test_k64_loop_tails_alpha_bf16_batched_and_odd_ldc():
     ref = oracle.gemm(ad, bd, 256, 256, 512, b_col=True)
     P.assert_contraction_close(c, ref, oracle.gemm_absdot(ad, bd, 256, 256, 512, b_col=True), 512)
 
+@pytest.mark.gpu
+def test_k64_loop_with_32x32_mfma():
+    """The K-step-64 loop of the 256x256 tile built on the 32x32x16 MFMA: ragged edges, several k-steps, alpha, batch, bf16 C."""
+    _check(configs.GemmWorkload(M=512, N=256, K=128), tile=256, kstep=65)
+    _check(configs.GemmWorkload(M=300, N=520, K=576), tile=256, kstep=65, alpha=0.25)
+    _check(configs.GemmWorkload(M=258, N=130, K=64), tile=256, kstep=65, batch=2, c_bf16=True)
+    _check(configs.GemmWorkload(M=1024, N=768, K=1024), tile=256, kstep=65, c_bf16=True)
+
+
 
 def test_deep_ring_loop():
     # K-step-32 loop with the ring filling the LDS (16 stages of a 64x64 tile, 8 of a 128x128 one):
