@@ -204,7 +204,9 @@ perf_status perf_eltwise(perf_eltwise_op op, const void *a, const void *b, void 
  *   perf_conv2d_variant: variant 1 = weights in registers (3x3, 64 -> 128 channels, bf16),
  *     2 = implicit GEMM on the shared main loop (bf16, C a multiple of 32), 3 = channel-blocked
  *     direct kernel, 4 = one thread per output, 5 = one filter row per 16-wide MFMA step (bf16,
- *     stride 1, few input channels: 5x5 with 3 channels, 3x3 with 3 or 4; W*C even). */
+ *     stride 1, few input channels: 5x5 with 3 channels, 3x3 with 3 or 4; W*C even),
+ *     6 = variant 1 with the input rows under a workgroup's pixel range resident in LDS
+ *     (stride 1; N*P*Q / 256 pixels per range must divide P*Q, and the rows must fit). */
 perf_status perf_gemm_variant(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K,
                               perf_layout la, int64_t lda, perf_layout lb, int64_t ldb, int64_t ldc,
                               int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC,

@@ -126,7 +126,7 @@ def perf_gemm_variant(A, B, C, M, N, K, la, lda, lb, ldb, ldc, batch, strideA, s
                                           alpha, ab_dt, c_dt, tile, kstep, stream), check)
 
 
-CONV_WREG, CONV_MFMA, CONV_SMALLC, CONV_DIRECT, CONV_ROWMFMA = 1, 2, 3, 4, 5
+CONV_WREG, CONV_MFMA, CONV_SMALLC, CONV_DIRECT, CONV_ROWMFMA, CONV_WRES = 1, 2, 3, 4, 5, 6
 
 
 def perf_conv2d_variant(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, xw_dt, y_dt, variant,

@@ -10,6 +10,8 @@
 // hardware's buffer range check turns into zeros.
 //
 //  * conv2d_wreg_kernel: bf16, 3x3 filter, 64 -> 128 channels: weights held in registers.
+//  * conv2d_wres_kernel: the same with the input rows of a workgroup's pixel range resident in
+//    LDS (stride 1, ranges inside one image, rows that fit): the benchmark's shape.
 //  * conv2d_mfma_kernel: bf16, C a multiple of 32; main loop shared with the GEMM.
 //  * conv2d_rowmfma_kernel: few input channels with S*C <= 16 (e.g. the 3-channel 5x5 first
 //    layer of the paper's "conv 1"): one filter row per 16-wide MFMA K-step, stride 1.
@@ -18,6 +20,7 @@
 //  * conv2d_direct_kernel: any other legal case; one thread per output element.
 #include "mfma_tile.h"
 #include "host_utils.h"
+#include <algorithm>
 
 namespace perf {
 
@@ -111,6 +114,68 @@ __device__ __forceinline__ void stage_acc(const float16_t &acc, char *stg)
     }
 }
 
+// Weights of one MFMA wave's 32 output channels -> registers (both weights-in-registers
+// kernels).  Fragment kk covers K indices kk*16 .. +15 of the filter (r, s, c order); a lane
+// holds channel lane%32 and the 8 K values starting at 8*(lane/32).  Read straight from
+// memory that pattern touches 32 different rows per instruction, so the wave's 36 KiB go
+// through a private LDS region (`region` + wave * 2 * kQBytes, 18 KiB per wave) with coalesced
+// global->LDS loads, in four quarters of R*S*C/4 K values through two sub-regions, so that
+// two quarters are always in flight while a third is read into registers.  A row's chunks of
+// 16 bytes are stored rotated by row/8 chunks, which spreads the 16 rows read by one
+// ds_read_b128 phase over all 16 bank slots (row pitch 18 chunks = 2 slots).
+template <int R, int S, int C>
+__device__ __forceinline__ void load_weight_frags(bf16x8_t (&wf)[R * S * C / 16], char *region, const uint16_t *w,
+                                                  int wave, int lane)
+{
+    constexpr int KSUB = R * S * C / 16;
+    constexpr int kQC = R * S * C / 32;       // 16-byte chunks per weight row and quarter (18)
+    constexpr int kQLoads = 32 * kQC / 64;    // wave loads per quarter (9)
+    constexpr int kQBytes = 32 * kQC * 16;
+    static_assert((32 * kQC) % 64 == 0 && KSUB % 4 == 0 && R * S * C == 32 * kQC, "whole wave loads per quarter");
+    char *wreg = region + wave * (2 * kQBytes);
+    const rsrc_t wr = make_rsrc(w + (int64_t)wave * 32 * (R * S * C), (uint32_t)(32 * R * S * C * 2));
+    uint32_t wvo[kQLoads];
+#pragma unroll
+    for (int i = 0; i < kQLoads; ++i) {
+        const int L = i * 64 + lane, row = L / kQC;
+        int c = L % kQC - (row >> 3);
+        c = c < 0 ? c + kQC : c;
+        wvo[i] = (uint32_t)(row * (4 * kQC) + c) * 16u;
+    }
+    const int frow = lane & 31;
+    auto issue_q = [&](int q, int sub) {
+#pragma unroll
+        for (int i = 0; i < kQLoads; ++i) {
+            const uint32_t vo = wvo[i];
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (__attribute__((address_space(3))) void *)(wreg + sub * kQBytes + i * 1024),
+                                                     16, vo, q * (kQC * 16), 0, 0);
+        }
+    };
+    auto read_q = [&](int q, int sub) {
+#pragma unroll
+        for (int kk = 0; kk < KSUB / 4; ++kk) {
+            int p = 2 * kk + (lane >> 5) + (frow >> 3);
+            p = p >= kQC ? p - kQC : p;
+            wf[q * (KSUB / 4) + kk] = *reinterpret_cast<const bf16x8_t *>(wreg + sub * kQBytes + (frow * kQC + p) * 16);
+        }
+    };
+    issue_q(0, 0);
+    issue_q(1, 1);
+    wait_vmem<kQLoads>();
+    read_q(0, 0);
+    wait_vmem_and_lds<kQLoads>();
+    issue_q(2, 0);
+    wait_vmem<kQLoads>();
+    read_q(1, 1);
+    wait_vmem_and_lds<kQLoads>();
+    issue_q(3, 1);
+    wait_vmem<kQLoads>();
+    read_q(2, 0);
+    wait_vmem<0>();
+    read_q(3, 1);
+    wait_vmem_and_lds<0>();
+}
+
 // For filters small enough that a wavefront can keep its share of them in registers
 // (here: 128 output channels, 4 waves x 32 channels, R*S*C = 576 -> 36 operand fragments
 // = 144 VGPRs per lane), the contraction is turned around: the weights never move after
@@ -170,65 +235,11 @@ __global__ __launch_bounds__(512) void conv2d_wreg_kernel(const uint16_t *__rest
     if (wave < 4) {
         // ------------------------------ MFMA waves ------------------------------
         __builtin_amdgcn_s_setprio(2);
-        // Weights of this wave's 32 channels -> registers.  Fragment kk covers K indices
-        // kk*16 .. +15; a lane holds channel lane%32 and the 8 K values starting at 8*(lane/32).
-        // Read straight from memory that pattern touches 32 different rows per instruction, so
-        // the wave's 36 KiB go through a private LDS region with coalesced global->LDS loads,
-        // in four quarters of 144 K values through two sub-regions, so that two quarters are
-        // always in flight while a third is read into registers (the region overlaps ring
-        // slot 2 and the output staging, which are not in use before the first barrier; slots
-        // 0 and 1 are being filled by the memory waves meanwhile).  A row's 18 chunks of
-        // 16 bytes are stored rotated by row/8 chunks, which spreads the 16 rows read by one
-        // ds_read_b128 phase over all 16 bank slots (row pitch 18 chunks = 2 slots).
-        constexpr int kQC = R * S * C / 32;       // 16-byte chunks per weight row and quarter (18)
-        constexpr int kQLoads = 32 * kQC / 64;    // wave loads per quarter (9)
-        constexpr int kQBytes = 32 * kQC * 16;
-        static_assert((32 * kQC) % 64 == 0 && KSUB % 4 == 0 && R * S * C == 32 * kQC, "whole wave loads per quarter");
+        // Weights of this wave's 32 channels -> registers, through a private LDS region that
+        // overlaps ring slot 2 and the output staging, which are not in use before the first
+        // barrier; slots 0 and 1 are being filled by the memory waves meanwhile.
         bf16x8_t wf[KSUB];
-        {
-            char *wreg = smem + 2 * kSlot + wave * (2 * kQBytes);
-            const rsrc_t wr = make_rsrc(w + (int64_t)wave * 32 * (R * S * C), (uint32_t)(32 * R * S * C * 2));
-            uint32_t wvo[kQLoads];
-#pragma unroll
-            for (int i = 0; i < kQLoads; ++i) {
-                const int L = i * 64 + lane, row = L / kQC;
-                int c = L % kQC - (row >> 3);
-                c = c < 0 ? c + kQC : c;
-                wvo[i] = (uint32_t)(row * (4 * kQC) + c) * 16u;
-            }
-            const int frow = lane & 31;
-            auto issue_q = [&](int q, int sub) {
-#pragma unroll
-                for (int i = 0; i < kQLoads; ++i) {
-                    const uint32_t vo = wvo[i];
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (__attribute__((address_space(3))) void *)(wreg + sub * kQBytes + i * 1024),
-                                                             16, vo, q * (kQC * 16), 0, 0);
-                }
-            };
-            auto read_q = [&](int q, int sub) {
-#pragma unroll
-                for (int kk = 0; kk < KSUB / 4; ++kk) {
-                    int p = 2 * kk + (lane >> 5) + (frow >> 3);
-                    p = p >= kQC ? p - kQC : p;
-                    wf[q * (KSUB / 4) + kk] = *reinterpret_cast<const bf16x8_t *>(wreg + sub * kQBytes + (frow * kQC + p) * 16);
-                }
-            };
-            issue_q(0, 0);
-            issue_q(1, 1);
-            wait_vmem<kQLoads>();
-            read_q(0, 0);
-            wait_vmem_and_lds<kQLoads>();
-            issue_q(2, 0);
-            wait_vmem<kQLoads>();
-            read_q(1, 1);
-            wait_vmem_and_lds<kQLoads>();
-            issue_q(3, 1);
-            wait_vmem<kQLoads>();
-            read_q(2, 0);
-            wait_vmem<0>();
-            read_q(3, 1);
-            wait_vmem_and_lds<0>();
-        }
+        load_weight_frags<R, S, C>(wf, smem + 2 * kSlot, w, wave, lane);
         const int frag_lo = frag_offset(lane & 31, lane >> 5);        // k-substep 0 of a sub-tile
         const int frag_hi = frag_offset(lane & 31, 2 + (lane >> 5));  // k-substep 1
         // fragment kk of a block: sub-tile kk/2 (32 channels = 2 k-substeps; sub-tiles are stored
@@ -400,6 +411,231 @@ __global__ __launch_bounds__(512) void conv2d_wreg_kernel(const uint16_t *__rest
             fire_block(b + 3);
             store_block(b - 1, b > 0);
             prep_block();
+        }
+        wg_barrier();  // the last block is staged
+        store_block(nblocks - 1, nblocks > 0);
+        wait_vmem_and_lds<0>();
+    }
+}
+
+// The same division of labour with the input RESIDENT in LDS (stride 1): a workgroup's pixel
+// range covers a few output rows of one image, and the input rows under them (range rows +
+// R - 1, each with its left and right padding columns, zero-filled by the buffer range check)
+// fit the LDS as they are: 9 input rows of 58 pixels for 7 output rows of 56.  They are
+// fetched ONCE, in the prologue, instead of once per filter tap as im2col slices, so in the
+// steady state the LDS port carries only the operand reads and the output staging (160 KiB
+// per 32-pixel block instead of 196), the vector-memory path only the stores, and the MFMA
+// waves wait for nothing but their own reads.  A pixel takes 144 bytes (128 of channels + 16
+// of padding): with that pitch the 16-byte slots of consecutive pixels fall on 9p mod 16, all
+// different within any 16 lanes, so every ds_read_b128 of an operand is conflict free without
+// a swizzle, and filter tap (r, s) and the k-substep become an immediate offset
+// (s * 144 + ks * 32) on one of R per-lane row addresses.  The patch is filled in linear
+// order, 9 chunks of 16 bytes per pixel, the ninth reading out of range.
+template <int R, int S, int C, typename CT>
+__global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__restrict__ x,
+                                                          const uint16_t *__restrict__ w, CT *__restrict__ y,
+                                                          ConvGeom g, int px_per_wg, int patch_rows)
+{
+    constexpr int KOUT = 128;               // 4 MFMA waves x 32 channels
+    constexpr int KSUB = R * S * C / 16;    // MFMA k-substeps per pixel block
+    constexpr int kPerTap = C / 16;         // k-substeps per filter tap
+    constexpr int kPix = C * 2 + 16;        // LDS bytes per input pixel
+    constexpr int kChunks = kPix / 16;      // 16-byte chunks per pixel, the last one padding
+    constexpr int kWeightRegion = 128 * R * S * C;  // prologue: two quarters of every wave's weights
+    constexpr int kOutPitch = KOUT * (int)sizeof(CT) + 16;
+    constexpr int kOutBytes = 32 * kOutPitch;
+    constexpr int kRowLanes = KOUT * (int)sizeof(CT) / 16;  // lanes per pixel row of 16-byte pieces
+    constexpr int kStores = 8 * kRowLanes / 64;             // store instructions per memory wave per block (8 rows each)
+    constexpr int kWin = 9;                                 // operand window of the MFMA waves
+    constexpr int kBar = KSUB - kWin;                       // MFMAs of a block in front of its barrier: behind it the window reads the next block
+    constexpr int kFill = 3;                                // patch loads per memory wave and block in the steady state
+    static_assert(C == 64 && KSUB % kWin == 0 && 2 * kOutBytes <= kWeightRegion, "layout assumptions");
+    static_assert(256 % kChunks == 4 && 256 / kChunks == 28, "the fill's step of 256 chunks is 28 pixels and 4 chunks");
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    char *const out_stage = smem;               // (the weight region is free after the first barrier)
+    char *const patch = smem + kWeightRegion;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int Mtot = g.N * g.P * g.Q;
+    const int wg = gridDim.x % 8 == 0 ? (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
+    const int start = wg * px_per_wg, end = min(start + px_per_wg, Mtot);
+    const int nblocks = (end - start + 31) / 32;
+    // the range lies inside one image (the host checks it): first pixel = (n0, oh0, q0)
+    const int n0 = start / (g.P * g.Q), pq0 = start - n0 * (g.P * g.Q);
+    const int oh0 = pq0 / g.Q, q0 = pq0 - oh0 * g.Q;
+    const int Wv = g.W + 2 * g.pw;  // pixels per patch row; patch row v holds input row oh0 - ph + v
+    // Both kinds of wave execute exactly 2 + nblocks workgroup barriers.
+
+    if (wave < 4) {
+        // ------------------------------ MFMA waves ------------------------------
+        __builtin_amdgcn_s_setprio(2);
+        bf16x8_t wf[KSUB];
+        load_weight_frags<R, S, C>(wf, smem, w, wave, lane);
+        typedef const __attribute__((address_space(3))) char lds_char_t;
+        typedef const __attribute__((address_space(3))) bf16x8_t lds_frag_t;
+        lds_char_t *const lds0 = (lds_char_t *)smem;
+        // fragment kk = filter tap kk / kPerTap = (r, s), k-substep kk % kPerTap, relative to the
+        // lane's address of the pixel under tap (r, 0)
+        auto read_frag = [&](const uint32_t (&rowaddr)[R], int kk) {
+            const int tap = kk / kPerTap, r = tap / S, sft = tap % S;
+            return *(lds_frag_t *)(lds0 + rowaddr[r] + sft * kPix + (kk % kPerTap) * 32);
+        };
+        // this lane's pixel of block 0: column q0 + lane%32 of the range's first row, or past its end
+        // in the second (Q >= 32: one wrap at most); a lane holds channels 8*(lane/32).. of a k-substep
+        int ow = q0 + (lane & 31);
+        uint32_t pix_addr = (uint32_t)kWeightRegion + (uint32_t)(lane >> 5) * 16u;
+        if (ow >= g.Q) {
+            ow -= g.Q;
+            pix_addr += (uint32_t)(Wv * kPix);
+        }
+        pix_addr += (uint32_t)(ow * kPix);
+        const uint32_t row_pitch = (uint32_t)(Wv * kPix), wrap_extra = (uint32_t)((Wv - g.Q) * kPix);
+        uint32_t cur[R], nxt[R];
+        auto rows_of = [&](uint32_t (&a)[R]) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) a[r] = pix_addr + (uint32_t)r * row_pitch;
+        };
+        auto next_block = [&]() {  // the lane's pixel 32 further on in the flattened (row, column) order
+            ow += 32;
+            const bool wrap = ow >= g.Q;
+            ow = wrap ? ow - g.Q : ow;
+            pix_addr += 32u * kPix + (wrap ? wrap_extra : 0u);
+        };
+        rows_of(cur);
+        // staging position: lane holds channels wave*32 + 8a + 4*(lane/32) + 0..3 of pixel lane%32
+        const int stage_wr = (lane & 31) * kOutPitch + (wave * 32 + 4 * (lane >> 5)) * (int)sizeof(CT);
+
+        wg_barrier();  // the patch is complete (and every wave is done with the weight region)
+        bf16x8_t af[kWin];
+#pragma unroll
+        for (int kk = 0; kk < kWin; ++kk) af[kk] = read_frag(cur, kk);
+        float16_t accs[2];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) accs[0][e] = accs[1][e] = 0.f;
+
+        // One block: `acc` collects block b, `prev` holds block b-1's results (zeros for b = 0,
+        // staged but never written out).  In the shadow of the first MFMAs `prev` is converted
+        // and staged, then cleared for block b+1.  The barrier tells the memory waves that it is
+        // staged, and the MFMA waves that the patch rows under block b+1 have landed.
+        for (int b0 = 0; b0 < nblocks; b0 += 2) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int b = b0 + h;
+                if (b >= nblocks) break;
+                float16_t &acc = accs[h];
+                float16_t &prev = accs[h ^ 1];
+                next_block();
+                rows_of(nxt);
+                // opaque to the optimiser: folded with the tap offsets they would turn into one address
+                // register per read, which does not fit the register budget of two waves per SIMD
+#pragma unroll
+                for (int r = 0; r < R; ++r) asm volatile("" : "+v"(cur[r]), "+v"(nxt[r]));
+                char *stg = out_stage + ((b - 1) & 1) * kOutBytes + stage_wr;
+#pragma unroll
+                for (int kk = 0; kk < KSUB; ++kk) {
+                    if (kk == kBar) {
+                        // the staging writes are older than the window's reads: at most kWin LDS
+                        // operations outstanding means they are done (lgkmcnt only)
+                        __builtin_amdgcn_s_waitcnt(0xC07F | (kWin << 8));
+                        wg_barrier();
+                    }
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
+                    af[kk % kWin] = kk + kWin < KSUB ? read_frag(cur, kk + kWin) : read_frag(nxt, kk + kWin - KSUB);
+                    if (kk >= 1 && kk < 5) {
+                        const int a = kk - 1;
+                        if constexpr (sizeof(CT) == 4) {
+                            *reinterpret_cast<float4_t *>(stg + 8 * a * 4) =
+                                float4_t{prev[4 * a], prev[4 * a + 1], prev[4 * a + 2], prev[4 * a + 3]};
+                        } else {
+                            *reinterpret_cast<uint2_t *>(stg + 8 * a * 2) =
+                                uint2_t{pack_bf16(prev[4 * a], prev[4 * a + 1]), pack_bf16(prev[4 * a + 2], prev[4 * a + 3])};
+                        }
+                    }
+                    if (kk >= 6 && kk < 10) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) prev[4 * (kk - 6) + e] = 0.f;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int r = 0; r < R; ++r) cur[r] = nxt[r];
+            }
+        }
+        // the last block's results
+        const float16_t last = ((nblocks - 1) & 1) ? accs[1] : accs[0];
+        stage_acc<CT>(last, out_stage + ((nblocks - 1) & 1) * kOutBytes + stage_wr);
+        wait_vmem_and_lds<0>();
+        wg_barrier();
+    } else {
+        // ------------------------------ memory waves ------------------------------
+        const int mw = wave - 4;
+        // Patch fill: chunk L of the patch (linear, kChunks per pixel) is written by lane L % 64 of
+        // wave load L / 64; the four waves take the loads in turn.  (row, column, chunk) of a
+        // lane's next chunk follow by steps of 256 chunks = 28 pixels and 4 chunks; the first 256
+        // chunks lie in row 0 (Wv >= 34 > 28).  Offsets are 32-bit: tensors below 2 GiB (host).
+        const rsrc_t xr = make_rsrc(x, (uint32_t)((int64_t)g.N * g.H * g.W * g.C * 2));
+        const int nloads = (patch_rows * Wv * kChunks + 63) / 64;
+        const int L0 = mw * 64 + lane;
+        int ch = L0 % kChunks, vcol = L0 / kChunks, vrow = 0;
+        int next_load = mw;
+        auto fire_one = [&]() {
+            const int ih = oh0 - g.ph + vrow, iw = vcol - g.pw;
+            const bool ok = ch < kChunks - 1 && vrow < patch_rows && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
+            const uint32_t vo = ok ? (uint32_t)(((n0 * g.H + ih) * g.W + iw) * C + ch * 8) * 2u : kOutOfRange;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void *)(patch + next_load * 1024), 16,
+                                                     vo, 0, 0, 0);
+            ch += 4;
+            vcol += 28;
+            if (ch >= kChunks) {
+                ch -= kChunks;
+                ++vcol;
+            }
+            if (vcol >= Wv) {
+                vcol -= Wv;
+                ++vrow;
+            }
+            next_load += 4;
+        };
+        // Before the first block: the rows under blocks 0 .. 3 (whole rounds of the four waves).
+        // From then on kFill loads per wave and block; what block b+1 reads has been issued by
+        // the end of step b-2 at the latest (the host checks this schedule for the shape).
+        const int rows0 = min(patch_rows, (q0 + 127) / g.Q + R);
+        const int loads0 = min((nloads + 3) / 4 * 4, ((rows0 * Wv * kChunks + 63) / 64 + 3) / 4 * 4);
+        while (next_load < loads0 && next_load < nloads) fire_one();
+        // write-out of a staged block: this wave stores pixel rows mw*8 .. mw*8+7 through a
+        // buffer resource; rows past the range get an out-of-range offset and are dropped
+        const rsrc_t yr = make_rsrc(y, (uint32_t)((int64_t)Mtot * KOUT * sizeof(CT)));
+        auto store_block = [&](int b, bool enable) {
+            const char *stg = out_stage + (b & 1) * kOutBytes;
+#pragma unroll
+            for (int t = 0; t < kStores; ++t) {
+                const int row = mw * 8 + t * (64 / kRowLanes) + lane / kRowLanes;
+                const int m = start + b * 32 + row;
+                const uint4_t v = *reinterpret_cast<const uint4_t *>(stg + row * kOutPitch + (lane % kRowLanes) * 16);
+                const uint32_t off = (uint32_t)m * (uint32_t)(KOUT * sizeof(CT)) + (lane % kRowLanes) * 16;
+                __builtin_amdgcn_raw_buffer_store_b128(v, yr, (enable && m < end) ? off : kOutOfRange, 0, 2 /* nt */);
+            }
+        };
+        wait_vmem<0>();  // own part of the first rows has landed
+        wg_barrier();    // the first rows are complete; the MFMA waves are done with the weight region
+        // Memory operations complete in order, so "the loads of step b-2 have landed" is a bound on
+        // the number of younger operations: the loads of step b-1 and one block's stores (every
+        // step issues kStores stores, disabled ones while there is nothing to store).
+        int fired = 0;  // loads of the previous step
+        for (int b = 0; b < nblocks; ++b) {
+            if (fired == kFill) wait_vmem_and_lds<kFill + kStores>();
+            else if (fired == 0) wait_vmem_and_lds<kStores>();
+            else wait_vmem_and_lds<0>();  // (the step in which the fill runs out)
+            wg_barrier();  // block b-1 is staged; the rows under block b+1 are complete
+            fired = 0;
+#pragma unroll
+            for (int t = 0; t < kFill; ++t)
+                if (next_load < nloads) {
+                    fire_one();
+                    ++fired;
+                }
+            store_block(b - 1, b > 0);
         }
         wg_barrier();  // the last block is staged
         store_block(nblocks - 1, nblocks > 0);
@@ -677,6 +913,24 @@ static perf_status launch_conv_wreg(const void *x, const void *w, void *y, const
 }
 
 template <int R, int S, int C, typename CT>
+static perf_status launch_conv_wres(const void *x, const void *w, void *y, const ConvGeom &g, int px_per_wg,
+                                    int patch_rows, size_t lds, hipStream_t st)
+{
+    const int64_t Mtot = (int64_t)g.N * g.P * g.Q;
+    auto kern = conv2d_wres_kernel<R, S, C, CT>;
+    static size_t lds_set = 0;  // the dynamic-LDS cap is a per-function setting; raise it when a larger patch comes along
+    if (lds > lds_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return PERF_ERR_LAUNCH;
+        lds_set = lds;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(Mtot / px_per_wg)), dim3(512), lds, st, (const uint16_t *)x,
+                       (const uint16_t *)w, (CT *)y, g, px_per_wg, patch_rows);
+    return launch_status();
+}
+
+template <int R, int S, int C, typename CT>
 static perf_status launch_conv_rowmfma(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
 {
     const int tiles_w = (g.Q + 63) / 64, tiles_h = (g.P + 31) / 32;
@@ -734,7 +988,7 @@ static perf_status launch_conv_direct(const void *x, const void *w, void *y, con
 
 namespace perf {
 
-enum ConvVariant { kConvAuto = 0, kConvWreg = 1, kConvMfma = 2, kConvSmallC = 3, kConvDirect = 4, kConvRowMfma = 5 };
+enum ConvVariant { kConvAuto = 0, kConvWreg = 1, kConvMfma = 2, kConvSmallC = 3, kConvDirect = 4, kConvRowMfma = 5, kConvWres = 6 };
 
 // variant: kConvAuto = chosen here from the shape; otherwise the caller's choice (perf_conv2d_variant).
 static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N, int64_t H, int64_t W, int64_t C,
@@ -765,6 +1019,40 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
                          ((N * P * Q + 63) / 64) * ((K + 63) / 64) <= kMaxGridX;
     // filter shapes with a weights-in-registers instance
     const bool wreg_ok = mfma_ok && R == 3 && S == 3 && C == 64 && K == 128 && Q >= 32 && N * P * Q * K < (int64_t(1) << 29);
+    // ... with the input resident in LDS: stride 1, every workgroup's pixel range inside one image, and
+    // the input rows under the longest range (rounded up to whole 32-pixel blocks) fit beside the
+    // weight region: rows x (W + 2 pad_w) pixels x 144 bytes, filled in wave loads of 1 KiB
+    int wres_px = 0, wres_rows = 0;
+    size_t wres_lds = 0;
+    if (wreg_ok && stride_h == 1 && stride_w == 1) {
+        const int64_t Mpix = N * P * Q, blocks = (Mpix + 31) / 32;
+        const int64_t px = (Mpix + (blocks < 256 ? blocks : 256) - 1) / (blocks < 256 ? blocks : 256);
+        if ((P * Q) % px == 0) {
+            const int64_t nb = (px + 31) / 32, q0max = px % Q == 0 ? 0 : Q - 1;
+            const int64_t rows = (q0max + nb * 32 - 1) / Q + R;
+            const int64_t rc = (W + 2 * pad_w) * 9, nloads = (rows * rc + 63) / 64;  // 16-byte chunks per patch row; wave loads
+            const int64_t lds = 128 * R * S * C + nloads * 1024;
+            // the kernel's fill schedule: the rows under blocks 0..3 before the first block, then 12
+            // loads per block; at the barrier of block b the loads of steps <= b-2 have landed, and
+            // the rows under block b+1 must be among them, whatever column q0 the range starts in
+            bool fill_ok = true;
+            for (int64_t q0 = 0; q0 <= q0max && fill_ok; ++q0) {
+                const int64_t rows0 = std::min(rows, (q0 + 127) / Q + R);
+                const int64_t loads0 = std::min((nloads + 3) / 4 * 4, ((rows0 * rc + 63) / 64 + 3) / 4 * 4);
+                for (int64_t b = 0; b < nb; ++b) {
+                    const int64_t need = std::min(rows, (q0 + 32 * (b + 1) + 31) / Q + R) * rc;
+                    const int64_t have = std::min(nloads, loads0 + 12 * std::max<int64_t>(0, b - 1)) * 64;
+                    if (have < need) fill_ok = false;
+                }
+            }
+            if (lds <= 160 * 1024 && fill_ok) {
+                wres_px = (int)px;
+                wres_rows = (int)rows;
+                wres_lds = (size_t)lds;
+            }
+        }
+    }
+    const bool wres_ok = wres_px > 0;
     // few input channels: channel-blocked direct kernel, if a 16-channel block of weights fits its LDS budget
     const bool smallc_ok = R * S * C * 16 * 4 <= kSmallcLdsBytes && (K + 15) / 16 <= kMaxGridYZ;
     // few input channels, one filter row per MFMA K-step: bf16, stride 1, an instantiated filter shape
@@ -775,15 +1063,19 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
     if (variant == kConvAuto)
         // (the channel-blocked kernel has one thread per pixel: below ~64 workgroups of pixels the
         // thread-per-output kernel has more parallelism and measured faster)
-        variant = wreg_ok ? kConvWreg
+        variant = wres_ok   ? kConvWres
+                  : wreg_ok ? kConvWreg
                   : mfma_ok ? kConvMfma
                   : (rowmfma_ok && N * P * Q >= 16384)          ? kConvRowMfma
                   : (C < 32 && smallc_ok && N * P * Q >= 16384) ? kConvSmallC
                                                                 : kConvDirect;
     else if ((variant == kConvWreg && !wreg_ok) || (variant == kConvMfma && !mfma_ok) ||
-             (variant == kConvSmallC && !smallc_ok) || (variant == kConvRowMfma && !rowmfma_ok) || variant < kConvWreg ||
-             variant > kConvRowMfma)
+             (variant == kConvSmallC && !smallc_ok) || (variant == kConvRowMfma && !rowmfma_ok) ||
+             (variant == kConvWres && !wres_ok) || variant < kConvWreg || variant > kConvWres)
         return PERF_ERR_UNSUPPORTED;
+    if (variant == kConvWres)
+        return y_dt == PERF_F32 ? launch_conv_wres<3, 3, 64, float>(x, w, y, g, wres_px, wres_rows, wres_lds, st)
+                                : launch_conv_wres<3, 3, 64, uint16_t>(x, w, y, g, wres_px, wres_rows, wres_lds, st);
     if (variant == kConvRowMfma)
         return y_dt == PERF_F32 ? dispatch_conv_rowmfma<float>(x, w, y, g, st) : dispatch_conv_rowmfma<uint16_t>(x, w, y, g, st);
     if (variant == kConvWreg)

@@ -51,6 +51,27 @@ def test_weights_in_registers_kernel(kw, y_bf16):
     _check(configs.ConvWorkload(**kw), y_bf16=y_bf16, variant=perf.CONV_WREG)
 
 
+@pytest.mark.parametrize("kw", [dict(N=2), dict(N=8), dict(N=16), dict(N=1, H=32, W=32), dict(N=4, H=58, W=58, pad=0),
+                                dict(N=2, H=16, W=128), dict(N=1, H=64, W=40)])
+@pytest.mark.parametrize("y_bf16", [True, False])
+def test_input_resident_kernel(kw, y_bf16):
+    # ranges of 32 .. 196 pixels that start anywhere in a row (lanes wrap to the next row inside a
+    # block), ragged last blocks, one block per workgroup, no padding, rows wider than the default
+    import paper_2511_03586_amd as perf
+    _check(configs.ConvWorkload(**kw), y_bf16=y_bf16, variant=perf.CONV_WRES)
+
+
+def test_input_resident_kernel_refuses_what_it_cannot_run():
+    import torch
+    import paper_2511_03586_amd as perf
+    buf = torch.zeros(1 << 22, dtype=torch.int16, device="cuda")
+    # stride 2; pixel ranges that would straddle images (33 x 35 outputs, ranges of 32); rows too wide for the LDS
+    for n, h, w_, st in [(2, 56, 56, 2), (3, 33, 35, 1), (1, 32, 1024, 1)]:
+        rc = perf.perf_conv2d_variant(buf.data_ptr(), buf.data_ptr(), buf.data_ptr(), n, h, w_, 64, 128, 3, 3, st, st, 1, 1,
+                                      perf.PERF_BF16, perf.PERF_BF16, perf.CONV_WRES, G.stream(), check=False)
+        assert rc == perf.PERF_ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("kw,y_bf16", [
     (dict(N=16, H=56, W=56, C=32, K=256), True),     # 784 tiles of 128 pixels x 128 channels
     (dict(N=32, H=56, W=56, C=32, K=48), True),      # 784 tiles of 128 x 64, ragged channels
