@@ -620,13 +620,15 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
         wait_vmem<0>();  // own part of the first rows has landed
         wg_barrier();    // the first rows are complete; the MFMA waves are done with the weight region
         // Memory operations complete in order, so "the loads of step b-2 have landed" is a bound on
-        // the number of younger operations: the loads of step b-1 and one block's stores (every
-        // step issues kStores stores, disabled ones while there is nothing to store).
+        // the number of younger operations: the stores of step b-2 and the loads and stores of
+        // step b-1 (every step issues kStores stores, disabled ones while there is nothing to
+        // store), so two blocks of stores stay in flight.
+        static_assert(kFill + 2 * kStores < 64, "vmcnt is a 6-bit counter");
         int fired = 0;  // loads of the previous step
         for (int b = 0; b < nblocks; ++b) {
-            if (fired == kFill) wait_vmem_and_lds<kFill + kStores>();
-            else if (fired == 0) wait_vmem_and_lds<kStores>();
-            else wait_vmem_and_lds<0>();  // (the step in which the fill runs out)
+            if (fired == kFill) wait_vmem_and_lds<kFill + 2 * kStores>();
+            else if (fired == 0) wait_vmem_and_lds<2 * kStores>();
+            else wait_vmem_and_lds<kStores>();  // (the step after the one in which the fill ran out)
             wg_barrier();  // block b-1 is staged; the rows under block b+1 are complete
             fired = 0;
 #pragma unroll
