@@ -1028,8 +1028,11 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
     size_t wres_lds = 0;
     if (wreg_ok && stride_h == 1 && stride_w == 1) {
         const int64_t Mpix = N * P * Q, blocks = (Mpix + 31) / 32;
-        const int64_t px = (Mpix + (blocks < 256 ? blocks : 256) - 1) / (blocks < 256 ? blocks : 256);
-        if ((P * Q) % px == 0) {
+        // one workgroup per CU if its rows fit, else the smallest whole number of rounds of 256
+        for (int64_t rounds = 1; rounds <= 8 && wres_px == 0; ++rounds) {
+            const int64_t grid = blocks < 256 * rounds ? blocks : 256 * rounds;
+            const int64_t px = (Mpix + grid - 1) / grid;
+            if ((P * Q) % px != 0) continue;
             const int64_t nb = (px + 31) / 32, q0max = px % Q == 0 ? 0 : Q - 1;
             const int64_t rows = (q0max + nb * 32 - 1) / Q + R;
             const int64_t rc = (W + 2 * pad_w) * 9, nloads = (rows * rc + 63) / 64;  // 16-byte chunks per patch row; wave loads
@@ -1041,9 +1044,9 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
             for (int64_t q0 = 0; q0 <= q0max && fill_ok; ++q0) {
                 const int64_t rows0 = std::min(rows, (q0 + 127) / Q + R);
                 const int64_t loads0 = std::min((nloads + 3) / 4 * 4, ((rows0 * rc + 63) / 64 + 3) / 4 * 4);
-                for (int64_t b = 0; b < nb; ++b) {
-                    const int64_t need = std::min(rows, (q0 + 32 * (b + 1) + 31) / Q + R) * rc;
-                    const int64_t have = std::min(nloads, loads0 + 12 * std::max<int64_t>(0, b - 1)) * 64;
+                for (int64_t b2 = 0; b2 < nb; ++b2) {
+                    const int64_t need = std::min(rows, (q0 + 32 * (b2 + 1) + 31) / Q + R) * rc;
+                    const int64_t have = std::min(nloads, loads0 + 12 * std::max<int64_t>(0, b2 - 1)) * 64;
                     if (have < need) fill_ok = false;
                 }
             }

@@ -52,11 +52,12 @@ def test_weights_in_registers_kernel(kw, y_bf16):
 
 
 @pytest.mark.parametrize("kw", [dict(N=2), dict(N=8), dict(N=16), dict(N=1, H=32, W=32), dict(N=4, H=58, W=58, pad=0),
-                                dict(N=2, H=16, W=128), dict(N=1, H=64, W=40)])
+                                dict(N=2, H=16, W=128), dict(N=1, H=64, W=40), dict(N=4, H=60, W=120)])
 @pytest.mark.parametrize("y_bf16", [True, False])
 def test_input_resident_kernel(kw, y_bf16):
     # ranges of 32 .. 196 pixels that start anywhere in a row (lanes wrap to the next row inside a
-    # block), ragged last blocks, one block per workgroup, no padding, rows wider than the default
+    # block), ragged last blocks, one block per workgroup, no padding, rows wider than the default,
+    # 900 workgroups of one block because no larger range divides the image
     import paper_2511_03586_amd as perf
     _check(configs.ConvWorkload(**kw), y_bf16=y_bf16, variant=perf.CONV_WRES)
 
