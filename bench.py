@@ -168,7 +168,7 @@ def build_workloads(torch, perf):
     x5 = rotated(G.dev(d5["x_bf16"]), 16)
     w5 = G.dev(d5["w_bf16"])
     y5 = torch.empty((16, c5.N, c5.P, c5.Q, c5.K), dtype=torch.int16, device="cuda")
-    wls.append(Workload("conv2d_32x56x56x64_k128_3x3_bf16", "conv2d_wreg_kernel<3,3,64,bf16>", "mfma", c5.flops(),
+    wls.append(Workload("conv2d_32x56x56x64_k128_3x3_bf16", "conv2d_wres_kernel<3,3,64,bf16>", "mfma", c5.flops(),
                         lambda i: perf.perf_conv2d(x5[i % 16].data_ptr(), w5.data_ptr(), y5[i % 16].data_ptr(), c5.N,
                                                    c5.H, c5.W, c5.C, c5.K, c5.R, c5.S, 1, 1, 1, 1, BF16, BF16, st()),
                         16))

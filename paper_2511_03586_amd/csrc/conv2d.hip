@@ -465,6 +465,10 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
     const int n0 = start / (g.P * g.Q), pq0 = start - n0 * (g.P * g.Q);
     const int oh0 = pq0 / g.Q, q0 = pq0 - oh0 * g.Q;
     const int Wv = g.W + 2 * g.pw;  // pixels per patch row; patch row v holds input row oh0 - ph + v
+    // chunks per patch row: the Wv pixels and padding up to 9 Q + 32, so that a lane whose pixel
+    // wraps to the next output row moves on by a multiple of 256 bytes more than its neighbours:
+    // the 16 lanes of a read keep 16 different bank slots across the wrap
+    const int row_chunks = kChunks * g.Q + 32;
     // Both kinds of wave execute exactly 2 + nblocks workgroup barriers.
 
     if (wave < 4) {
@@ -487,10 +491,10 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
         uint32_t pix_addr = (uint32_t)kWeightRegion + (uint32_t)(lane >> 5) * 16u;
         if (ow >= g.Q) {
             ow -= g.Q;
-            pix_addr += (uint32_t)(Wv * kPix);
+            pix_addr += (uint32_t)(row_chunks * 16);
         }
         pix_addr += (uint32_t)(ow * kPix);
-        const uint32_t row_pitch = (uint32_t)(Wv * kPix), wrap_extra = (uint32_t)((Wv - g.Q) * kPix);
+        const uint32_t row_pitch = (uint32_t)(row_chunks * 16), wrap_extra = (uint32_t)(row_chunks * 16 - g.Q * kPix);
         uint32_t cur[R], nxt[R];
         auto rows_of = [&](uint32_t (&a)[R]) {
 #pragma unroll
@@ -505,6 +509,10 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
         rows_of(cur);
         // staging position: lane holds channels wave*32 + 8a + 4*(lane/32) + 0..3 of pixel lane%32
         const int stage_wr = (lane & 31) * kOutPitch + (wave * 32 + 4 * (lane >> 5)) * (int)sizeof(CT);
+        // bf16: after a permlane32 swap of element groups a and a+1 a lane holds 8 consecutive
+        // channels, cg*32 + 8 (a + lane/32) + 0..7, of its pixel: 16-byte writes (8-byte ones at
+        // this pitch put lanes p and p+16 on the same banks)
+        const int stage_wr16 = (lane & 31) * kOutPitch + (wave * 32 + 8 * (lane >> 5)) * 2;
 
         wg_barrier();  // the patch is complete (and every wave is done with the weight region)
         bf16x8_t af[kWin];
@@ -532,6 +540,7 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
 #pragma unroll
                 for (int r = 0; r < R; ++r) asm volatile("" : "+v"(cur[r]), "+v"(nxt[r]));
                 char *stg = out_stage + ((b - 1) & 1) * kOutBytes + stage_wr;
+                char *stg16 = out_stage + ((b - 1) & 1) * kOutBytes + stage_wr16;
 #pragma unroll
                 for (int kk = 0; kk < KSUB; ++kk) {
                     if (kk == kBar) {
@@ -542,14 +551,21 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
                     }
                     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
                     af[kk % kWin] = kk + kWin < KSUB ? read_frag(cur, kk + kWin) : read_frag(nxt, kk + kWin - KSUB);
-                    if (kk >= 1 && kk < 5) {
-                        const int a = kk - 1;
-                        if constexpr (sizeof(CT) == 4) {
+                    if constexpr (sizeof(CT) == 4) {
+                        if (kk >= 1 && kk < 5) {
+                            const int a = kk - 1;
                             *reinterpret_cast<float4_t *>(stg + 8 * a * 4) =
                                 float4_t{prev[4 * a], prev[4 * a + 1], prev[4 * a + 2], prev[4 * a + 3]};
-                        } else {
-                            *reinterpret_cast<uint2_t *>(stg + 8 * a * 2) =
-                                uint2_t{pack_bf16(prev[4 * a], prev[4 * a + 1]), pack_bf16(prev[4 * a + 2], prev[4 * a + 3])};
+                        }
+                    } else {
+                        if (kk == 1 || kk == 3) {
+                            const int a = kk - 1;  // element groups a and a + 1
+                            const uint32_t x0 = pack_bf16(prev[4 * a], prev[4 * a + 1]), x1 = pack_bf16(prev[4 * a + 2], prev[4 * a + 3]);
+                            const uint32_t y0 = pack_bf16(prev[4 * a + 4], prev[4 * a + 5]), y1 = pack_bf16(prev[4 * a + 6], prev[4 * a + 7]);
+                            // (lower half-wave: own group a, then the upper lane's; upper: the lower lane's group a+1, then own)
+                            const auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+                            const auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+                            *reinterpret_cast<uint4_t *>(stg16 + 8 * a * 2) = uint4_t{s0[0], s1[0], s0[1], s1[1]};
                         }
                     }
                     if (kk >= 6 && kk < 10) {
@@ -570,29 +586,25 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
     } else {
         // ------------------------------ memory waves ------------------------------
         const int mw = wave - 4;
-        // Patch fill: chunk L of the patch (linear, kChunks per pixel) is written by lane L % 64 of
-        // wave load L / 64; the four waves take the loads in turn.  (row, column, chunk) of a
-        // lane's next chunk follow by steps of 256 chunks = 28 pixels and 4 chunks; the first 256
-        // chunks lie in row 0 (Wv >= 34 > 28).  Offsets are 32-bit: tensors below 2 GiB (host).
+        // Patch fill: chunk L of the patch (linear: rows of row_chunks chunks, kChunks per pixel,
+        // padding behind the last pixel) is written by lane L % 64 of wave load L / 64; the four
+        // waves take the loads in turn, a lane's next chunk is 256 further on.  Padding chunks and
+        // pixels outside the image read out of range, i.e. zeros.  Offsets are 32-bit: tensors
+        // below 2 GiB (host).
         const rsrc_t xr = make_rsrc(x, (uint32_t)((int64_t)g.N * g.H * g.W * g.C * 2));
-        const int nloads = (patch_rows * Wv * kChunks + 63) / 64;
-        const int L0 = mw * 64 + lane;
-        int ch = L0 % kChunks, vcol = L0 / kChunks, vrow = 0;
+        const int nloads = (patch_rows * row_chunks + 63) / 64;
+        int rem = mw * 64 + lane, vrow = 0;  // chunk `rem` of patch row `vrow` (the first 256 chunks lie in row 0)
         int next_load = mw;
         auto fire_one = [&]() {
+            const int vcol = rem / kChunks, ch = rem - vcol * kChunks;
             const int ih = oh0 - g.ph + vrow, iw = vcol - g.pw;
             const bool ok = ch < kChunks - 1 && vrow < patch_rows && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
             const uint32_t vo = ok ? (uint32_t)(((n0 * g.H + ih) * g.W + iw) * C + ch * 8) * 2u : kOutOfRange;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void *)(patch + next_load * 1024), 16,
                                                      vo, 0, 0, 0);
-            ch += 4;
-            vcol += 28;
-            if (ch >= kChunks) {
-                ch -= kChunks;
-                ++vcol;
-            }
-            if (vcol >= Wv) {
-                vcol -= Wv;
+            rem += 256;  // (row_chunks >= 9 * 32 + 32 > 256: one wrap at most)
+            if (rem >= row_chunks) {
+                rem -= row_chunks;
                 ++vrow;
             }
             next_load += 4;
@@ -601,7 +613,7 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
         // From then on kFill loads per wave and block; what block b+1 reads has been issued by
         // the end of step b-2 at the latest (the host checks this schedule for the shape).
         const int rows0 = min(patch_rows, (q0 + 127) / g.Q + R);
-        const int loads0 = min((nloads + 3) / 4 * 4, ((rows0 * Wv * kChunks + 63) / 64 + 3) / 4 * 4);
+        const int loads0 = min((nloads + 3) / 4 * 4, ((rows0 * row_chunks + 63) / 64 + 3) / 4 * 4);
         while (next_load < loads0 && next_load < nloads) fire_one();
         // write-out of a staged block: this wave stores pixel rows mw*8 .. mw*8+7 through a
         // buffer resource; rows past the range get an out-of-range offset and are dropped
@@ -1023,7 +1035,7 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
     const bool wreg_ok = mfma_ok && R == 3 && S == 3 && C == 64 && K == 128 && Q >= 32 && N * P * Q * K < (int64_t(1) << 29);
     // ... with the input resident in LDS: stride 1, every workgroup's pixel range inside one image, and
     // the input rows under the longest range (rounded up to whole 32-pixel blocks) fit beside the
-    // weight region: rows x (W + 2 pad_w) pixels x 144 bytes, filled in wave loads of 1 KiB
+    // weight region: rows x (9 Q + 32) chunks of 16 bytes, filled in wave loads of 1 KiB
     int wres_px = 0, wres_rows = 0;
     size_t wres_lds = 0;
     if (wreg_ok && stride_h == 1 && stride_w == 1) {
@@ -1035,7 +1047,7 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
             if ((P * Q) % px != 0) continue;
             const int64_t nb = (px + 31) / 32, q0max = px % Q == 0 ? 0 : Q - 1;
             const int64_t rows = (q0max + nb * 32 - 1) / Q + R;
-            const int64_t rc = (W + 2 * pad_w) * 9, nloads = (rows * rc + 63) / 64;  // 16-byte chunks per patch row; wave loads
+            const int64_t rc = 9 * Q + 32, nloads = (rows * rc + 63) / 64;  // 16-byte chunks per patch row (pixels + padding); wave loads
             const int64_t lds = 128 * R * S * C + nloads * 1024;
             // the kernel's fill schedule: the rows under blocks 0..3 before the first block, then 12
             // loads per block; at the barrier of block b the loads of steps <= b-2 have landed, and
