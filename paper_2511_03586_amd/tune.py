@@ -23,7 +23,7 @@ import paper_2511_03586_amd as perf
 # 33: K-step 32 with the deep ring; 65: K-step 64 built on the 32x32x16 MFMA (256x256 tile only)
 GEMM_SPACE = [(tile, kstep) for tile in (64, 128, 256) for kstep in (32, 64)] + [(64, 33), (128, 33), (256, 65)]
 CONV_SPACE = [perf.CONV_WRES, perf.CONV_WREG, perf.CONV_MFMA, perf.CONV_ROWMFMA, perf.CONV_SMALLC, perf.CONV_DIRECT]
-CONV_NAMES = {perf.CONV_WRES: "weights-in-registers-input-in-lds", perf.CONV_WREG: "weights-in-registers", perf.CONV_MFMA: "implicit-gemm", perf.CONV_ROWMFMA: "filter-row-per-mfma",
+CONV_NAMES = {perf.CONV_WRES: "weights-in-regs, input-in-lds", perf.CONV_WREG: "weights-in-registers", perf.CONV_MFMA: "implicit-gemm", perf.CONV_ROWMFMA: "filter-row-per-mfma",
               perf.CONV_SMALLC: "channel-blocked-direct", perf.CONV_DIRECT: "thread-per-output"}
 
 
