@@ -62,6 +62,16 @@ def test_input_resident_kernel(kw, y_bf16):
     _check(configs.ConvWorkload(**kw), y_bf16=y_bf16, variant=perf.CONV_WRES)
 
 
+def test_input_resident_kernel_edge_shapes():
+    # a single image row (two of the three patch rows lie outside the image), padding wider than
+    # the filter's half width, different padding per axis, the narrowest rows the kernel takes
+    import paper_2511_03586_amd as perf
+    _check(configs.ConvWorkload(N=3, H=1, W=32), variant=perf.CONV_WRES)
+    _check(configs.ConvWorkload(N=2, H=5, W=30, pad=2), variant=perf.CONV_WRES, y_bf16=False)
+    _check(configs.ConvWorkload(N=1, H=34, W=32), pad=(0, 1), variant=perf.CONV_WRES)
+    _check(configs.ConvWorkload(N=1, H=32, W=34), pad=(1, 0), variant=perf.CONV_WRES, y_bf16=False)
+
+
 def test_input_resident_kernel_refuses_what_it_cannot_run():
     import torch
     import paper_2511_03586_amd as perf
