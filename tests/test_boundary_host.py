@@ -200,6 +200,12 @@ def test_variant_entry_points_refuse_without_touching_the_device():
     c = perf.perf_conv2d_variant(FAKE, FAKE + 4096, FAKE + 8192, 1, 8, 8, 3, 4, 3, 3, 1, 1, 1, 1, perf.PERF_BF16,
                                  perf.PERF_BF16, 9, check=False)
     assert c == perf.PERF_ERR_UNSUPPORTED
+    # the input-resident 3x3 kernel: stride 2; pixel ranges that would straddle images (33 x 35 outputs in
+    # ranges of 32); rows too wide for the LDS; all refused before anything is launched
+    for n, h, w_, st in [(2, 56, 56, 2), (3, 33, 35, 1), (1, 32, 1024, 1)]:
+        c = perf.perf_conv2d_variant(FAKE, FAKE + 4096, FAKE + 8192, n, h, w_, 64, 128, 3, 3, st, st, 1, 1, perf.PERF_BF16,
+                                     perf.PERF_BF16, perf.CONV_WRES, check=False)
+        assert c == perf.PERF_ERR_UNSUPPORTED
     c = perf.perf_conv2d_variant(FAKE, FAKE + 4096, FAKE + 8192, 1, 8, 8, 3, 4, 3, 3, 0, 1, 1, 1, perf.PERF_BF16,
                                  perf.PERF_BF16, perf.CONV_DIRECT, check=False)
     assert c == perf.PERF_ERR_SHAPE
