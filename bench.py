@@ -13,7 +13,11 @@ every iteration): each workload cycles through enough pre-filled buffer sets tha
 hold a working set from one launch to the next. Per-kernel durations are measured with HIP
 events on the launch stream inside the timed region.
 
-Prints ONE JSON line (see the design doc for the fields).
+Prints ONE JSON line: `value` = geometric mean of the workloads' fractions of the MI355X roofline
+(HBM 8 TB/s or dense bf16 MFMA 2.5 PFLOP/s, whichever bounds the workload), `ms_per_step` = the sum of
+one launch of each configuration's kernels, `roofline` = the longest kernel's line, `workloads` /
+`paper_shapes` = one entry per timed kernel (time, achieved rate, fraction, HBM traffic from the counter
+profile), the measured copy and MFMA-loop ceilings, and `cpu_baseline` = the CPU oracle timed on this host.
 """
 from __future__ import annotations
 
