@@ -609,10 +609,10 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
             }
             next_load += 4;
         };
-        // Before the first block: the rows under blocks 0 .. 3 (whole rounds of the four waves).
+        // Before the first block: the rows under blocks 0 .. 2 (whole rounds of the four waves).
         // From then on kFill loads per wave and block; what block b+1 reads has been issued by
         // the end of step b-2 at the latest (the host checks this schedule for the shape).
-        const int rows0 = min(patch_rows, (q0 + 127) / g.Q + R);
+        const int rows0 = min(patch_rows, (q0 + 95) / g.Q + R);
         const int loads0 = min((nloads + 3) / 4 * 4, ((rows0 * row_chunks + 63) / 64 + 3) / 4 * 4);
         while (next_load < loads0 && next_load < nloads) fire_one();
         // write-out of a staged block: this wave stores pixel rows mw*8 .. mw*8+7 through a
@@ -1049,12 +1049,12 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
             const int64_t rows = (q0max + nb * 32 - 1) / Q + R;
             const int64_t rc = 9 * Q + 32, nloads = (rows * rc + 63) / 64;  // 16-byte chunks per patch row (pixels + padding); wave loads
             const int64_t lds = 128 * R * S * C + nloads * 1024;
-            // the kernel's fill schedule: the rows under blocks 0..3 before the first block, then 12
+            // the kernel's fill schedule: the rows under blocks 0..2 before the first block, then 12
             // loads per block; at the barrier of block b the loads of steps <= b-2 have landed, and
             // the rows under block b+1 must be among them, whatever column q0 the range starts in
             bool fill_ok = true;
             for (int64_t q0 = 0; q0 <= q0max && fill_ok; ++q0) {
-                const int64_t rows0 = std::min(rows, (q0 + 127) / Q + R);
+                const int64_t rows0 = std::min(rows, (q0 + 95) / Q + R);
                 const int64_t loads0 = std::min((nloads + 3) / 4 * 4, ((rows0 * rc + 63) / 64 + 3) / 4 * 4);
                 for (int64_t b2 = 0; b2 < nb; ++b2) {
                     const int64_t need = std::min(rows, (q0 + 32 * (b2 + 1) + 31) / Q + R) * rc;
