@@ -1036,7 +1036,7 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
     // ... with the input resident in LDS: stride 1, every workgroup's pixel range inside one image, and
     // the input rows under the longest range (rounded up to whole 32-pixel blocks) fit beside the
     // weight region: rows x (9 Q + 32) chunks of 16 bytes, filled in wave loads of 1 KiB
-    int wres_px = 0, wres_rows = 0;
+    int wres_px = 0, wres_rows = 0, wres_rounds = 0;
     size_t wres_lds = 0;
     if (wreg_ok && stride_h == 1 && stride_w == 1) {
         const int64_t Mpix = N * P * Q, blocks = (Mpix + 31) / 32;
@@ -1065,6 +1065,7 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
             if (lds <= 160 * 1024 && fill_ok) {
                 wres_px = (int)px;
                 wres_rows = (int)rows;
+                wres_rounds = (int)rounds;
                 wres_lds = (size_t)lds;
             }
         }
@@ -1080,8 +1081,10 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
     if (variant == kConvAuto)
         // (the channel-blocked kernel has one thread per pixel: below ~64 workgroups of pixels the
         // thread-per-output kernel has more parallelism and measured faster)
-        variant = wres_ok   ? kConvWres
-                  : wreg_ok ? kConvWreg
+        // (every workgroup of the input-resident kernel pays the weight prologue: measured ahead of the ring
+        // kernel with one or two rounds of workgroups, 65 us against 63 with four, 128x56x56)
+        variant = (wres_ok && wres_rounds <= 2) ? kConvWres
+                  : wreg_ok                     ? kConvWreg
                   : mfma_ok ? kConvMfma
                   : (rowmfma_ok && N * P * Q >= 16384)          ? kConvRowMfma
                   : (C < 32 && smallc_ok && N * P * Q >= 16384) ? kConvSmallC
