@@ -144,12 +144,14 @@ def test_mfma_exact_integers_identity_permutation_ones():
     assert np.array_equal(ones, np.full((70, 90), 320.0, np.float32))
 
 
-def test_config3_full_size_sampled_rows():
-    """4096^3 in the benchmark's launch configuration; 48 sampled rows of C (all columns)
-    are recomputed by the oracle, and the whole C is checked against row/column sums."""
+@pytest.mark.parametrize("tile,kstep", [(0, 0), (256, 65)])
+def test_config3_full_size_sampled_rows(tile, kstep):
+    """4096^3 in the benchmark's launch configuration (and with the 32x32x16 variant of its main
+    loop); 48 sampled rows of C (all columns) are recomputed by the oracle, and the whole C is
+    checked against row/column sums."""
     wl = configs.CONFIG3
     d = wl.make()
-    c = G.run_gemm(d["a_bf16"], d["b_bf16"], wl.M, wl.N, wl.K)[0]
+    c = G.run_gemm(d["a_bf16"], d["b_bf16"], wl.M, wl.N, wl.K, tile=tile, kstep=kstep)[0]
     rows = np.unique(np.concatenate([np.arange(0, wl.M, 89), [255, 256, 4095]]))
     a_s = oracle.widen(d["a_bf16"][rows], True)
     bd = oracle.widen(d["b_bf16"], True)
