@@ -182,6 +182,32 @@ def test_config5_full_size_sampled():
             P.assert_contraction_close(yg, ref, ad, 576, out_bf16=y_bf16)
 
 
+def test_config5_full_size_every_entry_exact_integers():
+    """Config 5's launch with small-integer activations (0..8) and weights (-8..8): all partial sums
+    are integers below 2^24, exact in fp32 in any order, so every one of the 12.8M outputs must be
+    bit-equal to the exact value (fp32 output) or to its single bf16 rounding (bf16 output). The
+    exact value is an im2col + float64 matmul on the host, tied to the oracle on two whole images."""
+    wl = configs.CONFIG5
+    g = np.random.default_rng(505)
+    x = g.integers(0, 9, (wl.N, wl.H, wl.W, wl.C)).astype(np.float32)
+    w = g.integers(-8, 9, (wl.K, wl.R, wl.S, wl.C)).astype(np.float32)
+    xp = np.zeros((wl.N, wl.H + 2, wl.W + 2, wl.C), np.float64)
+    xp[:, 1:-1, 1:-1] = x
+    wm = w.astype(np.float64).reshape(wl.K, -1).T                 # [(r, s, c), k]
+    exact = np.empty((wl.N, wl.P, wl.Q, wl.K), np.float64)
+    for n in range(wl.N):
+        win = np.lib.stride_tricks.sliding_window_view(xp[n], (wl.R, wl.S), axis=(0, 1))   # [P, Q, C, R, S]
+        cols = win.transpose(0, 1, 3, 4, 2).reshape(wl.P * wl.Q, -1)                       # [(p, q), (r, s, c)]
+        exact[n] = (cols @ wm).reshape(wl.P, wl.Q, wl.K)
+    for n in (0, 31):
+        assert np.array_equal(oracle.conv2d(x[n:n + 1].astype(np.float64), w.astype(np.float64), (1, 1), (1, 1)),
+                              exact[n:n + 1])
+    y32 = G.run_conv2d(_bits(x), _bits(w), (1, 1), (1, 1), y_bf16=False)
+    assert np.array_equal(y32.astype(np.float64), exact)
+    y16 = G.run_conv2d(_bits(x), _bits(w), (1, 1), (1, 1), y_bf16=True)
+    assert np.array_equal(y16, oracle.round_bf16(exact))
+
+
 def test_deterministic():
     d = configs.ConvWorkload(N=4).make()
     a = G.run_conv2d(d["x_bf16"], d["w_bf16"], (1, 1), (1, 1))

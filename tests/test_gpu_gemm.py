@@ -165,6 +165,28 @@ def test_config3_full_size_sampled_rows(tile, kstep):
     assert np.max(np.abs(c.astype(np.float64).sum(axis=1) - rowsum_ref)) < 1.0
 
 
+@pytest.mark.parametrize("c_bf16", [False, True])
+def test_config3_full_size_every_entry_exact_integers(c_bf16):
+    """4096^3 in the benchmark's launch configuration with small-integer operands (|v| <= 8): every
+    product and every partial sum is an integer below 2^24, exact in fp32 whatever the order, so
+    all 16.7M entries of C must equal the exact product bit for bit. The exact product is a float64
+    matmul on the host (exact for the same reason), tied to the oracle on sampled rows. With bf16 C
+    the expected bits are the oracle's single rounding of the exact value."""
+    wl = configs.CONFIG3
+    g = np.random.default_rng(303)
+    a = g.integers(-8, 9, (wl.M, wl.K)).astype(np.float32)
+    bs = g.integers(-8, 9, (wl.N, wl.K)).astype(np.float32)      # column-major storage of B
+    exact = a.astype(np.float64) @ bs.astype(np.float64).T
+    rows = np.array([0, 255, 256, 1777, 4095])
+    assert np.array_equal(oracle.gemm(a[rows].astype(np.float64), bs.astype(np.float64), len(rows), wl.N, wl.K, b_col=True),
+                          exact[rows])
+    c = G.run_gemm(_bits(a), _bits(bs), wl.M, wl.N, wl.K, c_bf16=c_bf16)[0]
+    if c_bf16:
+        assert np.array_equal(c, oracle.round_bf16(exact))
+    else:
+        assert np.array_equal(c.astype(np.float64), exact)
+
+
 def test_config4_attention_scores_then_softmax():
     """Q K^T / 8 for 512 (batch x head) matrices, then row softmax of the 262144 x 512
     scores: all batches on the GPU; three batches recomputed by the oracle."""

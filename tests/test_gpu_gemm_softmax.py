@@ -1,7 +1,8 @@
 """GPU parity: perf_gemm_softmax (fused kernel and the two-operator path) against the CPU oracle.
-Tolerance: the softmax of scores S has relative error |dS| + O(2^-23), and the fp32-accumulated
-bf16 scores obey |dS| <= K 2^-24 |alpha| sum_k |a||b| whatever the summation order; the gate is
-1e-5 (the bar for fp32 reductions) plus that bound, entries below 1e-30 by absolute error."""
+Gate: the bar for fp32 reductions, max relative error 1e-5 over probabilities >= 1e-30 (absolute
+1e-35 below), bf16 results one bf16 rounding (2^-8) more. The measured worst error of every case
+is printed (run pytest with -s to see it); the accumulation-order bound K 2^-24 |alpha| max sum|a||b|
+on the scores is printed beside it for comparison only, it is not the gate."""
 import numpy as np
 import pytest
 
@@ -19,12 +20,15 @@ def _inputs(M, N, K, batch, seed=0, sigma=1.0):
     return rng.f32_to_bf16_bits(q), rng.f32_to_bf16_bits(k)
 
 
-def _tol(ad, bd, M, N, K, alpha, batch):
+TOL = 1e-5
+
+
+def _score_bound(ad, bd, M, N, K, alpha, batch):
     worst = 0.0
     for i in range(batch):
         s = oracle.gemm_absdot(ad.reshape(batch, -1)[i], bd.reshape(batch, -1)[i], M, N, K, b_col=True)
         worst = max(worst, float(s.max()))
-    return 1e-5 + K * 2.0 ** -24 * abs(alpha) * worst
+    return K * 2.0 ** -24 * abs(alpha) * worst
 
 
 def _check(M, N, K, alpha=0.125, batch=1, p_bf16=False, seed=0, **kw):
@@ -32,12 +36,16 @@ def _check(M, N, K, alpha=0.125, batch=1, p_bf16=False, seed=0, **kw):
     p = G.run_gemm_softmax(a, b, M, N, K, alpha=alpha, batch=batch, p_bf16=p_bf16, **kw)
     ad, bd = oracle.widen(a, True), oracle.widen(b, True)
     ref = oracle.gemm_softmax(ad, bd, M, N, K, alpha=float(np.float32(alpha)), batch=batch)
-    tol = _tol(ad, bd, M, N, K, float(np.float32(alpha)), batch)
     if p_bf16:
         got = P.bf16_to_f64(p)
-        assert np.max(np.abs(got - ref) / np.maximum(ref, 2.0 ** -20)) <= 2.0 ** -8 + tol
+        err = float(np.max(np.abs(got - ref) / np.maximum(ref, 2.0 ** -20)))
+        print(f"gemm_softmax {M}x{N}x{K} batch {batch} alpha {alpha} bf16 P: max rel err {err:.3e}")
+        assert err <= 2.0 ** -8 + TOL
     else:
-        P.assert_softmax_close(p.reshape(-1, N), ref.reshape(-1, N), tol=tol)
+        rel, _ = P.softmax_max_rel_err(p.reshape(-1, N), ref.reshape(-1, N))
+        print(f"gemm_softmax {M}x{N}x{K} batch {batch} alpha {alpha}: max rel err {rel:.3e} "
+              f"(score-order bound {_score_bound(ad, bd, M, N, K, float(np.float32(alpha)), batch):.3e})")
+        P.assert_softmax_close(p.reshape(-1, N), ref.reshape(-1, N), tol=TOL)
         np.testing.assert_allclose(p.astype(np.float64).sum(-1), 1.0, atol=1e-5)
     return p, ref
 
@@ -62,7 +70,7 @@ def test_fused_alpha_signs_batches_bf16_output_and_padded_ld():
     bp = np.zeros((N, 88), np.uint16); bp[:, :K] = b[0]
     p = G.run_gemm_softmax(ap, bp, M, N, K, alpha=0.125, lda=72, ldb=88, ldp=84)
     ref = oracle.gemm_softmax(oracle.widen(a, True), oracle.widen(b, True), M, N, K, alpha=0.125)
-    P.assert_softmax_close(p.reshape(-1, N), ref.reshape(-1, N), tol=2e-5)
+    P.assert_softmax_close(p.reshape(-1, N), ref.reshape(-1, N), tol=TOL)
 
 
 def test_argmax_matches_scores():
@@ -90,7 +98,7 @@ def test_fp32_operands_take_the_two_operator_path():
     b = g.standard_normal((N, K)).astype(np.float32)
     p = G.run_gemm_softmax(a, b, M, N, K, alpha=0.3, ab_bf16=False)[0]
     ref = oracle.gemm_softmax(a.astype(np.float64), b.astype(np.float64), M, N, K, alpha=float(np.float32(0.3)))[0]
-    P.assert_softmax_close(p, ref, tol=2e-5)
+    P.assert_softmax_close(p, ref, tol=TOL)
 
 
 def test_config4_full_size_sampled_batches_and_row_sums():
@@ -110,8 +118,44 @@ def test_config4_full_size_sampled_batches_and_row_sums():
     for bi in (0, 1, 255, 511):
         ad, bd = oracle.widen(d["q_bf16"][bi], True), oracle.widen(d["k_bf16"][bi], True)
         ref = oracle.gemm_softmax(ad, bd, S, S, D, alpha=wl.alpha)[0]
-        tol = _tol(ad, bd, S, S, D, wl.alpha, 1)
-        P.assert_softmax_close(ph[bi].cpu().numpy(), ref, tol=tol)
+        got = ph[bi].cpu().numpy()
+        print(f"config 4 fused, matrix {bi}: max rel err {P.softmax_max_rel_err(got, ref)[0]:.3e}")
+        P.assert_softmax_close(got, ref, tol=TOL)
+
+
+def test_config4_full_size_every_entry_with_exact_scores():
+    """Config 4's launch with small-integer operands (|q|, |k| <= 3): every product and partial sum
+    is an integer below 2^24, so the fp32 scores are exact whatever the summation order, and
+    alpha = 1/8 is a power of two. Every one of the 134M probabilities is then compared, at the
+    1e-5 gate, with a float64 softmax of the exact integer scores computed on the host
+    (numpy matmul), which is itself tied to the oracle on three matrices."""
+    import torch
+    import paper_2511_03586_amd as perf
+    wl = configs.CONFIG4
+    S, D, B = wl.seq, wl.d, wl.batch
+    g = np.random.default_rng(404)
+    qi = g.integers(-3, 4, (B, S, D)).astype(np.float32)
+    ki = g.integers(-3, 4, (B, S, D)).astype(np.float32)
+    q, k = G.dev(rng.f32_to_bf16_bits(qi).ravel()), G.dev(rng.f32_to_bf16_bits(ki).ravel())
+    p = torch.zeros(B * S * S, dtype=torch.float32, device="cuda")
+    perf.perf_gemm_softmax(q.data_ptr(), k.data_ptr(), p.data_ptr(), S, S, D, D, D, S, B, S * D, S * D, S * S,
+                           wl.alpha, perf.PERF_BF16, perf.PERF_F32, G.stream())
+    torch.cuda.synchronize()
+    ph = p.view(B, S, S).cpu().numpy()
+    worst = 0.0
+    for b0 in range(0, B, 32):
+        s = wl.alpha * np.matmul(qi[b0:b0 + 32].astype(np.float64), ki[b0:b0 + 32].astype(np.float64).transpose(0, 2, 1))
+        e = np.exp(s - s.max(axis=-1, keepdims=True))
+        ref = e / e.sum(axis=-1, keepdims=True)
+        if b0 in (0, 256):
+            bi = b0 + 5
+            tie = oracle.gemm_softmax(qi[bi].astype(np.float64), ki[bi].astype(np.float64), S, S, D, alpha=wl.alpha)
+            assert np.max(np.abs(tie.reshape(S, S) - ref[5]) / ref[5]) <= 1e-12
+        rel, small = P.softmax_max_rel_err(ph[b0:b0 + 32].reshape(-1, S), ref.reshape(-1, S))
+        worst = max(worst, rel)
+        assert small <= 1e-35
+    print(f"config 4 fused, exact scores, all {B * S * S} entries: max rel err {worst:.3e}")
+    assert worst <= TOL
 
 
 def test_deterministic():
