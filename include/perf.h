@@ -10,8 +10,9 @@
  *
  * Conventions shared by every entry point
  *  - All data pointers are DEVICE pointers (HBM), owned by the caller.  The library
- *    allocates no device memory and keeps no state between calls (the one operator that
- *    needs scratch memory, perf_batchnorm, takes it from the caller).
+ *    allocates no device memory and keeps no state between calls (the operators that need
+ *    scratch memory, perf_batchnorm and perf_reduce_mean_ws, take it from the caller;
+ *    perf_batchnorm_static uses a fixed device array instead, see there).
  *  - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL = the default
  *    stream) and return without synchronising.  Buffers must stay alive and unmodified
  *    until the stream has run the enqueued kernels.
@@ -157,6 +158,23 @@ perf_status perf_batchnorm(const void *x, const void *gamma, const void *beta, v
                            float *rstd_out, void *workspace, int64_t N, int64_t C, int64_t H, int64_t W,
                            float eps, perf_dtype x_dt, perf_dtype param_dt, perf_dtype y_dt,
                            perf_stream stream);
+
+/* perf_batchnorm for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operator, same
+ * kernels, same results bit for bit; the scratch lives in a file-scope device array of
+ * perf_batchnorm_static_max_bytes() (256 KiB) that every GPU the library runs on holds until the
+ * process ends.  The call allocates nothing and frees nothing.  Problems whose
+ * perf_batchnorm_workspace_bytes exceeds that size return UNSUPPORTED (e.g. 8 x 64 x 300 x 300 needs
+ * 37 KiB, 8 x 3 x 2048 x 2048 72 KiB).  All calls on one GPU share the one array: calls that may run
+ * concurrently on that GPU (different streams, different host threads) race on it; calls on one
+ * stream are safe.  Nothing in the array needs clearing between calls (every word read was
+ * written by the same call).
+ * Errors: as perf_batchnorm without the workspace checks; LAUNCH also if the array's device
+ * address cannot be resolved. */
+int64_t perf_batchnorm_static_max_bytes(void);
+perf_status perf_batchnorm_static(const void *x, const void *gamma, const void *beta, void *y, float *mean_out,
+                                  float *rstd_out, int64_t N, int64_t C, int64_t H, int64_t W, float eps,
+                                  perf_dtype x_dt, perf_dtype param_dt, perf_dtype y_dt, perf_stream stream);
 
 /* Mean along one axis of a rows x cols matrix ("reducemean" row of the operator table; the
  * table does not say which axis, both are provided): axis 1: y[i] = mean_j x[i][j] (rows

@@ -42,6 +42,9 @@ SIGNATURES = {
     "perf_batchnorm_workspace_bytes": (_i64, [_i64, _i64, _i64, _i64]),
     "perf_batchnorm": (_int, [_ptr, _ptr, _ptr, _ptr, _ptr, _ptr, _ptr, _i64, _i64, _i64, _i64, _f32, _int, _int, _int,
                               _ptr]),
+    "perf_batchnorm_static_max_bytes": (_i64, []),
+    "perf_batchnorm_static": (_int, [_ptr, _ptr, _ptr, _ptr, _ptr, _ptr, _i64, _i64, _i64, _i64, _f32, _int, _int, _int,
+                                     _ptr]),
     "perf_copy": (_int, [_ptr, _ptr, _i64, _ptr]),
     "perf_mfma_probe": (_int, [_ptr, _i64, _ptr]),
     "perf_mfma_probe_random": (_int, [_ptr, _i64, _ptr]),
@@ -173,6 +176,17 @@ def perf_batchnorm(x, gamma, beta, y, mean_out, rstd_out, workspace, N, C, H, W,
     return _check("perf_batchnorm",
                   lib().perf_batchnorm(x, gamma, beta, y, mean_out, rstd_out, workspace, N, C, H, W, eps, x_dt,
                                        param_dt, y_dt, stream), check)
+
+
+def perf_batchnorm_static_max_bytes() -> int:
+    return int(lib().perf_batchnorm_static_max_bytes())
+
+
+def perf_batchnorm_static(x, gamma, beta, y, mean_out, rstd_out, N, C, H, W, eps, x_dt=PERF_F32,
+                          param_dt=PERF_F32, y_dt=PERF_F32, stream=None, check=True) -> int:
+    return _check("perf_batchnorm_static",
+                  lib().perf_batchnorm_static(x, gamma, beta, y, mean_out, rstd_out, N, C, H, W, eps, x_dt,
+                                              param_dt, y_dt, stream), check)
 
 
 def perf_copy(src, dst, nbytes, stream=None, check=True) -> int:

@@ -12,6 +12,7 @@
 //  * bn_apply_kernel: streaming y = (x - mean) * scale + beta, 16-byte accesses.
 // The partials live in a caller-supplied workspace (perf_batchnorm_workspace_bytes): no
 // atomics, results bit-identical from run to run.
+#include <atomic>
 #include "row_io.h"
 #include "host_utils.h"
 
@@ -258,23 +259,58 @@ extern "C" int64_t perf_batchnorm_workspace_bytes(int64_t N, int64_t C, int64_t 
     return 4 * (3 * C * N * segs + 2 * C);
 }
 
-extern "C" perf_status perf_batchnorm(const void *x, const void *gamma, const void *beta, void *y, float *mean_out,
-                                      float *rstd_out, void *workspace, int64_t N, int64_t C, int64_t H, int64_t W,
-                                      float eps, perf_dtype x_dt, perf_dtype param_dt, perf_dtype y_dt, perf_stream stream)
+namespace perf {
+
+// Scratch of perf_batchnorm_static: the segment partials and the per-channel coefficients that
+// perf_batchnorm keeps in the caller's workspace.  One copy per GPU, held until the process ends.
+constexpr int64_t kBnStaticFloats = 65536;  // 256 KiB
+static __device__ __align__(256) float bn_static_scratch[kBnStaticFloats];
+
+constexpr int kBnMaxDevices = 64;
+static std::atomic<float *> bn_static_ptr[kBnMaxDevices];
+
+// Device address of this GPU's copy of the array (the array's name is only a host-side handle).
+// Looked up once per device, with that device current; no allocation is involved.
+static float *bn_static_address()
 {
-    using namespace perf;
-    if (!x || !gamma || !beta || !y || !workspace) return PERF_ERR_NULL;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kBnMaxDevices) return nullptr;
+    float *p = bn_static_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void *sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(bn_static_scratch)) != hipSuccess || !sym) return nullptr;
+        p = static_cast<float *>(sym);
+        bn_static_ptr[dev].store(p, std::memory_order_release);  // every thread computes the same value
+    }
+    return p;
+}
+
+}  // namespace perf
+
+namespace perf {
+
+// Host-side argument checks shared by both entry points (no HIP call).
+static perf_status bn_check(const void *x, const void *gamma, const void *beta, const void *y, const float *mean_out,
+                            const float *rstd_out, int64_t N, int64_t C, int64_t H, int64_t W, float eps, int x_dt,
+                            int param_dt, int y_dt)
+{
+    if (!x || !gamma || !beta || !y) return PERF_ERR_NULL;
     if (!dtype_ok(x_dt) || !dtype_ok(param_dt) || !dtype_ok(y_dt)) return PERF_ERR_DTYPE;
     if (!bn_shape_ok(N, C, H, W) || !(eps >= 0.f) || !std::isfinite(eps)) return PERF_ERR_SHAPE;
     if (!aligned(x, dtype_size(x_dt)) || !aligned(y, dtype_size(y_dt)) || !aligned(gamma, dtype_size(param_dt)) ||
-        !aligned(beta, dtype_size(param_dt)) || !aligned(workspace, 4) || (mean_out && !aligned(mean_out, 4)) ||
-        (rstd_out && !aligned(rstd_out, 4)))
+        !aligned(beta, dtype_size(param_dt)) || (mean_out && !aligned(mean_out, 4)) || (rstd_out && !aligned(rstd_out, 4)))
         return PERF_ERR_ALIGN;
+    return PERF_OK;
+}
+
+static perf_status bn_run(const void *x, const void *gamma, const void *beta, void *y, float *mean_out, float *rstd_out,
+                          float *workspace, int64_t N, int64_t C, int64_t H, int64_t W, float eps, int x_dt, int param_dt,
+                          int y_dt, perf_stream stream)
+{
     const int64_t HW = H * W, ex = 16 / dtype_size(x_dt);
     // 16-byte path: every plane starts 16-byte aligned in x and y, and holds whole chunks
     const bool vec = HW % ex == 0 && aligned(x, 16) && aligned(y, 16) && (HW * dtype_size(y_dt)) % 16 == 0;
-    BnArgs a{x, gamma, beta, y, mean_out, rstd_out, static_cast<float *>(workspace), N, C, HW, eps,
-             static_cast<hipStream_t>(stream)};
+    BnArgs a{x, gamma, beta, y, mean_out, rstd_out, workspace, N, C, HW, eps, static_cast<hipStream_t>(stream)};
     if (x_dt == PERF_F32) {
         if (param_dt == PERF_F32) launch_bn_y<float, float>(a, vec, y_dt);
         else launch_bn_y<float, uint16_t>(a, vec, y_dt);
@@ -283,4 +319,36 @@ extern "C" perf_status perf_batchnorm(const void *x, const void *gamma, const vo
         else launch_bn_y<uint16_t, uint16_t>(a, vec, y_dt);
     }
     return launch_status();
+}
+
+}  // namespace perf
+
+extern "C" perf_status perf_batchnorm(const void *x, const void *gamma, const void *beta, void *y, float *mean_out,
+                                      float *rstd_out, void *workspace, int64_t N, int64_t C, int64_t H, int64_t W,
+                                      float eps, perf_dtype x_dt, perf_dtype param_dt, perf_dtype y_dt, perf_stream stream)
+{
+    using namespace perf;
+    if (!workspace) return PERF_ERR_NULL;
+    const perf_status s = bn_check(x, gamma, beta, y, mean_out, rstd_out, N, C, H, W, eps, x_dt, param_dt, y_dt);
+    if (s != PERF_OK) return s;
+    if (!aligned(workspace, 4)) return PERF_ERR_ALIGN;
+    return bn_run(x, gamma, beta, y, mean_out, rstd_out, static_cast<float *>(workspace), N, C, H, W, eps, x_dt, param_dt,
+                  y_dt, stream);
+}
+
+extern "C" int64_t perf_batchnorm_static_max_bytes(void) { return 4 * perf::kBnStaticFloats; }
+
+extern "C" perf_status perf_batchnorm_static(const void *x, const void *gamma, const void *beta, void *y,
+                                             float *mean_out, float *rstd_out, int64_t N, int64_t C, int64_t H,
+                                             int64_t W, float eps, perf_dtype x_dt, perf_dtype param_dt,
+                                             perf_dtype y_dt, perf_stream stream)
+{
+    using namespace perf;
+    const perf_status s = bn_check(x, gamma, beta, y, mean_out, rstd_out, N, C, H, W, eps, x_dt, param_dt, y_dt);
+    if (s != PERF_OK) return s;
+    if (perf_batchnorm_workspace_bytes(N, C, H, W) > perf_batchnorm_static_max_bytes())
+        return PERF_ERR_UNSUPPORTED;  // the problem needs more scratch than the built-in array holds
+    float *scratch = bn_static_address();  // first HIP call: every check above ran without one
+    if (!scratch) return PERF_ERR_LAUNCH;
+    return bn_run(x, gamma, beta, y, mean_out, rstd_out, scratch, N, C, H, W, eps, x_dt, param_dt, y_dt, stream);
 }

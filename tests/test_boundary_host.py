@@ -227,3 +227,20 @@ def test_batchnorm_argument_errors_and_workspace_size():
     assert perf.perf_batchnorm_workspace_bytes(8, 64, 300, 300) == 4 * (3 * 64 * 8 * 6 + 2 * 64)
     assert perf.perf_batchnorm_workspace_bytes(1, 1, 1, 1) == 4 * (3 + 2)
     assert perf.perf_batchnorm_workspace_bytes(0, 1, 1, 1) == -1
+
+
+def test_batchnorm_static_argument_errors_and_size_limit():
+    f = lambda **k: perf.perf_batchnorm_static(**{**dict(x=FAKE, gamma=FAKE + 4096, beta=FAKE + 8192, y=FAKE + 12288,
+                                                         mean_out=None, rstd_out=None, N=2, C=3, H=4, W=5, eps=1e-5,
+                                                         check=False), **k})
+    for k in ("x", "gamma", "beta", "y"):
+        assert f(**{k: None}) == perf.PERF_ERR_NULL
+    assert f(N=0) == perf.PERF_ERR_SHAPE and f(eps=-1.0) == perf.PERF_ERR_SHAPE
+    assert f(x_dt=9) == perf.PERF_ERR_DTYPE
+    assert f(y=FAKE + 2) == perf.PERF_ERR_ALIGN
+    # 64 x 64 planes of 2048 x 2048 need 12 MiB of partials: beyond the 256 KiB built-in array,
+    # refused before any device call
+    assert perf.perf_batchnorm_static_max_bytes() == 256 * 1024
+    assert perf.perf_batchnorm_workspace_bytes(64, 64, 2048, 2048) > perf.perf_batchnorm_static_max_bytes()
+    assert f(N=64, C=64, H=2048, W=2048) == perf.PERF_ERR_UNSUPPORTED
+    assert perf.perf_batchnorm_workspace_bytes(8, 3, 2048, 2048) <= perf.perf_batchnorm_static_max_bytes()
