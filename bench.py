@@ -52,6 +52,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--only", default="", help="comma-separated workload names (profiling aid)")
     ap.add_argument("--no-paper-shapes", action="store_true", help="skip the second workload (the paper's table shapes)")
+    ap.add_argument("--copy-study", action="store_true",
+                    help="instead of the benchmark: sweep the streaming probe (copy / read / write, vectors per thread, "
+                         "workgroup size, grid, cache policy) and print one JSON line with every point")
     return ap.parse_args()
 
 
@@ -304,6 +307,26 @@ def build_paper_workloads(torch, perf):
                                 xb[i % 2].data_ptr(), gb.data_ptr(), bb2.data_ptr(), yb[i % 2].data_ptr(), None, None,
                                 wsb.data_ptr(), d[0], d[1], d[2], d[3], 1e-5, F32, F32, F32, st()), 2,
                             "three launches; priced at two reads + one write of the tensor"))
+    # rows beyond a wavefront's registers (not in the paper's table): one workgroup per row, the row parked in LDS
+    xw = G.dev(configs.SoftmaxWorkload(rows=512, cols=16384, config=23).make()["x"]).repeat(16, 1); keep.append(xw)
+    yw = torch.empty_like(xw); keep.append(yw)
+    wls.append(Workload("long_softmax_8192x16384_f32", "softmax_wide_kernel<1024,vec>", "hbm", 8 * 8192 * 16384,
+                        lambda i: perf.perf_softmax(xw.data_ptr(), yw.data_ptr(), 8192, 16384, 16384, 16384, F32, F32, 1.0,
+                                                    st()), 1, "64 KiB rows: 16 waves per row, row held in LDS, one read of HBM"))
+    dl = configs.LayerNormWorkload(rows=512, cols=16384, config=24).make()
+    xl2 = sets(G.dev(dl["x_bf16"]).repeat(8, 1), 2)
+    yl2 = torch.empty_like(xl2); keep.append(yl2)
+    gl2, bl2 = G.dev(dl["gamma"]), G.dev(dl["beta"]); keep.extend([gl2, bl2])
+    wls.append(Workload("long_layernorm_4096x16384_bf16", "norm_wide_kernel<bf16,f32,bf16,256,layernorm>", "hbm",
+                        4 * 4096 * 16384,
+                        lambda i: perf.perf_layernorm(xl2[i % 2].data_ptr(), gl2.data_ptr(), bl2.data_ptr(),
+                                                      yl2[i % 2].data_ptr(), None, None, 4096, 16384, 16384, 16384, 1e-5,
+                                                      BF16, F32, BF16, st()), 2,
+                        "32 KiB rows: 4 waves per row, row held in LDS, one read of HBM"))
+    wls.append(Workload("long_rmsnorm_4096x16384_bf16", "norm_wide_kernel<bf16,f32,bf16,256,rmsnorm>", "hbm",
+                        4 * 4096 * 16384,
+                        lambda i: perf.perf_rmsnorm(xl2[i % 2].data_ptr(), gl2.data_ptr(), yl2[i % 2].data_ptr(), None, 4096,
+                                                    16384, 16384, 16384, 1e-5, BF16, F32, BF16, st()), 2))
     yl = torch.empty_like(xm); keep.append(yl)
     wls.append(Workload("paper_relu_4096x4096_f32", "eltwise_kernel<relu,f32>", "hbm", 8 * 4096 * 4096,
                         lambda i: perf.perf_eltwise(perf.PERF_RELU, xm[i % 8].data_ptr(), None, yl[i % 8].data_ptr(),
@@ -328,6 +351,41 @@ def measure_copy_ceiling(torch, perf, moved_bytes=2 << 30, iters=20):
     e1.record()
     torch.cuda.synchronize()
     return 2.0 * n * iters / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
+def copy_study(torch, perf, nbytes=1 << 30, iters=10):
+    """Sweep of the streaming probe (copy, read-only, write-only; vectors per thread, workgroup size,
+    one pass per workgroup or a persistent grid, non-temporal or plain accesses) over 1 GiB buffers,
+    rotated so that 2 GiB are touched between reuses.  Returns rows of (mode, unroll, threads, grid,
+    policy, GB/s) sorted by rate; GB/s counts bytes read plus bytes written."""
+    st = torch.cuda.current_stream().cuda_stream
+    nsets = 2
+    src = torch.empty((nsets, nbytes), dtype=torch.uint8, device="cuda").fill_(5)
+    dst = torch.empty_like(src)
+    rows = []
+    for mode, name in ((0, "copy"), (1, "read"), (2, "write")):
+        policies = (0, 1, 2, 3) if mode == 0 else (0, 1) if mode == 1 else (0, 2)
+        for policy in policies:
+            for unroll in (1, 2, 4, 8, 16):
+                for threads in (256, 512, 1024):
+                    for grid in (0, 256 * 2048 // threads, 4 * 256 * 2048 // threads):
+                        def go(i):
+                            perf.perf_stream_probe(src[i % nsets].data_ptr(), dst[i % nsets].data_ptr(), nbytes, mode,
+                                                   unroll, threads, grid, policy, st)
+                        for i in range(2):
+                            go(i)
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        for i in range(iters):
+                            go(i)
+                        e1.record()
+                        torch.cuda.synchronize()
+                        moved = nbytes * (2 if mode == 0 else 1)
+                        rows.append({"mode": name, "unroll": unroll, "threads": threads, "grid": grid,
+                                     "nt_loads": bool(policy & 1), "nt_stores": bool(policy & 2),
+                                     "gbs": round(moved * iters / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)})
+    rows.sort(key=lambda r: (r["mode"], -r["gbs"]))
+    return rows
 
 
 def measure_mfma_ceiling(torch, perf, iters=2000, reps=5, random_operands=False):
@@ -432,6 +490,9 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     perf.lib()  # fail loudly if the HIP library is missing
+    if args.copy_study:
+        print(json.dumps({"copy_study": copy_study(torch, perf)}))
+        return
 
     wls, keep = build_workloads(torch, perf)
     if args.only:

@@ -241,6 +241,19 @@ perf_status perf_conv2d_variant(const void *x, const void *w, void *y, int64_t N
  * of the paper's operators.  Errors: NULL, SHAPE (bytes < 0), LAUNCH. */
 perf_status perf_copy(const void *src, void *dst, int64_t bytes, perf_stream stream);
 
+/* Streaming probe behind the benchmark's copy-ceiling study (not one of the paper's operators):
+ * the copy kernel's access pattern with its knobs exposed, and its read and write halves alone.
+ *   mode     0 = copy src -> dst, 1 = read src only (dst receives at most 16 bytes), 2 = write dst only
+ *   bytes    a multiple of 16, >= 16; src and dst device, 16-byte aligned, at least `bytes` long
+ *   unroll   16-byte vectors per thread and iteration: 1, 2, 4, 8 or 16
+ *   threads  workgroup size: 64, 128, 256, 512 or 1024
+ *   grid     0 = one pass per workgroup; otherwise that many workgroups, which loop over the data
+ *   policy   bit 0 = non-temporal loads, bit 1 = non-temporal stores
+ * Errors: NULL, SHAPE (bytes, mode, threads, grid or policy out of range), ALIGN, UNSUPPORTED
+ * (unroll), LAUNCH. */
+perf_status perf_stream_probe(const void *src, void *dst, int64_t bytes, int mode, int unroll, int threads,
+                              int64_t grid, int policy, perf_stream stream);
+
 /* Register-only bf16 MFMA loop, the measured matrix-core ceiling printed beside the GEMM and
  * convolution figures (not one of the paper's operators): 4096 wavefronts (1024 workgroups
  * of 256 threads) each issue iters * 32 v_mfma_f32_32x32x16_bf16 on 16 independent

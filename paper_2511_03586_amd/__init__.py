@@ -46,6 +46,7 @@ SIGNATURES = {
     "perf_batchnorm_static": (_int, [_ptr, _ptr, _ptr, _ptr, _ptr, _ptr, _i64, _i64, _i64, _i64, _f32, _int, _int, _int,
                                      _ptr]),
     "perf_copy": (_int, [_ptr, _ptr, _i64, _ptr]),
+    "perf_stream_probe": (_int, [_ptr, _ptr, _i64, _int, _int, _int, _i64, _int, _ptr]),
     "perf_mfma_probe": (_int, [_ptr, _i64, _ptr]),
     "perf_mfma_probe_random": (_int, [_ptr, _i64, _ptr]),
     "perf_status_string": (ctypes.c_char_p, [_int]),
@@ -191,6 +192,11 @@ def perf_batchnorm_static(x, gamma, beta, y, mean_out, rstd_out, N, C, H, W, eps
 
 def perf_copy(src, dst, nbytes, stream=None, check=True) -> int:
     return _check("perf_copy", lib().perf_copy(src, dst, nbytes, stream), check)
+
+
+def perf_stream_probe(src, dst, nbytes, mode, unroll, threads, grid, policy, stream=None, check=True) -> int:
+    return _check("perf_stream_probe",
+                  lib().perf_stream_probe(src, dst, nbytes, mode, unroll, threads, grid, policy, stream), check)
 
 
 MFMA_PROBE_SINK_FLOATS = 4096

@@ -11,9 +11,12 @@
 //    Welford/Chan merge of per-lane (mean, M2) was measured less accurate: it rounds
 //    per-lane means to fp32, which costs |mean|/sigma * 2^-24 per merge.  gamma and beta
 //    are staged once per workgroup in LDS as fp32 and re-used for every row.
+//  * norm_wide_kernel (wide_rows.h): rows beyond a wavefront's registers, one workgroup per
+//    row, the row parked in LDS: still one read of HBM.
 //  * layernorm_block_kernel: general fallback (any length, any alignment), one workgroup
 //    per row, three passes over global memory with the same arithmetic.
 #include "row_io.h"
+#include "wide_rows.h"
 #include "host_utils.h"
 
 namespace perf {
@@ -186,6 +189,8 @@ struct LnArgs {
     int64_t rows, cols, ldx, ldy;
     float eps;
     hipStream_t st;
+    bool params_vec;  // gamma and beta are 16-byte aligned
+    bool failed;
 };
 
 template <typename XT, typename PT, typename YT, int NC>
@@ -203,7 +208,7 @@ static void launch_rows_nc(const LnArgs &a)
 }
 
 template <typename XT, typename PT, typename YT>
-static void launch_typed(const LnArgs &a, bool vec_ok)
+static void launch_typed(LnArgs &a, bool vec_ok)
 {
     constexpr int E = Elem<XT>::kPerChunk;
     const int64_t chunks = (a.cols + 64 * E - 1) / (64 * E);  // chunks per lane
@@ -213,6 +218,10 @@ static void launch_typed(const LnArgs &a, bool vec_ok)
         else if (chunks <= 4) launch_rows_nc<XT, PT, YT, 4>(a);
         else if (chunks <= 8) launch_rows_nc<XT, PT, YT, 8>(a);
         else launch_rows_nc<XT, PT, YT, 16>(a);
+    } else if (vec_ok && a.params_vec) {
+        // longer rows: a workgroup per row, the row parked in LDS (one read of HBM)
+        a.failed = !launch_norm_wide<XT, PT, YT, false>(a.x, a.gamma, a.beta, a.y, a.mean_out, a.rstd_out, a.rows, a.cols,
+                                                        a.ldx, a.ldy, a.eps, a.st);
     } else {
         int64_t blocks = a.rows < 65536 ? a.rows : 65536;
         hipLaunchKernelGGL((layernorm_block_kernel<XT, PT, YT>), dim3((unsigned)blocks), dim3(256), 0, a.st,
@@ -222,14 +231,14 @@ static void launch_typed(const LnArgs &a, bool vec_ok)
 }
 
 template <typename XT, typename PT>
-static void launch_y(const LnArgs &a, bool vec_ok, int y_dt)
+static void launch_y(LnArgs &a, bool vec_ok, int y_dt)
 {
     if (y_dt == PERF_F32) launch_typed<XT, PT, float>(a, vec_ok);
     else launch_typed<XT, PT, uint16_t>(a, vec_ok);
 }
 
 template <typename XT>
-static void launch_p(const LnArgs &a, bool vec_ok, int p_dt, int y_dt)
+static void launch_p(LnArgs &a, bool vec_ok, int p_dt, int y_dt)
 {
     if (p_dt == PERF_F32) launch_y<XT, float>(a, vec_ok, y_dt);
     else launch_y<XT, uint16_t>(a, vec_ok, y_dt);
@@ -255,8 +264,9 @@ extern "C" perf_status perf_layernorm(const void *x, const void *gamma, const vo
     // the register path needs whole 16-byte chunks of x and 16-byte aligned groups of y
     const bool vec_ok = cols % ex == 0 && ldx % ex == 0 && aligned(x, 16) && aligned(y, 16) &&
                         (ldy * dtype_size(y_dt)) % 16 == 0;
-    LnArgs a{x, gamma, beta, y, mean_out, rstd_out, rows, cols, ldx, ldy, eps, static_cast<hipStream_t>(stream)};
+    LnArgs a{x, gamma, beta, y, mean_out, rstd_out, rows, cols, ldx, ldy, eps, static_cast<hipStream_t>(stream),
+             aligned(gamma, 16) && aligned(beta, 16), false};
     if (x_dt == PERF_F32) launch_p<float>(a, vec_ok, param_dt, y_dt);
     else launch_p<uint16_t>(a, vec_ok, param_dt, y_dt);
-    return launch_status();
+    return a.failed ? PERF_ERR_LAUNCH : launch_status();
 }

@@ -30,6 +30,77 @@ __global__ __launch_bounds__(64) void copy_tail_kernel(const unsigned char *__re
     for (int64_t i = threadIdx.x; i < n; i += 64) dst[i] = src[i];
 }
 
+// Streaming probe: the copy kernel's access pattern with its knobs exposed, and its two
+// halves on their own.  MODE 0 copy, 1 read only (a per-thread xor keeps the loads alive; one
+// dword per workgroup is written to dst), 2 write only.  U = 16-byte vectors per thread and
+// iteration (all loads of an iteration are issued before its first store); NTL / NTS =
+// non-temporal loads / stores.  The block size is the launch's; with fewer workgroups than
+// passes the workgroups loop (persistent grid).
+template <int MODE, int U, bool NTL, bool NTS>
+__global__ void stream_probe_kernel(const uint4_t *__restrict__ src, uint4_t *__restrict__ dst, int64_t nvec)
+{
+    const int64_t T = blockDim.x;
+    const int64_t stride = (int64_t)gridDim.x * T * U;
+    uint4_t keep = {0u, 0u, 0u, 0u};
+    for (int64_t base = (int64_t)blockIdx.x * T * U + threadIdx.x; base < nvec; base += stride) {
+        uint4_t v[U];
+        if constexpr (MODE != 2) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (base + u * T < nvec) v[u] = NTL ? __builtin_nontemporal_load(src + base + u * T) : src[base + u * T];
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = uint4_t{(uint32_t)base, 1u, 2u, (uint32_t)u};
+        }
+        if constexpr (MODE != 1) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (base + u * T < nvec) {
+                    if (NTS) __builtin_nontemporal_store(v[u], dst + base + u * T);
+                    else dst[base + u * T] = v[u];
+                }
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (base + u * T < nvec) keep ^= v[u];
+        }
+    }
+    if constexpr (MODE == 1) {
+        // practically never true for real data, but the compiler cannot know: the loads stay
+        if ((keep[0] ^ keep[1] ^ keep[2] ^ keep[3]) == 0x9E3779B9u && threadIdx.x == 0)
+            reinterpret_cast<uint32_t *>(dst)[blockIdx.x % 4] = keep[0];
+    }
+}
+
+template <int MODE, int U>
+static void launch_stream_probe(const void *src, void *dst, int64_t nvec, int threads, int64_t grid, int policy,
+                                hipStream_t st)
+{
+    const dim3 g((unsigned)grid), b((unsigned)threads);
+    const uint4_t *s = (const uint4_t *)src;
+    uint4_t *d = (uint4_t *)dst;
+    switch (policy & 3) {
+    case 0: hipLaunchKernelGGL((stream_probe_kernel<MODE, U, false, false>), g, b, 0, st, s, d, nvec); break;
+    case 1: hipLaunchKernelGGL((stream_probe_kernel<MODE, U, true, false>), g, b, 0, st, s, d, nvec); break;
+    case 2: hipLaunchKernelGGL((stream_probe_kernel<MODE, U, false, true>), g, b, 0, st, s, d, nvec); break;
+    default: hipLaunchKernelGGL((stream_probe_kernel<MODE, U, true, true>), g, b, 0, st, s, d, nvec); break;
+    }
+}
+
+template <int MODE>
+static bool dispatch_stream_probe(const void *src, void *dst, int64_t nvec, int unroll, int threads, int64_t grid,
+                                  int policy, hipStream_t st)
+{
+    switch (unroll) {
+    case 1: launch_stream_probe<MODE, 1>(src, dst, nvec, threads, grid, policy, st); return true;
+    case 2: launch_stream_probe<MODE, 2>(src, dst, nvec, threads, grid, policy, st); return true;
+    case 4: launch_stream_probe<MODE, 4>(src, dst, nvec, threads, grid, policy, st); return true;
+    case 8: launch_stream_probe<MODE, 8>(src, dst, nvec, threads, grid, policy, st); return true;
+    case 16: launch_stream_probe<MODE, 16>(src, dst, nvec, threads, grid, policy, st); return true;
+    }
+    return false;
+}
+
 // Register-only bf16 MFMA loop: 16 independent 32x32 accumulators per wave (the GEMM's
 // 4x4 wave tile), two MFMAs per accumulator and iteration issued back to back as in the
 // GEMM main loop, operands constant.  No memory traffic inside the loop, so its rate is
@@ -125,6 +196,27 @@ extern "C" perf_status perf_copy(const void *src, void *dst, int64_t bytes, perf
     if (done < bytes)
         hipLaunchKernelGGL(copy_tail_kernel, dim3(1), dim3(64), 0, st, (const unsigned char *)src + done,
                            (unsigned char *)dst + done, bytes - done);
+    return launch_status();
+}
+
+extern "C" perf_status perf_stream_probe(const void *src, void *dst, int64_t bytes, int mode, int unroll, int threads,
+                                         int64_t grid, int policy, perf_stream stream)
+{
+    using namespace perf;
+    if (!src || !dst) return PERF_ERR_NULL;
+    if (bytes < 16 || bytes % 16 != 0 || mode < 0 || mode > 2 || policy < 0 || policy > 3 || grid < 0 ||
+        grid > kMaxGridX || (threads != 64 && threads != 128 && threads != 256 && threads != 512 && threads != 1024))
+        return PERF_ERR_SHAPE;
+    if (!aligned(src, 16) || !aligned(dst, 16)) return PERF_ERR_ALIGN;
+    if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8 && unroll != 16) return PERF_ERR_UNSUPPORTED;
+    const int64_t nvec = bytes / 16;
+    int64_t passes = (nvec + (int64_t)threads * unroll - 1) / ((int64_t)threads * unroll);
+    if (passes > kMaxGridX) return PERF_ERR_SHAPE;
+    if (grid == 0 || grid > passes) grid = passes;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (mode == 0) dispatch_stream_probe<0>(src, dst, nvec, unroll, threads, grid, policy, st);
+    else if (mode == 1) dispatch_stream_probe<1>(src, dst, nvec, unroll, threads, grid, policy, st);
+    else dispatch_stream_probe<2>(src, dst, nvec, unroll, threads, grid, policy, st);
     return launch_status();
 }
 

@@ -8,9 +8,12 @@
 //
 //  * softmax_rows_kernel: one wavefront owns RPW whole rows at a time (cols <= 2048,
 //    16-byte aligned).  Reductions are DPP / permlane butterflies, no LDS, no barrier.
-//  * softmax_block_kernel: general fallback, one 256-thread workgroup per row, any
-//    length or alignment; a streaming (max, sum) pair per thread is merged through LDS,
-//    and the row is kept in LDS when it fits so HBM is still read once.
+//  * softmax_wgrow_kernel: rows of 8 .. 128 KiB, one workgroup (4 or 16 waves) per row, the
+//    row in the workgroup's registers, the next row's loads in flight meanwhile.
+//  * softmax_wide_kernel: still longer or unaligned rows, one workgroup per row:
+//    the row goes to LDS (up to 144 KiB, 16-byte accesses when aligned) and is read from HBM
+//    once; what a longer row has beyond that is read twice.
+#include <atomic>
 #include "softmax_math.h"
 #include "host_utils.h"
 
@@ -75,50 +78,203 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(const float *__restri
     }
 }
 
-// General fallback: one workgroup per row, scalar accesses.
-constexpr int kBlockCache = 12288;  // floats of a row kept in LDS (48 KiB)
-
-__global__ __launch_bounds__(256) void softmax_block_kernel(const float *__restrict__ x, float *__restrict__ y,
-                                                            int64_t rows, int64_t cols, int64_t ldx, int64_t ldy,
-                                                            ExpConst k)
+// Rows that do not fit a wavefront's registers: one workgroup of THREADS per row.  The row
+// is read from HBM once into LDS (its first `cap` floats; 16-byte accesses when VEC), the
+// exponentials replace it there, and the normalised row is written from there.  What lies
+// beyond `cap` (rows longer than the LDS) is read a second time instead.  Any length, any
+// alignment (VEC = false: element accesses).
+template <int THREADS>
+__device__ __forceinline__ float block_reduce_max(float v, float *red)
 {
-    __shared__ float cache[kBlockCache];
-    __shared__ float red_m[4], red_z[4];
-    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    v = wave_allreduce(v, OpMax{});
+    __syncthreads();  // red may still be read from its previous use
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = red[0];
+#pragma unroll
+    for (int w = 1; w < THREADS / 64; ++w) r = __builtin_fmaxf(r, red[w]);
+    return r;
+}
+template <int THREADS>
+__device__ __forceinline__ float block_reduce_sum(float v, float *red)
+{
+    v = wave_allreduce(v, OpSum{});
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = 0.f;
+#pragma unroll
+    for (int w = 0; w < THREADS / 64; ++w) r += red[w];  // fixed order: bit-identical reruns
+    return r;
+}
+
+// Rows of 8 KiB .. 128 KiB: one workgroup of THREADS per row, the row in the workgroup's
+// registers (NV 16-byte vectors per thread), LDS only for the two cross-wave reductions.  The
+// next row's loads are issued before this row's arithmetic, so a workgroup always has a row in
+// flight and reads, exponentials and writes of different rows overlap.
+template <int THREADS, int NV>
+__global__ __launch_bounds__(THREADS) void softmax_wgrow_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                                int64_t rows, int cols, int64_t ldx, int64_t ldy,
+                                                                ExpConst k)
+{
+    __shared__ float red[THREADS / 64];
+    const int tid = threadIdx.x, n4 = cols / 4;
+    float4_t cur[NV], nxt[NV];
+    auto load_row = [&](float4_t (&v)[NV], int64_t r) {
+        const float4_t *xr = reinterpret_cast<const float4_t *>(x + r * ldx);
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int c = j * THREADS + tid;
+            if (c < n4) v[j] = __builtin_nontemporal_load(xr + c);
+            else v[j] = float4_t{-FLT_MAX, -FLT_MAX, -FLT_MAX, -FLT_MAX} * k.sign;
+        }
+    };
+    int64_t r = blockIdx.x;
+    if (r < rows) load_row(cur, r);
+    for (; r < rows; r += gridDim.x) {
+        if (r + gridDim.x < rows) load_row(nxt, r + gridDim.x);
+        float m = -FLT_MAX;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            cur[j] *= k.sign;  // exact; turns the scale < 0 case into a max problem
+            m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fmaxf(cur[j][0], cur[j][1]), __builtin_fmaxf(cur[j][2], cur[j][3])));
+        }
+        m = block_reduce_max<THREADS>(m, red);
+        float z = 0.f;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const bool valid = j * THREADS + tid < n4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float t = exp_scaled(cur[j][e] - m, k.c_hi, k.c_lo);
+                cur[j][e] = valid ? t : 0.f;
+                z += cur[j][e];
+            }
+        }
+        const float inv = 1.0f / block_reduce_sum<THREADS>(z, red);
+        float4_t *yr = reinterpret_cast<float4_t *>(y + r * ldy);
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int c = j * THREADS + tid;
+            if (c < n4) __builtin_nontemporal_store(cur[j] * inv, yr + c);
+        }
+#pragma unroll
+        for (int j = 0; j < NV; ++j) cur[j] = nxt[j];
+    }
+}
+
+template <int THREADS, int NV>
+static perf_status launch_wgrow(const float *x, float *y, int64_t rows, int cols, int64_t ldx, int64_t ldy, ExpConst k,
+                                hipStream_t st)
+{
+    const int64_t per_cu = 2048 / THREADS;  // all wave slots of a CU
+    const int64_t blocks = rows < 256 * per_cu ? rows : 256 * per_cu;
+    hipLaunchKernelGGL((softmax_wgrow_kernel<THREADS, NV>), dim3((unsigned)blocks), dim3(THREADS), 0, st, x, y, rows, cols,
+                       ldx, ldy, k);
+    return launch_status();
+}
+
+template <int THREADS, bool VEC>
+__global__ __launch_bounds__(THREADS) void softmax_wide_kernel(const float *__restrict__ x, float *__restrict__ y,
+                                                               int64_t rows, int64_t cols, int64_t ldx, int64_t ldy,
+                                                               ExpConst k, int64_t cap)
+{
+    extern __shared__ float4_t cache4[];  // cap floats (cap is a multiple of 4)
+    float *const cache = reinterpret_cast<float *>(cache4);
+    __shared__ float red[THREADS / 64];
+    const int tid = threadIdx.x;
+    constexpr int kU = 4;  // independent loads in flight per thread
 
     for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
         const float *xr = x + r * ldx;
         float *yr = y + r * ldy;
-        // streaming (max, sum): s always holds sum exp(c*(x - m)) for the current m
-        float m = -FLT_MAX, s = 0.f;
-        for (int64_t c = tid; c < cols; c += 256) {
-            float v = xr[c] * k.sign;
-            if (c < kBlockCache) cache[c] = v;
-            if (v > m) {
-                s *= exp_scaled(m - v, k.c_hi, k.c_lo);
-                m = v;
-            }
-            s += exp_scaled(v - m, k.c_hi, k.c_lo);
-        }
-        float wm = wave_allreduce(m, OpMax{});
-        s *= exp_scaled(m - wm, k.c_hi, k.c_lo);
-        s = wave_allreduce(s, OpSum{});
-        if (lane == 0) {
-            red_m[wid] = wm;
-            red_z[wid] = s;
-        }
-        __syncthreads();
-        float gm = __builtin_fmaxf(__builtin_fmaxf(red_m[0], red_m[1]), __builtin_fmaxf(red_m[2], red_m[3]));
-        float z = 0.f;
+        float m = -FLT_MAX;
+        if constexpr (VEC) {
+            const float4_t *xr4 = reinterpret_cast<const float4_t *>(xr);
+            float4_t *yr4 = reinterpret_cast<float4_t *>(yr);
+            const int64_t n4 = cols / 4, cap4 = cap / 4;
+            auto take = [&](int64_t c, float4_t v) {
+                v *= k.sign;  // exact; turns the scale < 0 case into a max problem
+                if (c < cap4) cache4[c] = v;
+                m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fmaxf(v[0], v[1]), __builtin_fmaxf(v[2], v[3])));
+            };
+            int64_t c = tid;
+            for (; c + (kU - 1) * THREADS < n4; c += kU * THREADS) {
+                float4_t v[kU];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) z += red_z[w] * exp_scaled(red_m[w] - gm, k.c_hi, k.c_lo);
-        const float inv = 1.0f / z;
-        for (int64_t c = tid; c < cols; c += 256) {
-            float v = c < kBlockCache ? cache[c] : xr[c] * k.sign;
-            yr[c] = exp_scaled(v - gm, k.c_hi, k.c_lo) * inv;
+                for (int u = 0; u < kU; ++u) v[u] = __builtin_nontemporal_load(xr4 + c + u * THREADS);
+#pragma unroll
+                for (int u = 0; u < kU; ++u) take(c + u * THREADS, v[u]);
+            }
+            for (; c < n4; c += THREADS) take(c, __builtin_nontemporal_load(xr4 + c));
+            m = block_reduce_max<THREADS>(m, red);
+            float z = 0.f;
+            for (c = tid; c < n4; c += THREADS) {
+                float4_t v = c < cap4 ? cache4[c] : xr4[c] * k.sign;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[e] = exp_scaled(v[e] - m, k.c_hi, k.c_lo);
+                    z += v[e];
+                }
+                if (c < cap4) cache4[c] = v;
+            }
+            const float inv = 1.0f / block_reduce_sum<THREADS>(z, red);
+            for (c = tid; c < n4; c += THREADS) {
+                float4_t v;
+                if (c < cap4) {
+                    v = cache4[c];
+                } else {
+                    v = xr4[c] * k.sign;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = exp_scaled(v[e] - m, k.c_hi, k.c_lo);
+                }
+                __builtin_nontemporal_store(v * inv, yr4 + c);
+            }
+        } else {
+            for (int64_t c = tid; c < cols; c += THREADS) {
+                const float v = xr[c] * k.sign;
+                if (c < cap) cache[c] = v;
+                m = __builtin_fmaxf(m, v);
+            }
+            m = block_reduce_max<THREADS>(m, red);
+            float z = 0.f;
+            for (int64_t c = tid; c < cols; c += THREADS) {
+                const float e = exp_scaled((c < cap ? cache[c] : xr[c] * k.sign) - m, k.c_hi, k.c_lo);
+                if (c < cap) cache[c] = e;
+                z += e;
+            }
+            const float inv = 1.0f / block_reduce_sum<THREADS>(z, red);
+            for (int64_t c = tid; c < cols; c += THREADS)
+                yr[c] = (c < cap ? cache[c] : exp_scaled(xr[c] * k.sign - m, k.c_hi, k.c_lo)) * inv;
         }
-        __syncthreads();  // cache and red_* are reused by the next row
+        __syncthreads();  // the cache is reused by the next row
     }
+}
+
+constexpr int64_t kWideLdsBytes = 144 * 1024;  // of the CU's 160 KiB; rows up to 36864 floats are read once
+
+template <int THREADS, bool VEC>
+static perf_status launch_wide(const float *x, float *y, int64_t rows, int64_t cols, int64_t ldx, int64_t ldy, ExpConst k,
+                               hipStream_t st)
+{
+    int64_t cap = (cols + 3) / 4 * 4;
+    if (cap * 4 > kWideLdsBytes) cap = kWideLdsBytes / 4;
+    const size_t lds = (size_t)cap * 4;
+    auto kern = softmax_wide_kernel<THREADS, VEC>;
+    static std::atomic<size_t> lds_set{0};  // the dynamic-LDS cap is a per-function attribute: raise it when a longer row comes
+    if (lds > lds_set.load()) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)kWideLdsBytes) != hipSuccess)
+            return PERF_ERR_LAUNCH;
+        lds_set.store((size_t)kWideLdsBytes);
+    }
+    // as many workgroups per CU as LDS and wave slots allow, at most eight rounds of rows per launch
+    int64_t per_cu = (160 * 1024) / (int64_t)(lds + 256);
+    const int64_t by_waves = 2048 / THREADS;
+    per_cu = per_cu < 1 ? 1 : per_cu > by_waves ? by_waves : per_cu;
+    int64_t blocks = rows < 256 * per_cu ? rows : 256 * per_cu;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(THREADS), lds, st, x, y, rows, cols, ldx, ldy, k, cap);
+    return launch_status();
 }
 
 template <int NV, int RPW>
@@ -156,9 +312,19 @@ extern "C" perf_status perf_softmax(const void *x, void *y, int64_t rows, int64_
         else if (c <= 1024) launch_rows<4, 2>(xp, yp, rows, c, ldx, ldy, k, st);
         else launch_rows<8, 1>(xp, yp, rows, c, ldx, ldy, k, st);
     } else {
-        int64_t blocks = rows < 256 * 256 ? rows : 256 * 256;
-        hipLaunchKernelGGL(softmax_block_kernel, dim3((unsigned)blocks), dim3(256), 0, st, xp, yp, rows, cols, ldx, ldy,
-                           k);
+        // one workgroup per row: 16 waves for rows beyond 32 KiB, else 4; element accesses if unaligned
+        const bool vec_wide = cols % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(x, 16) && aligned(y, 16);
+        if (vec_wide && cols <= 32768) {  // the row in a workgroup's registers
+            const int c = (int)cols;
+            if (c <= 4096) return launch_wgrow<256, 4>(xp, yp, rows, c, ldx, ldy, k, st);
+            if (c <= 8192) return launch_wgrow<256, 8>(xp, yp, rows, c, ldx, ldy, k, st);
+            if (c <= 16384) return launch_wgrow<1024, 4>(xp, yp, rows, c, ldx, ldy, k, st);
+            return launch_wgrow<1024, 8>(xp, yp, rows, c, ldx, ldy, k, st);
+        }
+        if (cols > 8192) return vec_wide ? launch_wide<1024, true>(xp, yp, rows, cols, ldx, ldy, k, st)
+                                         : launch_wide<1024, false>(xp, yp, rows, cols, ldx, ldy, k, st);
+        return vec_wide ? launch_wide<256, true>(xp, yp, rows, cols, ldx, ldy, k, st)
+                        : launch_wide<256, false>(xp, yp, rows, cols, ldx, ldy, k, st);
     }
     return launch_status();
 }

@@ -12,6 +12,7 @@
 //    through LDS; workgroups that share 128-byte lines are placed on the same XCD.
 //  * eltwise_kernel: one pass, four 16-byte vectors per thread.
 #include "row_io.h"
+#include "wide_rows.h"
 #include "host_utils.h"
 
 namespace perf {
@@ -128,6 +129,8 @@ struct RmsArgs {
     int64_t rows, cols, ldx, ldy;
     float eps;
     hipStream_t st;
+    bool params_vec;  // gamma is 16-byte aligned
+    bool failed;
 };
 
 template <typename XT, typename PT, typename YT, int NC>
@@ -142,7 +145,7 @@ static void launch_rms_nc(const RmsArgs &a)
 }
 
 template <typename XT, typename PT, typename YT>
-static void launch_rms_typed(const RmsArgs &a, bool vec_ok)
+static void launch_rms_typed(RmsArgs &a, bool vec_ok)
 {
     constexpr int E = Elem<XT>::kPerChunk;
     const int64_t chunks = (a.cols + 64 * E - 1) / (64 * E);
@@ -150,6 +153,10 @@ static void launch_rms_typed(const RmsArgs &a, bool vec_ok)
         if (chunks <= 2) launch_rms_nc<XT, PT, YT, 2>(a);
         else if (chunks <= 8) launch_rms_nc<XT, PT, YT, 8>(a);
         else launch_rms_nc<XT, PT, YT, 16>(a);
+    } else if (vec_ok && a.params_vec) {
+        // longer rows: a workgroup per row, the row parked in LDS (one read of HBM)
+        a.failed = !launch_norm_wide<XT, PT, YT, true>(a.x, a.gamma, a.gamma, a.y, nullptr, a.rrms, a.rows, a.cols, a.ldx,
+                                                       a.ldy, a.eps, a.st);
     } else {
         const int64_t blocks = a.rows < 65536 ? a.rows : 65536;
         hipLaunchKernelGGL((rmsnorm_block_kernel<XT, PT, YT>), dim3((unsigned)blocks), dim3(256), 0, a.st,
@@ -158,14 +165,14 @@ static void launch_rms_typed(const RmsArgs &a, bool vec_ok)
 }
 
 template <typename XT, typename PT>
-static void launch_rms_y(const RmsArgs &a, bool vec_ok, int y_dt)
+static void launch_rms_y(RmsArgs &a, bool vec_ok, int y_dt)
 {
     if (y_dt == PERF_F32) launch_rms_typed<XT, PT, float>(a, vec_ok);
     else launch_rms_typed<XT, PT, uint16_t>(a, vec_ok);
 }
 
 template <typename XT>
-static void launch_rms_p(const RmsArgs &a, bool vec_ok, int p_dt, int y_dt)
+static void launch_rms_p(RmsArgs &a, bool vec_ok, int p_dt, int y_dt)
 {
     if (p_dt == PERF_F32) launch_rms_y<XT, float>(a, vec_ok, y_dt);
     else launch_rms_y<XT, uint16_t>(a, vec_ok, y_dt);
@@ -236,13 +243,13 @@ __global__ __launch_bounds__(256) void rowmean_kernel(const XT *__restrict__ x, 
 // workgroups share each line, and the group index is remapped so that they run on the same
 // XCD (workgroup ids are dealt round-robin to the 8 XCDs, whose L2s are private: without the
 // remap both XCDs fetch the line from memory).
-template <typename XT, typename YT, int CW>
-__global__ __launch_bounds__(256) void colmean_kernel(const XT *__restrict__ x, YT *__restrict__ y, int64_t rows,
-                                                      int64_t cols, int64_t ldx)
+template <typename XT, typename YT, int CW, int THREADS>
+__global__ __launch_bounds__(THREADS) void colmean_kernel(const XT *__restrict__ x, YT *__restrict__ y, int64_t rows,
+                                                          int64_t cols, int64_t ldx)
 {
     constexpr int E = Elem<XT>::kPerChunk;
-    constexpr int kRowLanes = 256 / CW;
-    constexpr int kUnroll = 16;  // 16 x 16 bytes in flight per thread: 64 KiB per workgroup
+    constexpr int kRowLanes = THREADS / CW;
+    constexpr int kUnroll = 4096 / THREADS;  // 64 KiB in flight per workgroup: 16 x 16 bytes per thread of 256, 4 of 1024
     __shared__ float part[kRowLanes][CW * E + 1];
     const int64_t group = gridDim.x % 8 == 0 ? (int64_t)(blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)
                                              : (int64_t)blockIdx.x;
@@ -276,14 +283,27 @@ __global__ __launch_bounds__(256) void colmean_kernel(const XT *__restrict__ x, 
     }
 #pragma unroll
     for (int e = 0; e < E; ++e) part[rl][cl * E + e] = acc[e];
+    // The row lanes' partial sums of a column are added in rounds of at most 8 terms per thread
+    // (one thread adding all kRowLanes of them in a row is 64 .. 256 dependent LDS reads: several
+    // microseconds at the end of a 20 us kernel); the order is fixed, so reruns are bit-identical.
+    constexpr int kCols = CW * E;
+    const int col = threadIdx.x % kCols, grp = threadIdx.x / kCols;
+    int n = kRowLanes;  // partial sums per column still to add
+    while (n > 1) {
+        const int step = n > 8 ? 8 : n, out = (n + step - 1) / step;
+        __syncthreads();
+        float s = 0.f;
+        const bool mine = grp < out;
+        if (mine)
+            for (int i = grp * step; i < min(n, (grp + 1) * step); ++i) s += part[i][col];
+        __syncthreads();
+        if (mine) part[grp][col] = s;
+        n = out;
+    }
     __syncthreads();
-    if (threadIdx.x < CW * E) {
-        const int64_t col = group * CW * E + threadIdx.x;
-        if (col < cols) {
-            float s = 0.f;
-            for (int i = 0; i < kRowLanes; ++i) s += part[i][threadIdx.x];
-            Elem<YT>::store1(y + col, s / (float)rows);
-        }
+    if (threadIdx.x < kCols) {
+        const int64_t c = group * kCols + threadIdx.x;
+        if (c < cols) Elem<YT>::store1(y + c, part[0][threadIdx.x] / (float)rows);
     }
 }
 
@@ -311,13 +331,16 @@ static void launch_mean(const void *x, void *y, int64_t rows, int64_t cols, int6
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), 0, st, (const XT *)x, (YT *)y, rows, cols, ldx);
     } else if (vec) {
         // whole 128-byte lines per workgroup when that still gives every CU a workgroup
+        // (fewer, 16-wave workgroups on whole lines, or 32-byte segments for more workgroups, measured
+        // no better on 4096 x 4096: 19.5 and 25.7 us against 18.5)
         constexpr int kWide = 8;
-        if ((cols + kWide * E - 1) / (kWide * E) >= 256)
-            hipLaunchKernelGGL((colmean_kernel<XT, YT, kWide>), dim3((unsigned)((cols + kWide * E - 1) / (kWide * E))),
-                               dim3(256), 0, st, (const XT *)x, (YT *)y, rows, cols, ldx);
+        const int64_t nwide = (cols + kWide * E - 1) / (kWide * E);
+        if (nwide >= 256)
+            hipLaunchKernelGGL((colmean_kernel<XT, YT, kWide, 256>), dim3((unsigned)nwide), dim3(256), 0, st, (const XT *)x,
+                               (YT *)y, rows, cols, ldx);
         else
-            hipLaunchKernelGGL((colmean_kernel<XT, YT, 4>), dim3((unsigned)((cols + 4 * E - 1) / (4 * E))), dim3(256), 0,
-                               st, (const XT *)x, (YT *)y, rows, cols, ldx);
+            hipLaunchKernelGGL((colmean_kernel<XT, YT, 4, 256>), dim3((unsigned)((cols + 4 * E - 1) / (4 * E))), dim3(256),
+                               0, st, (const XT *)x, (YT *)y, rows, cols, ldx);
     } else {
         hipLaunchKernelGGL((colmean_scalar_kernel<XT, YT>), dim3((unsigned)((cols + 255) / 256)), dim3(256), 0, st,
                            (const XT *)x, (YT *)y, rows, cols, ldx);
@@ -540,10 +563,10 @@ extern "C" perf_status perf_rmsnorm(const void *x, const void *gamma, void *y, f
     const int64_t ex = 16 / dtype_size(x_dt);
     const bool vec_ok = cols % ex == 0 && ldx % ex == 0 && aligned(x, 16) && aligned(y, 16) &&
                         (ldy * dtype_size(y_dt)) % 16 == 0;
-    RmsArgs a{x, gamma, y, rrms_out, rows, cols, ldx, ldy, eps, static_cast<hipStream_t>(stream)};
+    RmsArgs a{x, gamma, y, rrms_out, rows, cols, ldx, ldy, eps, static_cast<hipStream_t>(stream), aligned(gamma, 16), false};
     if (x_dt == PERF_F32) launch_rms_p<float>(a, vec_ok, param_dt, y_dt);
     else launch_rms_p<uint16_t>(a, vec_ok, param_dt, y_dt);
-    return launch_status();
+    return a.failed ? PERF_ERR_LAUNCH : launch_status();
 }
 
 extern "C" perf_status perf_reduce_mean(const void *x, void *y, int64_t rows, int64_t cols, int64_t ldx, int axis,

@@ -244,3 +244,13 @@ def test_batchnorm_static_argument_errors_and_size_limit():
     assert perf.perf_batchnorm_workspace_bytes(64, 64, 2048, 2048) > perf.perf_batchnorm_static_max_bytes()
     assert f(N=64, C=64, H=2048, W=2048) == perf.PERF_ERR_UNSUPPORTED
     assert perf.perf_batchnorm_workspace_bytes(8, 3, 2048, 2048) <= perf.perf_batchnorm_static_max_bytes()
+
+
+def test_stream_probe_argument_errors():
+    f = lambda **k: perf.perf_stream_probe(**{**dict(src=FAKE, dst=FAKE + 65536, nbytes=4096, mode=0, unroll=4, threads=256,
+                                                     grid=0, policy=3, check=False), **k})
+    assert f(src=None) == perf.PERF_ERR_NULL and f(dst=None) == perf.PERF_ERR_NULL
+    for bad in (dict(nbytes=0), dict(nbytes=24), dict(mode=3), dict(threads=96), dict(grid=-1), dict(policy=4)):
+        assert f(**bad) == perf.PERF_ERR_SHAPE, bad
+    assert f(src=FAKE + 8) == perf.PERF_ERR_ALIGN
+    assert f(unroll=3) == perf.PERF_ERR_UNSUPPORTED

@@ -69,6 +69,33 @@ def test_shapes_and_dtypes(rows, cols, x_bf16, y_bf16):
     _check(x, d["gamma"], d["beta"], 1e-5, x_bf16, False, y_bf16)
 
 
+@pytest.mark.parametrize("rows,cols,x_bf16,y_bf16,p_bf16", [
+    (300, 16384, True, True, False),      # 32 KiB rows: four waves per row, whole row in LDS
+    (40, 32768, True, True, True),        # 64 KiB rows: sixteen waves per row
+    (5, 4104, False, False, False),       # fp32 just past the register kernel (4096 columns)
+    (3, 36864, False, True, False),       # exactly the LDS capacity (144 KiB of fp32)
+    (3, 40000, False, False, False),      # beyond the LDS: the tail is read again from memory
+    (2, 80000, True, False, True),        # bf16 beyond the LDS (73728 columns fit)
+    (600, 8200, True, True, False),       # more rows than workgroups: the row loop
+])
+def test_rows_beyond_the_register_kernel(rows, cols, x_bf16, y_bf16, p_bf16):
+    d = configs.LayerNormWorkload(rows=rows, cols=cols).make()
+    x = d["x_bf16"] if x_bf16 else rng.bf16_bits_to_f32(d["x_bf16"]) + np.float32(0.001)
+    g, b = _params(cols, bf16=p_bf16)
+    _check(x, g, b, 1e-5, x_bf16, p_bf16, y_bf16)
+
+
+def test_long_rows_inplace_padded_and_large_offset():
+    d = configs.LayerNormWorkload(rows=9, cols=16384).make()
+    _check(d["x_bf16"], d["gamma"], d["beta"], 1e-5, True, False, True, inplace=True)
+    _check(d["x_bf16"], d["gamma"], d["beta"], 1e-5, True, False, True, ldx=16392, ldy=16400)
+    _check(d["x_bf16"], d["gamma"], d["beta"], 1e-5, True, False, True, ldx=16385, ldy=16387)   # general path
+    g = np.random.default_rng(3)
+    x = (1e3 + 0.1 * g.standard_normal((4, 20000))).astype(np.float32)    # mean 1e3, variance 1e-2
+    gm, bt = _params(20000)
+    _check(x, gm, bt, 1e-5, False, False, False)
+
+
 def test_bf16_params_padded_rows_inplace_no_stats():
     d = configs.LayerNormWorkload(rows=41, cols=2048).make()
     g16, b16 = _params(2048, bf16=True)

@@ -36,6 +36,19 @@ def test_shapes_cover_both_paths_and_tails(rows, cols):
     _check(x)
 
 
+@pytest.mark.parametrize("rows,cols", [
+    (300, 4096), (40, 16384), (600, 8192),   # four and sixteen waves per row, whole row in LDS; the row loop
+    (3, 36864), (3, 36868), (2, 50000),      # at the LDS capacity, just beyond it, well beyond it (tail read twice)
+    (2, 50001), (5, 2049),                   # element accesses
+])
+def test_rows_beyond_the_register_kernel(rows, cols):
+    x = configs.SoftmaxWorkload(rows=rows, cols=cols).make()["x"]
+    y, _ = _check(x)
+    P.assert_argmax_exact(y, x.astype(np.float64))
+    _check(x[:3], -0.5)
+    _check(x[:3], inplace=True)
+
+
 @pytest.mark.parametrize("scale", [0.125, -1.0, 0.0, 3.0])
 def test_scale(scale):
     x = configs.SoftmaxWorkload(rows=19, cols=512).make()["x"]

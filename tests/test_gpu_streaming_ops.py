@@ -61,6 +61,15 @@ def test_rmsnorm_bf16_shapes(rows, cols):
     _check_rmsnorm(rows, cols)
 
 
+def test_rmsnorm_rows_beyond_the_register_kernel():
+    _check_rmsnorm(200, 16384)                                   # four waves per row, row in LDS
+    _check_rmsnorm(20, 32768, p_bf16=True)                       # sixteen waves per row
+    _check_rmsnorm(3, 40000, x_bf16=False, y_bf16=False)         # beyond the LDS: the tail is read again
+    _check_rmsnorm(2, 80000, y_bf16=False)
+    _check_rmsnorm(5, 16384, inplace=True)
+    _check_rmsnorm(5, 16384, ldx=16392, ldy=16400)
+
+
 def test_rmsnorm_dtypes_padding_inplace():
     _check_rmsnorm(40, 2048, x_bf16=False, y_bf16=False)
     _check_rmsnorm(40, 4096, x_bf16=False, y_bf16=False)        # 16 chunks of fp32 per lane
@@ -197,3 +206,26 @@ def test_eltwise_bf16_and_unaligned():
     af = (g.standard_normal(1000)).astype(np.float32); bf = (g.standard_normal(1000)).astype(np.float32)
     got = _run_eltwise(perf.PERF_ADD, af, bf, False, offset=1)     # 4-byte aligned only: element kernel
     assert np.array_equal(got, af + bf)
+
+
+def test_stream_probe_copies_and_fills():
+    """The measurement aid behind the copy-ceiling study: copy mode must copy bit for bit in every
+    launch shape, write mode must fill exactly the requested bytes, read mode must leave dst alone
+    (but for its first 16 bytes)."""
+    import torch
+    n = 1 << 20
+    src = torch.randint(0, 255, (n + 64,), dtype=torch.uint8, device="cuda")
+    for unroll, threads, grid, policy in ((1, 64, 0, 0), (4, 256, 0, 3), (16, 1024, 7, 1), (8, 512, 300, 2), (2, 128, 0, 3)):
+        for nbytes in (n, n - 16 * 37, 16):
+            dst = torch.zeros(n + 64, dtype=torch.uint8, device="cuda")
+            perf.perf_stream_probe(src.data_ptr(), dst.data_ptr(), nbytes, 0, unroll, threads, grid, policy, G.stream())
+            torch.cuda.synchronize()
+            assert torch.equal(dst[:nbytes], src[:nbytes]) and not bool(dst[nbytes:].any())
+    dst = torch.zeros(n + 64, dtype=torch.uint8, device="cuda")
+    perf.perf_stream_probe(src.data_ptr(), dst.data_ptr(), n, 1, 8, 256, 0, 1, G.stream())
+    torch.cuda.synchronize()
+    assert not bool(dst[16:].any())
+    perf.perf_stream_probe(src.data_ptr(), dst.data_ptr(), n, 2, 8, 256, 0, 2, G.stream())
+    torch.cuda.synchronize()
+    v = dst[:n].view(torch.int32).view(-1, 4)
+    assert bool((v[:, 1] == 1).all()) and bool((v[:, 2] == 2).all()) and not bool(dst[n:].any())
