@@ -24,6 +24,12 @@
  *  - Outputs must not overlap inputs, except y == x exactly (same pointer, same ld, same
  *    dtype) for perf_softmax and perf_layernorm.
  *  - Kernels use no atomics: results are bit-identical from run to run.
+ *  - The calls may be made from several host threads at once (the only shared host state is a
+ *    set of idempotent per-kernel attribute settings behind atomic flags); perf_batchnorm_static
+ *    is the exception, see there.
+ *  - PERF_ERR_LAUNCH is taken from hipGetLastError() after the launch: an error that one of the
+ *    caller's own earlier HIP calls left pending is reported by (and cleared by) the next call
+ *    into this library.
  */
 #ifndef PERF_H
 #define PERF_H
@@ -84,9 +90,10 @@ perf_status perf_layernorm(const void *x, const void *gamma, const void *beta, v
  *   C   row-major, C[m*ldc + n] (ldc >= N), dtype f32 or bf16
  *   batch >= 1; matrix b starts strideA/strideB/strideC elements after matrix b-1
  *   (strides >= 0; strideC must be >= the extent of one C when batch > 1).
- * The MFMA path is taken for bf16 operands with A row-major and B column-major (both
+ * The bf16 MFMA path is taken for bf16 operands with A row-major and B column-major (both
  * K-contiguous), K a multiple of 32, lda/ldb/strides multiples of 8 and 16-byte aligned
- * pointers; every other legal combination runs a slower general kernel.
+ * pointers; every other legal combination (fp32 operands, other layouts, any K) runs a kernel
+ * built on the fp32 matrix instruction.
  * Errors: NULL, SHAPE, DTYPE, LAYOUT, ALIGN (pointer not aligned to its element size),
  * UNSUPPORTED (f32 operands with bf16 C), LAUNCH. */
 perf_status perf_gemm(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K,
@@ -101,8 +108,9 @@ perf_status perf_gemm(const void *A, const void *B, void *C, int64_t M, int64_t 
  * taps outside the image contribute 0;  P = (H + 2*pad_h - R)/stride_h + 1, Q likewise.
  *   x  device, NHWC dense;  w  device, KRSC dense;  y  device, NPQK dense
  *   xw_dt  dtype of x and w (bf16 or f32);  y_dt  f32 or bf16;  fp32 accumulation.
- * The MFMA path is taken for bf16 x/w with C a multiple of 32 and 16-byte aligned
- * pointers; other legal cases run a slower direct kernel.
+ * The bf16 MFMA path is taken for bf16 x/w with C a multiple of 32 and 16-byte aligned
+ * pointers; fp32 x/w (and bf16 with other channel counts) with at least 32 output channels run
+ * an implicit GEMM on the fp32 matrix instruction; the remaining cases run direct kernels.
  * Errors: NULL, SHAPE (any dim < 1, stride < 1, pad < 0, filter larger than the padded
  * image, more than 2^31-1 output pixels), DTYPE, ALIGN, LAUNCH. */
 perf_status perf_conv2d(const void *x, const void *w, void *y, int64_t N, int64_t H, int64_t W,
@@ -224,7 +232,34 @@ perf_status perf_eltwise(perf_eltwise_op op, const void *a, const void *b, void 
  *     direct kernel, 4 = one thread per output, 5 = one filter row per 16-wide MFMA step (bf16,
  *     stride 1, few input channels: 5x5 with 3 channels, 3x3 with 3 or 4; W*C even),
  *     6 = variant 1 with the input rows under a workgroup's pixel range resident in LDS
- *     (stride 1; N*P*Q / 256 pixels per range must divide P*Q, and the rows must fit). */
+ *     (stride 1; N*P*Q / 256 pixels per range must divide P*Q, and the rows must fit),
+ *     7 = implicit GEMM on the fp32 matrix instruction (any dtype, stride, padding, channel count). */
+/* The reduction operators with their launch shape chosen by the caller (same arguments, results
+ * and errors as perf_softmax / perf_layernorm; every variant computes the same arithmetic, only
+ * the summation tree differs with waves_per_row).  A knob left 0 keeps the library's rule; all
+ * knobs 0, or a choice that cannot run the problem, returns UNSUPPORTED.  Only the 16-byte
+ * aligned case has variants.
+ *   perf_softmax_variant:
+ *     waves_per_row  1 = a wavefront owns whole rows (cols <= 2048), rows_per_wave of them at a time:
+ *                        1, 2, 4 or 8, with ceil(cols / 256) rounded up to a power of two times
+ *                        rows_per_wave <= 16 (the lane's registers);
+ *                    4 or 16 = a workgroup of that many wavefronts owns a row (cols <= 8192 / 32768),
+ *                        rows_per_wave must be 0
+ *     grid           workgroups to launch (they loop over the rows); 0 = one pass (waves_per_row 1)
+ *                    or all wave slots of the chip (4, 16)
+ *   perf_layernorm_variant:
+ *     waves_per_row  1 (a wavefront per row: up to 16 chunks of 16 bytes per lane), 4 or 16 (a
+ *                    workgroup per row, row in its registers: up to 32 KiB / 64 KiB (bf16) or 128 KiB
+ *                    (f32) of input; gamma and beta 16-byte aligned)
+ *     grid           workgroups to launch; 0 = the library's (1536 of four waves, or all wave slots) */
+perf_status perf_softmax_variant(const void *x, void *y, int64_t rows, int64_t cols, int64_t ldx, int64_t ldy,
+                                 perf_dtype x_dt, perf_dtype y_dt, float scale, int rows_per_wave,
+                                 int waves_per_row, int64_t grid, perf_stream stream);
+perf_status perf_layernorm_variant(const void *x, const void *gamma, const void *beta, void *y, float *mean_out,
+                                   float *rstd_out, int64_t rows, int64_t cols, int64_t ldx, int64_t ldy, float eps,
+                                   perf_dtype x_dt, perf_dtype param_dt, perf_dtype y_dt, int waves_per_row,
+                                   int64_t grid, perf_stream stream);
+
 perf_status perf_gemm_variant(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K,
                               perf_layout la, int64_t lda, perf_layout lb, int64_t ldb, int64_t ldc,
                               int64_t batch, int64_t strideA, int64_t strideB, int64_t strideC,

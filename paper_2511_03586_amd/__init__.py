@@ -36,6 +36,9 @@ SIGNATURES = {
     "perf_reduce_mean_workspace_bytes": (_i64, [_i64, _i64, _int, _int]),
     "perf_reduce_mean_ws": (_int, [_ptr, _ptr, _ptr, _i64, _i64, _i64, _int, _int, _int, _ptr]),
     "perf_eltwise": (_int, [_int, _ptr, _ptr, _ptr, _i64, _int, _ptr]),
+    "perf_softmax_variant": (_int, [_ptr, _ptr, _i64, _i64, _i64, _i64, _int, _int, _f32, _int, _int, _i64, _ptr]),
+    "perf_layernorm_variant": (_int, [_ptr, _ptr, _ptr, _ptr, _ptr, _ptr, _i64, _i64, _i64, _i64, _f32,
+                                      _int, _int, _int, _int, _i64, _ptr]),
     "perf_gemm_variant": (_int, [_ptr, _ptr, _ptr, _i64, _i64, _i64, _int, _i64, _int, _i64, _i64, _i64, _i64, _i64, _i64,
                                  _f32, _int, _int, _int, _int, _ptr]),
     "perf_conv2d_variant": (_int, [_ptr, _ptr, _ptr] + [_i64] * 11 + [_int, _int, _int, _ptr]),
@@ -130,7 +133,21 @@ def perf_gemm_variant(A, B, C, M, N, K, la, lda, lb, ldb, ldc, batch, strideA, s
                                           alpha, ab_dt, c_dt, tile, kstep, stream), check)
 
 
-CONV_WREG, CONV_MFMA, CONV_SMALLC, CONV_DIRECT, CONV_ROWMFMA, CONV_WRES = 1, 2, 3, 4, 5, 6
+def perf_softmax_variant(x, y, rows, cols, ldx, ldy, x_dt, y_dt, scale, rows_per_wave, waves_per_row, grid,
+                         stream=None, check=True) -> int:
+    return _check("perf_softmax_variant",
+                  lib().perf_softmax_variant(x, y, rows, cols, ldx, ldy, x_dt, y_dt, scale, rows_per_wave, waves_per_row,
+                                             grid, stream), check)
+
+
+def perf_layernorm_variant(x, gamma, beta, y, mean_out, rstd_out, rows, cols, ldx, ldy, eps, x_dt, param_dt, y_dt,
+                           waves_per_row, grid, stream=None, check=True) -> int:
+    return _check("perf_layernorm_variant",
+                  lib().perf_layernorm_variant(x, gamma, beta, y, mean_out, rstd_out, rows, cols, ldx, ldy, eps,
+                                               x_dt, param_dt, y_dt, waves_per_row, grid, stream), check)
+
+
+CONV_WREG, CONV_MFMA, CONV_SMALLC, CONV_DIRECT, CONV_ROWMFMA, CONV_WRES, CONV_F32MFMA = 1, 2, 3, 4, 5, 6, 7
 
 
 def perf_conv2d_variant(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, xw_dt, y_dt, variant,

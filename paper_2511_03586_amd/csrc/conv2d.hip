@@ -18,7 +18,9 @@
 //  * conv2d_smallc_kernel: other few-channel cases: one thread per output pixel and block of
 //    KB output channels, weights broadcast from LDS, fp32 FMAs.
 //  * conv2d_direct_kernel: any other legal case; one thread per output element.
+#include <atomic>
 #include "mfma_tile.h"
+#include "f32mfma.h"
 #include "host_utils.h"
 #include <algorithm>
 
@@ -889,7 +891,7 @@ static perf_status launch_conv_mfma(const void *x, const void *w, void *y, const
     const int tiles_m = (int)((Mtot + BM - 1) / BM), tiles_n = (g.K + BN - 1) / BN;
     const size_t lds = Shape::kLdsBytes;
     auto kern = conv2d_mfma_kernel<TM, TN, WM, WN, CT>;
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds) != hipSuccess)
@@ -914,7 +916,7 @@ static perf_status launch_conv_wreg(const void *x, const void *w, void *y, const
     if ((Mtot + 31) / 32 < grid) grid = (int)((Mtot + 31) / 32);
     const int px_per_wg = (int)((Mtot + grid - 1) / grid);
     auto kern = conv2d_wreg_kernel<R, S, C, CT>;
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kLds) !=
             hipSuccess)
@@ -932,12 +934,14 @@ static perf_status launch_conv_wres(const void *x, const void *w, void *y, const
 {
     const int64_t Mtot = (int64_t)g.N * g.P * g.Q;
     auto kern = conv2d_wres_kernel<R, S, C, CT>;
-    static size_t lds_set = 0;  // the dynamic-LDS cap is a per-function setting; raise it when a larger patch comes along
-    if (lds > lds_set) {
+    // the dynamic-LDS cap is a per-function setting: raised once to the CU's 160 KiB (idempotent, so
+    // concurrent first calls are harmless)
+    static std::atomic<bool> attr_done{false};
+    if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess)
+                                160 * 1024) != hipSuccess)
             return PERF_ERR_LAUNCH;
-        lds_set = lds;
+        attr_done = true;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)(Mtot / px_per_wg)), dim3(512), lds, st, (const uint16_t *)x,
                        (const uint16_t *)w, (CT *)y, g, px_per_wg, patch_rows);
@@ -1002,7 +1006,27 @@ static perf_status launch_conv_direct(const void *x, const void *w, void *y, con
 
 namespace perf {
 
-enum ConvVariant { kConvAuto = 0, kConvWreg = 1, kConvMfma = 2, kConvSmallC = 3, kConvDirect = 4, kConvRowMfma = 5, kConvWres = 6 };
+enum ConvVariant {
+    kConvAuto = 0, kConvWreg = 1, kConvMfma = 2, kConvSmallC = 3, kConvDirect = 4, kConvRowMfma = 5, kConvWres = 6,
+    kConvF32Mfma = 7
+};
+
+// Implicit GEMM on the fp32 matrix instruction: any dtype, stride, padding and channel count.
+template <typename T, typename CT>
+static perf_status launch_conv_f32mfma(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
+{
+    const int64_t M = (int64_t)g.N * g.P * g.Q, Kred = (int64_t)g.R * g.S * g.C;
+    const bool big = ((M + 127) / 128) * ((g.K + 127) / 128) >= 256;
+    const int64_t edge = big ? 128 : 64;
+    const int64_t gx = (M + edge - 1) / edge, gy = (g.K + edge - 1) / edge;
+    if (gx > kMaxGridX || gy > kMaxGridYZ) return PERF_ERR_UNSUPPORTED;
+    const ConvRows<T> rows{(const T *)x, g.H, g.W, g.C, g.S, g.sh, g.sw, g.ph, g.pw, g.P, g.Q, M, Kred};
+    auto kern = big ? f32mfma_kernel<2, 2, ConvRows<T>, T, CT> : f32mfma_kernel<1, 1, ConvRows<T>, T, CT>;
+    // B(k, n) = w[n][k]: the KRSC filter of output channel n is a row of R*S*C values
+    hipLaunchKernelGGL(kern, dim3((unsigned)gx, (unsigned)gy, 1), dim3(256), 0, st, rows, (const T *)w, (CT *)y, M,
+                       (int64_t)g.K, Kred, (int64_t)1, Kred, (int64_t)g.K, (int64_t)0, (int64_t)0, (int64_t)0, (int64_t)1, 1.0f);
+    return launch_status();
+}
 
 // variant: kConvAuto = chosen here from the shape; otherwise the caller's choice (perf_conv2d_variant).
 static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N, int64_t H, int64_t W, int64_t C,
@@ -1078,6 +1102,8 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
                             ((R == 5 && S == 5 && C == 3) || (R == 3 && S == 3 && (C == 3 || C == 4))) &&
                             N * H * W * C < (int64_t(1) << 31) && N * ((P + 31) / 32) * ((Q + 63) / 64) <= kMaxGridX &&
                             (K + 15) / 16 <= kMaxGridYZ;
+    // fp32 matrix instruction: worth it from 32 output channels on (a 64-wide tile is then at least half used)
+    const bool f32mfma_ok = K >= 32 && R * S * C >= 16;
     if (variant == kConvAuto)
         // (the channel-blocked kernel has one thread per pixel: below ~64 workgroups of pixels the
         // thread-per-output kernel has more parallelism and measured faster)
@@ -1086,13 +1112,21 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
         variant = (wres_ok && wres_rounds <= 2) ? kConvWres
                   : wreg_ok                     ? kConvWreg
                   : mfma_ok ? kConvMfma
+                  : (f32mfma_ok && (xw_dt == PERF_F32 || C >= 32)) ? kConvF32Mfma
                   : (rowmfma_ok && N * P * Q >= 16384)          ? kConvRowMfma
                   : (C < 32 && smallc_ok && N * P * Q >= 16384) ? kConvSmallC
                                                                 : kConvDirect;
     else if ((variant == kConvWreg && !wreg_ok) || (variant == kConvMfma && !mfma_ok) ||
              (variant == kConvSmallC && !smallc_ok) || (variant == kConvRowMfma && !rowmfma_ok) ||
-             (variant == kConvWres && !wres_ok) || variant < kConvWreg || variant > kConvWres)
+             (variant == kConvWres && !wres_ok) || variant < kConvWreg || variant > kConvF32Mfma)
         return PERF_ERR_UNSUPPORTED;
+    if (variant == kConvF32Mfma) {
+        if (xw_dt == PERF_BF16)
+            return y_dt == PERF_F32 ? launch_conv_f32mfma<uint16_t, float>(x, w, y, g, st)
+                                    : launch_conv_f32mfma<uint16_t, uint16_t>(x, w, y, g, st);
+        return y_dt == PERF_F32 ? launch_conv_f32mfma<float, float>(x, w, y, g, st)
+                                : launch_conv_f32mfma<float, uint16_t>(x, w, y, g, st);
+    }
     if (variant == kConvWres)
         return y_dt == PERF_F32 ? launch_conv_wres<3, 3, 64, float>(x, w, y, g, wres_px, wres_rows, wres_lds, st)
                                 : launch_conv_wres<3, 3, 64, uint16_t>(x, w, y, g, wres_px, wres_rows, wres_lds, st);

@@ -4,8 +4,11 @@
 //  * gemm_mfma_kernel: bf16 operands, A row-major and B column-major (both K-contiguous),
 //    K a multiple of 32.  256x256, 128x128 or 64x64 workgroup tile; the K-step-64 loop of
 //    mfma_tile.h when K is a multiple of 64, else its K-step-32 loop.
-//  * gemm_general_kernel: any layout / dtype / size; 64x64 tile of fp32 FMAs.
+//  * f32mfma_kernel (f32mfma.h): any layout / dtype / size (fp32 operands, other layouts, odd K):
+//    the fp32 matrix instruction on operands staged through LDS as fp32.
+#include <atomic>
 #include "mfma_tile.h"
+#include "f32mfma.h"
 #include "host_utils.h"
 
 namespace perf {
@@ -101,64 +104,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t 
     }
 }
 
-// ---- general kernel ---------------------------------------------------------------
-template <typename T> __device__ __forceinline__ float load_ab(const T *p);
-template <> __device__ __forceinline__ float load_ab<float>(const float *p) { return *p; }
-template <> __device__ __forceinline__ float load_ab<uint16_t>(const uint16_t *p) { return bf16_to_f32(*p); }
-
-// 64x64 output tile, K-step 16, 256 threads each owning a 4x4 patch.  Element (m,k) of A
-// is A[m*a_sm + k*a_sk]; element (k,n) of B is B[k*b_sk + n*b_sn].
-template <typename T, typename CT>
-__global__ __launch_bounds__(256) void gemm_general_kernel(const T *__restrict__ A, const T *__restrict__ B,
-                                                           CT *__restrict__ C, int64_t M, int64_t N, int64_t K,
-                                                           int64_t a_sm, int64_t a_sk, int64_t b_sk, int64_t b_sn,
-                                                           int64_t ldc, int64_t strideA, int64_t strideB,
-                                                           int64_t strideC, int64_t batch, float alpha)
-{
-    __shared__ float As[16][65], Bs[16][65];
-    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-    const int64_t m0 = (int64_t)blockIdx.x * 64, n0 = (int64_t)blockIdx.y * 64;
-    for (int64_t bz = blockIdx.z; bz < batch; bz += gridDim.z) {
-        const T *Ab = A + bz * strideA;
-        const T *Bb = B + bz * strideB;
-        CT *Cb = C + bz * strideC;
-        float acc[4][4] = {};
-        for (int64_t k0 = 0; k0 < K; k0 += 16) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int idx = tid + i * 256;
-                // walk the contiguous dimension with consecutive threads
-                int am, ak, bn, bk;
-                if (a_sk == 1) { am = idx >> 4; ak = idx & 15; } else { am = idx & 63; ak = idx >> 6; }
-                if (b_sk == 1) { bn = idx >> 4; bk = idx & 15; } else { bn = idx & 63; bk = idx >> 6; }
-                As[ak][am] = (m0 + am < M && k0 + ak < K) ? load_ab<T>(Ab + (m0 + am) * a_sm + (k0 + ak) * a_sk) : 0.f;
-                Bs[bk][bn] = (n0 + bn < N && k0 + bk < K) ? load_ab<T>(Bb + (k0 + bk) * b_sk + (n0 + bn) * b_sn) : 0.f;
-            }
-            __syncthreads();
-#pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                float a[4], b[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) a[i] = As[k][ty * 4 + i];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) b[j] = Bs[k][tx * 4 + j];
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
-            }
-            __syncthreads();
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int64_t m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
-                if (m < M && n < N) store_c<CT>(Cb + m * ldc + n, alpha * acc[i][j]);
-            }
-    }
-}
-
 struct GemmArgs {
     const void *A, *B;
     void *C;
@@ -176,7 +121,7 @@ static perf_status launch_mfma(const GemmArgs &g)
     const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
     const size_t lds = Shape::kLdsBytes;
     auto kern = gemm_mfma_kernel<TM, TN, WM, WN, K64, CT, NS, MI32>;
-    static bool attr_done = false;  // raising the dynamic-LDS cap is a per-function, idempotent setting
+    static std::atomic<bool> attr_done{false};  // raising the dynamic-LDS cap is a per-function, idempotent setting
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds) != hipSuccess)
@@ -199,12 +144,16 @@ static perf_status launch_general(const GemmArgs &g)
 {
     const int64_t a_sm = g.la == PERF_ROW_MAJOR ? g.lda : 1, a_sk = g.la == PERF_ROW_MAJOR ? 1 : g.lda;
     const int64_t b_sk = g.lb == PERF_ROW_MAJOR ? g.ldb : 1, b_sn = g.lb == PERF_ROW_MAJOR ? 1 : g.ldb;
-    const int64_t gx = (g.M + 63) / 64, gy = (g.N + 63) / 64;
+    // 128 x 128 tiles when they give every CU a workgroup, else 64 x 64
+    const bool big = ((g.M + 127) / 128) * ((g.N + 127) / 128) * g.batch >= 256;
+    const int64_t edge = big ? 128 : 64;
+    const int64_t gx = (g.M + edge - 1) / edge, gy = (g.N + edge - 1) / edge;
     if (gx > kMaxGridX || gy > kMaxGridYZ) return PERF_ERR_UNSUPPORTED;
     const unsigned gz = (unsigned)(g.batch < kMaxGridYZ ? g.batch : kMaxGridYZ);
-    hipLaunchKernelGGL((gemm_general_kernel<T, CT>), dim3((unsigned)gx, (unsigned)gy, gz), dim3(256), 0, g.st,
-                       (const T *)g.A, (const T *)g.B, (CT *)g.C, g.M, g.N, g.K, a_sm, a_sk, b_sk, b_sn, g.ldc,
-                       g.strideA, g.strideB, g.strideC, g.batch, g.alpha);
+    const DenseRows<T> a_src{(const T *)g.A, a_sm, a_sk, g.M, g.K};
+    auto kern = big ? f32mfma_kernel<2, 2, DenseRows<T>, T, CT> : f32mfma_kernel<1, 1, DenseRows<T>, T, CT>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)gx, (unsigned)gy, gz), dim3(256), 0, g.st, a_src, (const T *)g.B, (CT *)g.C,
+                       g.M, g.N, g.K, b_sk, b_sn, g.ldc, g.strideA, g.strideB, g.strideC, g.batch, g.alpha);
     return launch_status();
 }
 

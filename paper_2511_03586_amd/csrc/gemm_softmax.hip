@@ -15,6 +15,7 @@
 //    matrix with the next strip's rows in flight.  With K = 64 two workgroups fit a CU
 //    (80 KiB of LDS, <= 256 registers), so one's exponentials overlap the other's stores.
 //  * any other legal case: perf_gemm into P followed by perf_softmax in place.
+#include <atomic>
 #include "mfma_tile.h"
 #include "softmax_math.h"
 #include "host_utils.h"
@@ -174,12 +175,14 @@ static perf_status launch_fused(const void *A, const void *B, void *P, int64_t M
     constexpr int kRowsB = (16 * T16N + 31) / 32 * 32;
     const size_t lds = (size_t)(K / 64) * (2 * 64 + kRowsB) * kRowBytes64;  // B, and two buffers for the row strips
     auto kern = gemm_softmax_kernel<T16N, MASK, PT>;
-    static size_t lds_set = 0;  // the dynamic-LDS cap is a per-function setting; raise it when a larger K comes along
-    if (lds > lds_set) {
+    // the dynamic-LDS cap is a per-function setting: raised once to the CU's 160 KiB (idempotent, so
+    // concurrent first calls are harmless)
+    static std::atomic<bool> attr_done{false};
+    if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess)
+                                160 * 1024) != hipSuccess)
             return PERF_ERR_LAUNCH;
-        lds_set = lds;
+        attr_done = true;
     }
     const float sign = alpha < 0.f ? -1.f : 1.f;
     const float c = (float)(std::fabs((double)alpha) * 1.4426950408889634074);  // |alpha| log2(e)

@@ -190,7 +190,9 @@ struct LnArgs {
     float eps;
     hipStream_t st;
     bool params_vec;  // gamma and beta are 16-byte aligned
-    bool failed;
+    int waves_per_row;  // 0 = by shape; 1, 4, 16 = the caller's choice (perf_layernorm_variant)
+    int64_t grid;       // 0 = by shape; else that many workgroups
+    int failed;         // 0 = launched, 1 = a HIP call failed, 2 = the chosen kernel cannot run the rows
 };
 
 template <typename XT, typename PT, typename YT, int NC>
@@ -199,7 +201,8 @@ static void launch_rows_nc(const LnArgs &a)
     constexpr int E = Elem<XT>::kPerChunk;
     const size_t lds_bytes = (size_t)2 * (E / 4) * NC * 64 * sizeof(float4_t);
     int64_t blocks = (a.rows + kLnWaves - 1) / kLnWaves;
-    if (blocks > 1536) blocks = 1536;  // six workgroups per CU (two rounds of the three that are resident); waves then loop over rows
+    const int64_t cap = a.grid > 0 ? a.grid : 1536;  // six workgroups per CU (two rounds of the three that are resident); waves then loop over rows
+    if (blocks > cap) blocks = cap;
     const bool even = a.cols == (int64_t)NC * 64 * E;
     auto kern = even ? layernorm_rows_kernel<XT, PT, YT, NC, true> : layernorm_rows_kernel<XT, PT, YT, NC, false>;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kLnThreads), lds_bytes, a.st, (const XT *)a.x,
@@ -212,16 +215,21 @@ static void launch_typed(LnArgs &a, bool vec_ok)
 {
     constexpr int E = Elem<XT>::kPerChunk;
     const int64_t chunks = (a.cols + 64 * E - 1) / (64 * E);  // chunks per lane
-    if (vec_ok && chunks <= 16) {
+    const bool variant = a.waves_per_row != 0 || a.grid != 0;
+    if (variant && (!vec_ok || (a.waves_per_row == 1 && chunks > 16) || (a.waves_per_row > 1 && !a.params_vec))) {
+        a.failed = 2;
+        return;
+    }
+    if (vec_ok && chunks <= 16 && a.waves_per_row <= 1) {
         if (chunks <= 1) launch_rows_nc<XT, PT, YT, 1>(a);
         else if (chunks <= 2) launch_rows_nc<XT, PT, YT, 2>(a);
         else if (chunks <= 4) launch_rows_nc<XT, PT, YT, 4>(a);
         else if (chunks <= 8) launch_rows_nc<XT, PT, YT, 8>(a);
         else launch_rows_nc<XT, PT, YT, 16>(a);
     } else if (vec_ok && a.params_vec) {
-        // longer rows: a workgroup per row, the row parked in LDS (one read of HBM)
-        a.failed = !launch_norm_wide<XT, PT, YT, false>(a.x, a.gamma, a.beta, a.y, a.mean_out, a.rstd_out, a.rows, a.cols,
-                                                        a.ldx, a.ldy, a.eps, a.st);
+        // longer rows: a workgroup per row, the row in its registers or parked in LDS (one read of HBM)
+        a.failed = launch_norm_wide<XT, PT, YT, false>(a.x, a.gamma, a.beta, a.y, a.mean_out, a.rstd_out, a.rows, a.cols,
+                                                       a.ldx, a.ldy, a.eps, a.st, a.waves_per_row, a.grid);
     } else {
         int64_t blocks = a.rows < 65536 ? a.rows : 65536;
         hipLaunchKernelGGL((layernorm_block_kernel<XT, PT, YT>), dim3((unsigned)blocks), dim3(256), 0, a.st,
@@ -246,15 +254,17 @@ static void launch_p(LnArgs &a, bool vec_ok, int p_dt, int y_dt)
 
 }  // namespace perf
 
-extern "C" perf_status perf_layernorm(const void *x, const void *gamma, const void *beta, void *y, float *mean_out,
-                                      float *rstd_out, int64_t rows, int64_t cols, int64_t ldx, int64_t ldy, float eps,
-                                      perf_dtype x_dt, perf_dtype param_dt, perf_dtype y_dt, perf_stream stream)
+namespace perf {
+
+static perf_status layernorm_impl(const void *x, const void *gamma, const void *beta, void *y, float *mean_out,
+                                  float *rstd_out, int64_t rows, int64_t cols, int64_t ldx, int64_t ldy, float eps,
+                                  int x_dt, int param_dt, int y_dt, int waves_per_row, int64_t grid, perf_stream stream)
 {
-    using namespace perf;
     if (!x || !gamma || !beta || !y) return PERF_ERR_NULL;
     if (!dtype_ok(x_dt) || !dtype_ok(param_dt) || !dtype_ok(y_dt)) return PERF_ERR_DTYPE;
     if (rows < 1 || cols < 1 || ldx < cols || ldy < cols || !(eps >= 0.f) || !std::isfinite(eps)) return PERF_ERR_SHAPE;
     if (rows > (INT64_MAX / 4) / ldx || rows > (INT64_MAX / 4) / ldy) return PERF_ERR_SHAPE;
+    if (grid < 0 || grid > kMaxGridX) return PERF_ERR_SHAPE;
     if (!aligned(x, dtype_size(x_dt)) || !aligned(y, dtype_size(y_dt)) || !aligned(gamma, dtype_size(param_dt)) ||
         !aligned(beta, dtype_size(param_dt)) || (mean_out && !aligned(mean_out, 4)) ||
         (rstd_out && !aligned(rstd_out, 4)))
@@ -265,8 +275,31 @@ extern "C" perf_status perf_layernorm(const void *x, const void *gamma, const vo
     const bool vec_ok = cols % ex == 0 && ldx % ex == 0 && aligned(x, 16) && aligned(y, 16) &&
                         (ldy * dtype_size(y_dt)) % 16 == 0;
     LnArgs a{x, gamma, beta, y, mean_out, rstd_out, rows, cols, ldx, ldy, eps, static_cast<hipStream_t>(stream),
-             aligned(gamma, 16) && aligned(beta, 16), false};
+             aligned(gamma, 16) && aligned(beta, 16), waves_per_row, grid, 0};
     if (x_dt == PERF_F32) launch_p<float>(a, vec_ok, param_dt, y_dt);
     else launch_p<uint16_t>(a, vec_ok, param_dt, y_dt);
+    if (a.failed == 2) return PERF_ERR_UNSUPPORTED;
     return a.failed ? PERF_ERR_LAUNCH : launch_status();
+}
+
+}  // namespace perf
+
+extern "C" perf_status perf_layernorm(const void *x, const void *gamma, const void *beta, void *y, float *mean_out,
+                                      float *rstd_out, int64_t rows, int64_t cols, int64_t ldx, int64_t ldy, float eps,
+                                      perf_dtype x_dt, perf_dtype param_dt, perf_dtype y_dt, perf_stream stream)
+{
+    return perf::layernorm_impl(x, gamma, beta, y, mean_out, rstd_out, rows, cols, ldx, ldy, eps, x_dt, param_dt, y_dt, 0,
+                                0, stream);
+}
+
+extern "C" perf_status perf_layernorm_variant(const void *x, const void *gamma, const void *beta, void *y,
+                                              float *mean_out, float *rstd_out, int64_t rows, int64_t cols, int64_t ldx,
+                                              int64_t ldy, float eps, perf_dtype x_dt, perf_dtype param_dt,
+                                              perf_dtype y_dt, int waves_per_row, int64_t grid, perf_stream stream)
+{
+    if ((waves_per_row != 0 && waves_per_row != 1 && waves_per_row != 4 && waves_per_row != 16) ||
+        (waves_per_row == 0 && grid == 0))
+        return PERF_ERR_UNSUPPORTED;
+    return perf::layernorm_impl(x, gamma, beta, y, mean_out, rstd_out, rows, cols, ldx, ldy, eps, x_dt, param_dt, y_dt,
+                                waves_per_row, grid, stream);
 }

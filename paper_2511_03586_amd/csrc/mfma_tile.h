@@ -340,15 +340,21 @@ struct WaveTile16 {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
     }
+    // Must be called between the last mfma16() on this tile and the first ordinary (VALU, store)
+    // read of `acc`: mfma16 is inline assembly, so the compiler's hazard recogniser does not see
+    // the matrix instruction and inserts no wait states of its own; this supplies the 16+ the
+    // hardware needs between an MFMA's issue and a VALU read of its result.
+    __device__ __forceinline__ void finish() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
 };
 
 // acc += a (16 n-rows x 32 k) * b (16 m-rows x 32 k)^T, in place.  Written as inline assembly
 // because the compiler does not tie the destination of this 4-register MFMA to its
 // accumulator input and then shuffles accumulators between the two register files (several
 // hundred copies per K-step at this register pressure); "+a" pins each accumulator to its
-// AGPRs.  The instruction is invisible to the hazard recogniser: callers keep VALU reads
-// of the accumulators at least 16 wait states behind the last one (mfma_mainloop_k64 ends
-// with the padding).
+// AGPRs.  The instruction is invisible to the hazard recogniser: every user calls
+// WaveTile16::finish() behind its last mfma16 and before anything else reads the accumulators
+// (mfma_mainloop_k64 does so on return; the 32x32x16 variant of the loop uses the builtin and is
+// the cross-check in the tests).
 __device__ __forceinline__ void mfma16(float4_t &acc, const bf16x8_t &a, const bf16x8_t &b)
 {
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
@@ -467,7 +473,7 @@ __device__ __forceinline__ void mfma_mainloop_k64(WaveTile16<2 * TM, 2 * TN> &t,
         src_b.advance();
     }
     wait_vmem_and_lds<0>();  // drain the over-issued loads and reads before LDS is reused or released
-    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // MFMA -> VALU read distance (see mfma16)
+    t.finish();  // MFMA -> VALU read distance (see mfma16)
 }
 
 // The same loop and schedule with v_mfma_f32_32x32x16_bf16: 32 MFMAs of 32 cycles per half-step
@@ -589,6 +595,7 @@ __device__ __forceinline__ void mfma_mainloop_k64_mi32(WaveTile<TM, TN> &t, char
 // of column tiles are exchanged between the lanes of rows 0-7 and 8-15 of a 16-lane group
 // (DPP row rotate by 8), so that one store instruction writes 8 rows of 32 contiguous
 // elements (128 bytes of fp32) instead of 16 rows of 16.
+// (A tile that was accumulated with mfma16 must have seen WaveTile16::finish() before this.)
 template <int T16M, int T16N, typename CT>
 __device__ __forceinline__ void store_tile16(const WaveTile16<T16M, T16N> &t, CT *C, int64_t ldc, int M, int N, int row0,
                                              int col0, float alpha, int lane)

@@ -24,6 +24,18 @@ __global__ __launch_bounds__(256) void copy_kernel(const uint4_t *__restrict__ s
     }
 }
 
+// dst 16-byte aligned, src not: a grid of threads, each assembling one 16-byte vector from a source
+// it may only assume byte alignment for.
+__global__ __launch_bounds__(256) void copy_unaligned_src_kernel(const unsigned char *__restrict__ src,
+                                                                 uint4_t *__restrict__ dst, int64_t nvec)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) {
+        uint4_t v;
+        __builtin_memcpy(&v, src + i * 16, 16);
+        __builtin_nontemporal_store(v, dst + i);
+    }
+}
+
 __global__ __launch_bounds__(64) void copy_tail_kernel(const unsigned char *__restrict__ src,
                                                        unsigned char *__restrict__ dst, int64_t n)
 {
@@ -184,18 +196,29 @@ extern "C" perf_status perf_copy(const void *src, void *dst, int64_t bytes, perf
     if (bytes < 0) return PERF_ERR_SHAPE;
     if (bytes == 0) return PERF_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool vec = aligned(src, 16) && aligned(dst, 16);
-    const int64_t nvec = vec ? bytes / 16 : 0;
+    const unsigned char *sp = static_cast<const unsigned char *>(src);
+    unsigned char *dp = static_cast<unsigned char *>(dst);
+    // head: the bytes in front of dst's first 16-byte boundary (a few, one small workgroup)
+    int64_t head = (int64_t)((16 - (reinterpret_cast<uintptr_t>(dp) & 15)) & 15);
+    if (head > bytes) head = bytes;
+    if (head > 0) hipLaunchKernelGGL(copy_tail_kernel, dim3(1), dim3(64), 0, st, sp, dp, head);
+    sp += head;
+    dp += head;
+    const int64_t nvec = (bytes - head) / 16;
     if (nvec > 0) {
-        int64_t blocks = (nvec + 256 * kCopyUnroll - 1) / (256 * kCopyUnroll);
-        if (blocks > 256 * 1024) blocks = 256 * 1024;  // one pass per workgroup measured faster than a long grid-stride loop
-        hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const uint4_t *)src, (uint4_t *)dst,
-                           nvec);
+        if (aligned(sp, 16)) {
+            int64_t blocks = (nvec + 256 * kCopyUnroll - 1) / (256 * kCopyUnroll);
+            if (blocks > 256 * 1024) blocks = 256 * 1024;  // one pass per workgroup measured faster than a long grid-stride loop
+            hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const uint4_t *)sp, (uint4_t *)dp, nvec);
+        } else {
+            int64_t blocks = (nvec + 255) / 256;
+            if (blocks > 256 * 64) blocks = 256 * 64;
+            hipLaunchKernelGGL(copy_unaligned_src_kernel, dim3((unsigned)blocks), dim3(256), 0, st, sp, (uint4_t *)dp, nvec);
+        }
     }
-    const int64_t done = nvec * 16;
+    const int64_t done = head + nvec * 16;
     if (done < bytes)
-        hipLaunchKernelGGL(copy_tail_kernel, dim3(1), dim3(64), 0, st, (const unsigned char *)src + done,
-                           (unsigned char *)dst + done, bytes - done);
+        hipLaunchKernelGGL(copy_tail_kernel, dim3(1), dim3(64), 0, st, sp + nvec * 16, dp + nvec * 16, bytes - done);
     return launch_status();
 }
 

@@ -165,10 +165,12 @@ __global__ __launch_bounds__(THREADS) void softmax_wgrow_kernel(const float *__r
 
 template <int THREADS, int NV>
 static perf_status launch_wgrow(const float *x, float *y, int64_t rows, int cols, int64_t ldx, int64_t ldy, ExpConst k,
-                                hipStream_t st)
+                                hipStream_t st, int64_t grid = 0)
 {
-    const int64_t per_cu = 2048 / THREADS;  // all wave slots of a CU
-    const int64_t blocks = rows < 256 * per_cu ? rows : 256 * per_cu;
+    // 16 workgroups per CU (more than are resident: the variant search measured 182 us against
+    // 200 with just the resident ones on 8192 x 16384)
+    int64_t blocks = rows < 256 * 16 ? rows : 256 * 16;
+    if (grid > 0) blocks = grid < rows ? grid : rows;
     hipLaunchKernelGGL((softmax_wgrow_kernel<THREADS, NV>), dim3((unsigned)blocks), dim3(THREADS), 0, st, x, y, rows, cols,
                        ldx, ldy, k);
     return launch_status();
@@ -261,12 +263,12 @@ static perf_status launch_wide(const float *x, float *y, int64_t rows, int64_t c
     if (cap * 4 > kWideLdsBytes) cap = kWideLdsBytes / 4;
     const size_t lds = (size_t)cap * 4;
     auto kern = softmax_wide_kernel<THREADS, VEC>;
-    static std::atomic<size_t> lds_set{0};  // the dynamic-LDS cap is a per-function attribute: raise it when a longer row comes
-    if (lds > lds_set.load()) {
+    static std::atomic<bool> attr_done{false};  // the dynamic-LDS cap is a per-function, idempotent setting
+    if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)kWideLdsBytes) != hipSuccess)
             return PERF_ERR_LAUNCH;
-        lds_set.store((size_t)kWideLdsBytes);
+        attr_done = true;
     }
     // as many workgroups per CU as LDS and wave slots allow, at most eight rounds of rows per launch
     int64_t per_cu = (160 * 1024) / (int64_t)(lds + 256);
@@ -279,24 +281,30 @@ static perf_status launch_wide(const float *x, float *y, int64_t rows, int64_t c
 
 template <int NV, int RPW>
 static void launch_rows(const float *x, float *y, int64_t rows, int cols, int64_t ldx, int64_t ldy, ExpConst k,
-                        hipStream_t st)
+                        hipStream_t st, int64_t grid = 0)
 {
     int64_t blocks = (rows + 4 * RPW - 1) / (4 * RPW);
     if (blocks > 256 * 64) blocks = 256 * 64;  // then waves loop over rows
+    if (grid > 0 && grid < blocks) blocks = grid;  // (a caller's choice of a persistent grid)
     hipLaunchKernelGGL((softmax_rows_kernel<NV, RPW>), dim3((unsigned)blocks), dim3(256), 0, st, x, y, rows, cols, ldx,
                        ldy, k);
 }
 
 }  // namespace perf
 
-extern "C" perf_status perf_softmax(const void *x, void *y, int64_t rows, int64_t cols, int64_t ldx, int64_t ldy,
-                                    perf_dtype x_dt, perf_dtype y_dt, float scale, perf_stream stream)
+namespace perf {
+
+// rows_per_wave / waves_per_row / grid: 0 = the library's shape rules; otherwise the caller's
+// choice (perf_softmax_variant), UNSUPPORTED if that kernel cannot run the problem.
+static perf_status softmax_impl(const void *x, void *y, int64_t rows, int64_t cols, int64_t ldx, int64_t ldy, int x_dt,
+                                int y_dt, float scale, int rows_per_wave, int waves_per_row, int64_t grid,
+                                perf_stream stream)
 {
-    using namespace perf;
     if (!x || !y) return PERF_ERR_NULL;
     if (!dtype_ok(x_dt) || !dtype_ok(y_dt)) return PERF_ERR_DTYPE;
     if (rows < 1 || cols < 1 || ldx < cols || ldy < cols || !std::isfinite(scale)) return PERF_ERR_SHAPE;
     if (rows > (INT64_MAX / 4) / ldx || rows > (INT64_MAX / 4) / ldy) return PERF_ERR_SHAPE;
+    if (grid < 0 || grid > kMaxGridX) return PERF_ERR_SHAPE;
     if (x_dt != PERF_F32 || y_dt != PERF_F32) return PERF_ERR_UNSUPPORTED;
     if (!aligned(x, 4) || !aligned(y, 4)) return PERF_ERR_ALIGN;
 
@@ -304,27 +312,71 @@ extern "C" perf_status perf_softmax(const void *x, void *y, int64_t rows, int64_
     const float *xp = static_cast<const float *>(x);
     float *yp = static_cast<float *>(y);
     const ExpConst k = make_exp_const(scale);
-    const bool vec_ok = cols <= 2048 && cols % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(x, 16) && aligned(y, 16);
-    if (vec_ok) {
+    const bool vec = cols % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(x, 16) && aligned(y, 16);
+    const bool variant = rows_per_wave != 0 || waves_per_row != 0 || grid != 0;
+    if (variant && !vec) return PERF_ERR_UNSUPPORTED;  // the element-access path has no knobs
+    if (waves_per_row == 0) waves_per_row = cols <= 2048 ? 1 : cols <= 8192 ? 4 : cols <= 32768 ? 16 : -1;
+
+    if (vec && waves_per_row == 1) {
+        // a wavefront per row, rows_per_wave rows at a time: NV 16-byte vectors per lane and row, at
+        // most 16 vectors (64 registers) per lane in all
         const int c = (int)cols;
-        if (c <= 256) launch_rows<1, 8>(xp, yp, rows, c, ldx, ldy, k, st);
-        else if (c <= 512) launch_rows<2, 4>(xp, yp, rows, c, ldx, ldy, k, st);
-        else if (c <= 1024) launch_rows<4, 2>(xp, yp, rows, c, ldx, ldy, k, st);
-        else launch_rows<8, 1>(xp, yp, rows, c, ldx, ldy, k, st);
-    } else {
-        // one workgroup per row: 16 waves for rows beyond 32 KiB, else 4; element accesses if unaligned
-        const bool vec_wide = cols % 4 == 0 && ldx % 4 == 0 && ldy % 4 == 0 && aligned(x, 16) && aligned(y, 16);
-        if (vec_wide && cols <= 32768) {  // the row in a workgroup's registers
-            const int c = (int)cols;
-            if (c <= 4096) return launch_wgrow<256, 4>(xp, yp, rows, c, ldx, ldy, k, st);
-            if (c <= 8192) return launch_wgrow<256, 8>(xp, yp, rows, c, ldx, ldy, k, st);
-            if (c <= 16384) return launch_wgrow<1024, 4>(xp, yp, rows, c, ldx, ldy, k, st);
-            return launch_wgrow<1024, 8>(xp, yp, rows, c, ldx, ldy, k, st);
+        const int nv = c <= 256 ? 1 : c <= 512 ? 2 : c <= 1024 ? 4 : 8;
+        if (cols > 2048) return PERF_ERR_UNSUPPORTED;
+        // the library's rule, from the variant search: 4 vectors per lane in flight (131072 x 1024:
+        // 171 us against 174.5 with 8; 262144 x 512: 171 against 176); problems of less than 256 MiB
+        // take one row per wave on a persistent grid of 16 workgroups per CU (24576 x 512: 17.8 us
+        // against 19.3)
+        if (rows_per_wave == 0) {
+            const bool small = rows * cols * 8 < (int64_t(256) << 20);
+            rows_per_wave = small ? 1 : nv >= 4 ? 1 : 4 / nv;
+            if (small && grid == 0) grid = 256 * 16;
         }
-        if (cols > 8192) return vec_wide ? launch_wide<1024, true>(xp, yp, rows, cols, ldx, ldy, k, st)
-                                         : launch_wide<1024, false>(xp, yp, rows, cols, ldx, ldy, k, st);
-        return vec_wide ? launch_wide<256, true>(xp, yp, rows, cols, ldx, ldy, k, st)
-                        : launch_wide<256, false>(xp, yp, rows, cols, ldx, ldy, k, st);
+#define PERF_SM_ROWS(NV, RPW)                                        \
+    if (nv == NV && rows_per_wave == RPW) {                          \
+        launch_rows<NV, RPW>(xp, yp, rows, c, ldx, ldy, k, st, grid); \
+        return launch_status();                                      \
     }
-    return launch_status();
+        PERF_SM_ROWS(1, 1) PERF_SM_ROWS(1, 2) PERF_SM_ROWS(1, 4) PERF_SM_ROWS(1, 8)
+        PERF_SM_ROWS(2, 1) PERF_SM_ROWS(2, 2) PERF_SM_ROWS(2, 4) PERF_SM_ROWS(2, 8)
+        PERF_SM_ROWS(4, 1) PERF_SM_ROWS(4, 2) PERF_SM_ROWS(4, 4)
+        PERF_SM_ROWS(8, 1) PERF_SM_ROWS(8, 2)
+#undef PERF_SM_ROWS
+        return PERF_ERR_UNSUPPORTED;
+    }
+    if (vec && (waves_per_row == 4 || waves_per_row == 16)) {
+        // a workgroup per row, the row in its registers (at most 8 vectors per thread)
+        if (rows_per_wave != 0) return PERF_ERR_UNSUPPORTED;
+        const int64_t threads = 64 * waves_per_row;
+        if (cols > threads * 8 * 4) return PERF_ERR_UNSUPPORTED;
+        const int c = (int)cols;
+        const bool small = cols <= threads * 4 * 4;
+        if (waves_per_row == 4) return small ? launch_wgrow<256, 4>(xp, yp, rows, c, ldx, ldy, k, st, grid)
+                                             : launch_wgrow<256, 8>(xp, yp, rows, c, ldx, ldy, k, st, grid);
+        return small ? launch_wgrow<1024, 4>(xp, yp, rows, c, ldx, ldy, k, st, grid)
+                     : launch_wgrow<1024, 8>(xp, yp, rows, c, ldx, ldy, k, st, grid);
+    }
+    if (variant) return PERF_ERR_UNSUPPORTED;
+    // rows beyond 128 KiB, or nothing aligned: a workgroup per row through LDS
+    if (cols > 8192) return vec ? launch_wide<1024, true>(xp, yp, rows, cols, ldx, ldy, k, st)
+                                : launch_wide<1024, false>(xp, yp, rows, cols, ldx, ldy, k, st);
+    return vec ? launch_wide<256, true>(xp, yp, rows, cols, ldx, ldy, k, st)
+               : launch_wide<256, false>(xp, yp, rows, cols, ldx, ldy, k, st);
+}
+
+}  // namespace perf
+
+extern "C" perf_status perf_softmax(const void *x, void *y, int64_t rows, int64_t cols, int64_t ldx, int64_t ldy,
+                                    perf_dtype x_dt, perf_dtype y_dt, float scale, perf_stream stream)
+{
+    return perf::softmax_impl(x, y, rows, cols, ldx, ldy, x_dt, y_dt, scale, 0, 0, 0, stream);
+}
+
+extern "C" perf_status perf_softmax_variant(const void *x, void *y, int64_t rows, int64_t cols, int64_t ldx,
+                                            int64_t ldy, perf_dtype x_dt, perf_dtype y_dt, float scale,
+                                            int rows_per_wave, int waves_per_row, int64_t grid, perf_stream stream)
+{
+    if (rows_per_wave < 0 || waves_per_row < 0 || (rows_per_wave == 0 && waves_per_row == 0 && grid == 0))
+        return PERF_ERR_UNSUPPORTED;
+    return perf::softmax_impl(x, y, rows, cols, ldx, ldy, x_dt, y_dt, scale, rows_per_wave, waves_per_row, grid, stream);
 }

@@ -155,8 +155,8 @@ static void launch_rms_typed(RmsArgs &a, bool vec_ok)
         else launch_rms_nc<XT, PT, YT, 16>(a);
     } else if (vec_ok && a.params_vec) {
         // longer rows: a workgroup per row, the row parked in LDS (one read of HBM)
-        a.failed = !launch_norm_wide<XT, PT, YT, true>(a.x, a.gamma, a.gamma, a.y, nullptr, a.rrms, a.rows, a.cols, a.ldx,
-                                                       a.ldy, a.eps, a.st);
+        a.failed = launch_norm_wide<XT, PT, YT, true>(a.x, a.gamma, a.gamma, a.y, nullptr, a.rrms, a.rows, a.cols, a.ldx,
+                                                      a.ldy, a.eps, a.st) != 0;
     } else {
         const int64_t blocks = a.rows < 65536 ? a.rows : 65536;
         hipLaunchKernelGGL((rmsnorm_block_kernel<XT, PT, YT>), dim3((unsigned)blocks), dim3(256), 0, a.st,

@@ -228,40 +228,48 @@ __global__ __launch_bounds__(THREADS) void norm_wgrow_kernel(const XT *__restric
 }
 
 // Launch: rows of up to 128 KiB in a workgroup's registers (4 waves up to 32 KiB, 16 beyond); longer
-// ones parked in LDS: 16 waves per row beyond 32 KiB of input, else 4; as many workgroups per CU as LDS and
-// wave slots allow.  Returns false if the attribute call failed.
+// ones parked in LDS: 16 waves per row beyond 32 KiB of input, else 4; as many workgroups per CU
+// as LDS and wave slots allow.  waves_per_row (4 or 16) and grid (workgroups), when not 0, are the
+// caller's choice among the register kernels.
+// Returns 0 = launched, 1 = the attribute call failed, 2 = the chosen kernel cannot run the rows.
 template <typename XT, typename PT, typename YT, bool RMS>
-static bool launch_norm_wide(const void *x, const void *gamma, const void *beta, void *y, float *stat0, float *stat1,
-                             int64_t rows, int64_t cols, int64_t ldx, int64_t ldy, float eps, hipStream_t st)
+static int launch_norm_wide(const void *x, const void *gamma, const void *beta, void *y, float *stat0, float *stat1,
+                            int64_t rows, int64_t cols, int64_t ldx, int64_t ldy, float eps, hipStream_t st,
+                            int waves_per_row = 0, int64_t grid = 0)
 {
     constexpr int E = Elem<XT>::kPerChunk;
     const int64_t nch = cols / E;
     // (bf16 rows unpack to twice the registers: 8 chunks per thread of a 16-wave workgroup would spill)
-    if (nch <= (E == 8 ? 4 : 8) * 1024) {
+    constexpr int64_t kMax16 = (E == 8 ? 4 : 8) * 1024;
+    if (waves_per_row == 0 && nch <= kMax16) waves_per_row = nch <= 8 * 256 ? 4 : 16;
+    if (waves_per_row != 0) {
         auto reg = [&](auto kern, int threads) {
-            const int64_t per_cu = 2048 / threads;  // all wave slots of a CU
-            const int64_t blocks = rows < 256 * per_cu ? rows : 256 * per_cu;
+            (void)threads;
+            int64_t blocks = rows < 256 * 16 ? rows : 256 * 16;  // 16 workgroups per CU, as for the softmax
+            if (grid > 0) blocks = grid < rows ? grid : rows;
             hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), 0, st, (const XT *)x, (const PT *)gamma,
                                (const PT *)beta, (YT *)y, stat0, stat1, rows, (int)cols, ldx, ldy, eps);
-            return true;
+            return 0;
         };
-        if (nch <= 8 * 256) return reg(norm_wgrow_kernel<XT, PT, YT, 256, 8, RMS>, 256);
-        if (nch <= 4 * 1024) return reg(norm_wgrow_kernel<XT, PT, YT, 1024, 4, RMS>, 1024);
-        if constexpr (E == 4) return reg(norm_wgrow_kernel<XT, PT, YT, 1024, 8, RMS>, 1024);
+        if (waves_per_row == 4 && nch <= 8 * 256) return reg(norm_wgrow_kernel<XT, PT, YT, 256, 8, RMS>, 256);
+        if (waves_per_row == 16 && nch <= 4 * 1024) return reg(norm_wgrow_kernel<XT, PT, YT, 1024, 4, RMS>, 1024);
+        if constexpr (E == 4)
+            if (waves_per_row == 16 && nch <= 8 * 1024) return reg(norm_wgrow_kernel<XT, PT, YT, 1024, 8, RMS>, 1024);
+        return 2;
     }
     const int64_t cap = nch * 16 > kWideRowLdsBytes ? kWideRowLdsBytes / 16 : nch;
     const size_t lds = (size_t)cap * 16;
     auto go = [&](auto kern, int threads) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)kWideRowLdsBytes) != hipSuccess)
-            return false;
+            return 1;
         int64_t per_cu = (160 * 1024) / (int64_t)(lds + 256);
         const int64_t by_waves = 2048 / threads;
         per_cu = per_cu < 1 ? 1 : per_cu > by_waves ? by_waves : per_cu;
         const int64_t blocks = rows < 256 * per_cu ? rows : 256 * per_cu;
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds, st, (const XT *)x, (const PT *)gamma,
                            (const PT *)beta, (YT *)y, stat0, stat1, rows, cols, ldx, ldy, eps, cap);
-        return true;
+        return 0;
     };
     if (nch * 16 > 32 * 1024) return go(norm_wide_kernel<XT, PT, YT, 1024, RMS>, 1024);
     return go(norm_wide_kernel<XT, PT, YT, 256, RMS>, 256);

@@ -150,6 +150,28 @@ def test_small_channel_kernel_channel_blocks_and_fp32_operands():
     assert np.max(np.abs(y - ref) / np.maximum(ad, 1e-30)) <= 36 * 2.0 ** -23
 
 
+@pytest.mark.parametrize("kw", [
+    dict(N=2, H=9, W=11, C=40, K=48),                         # bf16, channel count no multiple of 32: the automatic choice
+    dict(N=1, H=14, W=9, C=24, K=70, R=3, S=1, pad=0, stride=2),
+    dict(N=3, H=20, W=20, C=16, K=130, R=5, S=5, pad=2),      # three channel tiles of 64, ragged
+    dict(N=8, H=56, W=56, C=8, K=128),                        # 196 x 1 tiles of 128 x 128
+])
+def test_fp32_matrix_instruction_implicit_gemm(kw):
+    import paper_2511_03586_amd as perf
+    wl = configs.ConvWorkload(**kw)
+    _check(wl, variant=perf.CONV_F32MFMA)
+    _check(wl, y_bf16=False)                                  # routed there by the shape rules
+    # fp32 operands: every product rounded once more than with bf16 operands (bound with K + 1)
+    d = wl.make()
+    x, w = rng.bf16_bits_to_f32(d["x_bf16"]) * np.float32(1.001), rng.bf16_bits_to_f32(d["w_bf16"]) * np.float32(0.999)
+    for y_bf16 in (False, True):
+        y = G.run_conv2d(x, w, (wl.stride, wl.stride), (wl.pad, wl.pad), xw_bf16=False, y_bf16=y_bf16)
+        ref, ad = oracle.conv2d(x.astype(np.float64), w.astype(np.float64), (wl.stride, wl.stride), (wl.pad, wl.pad),
+                                want_absdot=True)
+        yg = P.bf16_to_f64(y) if y_bf16 else y
+        P.assert_contraction_close(yg, ref, ad, wl.R * wl.S * wl.C + 1, out_bf16=y_bf16)
+
+
 def test_delta_kernels_and_tap_counts_are_exact():
     C = 64
     x = rng.bf16_bits_to_f32(configs.ConvWorkload(N=1, H=5, W=7, C=C, K=C).make()["x_bf16"])

@@ -229,3 +229,26 @@ def test_stream_probe_copies_and_fills():
     torch.cuda.synchronize()
     v = dst[:n].view(torch.int32).view(-1, 4)
     assert bool((v[:, 1] == 1).all()) and bool((v[:, 2] == 2).all()) and not bool(dst[n:].any())
+
+
+def test_copy_any_alignment_and_size():
+    """perf_copy (the measured HBM ceiling) must copy bit for bit whatever the alignment of either
+    pointer; misaligned cases run grid-wide kernels too (64 MiB in well under a second)."""
+    import time
+    import torch
+    n = 1 << 20
+    src = torch.randint(0, 255, (n + 64,), dtype=torch.uint8, device="cuda")
+    for so, do, nbytes in ((0, 0, n), (0, 0, n - 5), (1, 0, n - 7), (0, 3, n - 9), (5, 9, n - 11), (7, 7, 3), (2, 1, 40), (0, 8, 16)):
+        dst = torch.zeros(n + 64, dtype=torch.uint8, device="cuda")
+        perf.perf_copy(src.data_ptr() + so, dst.data_ptr() + do, nbytes, G.stream())
+        torch.cuda.synchronize()
+        assert torch.equal(dst[do:do + nbytes], src[so:so + nbytes]), (so, do, nbytes)
+        assert not bool(dst[:do].any()) and not bool(dst[do + nbytes:].any())
+    big = torch.randint(0, 255, ((64 << 20) + 64,), dtype=torch.uint8, device="cuda")
+    out = torch.zeros_like(big)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    perf.perf_copy(big.data_ptr() + 1, out.data_ptr() + 2, 64 << 20, G.stream())
+    torch.cuda.synchronize()
+    assert time.perf_counter() - t0 < 0.5
+    assert torch.equal(out[2:2 + (64 << 20)], big[1:1 + (64 << 20)])
