@@ -279,7 +279,8 @@ def build_paper_workloads(torch, perf):
                                                  pb.M, pb.N, pb.K, ROW, pb.K, COL, pb.K, pb.N, nb, pb.M * pb.K,
                                                  pb.N * pb.K, pb.M * pb.N, 1.0, F32, F32, st()), 4,
                         "fp32 operands: 768 tiles of 128x128"))
-    for tag, wl, kern, note in (("paper_conv_8x64x64x56x56x3_bf16", configs.PAPER_CONV_2, "conv2d_mfma_kernel<1,1,2,2,bf16>", "392 tiles of 64 pixels x 64 channels"),
+    for tag, wl, kern, note in (("paper_conv_8x64x64x56x56x3_bf16", configs.PAPER_CONV_2, "conv2d_wsplit_kernel<3,3,64,bf16>",
+                                 "256 workgroups of 98 pixels x 64 channels, weights in registers; two steps of work behind the launch floor"),
                                 ("paper_conv_8x10x3x512x512x5_bf16", configs.PAPER_CONV_1, "conv2d_rowmfma_kernel<5,5,3,bf16>",
                                  "3 input channels: one filter row (15 values) per 16-wide MFMA K-step; 3 GFLOP over 52 MiB, "
                                  "so priced against HBM (input once, output once)")):
@@ -304,6 +305,19 @@ def build_paper_workloads(torch, perf):
                                 wl.R, wl.S, wl.stride, wl.stride, wl.pad, wl.pad, F32, F32, st()), 4,
                             "fp32 operands: 10 output channels, fp32 vector FMAs" if small_c else
                             "fp32 operands: implicit GEMM on the fp32 matrix instruction"))
+    # other channel counts through the weights-in-registers kernel with 64-channel slabs (additions, not table rows)
+    for tag, wl in (("conv2d_32x56x56x64_k64_3x3_bf16", configs.ConvWorkload(N=32, K=64)),
+                    ("conv2d_16x56x56x64_k256_3x3_bf16", configs.ConvWorkload(N=16, K=256)),
+                    ("conv2d_64x56x56x64_k256_3x3_bf16", configs.ConvWorkload(N=64, K=256))):
+        d = wl.make()
+        x = sets(G.dev(d["x_bf16"]), 4)
+        w = G.dev(d["w_bf16"]); keep.append(w)
+        y = torch.empty((4, wl.N, wl.P, wl.Q, wl.K), dtype=torch.int16, device="cuda"); keep.append(y)
+        wls.append(Workload(tag, "conv2d_wsplit_kernel<3,3,64,bf16>", "mfma", wl.flops(),
+                            lambda i, x=x, w=w, y=y, wl=wl: perf.perf_conv2d(
+                                x[i % 4].data_ptr(), w.data_ptr(), y[i % 4].data_ptr(), wl.N, wl.H, wl.W, wl.C, wl.K,
+                                wl.R, wl.S, wl.stride, wl.stride, wl.pad, wl.pad, BF16, BF16, st()), 4,
+                            "3x3, 64 input channels, K a multiple of 64: a workgroup per (pixel range, 64-channel slab)"))
     # streaming operators of the table: rmsnorm 3072x4096, reducemean 4096x4096 (either axis), add 3072x4096,
     # mul 6x14336, relu 4096x4096; fp32, entries N(1, var 3) like the LayerNorm recipe
     def normal_f32(cfg, shape):

@@ -233,7 +233,11 @@ perf_status perf_eltwise(perf_eltwise_op op, const void *a, const void *b, void 
  *     stride 1, few input channels: 5x5 with 3 channels, 3x3 with 3 or 4; W*C even),
  *     6 = variant 1 with the input rows under a workgroup's pixel range resident in LDS
  *     (stride 1; N*P*Q / 256 pixels per range must divide P*Q, and the rows must fit),
- *     7 = implicit GEMM on the fp32 matrix instruction (any dtype, stride, padding, channel count). */
+ *     7 = implicit GEMM on the fp32 matrix instruction (any dtype, stride, padding, channel count),
+ *     8 = weights in registers with a workgroup per (pixel range, slab of 64 output channels)
+ *     and the input rows passing through a ring in LDS (3x3, 64 input channels, bf16, stride 1,
+ *     K any multiple of 64, 32 <= Q and a ring of at least 6 rows of 144 Q + 512 bytes within
+ *     88 KiB; some range length N*P*Q / (256 r / (K/64)), r = 1 .. 8, must divide P*Q). */
 /* The reduction operators with their launch shape chosen by the caller (same arguments, results
  * and errors as perf_softmax / perf_layernorm; every variant computes the same arithmetic, only
  * the summation tree differs with waves_per_row).  A knob left 0 keeps the library's rule; all

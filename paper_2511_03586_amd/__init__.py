@@ -147,7 +147,7 @@ def perf_layernorm_variant(x, gamma, beta, y, mean_out, rstd_out, rows, cols, ld
                                                x_dt, param_dt, y_dt, waves_per_row, grid, stream), check)
 
 
-CONV_WREG, CONV_MFMA, CONV_SMALLC, CONV_DIRECT, CONV_ROWMFMA, CONV_WRES, CONV_F32MFMA = 1, 2, 3, 4, 5, 6, 7
+CONV_WREG, CONV_MFMA, CONV_SMALLC, CONV_DIRECT, CONV_ROWMFMA, CONV_WRES, CONV_F32MFMA, CONV_WSPLIT = 1, 2, 3, 4, 5, 6, 7, 8
 
 
 def perf_conv2d_variant(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, xw_dt, y_dt, variant,

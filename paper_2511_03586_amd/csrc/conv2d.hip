@@ -23,12 +23,26 @@
 #include "f32mfma.h"
 #include "host_utils.h"
 #include <algorithm>
+#include <utility>
 
 namespace perf {
 
 struct ConvGeom {
     int N, H, W, C, K, R, S, sh, sw, ph, pw, P, Q;
 };
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a
+// compile-time constant inside the body (template arguments, register-array indices).
+template <int... I, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F &&f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F &&>(f));
+}
 
 template <int TM, int TN, int WM, int WN, typename CT>
 __global__ __launch_bounds__(64 * WM * WN) void conv2d_mfma_kernel(const uint16_t *__restrict__ x,
@@ -659,6 +673,379 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
     }
 }
 
+// ---- weights-in-registers kernel, 64 output channels per workgroup ---------------------
+// The same division of labour once more, with the work cut the other way: a workgroup owns a
+// slab of 64 output channels and a pixel range twice as long (K / 64 workgroups share a range).
+// It takes in 72 KiB of weights instead of 144, so all of them are in flight at once, and the
+// first blocks are computed tap by tap as the taps arrive; the price is that every input row
+// is fetched by K / 64 workgroups (from the L2 they share: they sit on one XCD).
+//   * MFMA wave w holds the weights of channel group w & 1 (32 channels) and computes the pixel
+//     blocks of parity w >> 1: in step t the four waves work on blocks 2t and 2t+1, 64 pixels.
+//     An operand read serves 32 channels of one wave, so per pixel the LDS carries half the reads
+//     of the 128-channel kernels.
+//   * The input rows under a range do not fit the LDS any more; they pass through a ring of kNR
+//     rows, filled in linear order by the memory waves one step ahead of their use.
+//   * Barriers: one when the first rows are there, one per filter tap while the weights arrive
+//     (a tap's loads are split between the two waves that need it), one at the end of that phase,
+//     one after its first results are staged, then one per step, and a last one.
+struct WsplitPlan {
+    int px = 0;          // pixels per range (a divisor of P*Q); 0: the shape does not fit
+    int ranges = 0;      // pixel ranges (workgroups = ranges * K / 64)
+    int patch_rows = 0;  // input rows under the longest range
+    int row_chunks = 0;  // 16-byte chunks per ring row
+    int ring_rows = 0;   // rows of the ring: as many as the LDS holds beside the weight staging, 16 at most
+    int rounds = 0;
+    size_t lds = 0;
+};
+constexpr int kWsMinRows = 6, kWsMaxRows = 16;  // ring rows: a step's three filter rows, the wrap, one step ahead
+constexpr int kWsFill = 5;      // fill loads per memory wave and step
+constexpr int kWsStageBytes = 64 * 9 * 64 * 2;  // weight staging: 64 channels x 576 values
+
+// Fill schedule shared by the kernel and the host's check of it.  Chunk index L of the linear
+// patch = row L / row_chunks (row v holds input row oh0 - pad_h + v), chunk L % row_chunks; wave
+// load idx covers chunks 64 idx .. 64 idx + 63 and lands at ring offset (1024 idx) mod ring bytes.
+struct WsplitFill {
+    int Q, R, patch_rows, row_chunks, ring_rows, q0;
+    // rows that hold everything the range's pixels 0 .. px_last need
+    __host__ __device__ int rows_through(int px_last) const
+    {
+        const int r = (q0 + px_last) / Q + R;
+        return r < patch_rows ? r : patch_rows;
+    }
+    // chunks wanted once everything through step `t` is to be there; chunks that may be written
+    // while step `t_busy` is the oldest one still reading the ring
+    __host__ __device__ int wanted(int t) const { return rows_through(64 * t + 63) * row_chunks; }
+    __host__ __device__ int writable(int t_busy) const { return ((q0 + 64 * t_busy) / Q + ring_rows) * row_chunks; }
+    __host__ __device__ bool fires(int idx, int want, int cap) const
+    {
+        return idx * 64 < want && (idx + 1) * 64 <= cap && idx * 64 < patch_rows * row_chunks;
+    }
+};
+
+template <int R, int S, int C, typename CT>
+__global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__restrict__ x,
+                                                            const uint16_t *__restrict__ w, CT *__restrict__ y,
+                                                            ConvGeom g, int px_per_wg, int patch_rows, int row_chunks, int ring_rows)
+{
+    constexpr int KWG = 64;                 // output channels per workgroup
+    constexpr int KSUB = R * S * C / 16;    // MFMA k-substeps per pixel block
+    constexpr int kPerTap = C / 16, kTaps = R * S;
+    constexpr int kPix = C * 2 + 16;        // LDS bytes per input pixel
+    constexpr int kChunks = kPix / 16;
+    constexpr int kTapBytes = 32 * C * 2;   // one tap of one channel group in the staging: 4 KiB
+    constexpr int kOutPitch = KWG * (int)sizeof(CT) + 16;
+    constexpr int kOutBytes = 32 * kOutPitch;               // one staged block
+    constexpr int kRowLanes = KWG * (int)sizeof(CT) / 16;   // lanes per pixel row of 16-byte pieces
+    constexpr int kStores = 16 * kRowLanes / 64;            // store instructions per memory wave and step (16 pixel rows)
+    constexpr int kWin = 9, kBar = KSUB - kWin;
+    static_assert(C == 64 && KSUB % kWin == 0 && 4 * kOutBytes <= kWsStageBytes, "layout assumptions");
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    char *const out_stage = smem;                  // (the weight staging is free after the tap phase)
+    char *const ring = smem + kWsStageBytes;
+    const int ring_bytes = ring_rows * row_chunks * 16;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int Mtot = g.N * g.P * g.Q;
+    const int nslab = g.K / KWG;
+    const int wg = gridDim.x % 8 == 0 ? (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
+    const int range = wg / nslab, slab = wg - range * nslab;
+    const int start = range * px_per_wg, end = min(start + px_per_wg, Mtot);
+    const int nblocks = (end - start + 31) / 32, nsteps = (nblocks + 1) / 2;
+    const int n0 = start / (g.P * g.Q), pq0 = start - n0 * (g.P * g.Q);
+    const int oh0 = pq0 / g.Q, q0 = pq0 - oh0 * g.Q;
+    const uint32_t row_pitch = (uint32_t)(row_chunks * 16);
+    // Both kinds of wave execute 1 + kTaps + 1 + (nsteps >= 2) + max(nsteps - 2, 0) + 1 barriers.
+
+    // Ring fill: wave load idx (64 chunks of the linear patch) -> ring; a wave takes every `stride`-th.
+    const rsrc_t xr = make_rsrc(x, (uint32_t)((int64_t)g.N * g.H * g.W * g.C * 2));
+    const WsplitFill fs{g.Q, R, patch_rows, row_chunks, ring_rows, q0};
+    int rem, vrow, next_load, ring_off, fill_stride;  // this lane's chunk `rem` of patch row `vrow` of the wave's next load
+    auto fill_from = [&](int idx, int stride) {        // (one division per phase, none per load)
+        const int L = idx * 64 + lane;
+        vrow = L / row_chunks;
+        rem = L - vrow * row_chunks;
+        next_load = idx;
+        ring_off = (int)(((int64_t)idx * 1024) % ring_bytes);
+        fill_stride = stride;
+    };
+    auto fire = [&]() {
+        const int vcol = rem / kChunks, ch = rem - vcol * kChunks;
+        const int ih = oh0 - g.ph + vrow, iw = vcol - g.pw;
+        const bool ok = ch < kChunks - 1 && vrow < patch_rows && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
+        const uint32_t vo = ok ? (uint32_t)(((n0 * g.H + ih) * g.W + iw) * C + ch * 8) * 2u : kOutOfRange;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void *)(ring + ring_off), 16, vo, 0, 0, 0);
+        rem += 64 * fill_stride;
+        while (rem >= row_chunks) {  // (row_chunks >= 256: twice at most)
+            rem -= row_chunks;
+            ++vrow;
+        }
+        next_load += fill_stride;
+        ring_off += 1024 * fill_stride;
+        ring_off = ring_off >= ring_bytes ? ring_off - ring_bytes : ring_off;
+    };
+    // the rows under steps 0 and 1, issued by all eight waves (the MFMA waves have nothing else to do yet)
+    const int cap0 = ring_rows * row_chunks, want1 = fs.wanted(1);
+    fill_from(wave, 8);
+    while (fs.fires(next_load, want1, cap0)) fire();
+
+    if (wave < 4) {
+        // ------------------------------ MFMA waves ------------------------------
+        __builtin_amdgcn_s_setprio(2);
+        const int grp = wave & 1, par = wave >> 1;
+        typedef const __attribute__((address_space(3))) char lds_char_t;
+        typedef const __attribute__((address_space(3))) bf16x8_t lds_frag_t;
+        lds_char_t *const lds0 = (lds_char_t *)smem;
+        // weights of this wave's 32 channels: 18 of its group's 36 loads (the other parity issues the
+        // rest), tap by tap; a slot holds 32 channel rows of 128 bytes, chunk c of row ch at position
+        // c ^ (ch / 2) % 8 (the 16 rows of a ds_read_b128 phase then fall on 16 different bank slots)
+        {
+            const rsrc_t wr = make_rsrc(w + (int64_t)(slab * KWG + grp * 32) * (R * S * C), (uint32_t)(32 * R * S * C * 2));
+            uint32_t wvo[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int row = 8 * (2 * par + i) + (lane >> 3);
+                wvo[i] = (uint32_t)(row * (R * S * C * 2) + (((lane & 7) ^ ((row >> 1) & 7)) << 4));
+            }
+#pragma unroll
+            for (int t = 0; t < kTaps; ++t)
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const uint32_t vo = wvo[i];
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        wr, (__attribute__((address_space(3))) void *)(smem + (grp * kTaps + t) * kTapBytes + (2 * par + i) * 1024),
+                        16, vo, t * (C * 2), 0, 0);
+                }
+        }
+        uint32_t wrd[kPerTap];
+#pragma unroll
+        for (int j = 0; j < kPerTap; ++j)
+            wrd[j] = (uint32_t)(grp * kTaps * kTapBytes + (lane & 31) * (C * 2) + (((2 * j + (lane >> 5)) ^ (((lane & 31) >> 1) & 7)) << 4));
+        bf16x8_t wf[KSUB];
+
+        // this lane's pixel: column ow of ring row slot `slot`; a step moves it on by 64 pixels
+        int ow = q0 + 32 * par + (lane & 31), slot = 0;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            if (ow >= g.Q) {
+                ow -= g.Q;
+                ++slot;
+            }
+        const uint32_t lane_base = (uint32_t)kWsStageBytes + (uint32_t)(lane >> 5) * 16u;
+        auto rows_of = [&](uint32_t (&a)[R]) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                int sl = slot + r;
+                sl = sl >= ring_rows ? sl - ring_rows : sl;
+                a[r] = lane_base + (uint32_t)sl * row_pitch + (uint32_t)(ow * kPix);
+            }
+        };
+        auto next_step = [&]() {
+            ow += 64;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                if (ow >= g.Q) {
+                    ow -= g.Q;
+                    ++slot;
+                }
+            slot = slot >= ring_rows ? slot - ring_rows : slot;
+        };
+        auto read_frag = [&](const uint32_t (&rowaddr)[R], int kk) {
+            const int tap = kk / kPerTap, r = tap / S, sft = tap % S;
+            return *(lds_frag_t *)(lds0 + rowaddr[r] + sft * kPix + (kk % kPerTap) * 32);
+        };
+        const int stage_wr = (lane & 31) * kOutPitch + (grp * 32 + 4 * (lane >> 5)) * (int)sizeof(CT);
+
+        uint32_t a0[R], a1[R], cur[R], nxt[R];
+        rows_of(a0);
+        next_step();
+        rows_of(a1);
+        bf16x8_t af[kWin];
+        float16_t accs[2];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) accs[0][e] = accs[1][e] = 0.f;
+
+        wait_vmem<2 * kTaps>();  // own part of the first rows has landed (only the weight loads are younger)
+        wg_barrier();            // the rows under steps 0 and 1 are complete
+        // steps 0 and 1 (step 0 alone if there is no other), tap by tap as the weights arrive
+        auto tap_phase = [&](auto nbc) {
+            constexpr int NB = decltype(nbc)::value, TOT = KSUB * NB;
+            auto frag_at = [&](int p) {  // position p of the MFMA sequence: (tap, step, k-substep)
+                const int t = p / (kPerTap * NB), blk = (p / kPerTap) % NB, j = p % kPerTap;
+                return read_frag(blk ? a1 : a0, t * kPerTap + j);
+            };
+#pragma unroll
+            for (int p = 0; p < kWin; ++p) af[p] = frag_at(p);
+            // the wait for tap t+1 and the reads of its fragments sit in front of tap t's MFMAs
+            auto take_tap = [&](auto tc) {
+                constexpr int t = decltype(tc)::value;
+                wait_vmem<2 * (kTaps - 1 - t)>();  // own loads of tap t have landed
+                wg_barrier();                      // ... and the other parity's
+#pragma unroll
+                for (int j = 0; j < kPerTap; ++j) wf[t * kPerTap + j] = *(lds_frag_t *)(lds0 + wrd[j] + t * kTapBytes);
+            };
+            take_tap(std::integral_constant<int, 0>{});
+            static_for<kTaps>([&](auto tc) {
+                constexpr int t = decltype(tc)::value;
+                if constexpr (t + 1 < kTaps) take_tap(std::integral_constant<int, t + 1>{});
+#pragma unroll
+                for (int blk = 0; blk < NB; ++blk)
+#pragma unroll
+                    for (int j = 0; j < kPerTap; ++j) {
+                        const int p = (t * NB + blk) * kPerTap + j;
+                        accs[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[t * kPerTap + j], af[p % kWin], accs[blk], 0, 0, 0);
+                        if (p + kWin < TOT) af[p % kWin] = frag_at(p + kWin);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+            });
+        };
+        if (nsteps >= 2) tap_phase(std::integral_constant<int, 2>{});
+        else tap_phase(std::integral_constant<int, 1>{});
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        wg_barrier();  // every wave is done with the weight staging; the rows under step 2 have landed
+        if (nsteps >= 2) {
+            stage_acc<CT>(accs[0], out_stage + par * kOutBytes + stage_wr);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) accs[0][e] = 0.f;
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            wg_barrier();  // step 0 is staged
+        }
+        next_step();
+        rows_of(cur);
+#pragma unroll
+        for (int kk = 0; kk < kWin; ++kk) af[kk] = read_frag(cur, kk);
+
+        // One step: `acc` collects this wave's block of step t, `prev` holds that of step t-1, which
+        // is converted and staged in the shadow of the first MFMAs, then cleared for step t+1.  The
+        // barrier tells the memory waves that it is staged, and the MFMA waves that the rows under
+        // step t+1 have landed.
+        for (int t0 = 2; t0 < nsteps; t0 += 2) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int t = t0 + h;
+                if (t >= nsteps) break;
+                float16_t &acc = accs[h];
+                float16_t &prev = accs[h ^ 1];
+                next_step();
+                rows_of(nxt);
+#pragma unroll
+                for (int r = 0; r < R; ++r) asm volatile("" : "+v"(cur[r]), "+v"(nxt[r]));
+                char *stg = out_stage + (((t - 1) & 1) * 2 + par) * kOutBytes + stage_wr;
+#pragma unroll
+                for (int kk = 0; kk < KSUB; ++kk) {
+                    if (kk == kBar) {
+                        __builtin_amdgcn_s_waitcnt(0xC07F | (kWin << 8));
+                        wg_barrier();
+                    }
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
+                    af[kk % kWin] = kk + kWin < KSUB ? read_frag(cur, kk + kWin) : read_frag(nxt, kk + kWin - KSUB);
+                    if (kk >= 1 && kk < 5) {
+                        const int a = kk - 1;
+                        if constexpr (sizeof(CT) == 4) {
+                            *reinterpret_cast<float4_t *>(stg + 8 * a * 4) =
+                                float4_t{prev[4 * a], prev[4 * a + 1], prev[4 * a + 2], prev[4 * a + 3]};
+                        } else {
+                            *reinterpret_cast<uint2_t *>(stg + 8 * a * 2) =
+                                uint2_t{pack_bf16(prev[4 * a], prev[4 * a + 1]), pack_bf16(prev[4 * a + 2], prev[4 * a + 3])};
+                        }
+                    }
+                    if (kk >= 6 && kk < 10) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) prev[4 * (kk - 6) + e] = 0.f;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int r = 0; r < R; ++r) cur[r] = nxt[r];
+            }
+        }
+        // the last step's results
+        const float16_t last = ((nsteps - 1) & 1) ? accs[1] : accs[0];
+        stage_acc<CT>(last, out_stage + (((nsteps - 1) & 1) * 2 + par) * kOutBytes + stage_wr);
+        wait_vmem_and_lds<0>();
+        wg_barrier();
+    } else {
+        // ------------------------------ memory waves ------------------------------
+        const int mw = wave - 4;
+        const rsrc_t yr = make_rsrc(y, (uint32_t)((int64_t)Mtot * g.K * sizeof(CT)));
+        // write-out of a staged step: this wave stores 16 of its 64 pixel rows (64 channels each)
+        auto store_step = [&](int t, bool enable) {
+            const char *stg = out_stage + ((t & 1) * 2 + (mw >> 1)) * kOutBytes;
+#pragma unroll
+            for (int i = 0; i < kStores; ++i) {
+                const int row = (mw & 1) * 16 + i * (64 / kRowLanes) + lane / kRowLanes;  // pixel row of block mw >> 1
+                const int m = start + t * 64 + (mw >> 1) * 32 + row;
+                const uint4_t v = *reinterpret_cast<const uint4_t *>(stg + row * kOutPitch + (lane % kRowLanes) * 16);
+                const uint32_t off = (uint32_t)m * (uint32_t)(g.K * sizeof(CT)) + (uint32_t)(slab * KWG * sizeof(CT)) + (lane % kRowLanes) * 16;
+                __builtin_amdgcn_raw_buffer_store_b128(v, yr, (enable && m < end) ? off : kOutOfRange, 0, 2 /* nt */);
+            }
+        };
+        wait_vmem<0>();
+        wg_barrier();  // the rows under steps 0 and 1 are complete
+        // from here on the four memory waves share the fill: first the rows under step 2
+        fill_from((want1 + 63) / 64 + mw, 4);
+        {
+            const int want2 = fs.wanted(2);
+            while (fs.fires(next_load, want2, cap0)) fire();
+        }
+#pragma unroll
+        for (int t = 0; t < kTaps; ++t) wg_barrier();  // (the MFMA waves' tap phase)
+        wait_vmem_and_lds<0>();
+        wg_barrier();  // end of the tap phase: the rows under step 2 are complete; steps 0 and 1 no longer read the ring
+        // Every later iteration issues its fill loads first, then kStores stores: "the loads issued
+        // behind the previous barrier have landed" is then vmcnt <= kStores, however many they were.
+        // fill_next(): the iteration behind the barrier of step t wants everything through step t + 2
+        // and may write the rows below step t's first; both row numbers are stepped on by 64 pixels
+        // per call instead of being divided out (first call: t = 1, with step 2 as the oldest reader)
+        int want_col = q0 + 64 * 3 + 63, want_row = 0, busy_col = q0 + 64 * 2, busy_row = 0;
+        while (want_col >= g.Q) {
+            want_col -= g.Q;
+            ++want_row;
+        }
+        while (busy_col >= g.Q) {
+            busy_col -= g.Q;
+            ++busy_row;
+        }
+        bool first_fill = true;
+        auto fill_next = [&]() {
+            const int rows = want_row + R < patch_rows ? want_row + R : patch_rows;
+            const int want = rows * row_chunks, cap = (busy_row + ring_rows) * row_chunks;
+            for (int i = 0; i < kWsFill && fs.fires(next_load, want, cap); ++i) fire();
+            want_col += 64;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                if (want_col >= g.Q) {
+                    want_col -= g.Q;
+                    ++want_row;
+                }
+            if (!first_fill) {  // (the first two calls both have step 2 as the oldest reader)
+                busy_col += 64;
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    if (busy_col >= g.Q) {
+                        busy_col -= g.Q;
+                        ++busy_row;
+                    }
+            }
+            first_fill = false;
+        };
+        if (nsteps >= 2) {
+            wg_barrier();  // step 0 is staged
+            fill_next();   // wants step 3, step 2 reads
+            store_step(0, true);
+        }
+        for (int t = 2; t < nsteps; ++t) {
+            wait_vmem_and_lds<kStores>();
+            wg_barrier();  // step t-1 is staged; the rows under step t+1 are complete
+            fill_next();   // wants step t + 2; step t may still have operand reads in flight: its rows stay
+            store_step(t - 1, true);
+        }
+        wg_barrier();  // the last step is staged
+        store_step(nsteps - 1, nsteps > 0);
+        wait_vmem_and_lds<0>();
+    }
+}
+
 template <typename T> __device__ __forceinline__ float load_xw(const T *p);
 template <> __device__ __forceinline__ float load_xw<float>(const float *p) { return *p; }
 template <> __device__ __forceinline__ float load_xw<uint16_t>(const uint16_t *p) { return bf16_to_f32(*p); }
@@ -949,6 +1336,86 @@ static perf_status launch_conv_wres(const void *x, const void *w, void *y, const
 }
 
 template <int R, int S, int C, typename CT>
+static perf_status launch_conv_wsplit(const void *x, const void *w, void *y, const ConvGeom &g, const WsplitPlan &pl,
+                                      hipStream_t st)
+{
+    auto kern = conv2d_wsplit_kernel<R, S, C, CT>;
+    static std::atomic<bool> attr_done{false};  // the dynamic-LDS cap is a per-function, idempotent setting
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                160 * 1024) != hipSuccess)
+            return PERF_ERR_LAUNCH;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(pl.ranges * (g.K / 64))), dim3(512), pl.lds, st, (const uint16_t *)x,
+                       (const uint16_t *)w, (CT *)y, g, pl.px, pl.patch_rows, pl.row_chunks, pl.ring_rows);
+    return launch_status();
+}
+
+// Launch plan of the 64-channel-slab kernel (stride 1, 3x3): pixel ranges inside one image, the ring
+// and the weight staging within the LDS, and the fill schedule replayed for every column a range
+// can start in: what step t+1 reads must be issued one iteration before the barrier of step t
+// waits for it, within the ring's capacity at that time.
+static WsplitPlan plan_wsplit(int64_t N, int64_t P, int64_t Q, int64_t R, int64_t K)
+{
+    WsplitPlan plan;
+    if (K % 64 != 0 || Q < 32) return plan;
+    const int64_t nslab = K / 64, Mpix = N * P * Q;
+    const int row_chunks = (int)((9 * Q + 32 + 7) / 8 * 8);
+    const int ring_rows = (int)std::min<int64_t>((160 * 1024 - kWsStageBytes) / (row_chunks * 16), kWsMaxRows);
+    const size_t lds = (size_t)kWsStageBytes + (size_t)ring_rows * row_chunks * 16;
+    if (ring_rows < kWsMinRows || row_chunks < 256) return plan;
+    for (int64_t rounds = 1; rounds <= 8 && plan.px == 0; ++rounds) {
+        int64_t ranges = 256 * rounds / nslab;
+        if (ranges < 1) continue;
+        if (ranges > (Mpix + 63) / 64) ranges = (Mpix + 63) / 64;  // at least one step each
+        const int64_t px = (Mpix + ranges - 1) / ranges;
+        if ((P * Q) % px != 0) continue;
+        ranges = Mpix / px;
+        const int64_t nb = (px + 31) / 32, nsteps = (nb + 1) / 2, q0max = px % Q == 0 ? 0 : Q - 1;
+        const int64_t rows = (q0max + nsteps * 64 - 1) / Q + R;
+        bool ok = true;
+        for (int64_t q0 = 0; q0 <= q0max && ok; ++q0) {
+            const WsplitFill fs{(int)Q, (int)R, (int)rows, row_chunks, ring_rows, (int)q0};
+            const int cap0 = ring_rows * row_chunks;
+            // the kernel's first phase: all eight waves, wave v takes loads v, v + 8, ... below wanted(1);
+            // the four memory waves then go on from the first load beyond it, every fourth each
+            const int want1 = fs.wanted(1), first = (want1 + 63) / 64;
+            for (int idx = 0; idx < first && ok; ++idx)
+                ok = fs.fires(idx, want1, cap0) || idx * 64 >= (int)rows * row_chunks;  // (issued, or past the patch)
+            int next[4] = {first, first + 1, first + 2, first + 3};
+            auto run = [&](int want, int cap, int per_wave) {  // one fill iteration of the four memory waves
+                for (int mw = 0; mw < 4; ++mw)
+                    for (int i = 0; i < per_wave && fs.fires(next[mw], want, cap); ++i) next[mw] += 4;
+            };
+            auto covered = [&](int chunks) {  // every load that holds a chunk below `chunks` has been issued
+                const int loads = (std::min(chunks, (int)rows * row_chunks) + 63) / 64;
+                for (int mw = 0; mw < 4; ++mw)
+                    if (next[mw] < loads) return false;  // (next[mw]: the first load of wave mw not yet issued)
+                return true;
+            };
+            run(fs.wanted(2), cap0, 1 << 20);
+            ok = ok && covered(fs.wanted(std::min<int64_t>(2, nsteps - 1)));  // at the end of the tap phase
+            if (nsteps >= 2) run(fs.wanted(3), fs.writable(2), kWsFill);
+            for (int64_t t = 2; t < nsteps && ok; ++t) {
+                ok = covered(fs.wanted((int)std::min<int64_t>(t + 1, nsteps - 1)));  // at the barrier of step t
+                run(fs.wanted((int)t + 2), fs.writable((int)t), kWsFill);
+            }
+        }
+        if (ok) {
+            plan.px = (int)px;
+            plan.ranges = (int)ranges;
+            plan.patch_rows = (int)rows;
+            plan.row_chunks = row_chunks;
+            plan.ring_rows = ring_rows;
+            plan.rounds = (int)rounds;
+            plan.lds = lds;
+        }
+    }
+    return plan;
+}
+
+template <int R, int S, int C, typename CT>
 static perf_status launch_conv_rowmfma(const void *x, const void *w, void *y, const ConvGeom &g, hipStream_t st)
 {
     const int tiles_w = (g.Q + 63) / 64, tiles_h = (g.P + 31) / 32;
@@ -1008,7 +1475,7 @@ namespace perf {
 
 enum ConvVariant {
     kConvAuto = 0, kConvWreg = 1, kConvMfma = 2, kConvSmallC = 3, kConvDirect = 4, kConvRowMfma = 5, kConvWres = 6,
-    kConvF32Mfma = 7
+    kConvF32Mfma = 7, kConvWsplit = 8
 };
 
 // Implicit GEMM on the fp32 matrix instruction: any dtype, stride, padding and channel count.
@@ -1095,6 +1562,11 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
         }
     }
     const bool wres_ok = wres_px > 0;
+    // ... 64 output channels per workgroup, input rows through a ring
+    WsplitPlan wsplit;
+    if (mfma_ok && R == 3 && S == 3 && C == 64 && stride_h == 1 && stride_w == 1 && N * P * Q * K < (int64_t(1) << 29))
+        wsplit = plan_wsplit(N, P, Q, R, K);
+    const bool wsplit_ok = wsplit.px > 0;
     // few input channels: channel-blocked direct kernel, if a 16-channel block of weights fits its LDS budget
     const bool smallc_ok = R * S * C * 16 * 4 <= kSmallcLdsBytes && (K + 15) / 16 <= kMaxGridYZ;
     // few input channels, one filter row per MFMA K-step: bf16, stride 1, an instantiated filter shape
@@ -1111,6 +1583,7 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
         // kernel with one or two rounds of workgroups, 65 us against 63 with four, 128x56x56)
         variant = (wres_ok && wres_rounds <= 2) ? kConvWres
                   : wreg_ok                     ? kConvWreg
+                  : wsplit_ok                   ? kConvWsplit  // (other multiples of 64 output channels: 10.8 us against 22.2, 32x56x56 64->64)
                   : mfma_ok ? kConvMfma
                   : (f32mfma_ok && (xw_dt == PERF_F32 || C >= 32)) ? kConvF32Mfma
                   : (rowmfma_ok && N * P * Q >= 16384)          ? kConvRowMfma
@@ -1118,8 +1591,12 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
                                                                 : kConvDirect;
     else if ((variant == kConvWreg && !wreg_ok) || (variant == kConvMfma && !mfma_ok) ||
              (variant == kConvSmallC && !smallc_ok) || (variant == kConvRowMfma && !rowmfma_ok) ||
-             (variant == kConvWres && !wres_ok) || variant < kConvWreg || variant > kConvF32Mfma)
+             (variant == kConvWres && !wres_ok) || (variant == kConvWsplit && !wsplit_ok) || variant < kConvWreg ||
+             variant > kConvWsplit)
         return PERF_ERR_UNSUPPORTED;
+    if (variant == kConvWsplit)
+        return y_dt == PERF_F32 ? launch_conv_wsplit<3, 3, 64, float>(x, w, y, g, wsplit, st)
+                                : launch_conv_wsplit<3, 3, 64, uint16_t>(x, w, y, g, wsplit, st);
     if (variant == kConvF32Mfma) {
         if (xw_dt == PERF_BF16)
             return y_dt == PERF_F32 ? launch_conv_f32mfma<uint16_t, float>(x, w, y, g, st)

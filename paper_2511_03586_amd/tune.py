@@ -39,9 +39,10 @@ from workloads import rng  # noqa: E402  (seeded input generators: no operator a
 
 # kstep 33: K-step 32 with the deep ring; 65: K-step 64 built on the 32x32x16 MFMA (256x256 tile only)
 GEMM_AXES = {"tile": (64, 128, 256), "kstep": (32, 33, 64, 65)}
-CONV_AXES = {"variant": (perf.CONV_WRES, perf.CONV_WREG, perf.CONV_MFMA, perf.CONV_F32MFMA, perf.CONV_ROWMFMA,
+CONV_AXES = {"variant": (perf.CONV_WRES, perf.CONV_WREG, perf.CONV_WSPLIT, perf.CONV_MFMA, perf.CONV_F32MFMA, perf.CONV_ROWMFMA,
                          perf.CONV_SMALLC, perf.CONV_DIRECT)}
 CONV_NAMES = {perf.CONV_WRES: "weights-in-regs, input-in-lds", perf.CONV_WREG: "weights-in-registers",
+              perf.CONV_WSPLIT: "weights-in-regs, 64-channel slabs",
               perf.CONV_MFMA: "implicit-gemm", perf.CONV_F32MFMA: "implicit-gemm-fp32-mfma", perf.CONV_ROWMFMA: "filter-row-per-mfma",
               perf.CONV_SMALLC: "channel-blocked-direct", perf.CONV_DIRECT: "thread-per-output"}
 # grid_per_cu: workgroups per CU of a persistent grid; 0 = the kernel family's own default

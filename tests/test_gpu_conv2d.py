@@ -83,6 +83,30 @@ def test_input_resident_kernel_refuses_what_it_cannot_run():
         assert rc == perf.PERF_ERR_UNSUPPORTED
 
 
+@pytest.mark.parametrize("kw", [dict(N=2), dict(N=8, K=64), dict(N=2, K=64), dict(N=4, K=256), dict(N=4, H=40, W=40),
+                                dict(N=1, K=64), dict(N=8, H=28, W=32), dict(N=4, H=58, W=58, pad=0), dict(N=2, H=16, W=72)])
+@pytest.mark.parametrize("y_bf16", [True, False])
+def test_channel_slab_kernel(kw, y_bf16):
+    # 1, 2 and 4 slabs of 64 output channels; ranges that start anywhere in a row and span 2 .. 7 rows
+    # of the 8-row ring (so the ring wraps inside a range); one-step and odd-step ranges, ragged last
+    # blocks, no padding, the narrowest and widest rows the ring takes
+    import paper_2511_03586_amd as perf
+    _check(configs.ConvWorkload(**kw), y_bf16=y_bf16, variant=perf.CONV_WSPLIT)
+
+
+def test_channel_slab_kernel_refuses_what_it_cannot_run():
+    import torch
+    import paper_2511_03586_amd as perf
+    buf = torch.zeros(1 << 22, dtype=torch.int16, device="cuda")
+    # stride 2; no range length divides 33 x 35 outputs; rows too wide for the ring; K not a multiple of 64;
+    # rows too narrow for a fill load
+    for n, h, w_, k, st in [(2, 56, 56, 128, 2), (3, 33, 35, 128, 1), (1, 16, 512, 128, 1), (2, 56, 56, 96, 1),
+                            (2, 56, 24, 128, 1)]:
+        rc = perf.perf_conv2d_variant(buf.data_ptr(), buf.data_ptr(), buf.data_ptr(), n, h, w_, 64, k, 3, 3, st, st, 1, 1,
+                                      perf.PERF_BF16, perf.PERF_BF16, perf.CONV_WSPLIT, G.stream(), check=False)
+        assert rc == perf.PERF_ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("kw,y_bf16", [
     (dict(N=16, H=56, W=56, C=32, K=256), True),     # 784 tiles of 128 pixels x 128 channels
     (dict(N=32, H=56, W=56, C=32, K=48), True),      # 784 tiles of 128 x 64, ragged channels
