@@ -65,6 +65,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--only", default="", help="comma-separated workload names (profiling aid)")
     ap.add_argument("--no-paper-shapes", action="store_true", help="skip the second workload (the paper's table shapes)")
+    ap.add_argument("--lds-probe", action="store_true",
+                    help="print the LDS read probes (bytes per clock and CU by waves per CU and read width; "
+                         "cycles per MFMA of the MFMA + operand-read pattern) as one JSON line and exit")
     ap.add_argument("--copy-study", action="store_true",
                     help="instead of the benchmark: sweep the streaming probe (copy / read / write, vectors per thread, "
                          "workgroup size, grid, cache policy) and print one JSON line with every point")
@@ -232,7 +235,7 @@ def build_paper_workloads(torch, perf):
     ps = configs.PAPER_SOFTMAX
     xs = sets(G.dev(ps.make()["x"]), 8)
     ys = torch.empty_like(xs); keep.append(ys)
-    wls.append(Workload("paper_softmax_24576x512_f32", "softmax_rows_kernel", "hbm", ps.bytes_moved(),
+    wls.append(Workload("paper_softmax_24576x512_f32", "softmax_rows_kernel<2,1>", "hbm", ps.bytes_moved(),
                         lambda i: perf.perf_softmax(xs[i % 8].data_ptr(), ys[i % 8].data_ptr(), ps.rows, ps.cols,
                                                     ps.cols, ps.cols, F32, F32, 1.0, st()), 8))
     for tag, wl, n in (("paper_layernorm_16384x1024_f32", configs.PAPER_LAYERNORM_1, 4),
@@ -268,13 +271,13 @@ def build_paper_workloads(torch, perf):
     # the same two shapes with fp32 operands (the table states no dtype): the fp32 matrix instruction, 157.3 TFLOP/s peak
     amf = sets(G.dev(rng.uniform(rng.tensor_seed(pm.config, 0), (pm.M, pm.K), -1.0, 1.0)), 16)
     bmf = sets(G.dev(rng.uniform(rng.tensor_seed(pm.config, 1), (pm.N, pm.K), -1.0, 1.0)), 16)
-    wls.append(Workload("paper_matmul_768x1024x1024_f32", "gemm_f32mfma_kernel<1,1,f32,f32>", "mfma_f32", pm.flops(),
+    wls.append(Workload("paper_matmul_768x1024x1024_f32", "f32mfma_kernel<1,1,DenseRows<f32>,f32,f32>", "mfma_f32", pm.flops(),
                         lambda i: perf.perf_gemm(amf[i % 16].data_ptr(), bmf[i % 16].data_ptr(), cm[i % 16].data_ptr(),
                                                  pm.M, pm.N, pm.K, ROW, pm.K, COL, pm.K, pm.N, 1, 0, 0, 0, 1.0, F32,
                                                  F32, st()), 16, "fp32 operands: 192 tiles of 64x64"))
     abf = sets(G.dev(rng.uniform(rng.tensor_seed(pb.config, 0), (pb.M, pb.K), -1.0, 1.0)).repeat(nb, 1, 1), 4)
     bbf = sets(G.dev(rng.uniform(rng.tensor_seed(pb.config, 1), (pb.N, pb.K), -1.0, 1.0)).repeat(nb, 1, 1), 4)
-    wls.append(Workload("paper_bmm_192x256x128x256_f32", "gemm_f32mfma_kernel<2,2,f32,f32>", "mfma_f32", nb * pb.flops(),
+    wls.append(Workload("paper_bmm_192x256x128x256_f32", "f32mfma_kernel<2,2,DenseRows<f32>,f32,f32>", "mfma_f32", nb * pb.flops(),
                         lambda i: perf.perf_gemm(abf[i % 4].data_ptr(), bbf[i % 4].data_ptr(), cb[i % 4].data_ptr(),
                                                  pb.M, pb.N, pb.K, ROW, pb.K, COL, pb.K, pb.N, nb, pb.M * pb.K,
                                                  pb.N * pb.K, pb.M * pb.N, 1.0, F32, F32, st()), 4,
@@ -298,7 +301,7 @@ def build_paper_workloads(torch, perf):
         xf = sets(G.dev(rng.uniform(rng.tensor_seed(wl.config, 0), (wl.N, wl.H, wl.W, wl.C), 0.0, 1.0)), 4)
         wf = G.dev(rng.normal(rng.tensor_seed(wl.config, 1), (wl.K, wl.R, wl.S, wl.C), 0.0, 2.0 / (wl.R * wl.S * wl.C))); keep.append(wf)
         yf = torch.empty((4, wl.N, wl.P, wl.Q, wl.K), dtype=torch.float32, device="cuda"); keep.append(yf)
-        wls.append(Workload(tag.replace("_bf16", "_f32"), "conv2d_smallc_kernel<f32>" if small_c else "f32mfma_kernel<conv,f32>",
+        wls.append(Workload(tag.replace("_bf16", "_f32"), "conv2d_smallc_kernel<f32>" if small_c else "f32mfma_kernel<1,1,ConvRows<f32>,f32,f32>",
                             "alu" if small_c else "mfma_f32", wl.flops(),
                             lambda i, x=xf, w=wf, y=yf, wl=wl: perf.perf_conv2d(
                                 x[i % 4].data_ptr(), w.data_ptr(), y[i % 4].data_ptr(), wl.N, wl.H, wl.W, wl.C, wl.K,
@@ -333,7 +336,7 @@ def build_paper_workloads(torch, perf):
     wls.append(Workload("paper_reducemean_4096x4096_f32_axis1", "rowmean_kernel<f32>", "hbm", 4 * 4096 * 4096,
                         lambda i: perf.perf_reduce_mean(xm[i % 8].data_ptr(), ym[i % 8].data_ptr(), 4096, 4096, 4096, 1,
                                                         F32, F32, st()), 8))
-    wls.append(Workload("paper_reducemean_4096x4096_f32_axis0", "colmean_kernel<f32>", "hbm", 4 * 4096 * 4096,
+    wls.append(Workload("paper_reducemean_4096x4096_f32_axis0", "colmean_kernel<f32,f32,4,256>", "hbm", 4 * 4096 * 4096,
                         lambda i: perf.perf_reduce_mean(xm[i % 8].data_ptr(), ym[i % 8].data_ptr(), 4096, 4096, 4096, 0,
                                                         F32, F32, st()), 8,
                         "one workgroup per 16 columns (64-byte row segments), no workspace, no atomics"))
@@ -371,23 +374,23 @@ def build_paper_workloads(torch, perf):
                                 xb[i % 2].data_ptr(), gb.data_ptr(), bb2.data_ptr(), yb[i % 2].data_ptr(), None, None,
                                 wsb.data_ptr(), d[0], d[1], d[2], d[3], 1e-5, F32, F32, F32, st()), 2,
                             "three launches; priced at two reads + one write of the tensor"))
-    # rows beyond a wavefront's registers (not in the paper's table): one workgroup per row, the row parked in LDS
+    # rows beyond a wavefront's registers (not in the paper's table): one workgroup per row, the row in its registers
     xw = G.dev(configs.SoftmaxWorkload(rows=512, cols=16384, config=23).make()["x"]).repeat(16, 1); keep.append(xw)
     yw = torch.empty_like(xw); keep.append(yw)
-    wls.append(Workload("long_softmax_8192x16384_f32", "softmax_wide_kernel<1024,vec>", "hbm", 8 * 8192 * 16384,
+    wls.append(Workload("long_softmax_8192x16384_f32", "softmax_wgrow_kernel<1024,4>", "hbm", 8 * 8192 * 16384,
                         lambda i: perf.perf_softmax(xw.data_ptr(), yw.data_ptr(), 8192, 16384, 16384, 16384, F32, F32, 1.0,
-                                                    st()), 1, "64 KiB rows: 16 waves per row, row held in LDS, one read of HBM"))
+                                                    st()), 1, "64 KiB rows: 16 waves per row, row held in registers with the next row in flight, one read of HBM"))
     dl = configs.LayerNormWorkload(rows=512, cols=16384, config=24).make()
     xl2 = sets(G.dev(dl["x_bf16"]).repeat(8, 1), 2)
     yl2 = torch.empty_like(xl2); keep.append(yl2)
     gl2, bl2 = G.dev(dl["gamma"]), G.dev(dl["beta"]); keep.extend([gl2, bl2])
-    wls.append(Workload("long_layernorm_4096x16384_bf16", "norm_wide_kernel<bf16,f32,bf16,256,layernorm>", "hbm",
+    wls.append(Workload("long_layernorm_4096x16384_bf16", "norm_wgrow_kernel<bf16,f32,bf16,256,8,layernorm>", "hbm",
                         4 * 4096 * 16384,
                         lambda i: perf.perf_layernorm(xl2[i % 2].data_ptr(), gl2.data_ptr(), bl2.data_ptr(),
                                                       yl2[i % 2].data_ptr(), None, None, 4096, 16384, 16384, 16384, 1e-5,
                                                       BF16, F32, BF16, st()), 2,
-                        "32 KiB rows: 4 waves per row, row held in LDS, one read of HBM"))
-    wls.append(Workload("long_rmsnorm_4096x16384_bf16", "norm_wide_kernel<bf16,f32,bf16,256,rmsnorm>", "hbm",
+                        "32 KiB rows: 4 waves per row, row held in registers with the next row in flight, one read of HBM"))
+    wls.append(Workload("long_rmsnorm_4096x16384_bf16", "norm_wgrow_kernel<bf16,f32,bf16,256,8,rmsnorm>", "hbm",
                         4 * 4096 * 16384,
                         lambda i: perf.perf_rmsnorm(xl2[i % 2].data_ptr(), gl2.data_ptr(), yl2[i % 2].data_ptr(), None, 4096,
                                                     16384, 16384, 16384, 1e-5, BF16, F32, BF16, st()), 2))
@@ -449,6 +452,33 @@ def copy_study(torch, perf, nbytes=1 << 30, iters=10):
                                      "nt_loads": bool(policy & 1), "nt_stores": bool(policy & 2),
                                      "gbs": round(moved * iters / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)})
     rows.sort(key=lambda r: (r["mode"], -r["gbs"]))
+    return rows
+
+
+def lds_probe(torch, perf, iters=2000):
+    """LDS read rate by waves per CU and bytes per lane, and the cost of the convolution kernels' inner
+    pattern (one MFMA 32x32x16 + one ds_read_b128 per step), from the library's probe kernels."""
+    st = torch.cuda.current_stream().cuda_stream
+    cyc = torch.zeros(1, dtype=torch.int64, device="cuda")
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    rows = []
+    for waves in (4, 8, 16):
+        for nbytes in (16, 8, 4):
+            for _ in range(2):
+                cyc.zero_()
+                perf.perf_lds_probe(cyc.data_ptr(), sink.data_ptr(), waves, nbytes, 0, iters, st)
+            torch.cuda.synchronize()
+            c = int(cyc.item())
+            rows.append({"waves_per_cu": waves, "bytes_per_lane": nbytes, "cycles": c,
+                         "bytes_per_clk_per_cu": round(waves * iters * 16 * 64 * nbytes / c, 1)})
+    for waves in (4, 8):
+        for _ in range(2):
+            cyc.zero_()
+            perf.perf_lds_probe(cyc.data_ptr(), sink.data_ptr(), waves, 16, 1, iters // 4, st)
+        torch.cuda.synchronize()
+        c = int(cyc.item())
+        rows.append({"waves_per_cu": waves, "pattern": "mfma_32x32x16 + ds_read_b128, window 9",
+                     "cycles_per_mfma_of_the_slowest_wave": round(c / (iters // 4 * 36), 2)})
     return rows
 
 
@@ -556,6 +586,9 @@ def main():
     perf.lib()  # fail loudly if the HIP library is missing
     if args.copy_study:
         print(json.dumps({"copy_study": copy_study(torch, perf)}))
+        return
+    if args.lds_probe:
+        print(json.dumps({"lds_probe": lds_probe(torch, perf)}))
         return
 
     wls, keep = build_workloads(torch, perf)

@@ -306,6 +306,21 @@ perf_status perf_mfma_probe(float *sink, int64_t iters, perf_stream stream);
  * Arguments and errors as perf_mfma_probe. */
 perf_status perf_mfma_probe_random(float *sink, int64_t iters, perf_stream stream);
 
+/* LDS read probes behind the convolution analysis (not one of the paper's operators): 256
+ * workgroups of `waves` wavefronts (4, 8 or 16), every wavefront reading its own conflict-free
+ * region.  with_mfma = 0: iters * 16 reads of bytes_per_lane (4, 8 or 16) bytes per lane, 16 in
+ * flight; LDS bytes per clock and CU = waves * iters * 16 * 64 * bytes_per_lane / cycles.
+ * with_mfma = 1 (bytes_per_lane 16): the weights-in-registers kernels' inner pattern, one
+ * v_mfma_f32_32x32x16_bf16 plus the ds_read_b128 of the operand used nine MFMAs later,
+ * iters * 36 of them; cycles / (iters * 36) against 32 is what that pattern costs a wavefront.
+ *   cycles  device, one 64-bit value the caller has set to 0: raised (atomic max) to the shader cycles
+ *           the slowest wavefront of workgroup 0 spent in the loop
+ *   sink    device, one float, never written (keeps the reads live)
+ * Errors: NULL, SHAPE (waves, bytes_per_lane, iters < 1 or > 2^24), UNSUPPORTED (with_mfma and
+ * bytes_per_lane != 16), ALIGN, LAUNCH. */
+perf_status perf_lds_probe(long long *cycles, float *sink, int waves, int bytes_per_lane, int with_mfma,
+                           int64_t iters, perf_stream stream);
+
 /* Human-readable name of a status code; static storage, never freed. */
 const char *perf_status_string(perf_status s);
 

@@ -22,6 +22,7 @@
 #include "mfma_tile.h"
 #include "f32mfma.h"
 #include "host_utils.h"
+#include "timeline.h"
 #include <algorithm>
 #include <utility>
 
@@ -486,12 +487,14 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
     // the 16 lanes of a read keep 16 different bank slots across the wrap
     const int row_chunks = kChunks * g.Q + 32;
     // Both kinds of wave execute exactly 2 + nblocks workgroup barriers.
+    TL_BEGIN();
 
     if (wave < 4) {
         // ------------------------------ MFMA waves ------------------------------
         __builtin_amdgcn_s_setprio(2);
         bf16x8_t wf[KSUB];
         load_weight_frags<R, S, C>(wf, smem, w, wave, lane);
+        TL_STAMP(wave == 0, 0, 2);
         typedef const __attribute__((address_space(3))) char lds_char_t;
         typedef const __attribute__((address_space(3))) bf16x8_t lds_frag_t;
         lds_char_t *const lds0 = (lds_char_t *)smem;
@@ -531,6 +534,7 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
         const int stage_wr16 = (lane & 31) * kOutPitch + (wave * 32 + 8 * (lane >> 5)) * 2;
 
         wg_barrier();  // the patch is complete (and every wave is done with the weight region)
+        TL_STAMP(wave == 0, 0, 3);
         bf16x8_t af[kWin];
 #pragma unroll
         for (int kk = 0; kk < kWin; ++kk) af[kk] = read_frag(cur, kk);
@@ -555,6 +559,7 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
                 // register per read, which does not fit the register budget of two waves per SIMD
 #pragma unroll
                 for (int r = 0; r < R; ++r) asm volatile("" : "+v"(cur[r]), "+v"(nxt[r]));
+                TL_STEP(wave == 0, 0, 8 + b);
                 char *stg = out_stage + ((b - 1) & 1) * kOutBytes + stage_wr;
                 char *stg16 = out_stage + ((b - 1) & 1) * kOutBytes + stage_wr16;
 #pragma unroll
@@ -595,10 +600,12 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
             }
         }
         // the last block's results
+        TL_STAMP(wave == 0, 0, 4);
         const float16_t last = ((nblocks - 1) & 1) ? accs[1] : accs[0];
         stage_acc<CT>(last, out_stage + ((nblocks - 1) & 1) * kOutBytes + stage_wr);
         wait_vmem_and_lds<0>();
         wg_barrier();
+        TL_END(wave == 0, 0);
     } else {
         // ------------------------------ memory waves ------------------------------
         const int mw = wave - 4;
@@ -645,8 +652,11 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
                 __builtin_amdgcn_raw_buffer_store_b128(v, yr, (enable && m < end) ? off : kOutOfRange, 0, 2 /* nt */);
             }
         };
+        TL_STAMP(wave == 4, 1, 2);
         wait_vmem<0>();  // own part of the first rows has landed
+        TL_STAMP(wave == 4, 1, 3);
         wg_barrier();    // the first rows are complete; the MFMA waves are done with the weight region
+        TL_STAMP(wave == 4, 1, 4);
         // Memory operations complete in order, so "the loads of step b-2 have landed" is a bound on
         // the number of younger operations: the stores of step b-2 and the loads and stores of
         // step b-1 (every step issues kStores stores, disabled ones while there is nothing to
@@ -658,6 +668,7 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
             else if (fired == 0) wait_vmem_and_lds<2 * kStores>();
             else wait_vmem_and_lds<kStores>();  // (the step after the one in which the fill ran out)
             wg_barrier();  // block b-1 is staged; the rows under block b+1 are complete
+            TL_STEP(wave == 4, 1, 8 + b);
             fired = 0;
 #pragma unroll
             for (int t = 0; t < kFill; ++t)
@@ -670,6 +681,7 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
         wg_barrier();  // the last block is staged
         store_block(nblocks - 1, nblocks > 0);
         wait_vmem_and_lds<0>();
+        TL_END(wave == 4, 1);
     }
 }
 
@@ -693,11 +705,10 @@ struct WsplitPlan {
     int ranges = 0;      // pixel ranges (workgroups = ranges * K / 64)
     int patch_rows = 0;  // input rows under the longest range
     int row_chunks = 0;  // 16-byte chunks per ring row
-    int ring_rows = 0;   // rows of the ring: as many as the LDS holds beside the weight staging, 16 at most
+    int ring_rows = 0;   // rows of the ring: 8, or 16 where the LDS holds them beside the weight staging
     int rounds = 0;
     size_t lds = 0;
 };
-constexpr int kWsMinRows = 6, kWsMaxRows = 16;  // ring rows: a step's three filter rows, the wrap, one step ahead
 constexpr int kWsFill = 5;      // fill loads per memory wave and step
 constexpr int kWsStageBytes = 64 * 9 * 64 * 2;  // weight staging: 64 channels x 576 values
 
@@ -756,6 +767,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
     const int oh0 = pq0 / g.Q, q0 = pq0 - oh0 * g.Q;
     const uint32_t row_pitch = (uint32_t)(row_chunks * 16);
     // Both kinds of wave execute 1 + kTaps + 1 + (nsteps >= 2) + max(nsteps - 2, 0) + 1 barriers.
+    TL_BEGIN();
 
     // Ring fill: wave load idx (64 chunks of the linear patch) -> ring; a wave takes every `stride`-th.
     const rsrc_t xr = make_rsrc(x, (uint32_t)((int64_t)g.N * g.H * g.W * g.C * 2));
@@ -866,7 +878,9 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
         for (int e = 0; e < 16; ++e) accs[0][e] = accs[1][e] = 0.f;
 
         wait_vmem<2 * kTaps>();  // own part of the first rows has landed (only the weight loads are younger)
+        TL_STAMP(wave == 0, 0, 2);
         wg_barrier();            // the rows under steps 0 and 1 are complete
+        TL_STAMP(wave == 0, 0, 3);
         // steps 0 and 1 (step 0 alone if there is no other), tap by tap as the weights arrive
         auto tap_phase = [&](auto nbc) {
             constexpr int NB = decltype(nbc)::value, TOT = KSUB * NB;
@@ -881,6 +895,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
                 constexpr int t = decltype(tc)::value;
                 wait_vmem<2 * (kTaps - 1 - t)>();  // own loads of tap t have landed
                 wg_barrier();                      // ... and the other parity's
+                if constexpr (t == 0) TL_STAMP(wave == 0, 0, 4);
 #pragma unroll
                 for (int j = 0; j < kPerTap; ++j) wf[t * kPerTap + j] = *(lds_frag_t *)(lds0 + wrd[j] + t * kTapBytes);
             };
@@ -903,6 +918,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
         else tap_phase(std::integral_constant<int, 1>{});
         __builtin_amdgcn_s_waitcnt(0xC07F);
         wg_barrier();  // every wave is done with the weight staging; the rows under step 2 have landed
+        TL_STAMP(wave == 0, 0, 5);
         if (nsteps >= 2) {
             stage_acc<CT>(accs[0], out_stage + par * kOutBytes + stage_wr);
 #pragma unroll
@@ -930,6 +946,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
                 rows_of(nxt);
 #pragma unroll
                 for (int r = 0; r < R; ++r) asm volatile("" : "+v"(cur[r]), "+v"(nxt[r]));
+                TL_STEP(wave == 0, 0, 8 + t);
                 char *stg = out_stage + (((t - 1) & 1) * 2 + par) * kOutBytes + stage_wr;
 #pragma unroll
                 for (int kk = 0; kk < KSUB; ++kk) {
@@ -960,10 +977,12 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
             }
         }
         // the last step's results
+        TL_STAMP(wave == 0, 0, 6);
         const float16_t last = ((nsteps - 1) & 1) ? accs[1] : accs[0];
         stage_acc<CT>(last, out_stage + (((nsteps - 1) & 1) * 2 + par) * kOutBytes + stage_wr);
         wait_vmem_and_lds<0>();
         wg_barrier();
+        TL_END(wave == 0, 0);
     } else {
         // ------------------------------ memory waves ------------------------------
         const int mw = wave - 4;
@@ -980,8 +999,11 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
                 __builtin_amdgcn_raw_buffer_store_b128(v, yr, (enable && m < end) ? off : kOutOfRange, 0, 2 /* nt */);
             }
         };
+        TL_STAMP(wave == 4, 1, 2);
         wait_vmem<0>();
+        TL_STAMP(wave == 4, 1, 3);
         wg_barrier();  // the rows under steps 0 and 1 are complete
+        TL_STAMP(wave == 4, 1, 4);
         // from here on the four memory waves share the fill: first the rows under step 2
         fill_from((want1 + 63) / 64 + mw, 4);
         {
@@ -992,6 +1014,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
         for (int t = 0; t < kTaps; ++t) wg_barrier();  // (the MFMA waves' tap phase)
         wait_vmem_and_lds<0>();
         wg_barrier();  // end of the tap phase: the rows under step 2 are complete; steps 0 and 1 no longer read the ring
+        TL_STAMP(wave == 4, 1, 5);
         // Every later iteration issues its fill loads first, then kStores stores: "the loads issued
         // behind the previous barrier have landed" is then vmcnt <= kStores, however many they were.
         // fill_next(): the iteration behind the barrier of step t wants everything through step t + 2
@@ -1037,12 +1060,14 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
         for (int t = 2; t < nsteps; ++t) {
             wait_vmem_and_lds<kStores>();
             wg_barrier();  // step t-1 is staged; the rows under step t+1 are complete
+            TL_STEP(wave == 4, 1, 8 + t);
             fill_next();   // wants step t + 2; step t may still have operand reads in flight: its rows stay
             store_step(t - 1, true);
         }
         wg_barrier();  // the last step is staged
         store_step(nsteps - 1, nsteps > 0);
         wait_vmem_and_lds<0>();
+        TL_END(wave == 4, 1);
     }
 }
 
@@ -1362,9 +1387,11 @@ static WsplitPlan plan_wsplit(int64_t N, int64_t P, int64_t Q, int64_t R, int64_
     if (K % 64 != 0 || Q < 32) return plan;
     const int64_t nslab = K / 64, Mpix = N * P * Q;
     const int row_chunks = (int)((9 * Q + 32 + 7) / 8 * 8);
-    const int ring_rows = (int)std::min<int64_t>((160 * 1024 - kWsStageBytes) / (row_chunks * 16), kWsMaxRows);
+    // a fill load is 64 chunks of the linear patch and must not straddle the ring's end: the ring is a
+    // whole number of loads, i.e. (row_chunks being a multiple of 8) 8 rows, or 16 where they fit
+    const int ring_rows = (160 * 1024 - kWsStageBytes) / (row_chunks * 16) >= 16 ? 16 : 8;
     const size_t lds = (size_t)kWsStageBytes + (size_t)ring_rows * row_chunks * 16;
-    if (ring_rows < kWsMinRows || row_chunks < 256) return plan;
+    if (lds > 160 * 1024 || row_chunks < 256 || (ring_rows * row_chunks) % 64 != 0) return plan;
     for (int64_t rounds = 1; rounds <= 8 && plan.px == 0; ++rounds) {
         int64_t ranges = 256 * rounds / nslab;
         if (ranges < 1) continue;
@@ -1660,3 +1687,8 @@ extern "C" perf_status perf_conv2d_variant(const void *x, const void *w, void *y
     if (variant == perf::kConvAuto) return PERF_ERR_UNSUPPORTED;
     return perf::conv2d_impl(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, xw_dt, y_dt, stream, variant);
 }
+
+#ifdef PERF_TIMELINE
+// diagnostic build only: the stamps of the last launches of this file's kernels
+extern "C" int perf_timeline_fetch_conv(long long *host_out) { return perf::tl_fetch(host_out); }
+#endif

@@ -10,6 +10,7 @@
 #include "mfma_tile.h"
 #include "f32mfma.h"
 #include "host_utils.h"
+#include "timeline.h"
 
 namespace perf {
 
@@ -45,6 +46,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t 
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: LDS addresses stay scalar
+    TL_BEGIN();
     const int wm = wave / WN, wn = wave % WN;
     // Batches of small matrices (fewer than 8 tiles each): workgroups are dealt round-robin to
     // the 8 XCDs in linear grid order, so the tiles of one matrix would land on different
@@ -81,7 +83,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t 
             RowMajorSrc64<BN / (8 * NW), NW> src_b(Bb + (int64_t)n0 * ldb, min(BN, N - n0), ldb, K / 64, wave, lane);
             WaveTile16<2 * TM, 2 * TN> t;
             t.clear();
+            TL_STAMP(wave == 0, 0, 2);
             mfma_mainloop_k64<TM, TN, WM, WN>(t, smem, K / 64, wave, lane, a_row0, b_row0, src_a, src_b);
+            TL_STAMP(wave == 0, 0, 3);
             if constexpr (sizeof(CT) == 2) {
                 // bf16 C: through LDS, so that the stores are 16 bytes per lane in whole rows
                 wg_barrier();  // every wave has left the main loop and its loads have landed: LDS is free
@@ -93,6 +97,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const uint16_t 
             } else {
                 store_tile16<2 * TM, 2 * TN, CT>(t, Cb, ldc, M, N, m0 + a_row0, n0 + b_row0, alpha, lane);
             }
+            TL_STAMP(wave == 0, 0, 4);
+            TL_DRAIN();
+            TL_END(wave == 0, 0);
         } else {
             RowMajorSrc<Shape::kLoadsA, NW> src_a(Ab + (int64_t)m0 * lda, min(BM, M - m0), lda, ktiles, wave, lane);
             RowMajorSrc<Shape::kLoadsB, NW> src_b(Bb + (int64_t)n0 * ldb, min(BN, N - n0), ldb, ktiles, wave, lane);
@@ -264,3 +271,8 @@ extern "C" perf_status perf_gemm_variant(const void *A, const void *B, void *C, 
     return perf::gemm_impl(A, B, C, M, N, K, la, lda, lb, ldb, ldc, batch, strideA, strideB, strideC, alpha, ab_dt, c_dt,
                            stream, tile, kstep);
 }
+
+#ifdef PERF_TIMELINE
+// diagnostic build only: the stamps of the last launches of this file's kernels
+extern "C" int perf_timeline_fetch_gemm(long long *host_out) { return perf::tl_fetch(host_out); }
+#endif

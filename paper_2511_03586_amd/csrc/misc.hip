@@ -2,6 +2,7 @@
 // figures: a streaming copy (HBM) and a register-only MFMA loop (matrix cores).
 #include "device_utils.h"
 #include "host_utils.h"
+#include <type_traits>
 
 namespace perf {
 
@@ -166,6 +167,72 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ sin
     if (lane == 0) sink[blockIdx.x * 4 + (threadIdx.x >> 6)] = s;
 }
 
+// LDS read probes (256 workgroups, one per CU; every wave reads conflict-free, lane l at 16 l or, for
+// the operand pattern, pixel l % 32 at a pitch of 144 bytes plus 16 (l / 32) bytes):
+//   MFMA = false: 16 reads of BYTES per lane in flight, then all consumed; cycles of the slowest wave
+//                 of workgroup 0 for iters * 16 reads, from which the caller derives bytes per clock and CU.
+//   MFMA = true:  the convolution kernels' inner pattern, one v_mfma_f32_32x32x16_bf16 and one
+//                 ds_read_b128 of the operand needed nine MFMAs later, 36 per iteration; cycles of
+//                 the slowest wave for iters * 36 MFMAs (32 each is the matrix core's own time).
+template <int BYTES, bool MFMA>
+__global__ __launch_bounds__(1024) void lds_probe_kernel(long long *__restrict__ cycles, float *__restrict__ sink, int64_t iters)
+{
+    __shared__ __attribute__((aligned(1024))) char smem[65536];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = threadIdx.x; i < 65536 / 4; i += blockDim.x) reinterpret_cast<float *>(smem)[i] = 0.f;
+    __syncthreads();
+    float keep = 0.f;
+    long long c0 = 0, c1 = 0;
+    if constexpr (MFMA) {
+        typedef const __attribute__((address_space(3))) bf16x8_t lds_frag_t;
+        typedef const __attribute__((address_space(3))) char lds_char_t;
+        lds_char_t *base = (lds_char_t *)smem;
+        const uint32_t addr = (uint32_t)((wave & 3) * 8192 + (lane & 31) * 144 + (lane >> 5) * 16);
+        bf16x8_t wgt, af[9];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) wgt[e] = (__bf16)1.0f;
+#pragma unroll
+        for (int i = 0; i < 9; ++i) {
+            af[i] = *(lds_frag_t *)(base + addr + i * 32);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        float16_t acc;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+        c0 = __builtin_readcyclecounter();
+        for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int kk = 0; kk < 36; ++kk) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wgt, af[kk % 9], acc, 0, 0, 0);
+                af[kk % 9] = *(lds_frag_t *)(base + addr + ((kk + 9) % 16) * 32);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        c1 = __builtin_readcyclecounter();
+#pragma unroll
+        for (int e = 0; e < 16; ++e) keep += acc[e];
+    } else {
+        typedef float vecn_t __attribute__((ext_vector_type(BYTES == 4 ? 2 : BYTES / 4)));
+        using vec_t = std::conditional_t<BYTES == 4, float, vecn_t>;
+        const char *base = smem + (wave & 3) * 16384 + lane * BYTES;
+        c0 = __builtin_readcyclecounter();
+        for (int64_t it = 0; it < iters; ++it) {
+            vec_t v[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) v[k] = *reinterpret_cast<const vec_t *>(base + k * 64 * BYTES);
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                asm volatile("" : "+v"(v[k]));
+                if constexpr (BYTES == 4) keep += v[k];
+                else keep += v[k][0];
+            }
+        }
+        c1 = __builtin_readcyclecounter();
+    }
+    if (blockIdx.x == 0 && lane == 0) atomicMax(reinterpret_cast<unsigned long long *>(cycles), (unsigned long long)(c1 - c0));
+    if (keep == 12345.678f) sink[0] = keep;  // (never true: the reads stay live)
+}
+
 }  // namespace perf
 
 static perf_status mfma_probe(float *sink, int64_t iters, bool random, perf_stream stream)
@@ -187,6 +254,25 @@ extern "C" perf_status perf_mfma_probe(float *sink, int64_t iters, perf_stream s
 extern "C" perf_status perf_mfma_probe_random(float *sink, int64_t iters, perf_stream stream)
 {
     return mfma_probe(sink, iters, true, stream);
+}
+
+extern "C" perf_status perf_lds_probe(long long *cycles, float *sink, int waves, int bytes_per_lane, int with_mfma,
+                                      int64_t iters, perf_stream stream)
+{
+    using namespace perf;
+    if (!cycles || !sink) return PERF_ERR_NULL;
+    if ((waves != 4 && waves != 8 && waves != 16) || (bytes_per_lane != 4 && bytes_per_lane != 8 && bytes_per_lane != 16) ||
+        iters < 1 || iters > (int64_t(1) << 24))
+        return PERF_ERR_SHAPE;
+    if (with_mfma && bytes_per_lane != 16) return PERF_ERR_UNSUPPORTED;
+    if (!aligned(cycles, 8) || !aligned(sink, 4)) return PERF_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const dim3 grid(256), block(64 * waves);
+    if (with_mfma) hipLaunchKernelGGL((lds_probe_kernel<16, true>), grid, block, 0, st, cycles, sink, iters);
+    else if (bytes_per_lane == 16) hipLaunchKernelGGL((lds_probe_kernel<16, false>), grid, block, 0, st, cycles, sink, iters);
+    else if (bytes_per_lane == 8) hipLaunchKernelGGL((lds_probe_kernel<8, false>), grid, block, 0, st, cycles, sink, iters);
+    else hipLaunchKernelGGL((lds_probe_kernel<4, false>), grid, block, 0, st, cycles, sink, iters);
+    return launch_status();
 }
 
 extern "C" perf_status perf_copy(const void *src, void *dst, int64_t bytes, perf_stream stream)

@@ -112,6 +112,12 @@ def test_mfma_probe_argument_errors():
     assert perf.perf_mfma_probe(FAKE, 0, check=False) == perf.PERF_ERR_SHAPE
     assert perf.perf_mfma_probe(FAKE, (1 << 24) + 1, check=False) == perf.PERF_ERR_SHAPE
     assert perf.perf_mfma_probe(FAKE + 2, 1, check=False) == perf.PERF_ERR_ALIGN
+    assert perf.perf_lds_probe(None, FAKE, 4, 16, 0, 1, check=False) == perf.PERF_ERR_NULL
+    assert perf.perf_lds_probe(FAKE, FAKE, 5, 16, 0, 1, check=False) == perf.PERF_ERR_SHAPE
+    assert perf.perf_lds_probe(FAKE, FAKE, 4, 12, 0, 1, check=False) == perf.PERF_ERR_SHAPE
+    assert perf.perf_lds_probe(FAKE, FAKE, 4, 16, 0, 0, check=False) == perf.PERF_ERR_SHAPE
+    assert perf.perf_lds_probe(FAKE, FAKE, 4, 8, 1, 1, check=False) == perf.PERF_ERR_UNSUPPORTED
+    assert perf.perf_lds_probe(FAKE + 4, FAKE, 4, 16, 0, 1, check=False) == perf.PERF_ERR_ALIGN
     assert perf.perf_mfma_probe_random(None, 1, check=False) == perf.PERF_ERR_NULL
     assert perf.perf_mfma_probe_random(FAKE, 0, check=False) == perf.PERF_ERR_SHAPE
     assert perf.perf_mfma_probe_random(FAKE + 2, 1, check=False) == perf.PERF_ERR_ALIGN

@@ -84,11 +84,13 @@ def test_input_resident_kernel_refuses_what_it_cannot_run():
 
 
 @pytest.mark.parametrize("kw", [dict(N=2), dict(N=8, K=64), dict(N=2, K=64), dict(N=4, K=256), dict(N=4, H=40, W=40),
-                                dict(N=1, K=64), dict(N=8, H=28, W=32), dict(N=4, H=58, W=58, pad=0), dict(N=2, H=16, W=72)])
+                                dict(N=1, K=64), dict(N=8, H=28, W=32), dict(N=4, H=58, W=58, pad=0), dict(N=2, H=16, W=72),
+                                dict(N=8, K=256), dict(N=4, K=512), dict(N=32, H=24, W=32, K=512)])
 @pytest.mark.parametrize("y_bf16", [True, False])
 def test_channel_slab_kernel(kw, y_bf16):
-    # 1, 2 and 4 slabs of 64 output channels; ranges that start anywhere in a row and span 2 .. 7 rows
-    # of the 8-row ring (so the ring wraps inside a range); one-step and odd-step ranges, ragged last
+    # 1, 2, 4 and 8 slabs of 64 output channels; ranges that start anywhere in a row; ranges of 392 pixels
+    # whose 10 or 11 input rows pass through the 8-row ring (its slots are reused inside a range) and of
+    # 768 pixels (a whole image, 26 rows) through the 16-row ring of a narrow image; one-step and odd-step ranges, ragged last
     # blocks, no padding, the narrowest and widest rows the ring takes
     import paper_2511_03586_amd as perf
     _check(configs.ConvWorkload(**kw), y_bf16=y_bf16, variant=perf.CONV_WSPLIT)

@@ -231,6 +231,29 @@ def test_stream_probe_copies_and_fills():
     assert bool((v[:, 1] == 1).all()) and bool((v[:, 2] == 2).all()) and not bool(dst[n:].any())
 
 
+def test_lds_probe_reports_plausible_rates():
+    """The LDS probes behind the convolution analysis: the loop runs, the cycle count is written, and
+    the rates lie where the hardware allows (one CU: at most 64 banks x 4 bytes x 2 per clock; one MFMA
+    32x32x16 takes 32 cycles, so the MFMA + read pattern cannot cost less)."""
+    import torch
+    cyc = torch.zeros(1, dtype=torch.int64, device="cuda")
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    iters = 500
+    for waves, nbytes in ((4, 16), (8, 16), (16, 16), (8, 8), (16, 4)):
+        cyc.zero_()
+        perf.perf_lds_probe(cyc.data_ptr(), sink.data_ptr(), waves, nbytes, 0, iters, G.stream())
+        torch.cuda.synchronize()
+        rate = waves * iters * 16 * 64 * nbytes / int(cyc.item())
+        assert 16.0 < rate <= 512.0, (waves, nbytes, rate)
+    for waves in (4, 8):
+        cyc.zero_()
+        perf.perf_lds_probe(cyc.data_ptr(), sink.data_ptr(), waves, 16, 1, iters, G.stream())
+        torch.cuda.synchronize()
+        per_mfma = int(cyc.item()) / (iters * 36)
+        assert 31.0 < per_mfma < 80.0, (waves, per_mfma)
+    assert float(sink.item()) == 0.0
+
+
 def test_copy_any_alignment_and_size():
     """perf_copy (the measured HBM ceiling) must copy bit for bit whatever the alignment of either
     pointer; misaligned cases run grid-wide kernels too (64 MiB in well under a second)."""
