@@ -688,18 +688,23 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
 // ---- weights-in-registers kernel, 64 output channels per workgroup ---------------------
 // The same division of labour once more, with the work cut the other way: a workgroup owns a
 // slab of 64 output channels and a pixel range twice as long (K / 64 workgroups share a range).
-// It takes in 72 KiB of weights instead of 144, so all of them are in flight at once, and the
-// first blocks are computed tap by tap as the taps arrive; the price is that every input row
-// is fetched by K / 64 workgroups (from the L2 they share: they sit on one XCD).
+// It takes in 72 KiB of weights instead of 144, all of them in flight at once and staged in LDS in
+// one piece (the 128-channel kernels take theirs in two dependent halves); the price is that every
+// input row is fetched by K / 64 workgroups (from the L2 they share: they sit on one XCD).
 //   * MFMA wave w holds the weights of channel group w & 1 (32 channels) and computes the pixel
 //     blocks of parity w >> 1: in step t the four waves work on blocks 2t and 2t+1, 64 pixels.
 //     An operand read serves 32 channels of one wave, so per pixel the LDS carries half the reads
 //     of the 128-channel kernels.
 //   * The input rows under a range do not fit the LDS any more; they pass through a ring of kNR
 //     rows, filled in linear order by the memory waves one step ahead of their use.
-//   * Barriers: one when the first rows are there, one per filter tap while the weights arrive
-//     (a tap's loads are split between the two waves that need it), one at the end of that phase,
-//     one after its first results are staged, then one per step, and a last one.
+//   * The MFMA waves issue their weight loads first (a tap's loads are split between the two waves
+//     that need it), then a share of the first rows, and wait for all of them before the first
+//     barrier: behind it every weight is in LDS, and the first two steps run tap-major, reading each
+//     tap's weights into registers just ahead of its MFMAs.  (Starting the taps one by one as they
+//     land, with a barrier per tap, measured 2.4K cycles slower: every barrier also waited for the
+//     memory waves, which were busy issuing the next rows into a saturated memory pipeline.)
+//   * Barriers: one when the first rows and the weights are there, one at the end of the first two
+//     steps, one after their first results are staged, then one per step, and a last one.
 struct WsplitPlan {
     int px = 0;          // pixels per range (a divisor of P*Q); 0: the shape does not fit
     int ranges = 0;      // pixel ranges (workgroups = ranges * K / 64)
@@ -750,6 +755,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
     constexpr int kStores = 16 * kRowLanes / 64;            // store instructions per memory wave and step (16 pixel rows)
     constexpr int kWin = 9, kBar = KSUB - kWin;
     static_assert(C == 64 && KSUB % kWin == 0 && 4 * kOutBytes <= kWsStageBytes, "layout assumptions");
+    static_assert(13 + R <= kBar, "the next step's row addresses are ready before the window reads them");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     char *const out_stage = smem;                  // (the weight staging is free after the tap phase)
     char *const ring = smem + kWsStageBytes;
@@ -766,7 +772,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
     const int n0 = start / (g.P * g.Q), pq0 = start - n0 * (g.P * g.Q);
     const int oh0 = pq0 / g.Q, q0 = pq0 - oh0 * g.Q;
     const uint32_t row_pitch = (uint32_t)(row_chunks * 16);
-    // Both kinds of wave execute 1 + kTaps + 1 + (nsteps >= 2) + max(nsteps - 2, 0) + 1 barriers.
+    // Both kinds of wave execute 1 + 1 + (nsteps >= 2) + max(nsteps - 2, 0) + 1 barriers.
     TL_BEGIN();
 
     // Ring fill: wave load idx (64 chunks of the linear patch) -> ring; a wave takes every `stride`-th.
@@ -796,10 +802,13 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
         ring_off += 1024 * fill_stride;
         ring_off = ring_off >= ring_bytes ? ring_off - ring_bytes : ring_off;
     };
-    // the rows under steps 0 and 1, issued by all eight waves (the MFMA waves have nothing else to do yet)
+    // the rows under steps 0 and 1 are issued by all eight waves, every eighth load each (the MFMA
+    // waves behind their weight loads, whose first-touch latency then overlaps the rows')
     const int cap0 = ring_rows * row_chunks, want1 = fs.wanted(1);
-    fill_from(wave, 8);
-    while (fs.fires(next_load, want1, cap0)) fire();
+    if (wave >= 4) {
+        fill_from(wave, 8);
+        while (fs.fires(next_load, want1, cap0)) fire();
+    }
 
     if (wave < 4) {
         // ------------------------------ MFMA waves ------------------------------
@@ -829,6 +838,8 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
                         16, vo, t * (C * 2), 0, 0);
                 }
         }
+        fill_from(wave, 8);
+        while (fs.fires(next_load, want1, cap0)) fire();
         uint32_t wrd[kPerTap];
 #pragma unroll
         for (int j = 0; j < kPerTap; ++j)
@@ -877,11 +888,11 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
 #pragma unroll
         for (int e = 0; e < 16; ++e) accs[0][e] = accs[1][e] = 0.f;
 
-        wait_vmem<2 * kTaps>();  // own part of the first rows has landed (only the weight loads are younger)
+        wait_vmem<0>();  // own weight loads and own part of the first rows have landed
         TL_STAMP(wave == 0, 0, 2);
-        wg_barrier();            // the rows under steps 0 and 1 are complete
+        wg_barrier();    // the weights and the rows under steps 0 and 1 are complete
         TL_STAMP(wave == 0, 0, 3);
-        // steps 0 and 1 (step 0 alone if there is no other), tap by tap as the weights arrive
+        // steps 0 and 1 (step 0 alone if there is no other), tap-major: a tap's weights are read just ahead of its MFMAs
         auto tap_phase = [&](auto nbc) {
             constexpr int NB = decltype(nbc)::value, TOT = KSUB * NB;
             auto frag_at = [&](int p) {  // position p of the MFMA sequence: (tap, step, k-substep)
@@ -890,11 +901,9 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
             };
 #pragma unroll
             for (int p = 0; p < kWin; ++p) af[p] = frag_at(p);
-            // the wait for tap t+1 and the reads of its fragments sit in front of tap t's MFMAs
+            // the reads of tap t+1's fragments sit in front of tap t's MFMAs
             auto take_tap = [&](auto tc) {
                 constexpr int t = decltype(tc)::value;
-                wait_vmem<2 * (kTaps - 1 - t)>();  // own loads of tap t have landed
-                wg_barrier();                      // ... and the other parity's
                 if constexpr (t == 0) TL_STAMP(wave == 0, 0, 4);
 #pragma unroll
                 for (int j = 0; j < kPerTap; ++j) wf[t * kPerTap + j] = *(lds_frag_t *)(lds0 + wrd[j] + t * kTapBytes);
@@ -942,14 +951,23 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
                 if (t >= nsteps) break;
                 float16_t &acc = accs[h];
                 float16_t &prev = accs[h ^ 1];
-                next_step();
-                rows_of(nxt);
+                // (opaque to the optimiser: folded with the tap offsets the row addresses would turn into one
+                // register per read)
 #pragma unroll
-                for (int r = 0; r < R; ++r) asm volatile("" : "+v"(cur[r]), "+v"(nxt[r]));
+                for (int r = 0; r < R; ++r) asm volatile("" : "+v"(cur[r]));
                 TL_STEP(wave == 0, 0, 8 + t);
                 char *stg = out_stage + (((t - 1) & 1) * 2 + par) * kOutBytes + stage_wr;
 #pragma unroll
                 for (int kk = 0; kk < KSUB; ++kk) {
+                    // the next step's row addresses, computed in the shadow of MFMAs well before their first use
+                    if (kk == 12) next_step();
+                    if (kk >= 13 && kk < 13 + R) {
+                        const int r = kk - 13;
+                        int sl = slot + r;
+                        sl = sl >= ring_rows ? sl - ring_rows : sl;
+                        nxt[r] = lane_base + (uint32_t)sl * row_pitch + (uint32_t)(ow * kPix);
+                        asm volatile("" : "+v"(nxt[r]));
+                    }
                     if (kk == kBar) {
                         __builtin_amdgcn_s_waitcnt(0xC07F | (kWin << 8));
                         wg_barrier();
@@ -1010,10 +1028,8 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
             const int want2 = fs.wanted(2);
             while (fs.fires(next_load, want2, cap0)) fire();
         }
-#pragma unroll
-        for (int t = 0; t < kTaps; ++t) wg_barrier();  // (the MFMA waves' tap phase)
         wait_vmem_and_lds<0>();
-        wg_barrier();  // end of the tap phase: the rows under step 2 are complete; steps 0 and 1 no longer read the ring
+        wg_barrier();  // end of the first two steps: the rows under step 2 are complete; steps 0 and 1 no longer read the ring
         TL_STAMP(wave == 4, 1, 5);
         // Every later iteration issues its fill loads first, then kStores stores: "the loads issued
         // behind the previous barrier have landed" is then vmcnt <= kStores, however many they were.
