@@ -710,32 +710,34 @@ struct WsplitPlan {
     int ranges = 0;      // pixel ranges (workgroups = ranges * K / 64)
     int patch_rows = 0;  // input rows under the longest range
     int row_chunks = 0;  // 16-byte chunks per ring row
-    int ring_rows = 0;   // rows of the ring: 8, or 16 where the LDS holds them beside the weight staging
+    int ring_rows = 0;   // rows of the ring: as many as the LDS holds beside the weight staging, 16 at most
     int rounds = 0;
     size_t lds = 0;
 };
 constexpr int kWsFill = 5;      // fill loads per memory wave and step
 constexpr int kWsStageBytes = 64 * 9 * 64 * 2;  // weight staging: 64 channels x 576 values
+constexpr int kWsGroup = 7;     // patch pixels per fill load: 7 x 9 chunks of 16 bytes (+ 1 of the next pixel)
 
-// Fill schedule shared by the kernel and the host's check of it.  Chunk index L of the linear
-// patch = row L / row_chunks (row v holds input row oh0 - pad_h + v), chunk L % row_chunks; wave
-// load idx covers chunks 64 idx .. 64 idx + 63 and lands at ring offset (1024 idx) mod ring bytes.
+// Fill schedule shared by the kernel and the host's check of it.  A patch row (row v holds input
+// row oh0 - pad_h + v, W + 2 pad_w pixels) is fetched in groups of kWsGroup pixels, one load each:
+// a lane's pixel within the group and its chunk within the pixel never change, so a load costs the
+// memory waves a dozen instructions (they are the critical path of a step: with loads of 64
+// consecutive chunks, whose lanes had to divide their position out every time, a step took 1.65K
+// cycles against 1.48K without any fill).  Load idx = row idx / groups, group idx % groups; it
+// lands in ring row (idx / groups) % ring_rows at pixel kWsGroup * group.
 struct WsplitFill {
-    int Q, R, patch_rows, row_chunks, ring_rows, q0;
+    int Q, R, patch_rows, groups, ring_rows, q0;
     // rows that hold everything the range's pixels 0 .. px_last need
     __host__ __device__ int rows_through(int px_last) const
     {
         const int r = (q0 + px_last) / Q + R;
         return r < patch_rows ? r : patch_rows;
     }
-    // chunks wanted once everything through step `t` is to be there; chunks that may be written
+    // loads wanted once everything through step `t` is to be there; loads that may be issued
     // while step `t_busy` is the oldest one still reading the ring
-    __host__ __device__ int wanted(int t) const { return rows_through(64 * t + 63) * row_chunks; }
-    __host__ __device__ int writable(int t_busy) const { return ((q0 + 64 * t_busy) / Q + ring_rows) * row_chunks; }
-    __host__ __device__ bool fires(int idx, int want, int cap) const
-    {
-        return idx * 64 < want && (idx + 1) * 64 <= cap && idx * 64 < patch_rows * row_chunks;
-    }
+    __host__ __device__ int wanted(int t) const { return rows_through(64 * t + 63) * groups; }
+    __host__ __device__ int writable(int t_busy) const { return ((q0 + 64 * t_busy) / Q + ring_rows) * groups; }
+    __host__ __device__ bool fires(int idx, int want, int cap) const { return idx < want && idx < cap && idx < patch_rows * groups; }
 };
 
 template <int R, int S, int C, typename CT>
@@ -759,7 +761,6 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     char *const out_stage = smem;                  // (the weight staging is free after the tap phase)
     char *const ring = smem + kWsStageBytes;
-    const int ring_bytes = ring_rows * row_chunks * 16;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -775,36 +776,47 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
     // Both kinds of wave execute 1 + 1 + (nsteps >= 2) + max(nsteps - 2, 0) + 1 barriers.
     TL_BEGIN();
 
-    // Ring fill: wave load idx (64 chunks of the linear patch) -> ring; a wave takes every `stride`-th.
+    // Ring fill: load idx = (patch row, pixel group); a wave takes every `stride`-th.  Per lane: pixel
+    // lane / 9 of the group, chunk lane % 9 of the pixel (the ninth is padding: zeros); per load,
+    // scalars only.  Lane 63 fetches chunk 0 of the pixel behind the group, the same value that the
+    // next group's lane 0 writes there, and the row's last group starts 7 pixels before the row's end
+    // (overlapping its neighbour, again with identical values), so every lane of every load writes
+    // inside its own ring row whatever the order in which the loads land.
     const rsrc_t xr = make_rsrc(x, (uint32_t)((int64_t)g.N * g.H * g.W * g.C * 2));
-    const WsplitFill fs{g.Q, R, patch_rows, row_chunks, ring_rows, q0};
-    int rem, vrow, next_load, ring_off, fill_stride;  // this lane's chunk `rem` of patch row `vrow` of the wave's next load
-    auto fill_from = [&](int idx, int stride) {        // (one division per phase, none per load)
-        const int L = idx * 64 + lane;
-        vrow = L / row_chunks;
-        rem = L - vrow * row_chunks;
+    const int Wv = g.W + 2 * g.pw, groups = (Wv + kWsGroup - 1) / kWsGroup;
+    const WsplitFill fs{g.Q, R, patch_rows, groups, ring_rows, q0};
+    const int lane_px = lane / kChunks, lane_ch = lane - lane_px * kChunks;
+    const uint32_t lane_off = (uint32_t)(lane_px * (C * 2) + lane_ch * 16);
+    int next_load, fill_row, fill_grp, fill_slot, fill_stride;  // the wave's next load: patch row, group, ring row
+    auto fill_from = [&](int idx, int stride) {  // (one division per phase, none per load)
         next_load = idx;
-        ring_off = (int)(((int64_t)idx * 1024) % ring_bytes);
+        fill_row = idx / groups;
+        fill_grp = idx - fill_row * groups;
+        fill_slot = fill_row % ring_rows;
         fill_stride = stride;
     };
     auto fire = [&]() {
-        const int vcol = rem / kChunks, ch = rem - vcol * kChunks;
-        const int ih = oh0 - g.ph + vrow, iw = vcol - g.pw;
-        const bool ok = ch < kChunks - 1 && vrow < patch_rows && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
-        const uint32_t vo = ok ? (uint32_t)(((n0 * g.H + ih) * g.W + iw) * C + ch * 8) * 2u : kOutOfRange;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void *)(ring + ring_off), 16, vo, 0, 0, 0);
-        rem += 64 * fill_stride;
-        while (rem >= row_chunks) {  // (row_chunks >= 256: twice at most)
-            rem -= row_chunks;
-            ++vrow;
-        }
+        const int ih = oh0 - g.ph + fill_row, px0 = min(fill_grp * kWsGroup, Wv - kWsGroup);
+        // columns of the image this row offers: none if the row lies above or below it (zeros are written)
+        const uint32_t cols = (unsigned)ih < (unsigned)g.H ? (uint32_t)g.W : 0u;
+        const uint32_t row_byte = (uint32_t)((n0 * g.H + ih) * g.W + px0 - g.pw) * (uint32_t)(C * 2);  // (wraps for unused rows)
+        const uint32_t iw = (uint32_t)(px0 - g.pw + lane_px);
+        const uint32_t vo = (lane_ch < kChunks - 1 && iw < cols) ? row_byte + lane_off : kOutOfRange;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            xr, (__attribute__((address_space(3))) void *)(ring + fill_slot * (int)row_pitch + px0 * kPix), 16, vo, 0, 0, 0);
         next_load += fill_stride;
-        ring_off += 1024 * fill_stride;
-        ring_off = ring_off >= ring_bytes ? ring_off - ring_bytes : ring_off;
+        fill_grp += fill_stride;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)  // (at least 5 groups per row, strides of 4 or 8)
+            if (fill_grp >= groups) {
+                fill_grp -= groups;
+                ++fill_row;
+                fill_slot = fill_slot + 1 == ring_rows ? 0 : fill_slot + 1;
+            }
     };
     // the rows under steps 0 and 1 are issued by all eight waves, every eighth load each (the MFMA
     // waves behind their weight loads, whose first-touch latency then overlaps the rows')
-    const int cap0 = ring_rows * row_chunks, want1 = fs.wanted(1);
+    const int cap0 = ring_rows * groups, want1 = fs.wanted(1);
     if (wave >= 4) {
         fill_from(wave, 8);
         while (fs.fires(next_load, want1, cap0)) fire();
@@ -930,15 +942,16 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
         TL_STAMP(wave == 0, 0, 5);
         if (nsteps >= 2) {
             stage_acc<CT>(accs[0], out_stage + par * kOutBytes + stage_wr);
-#pragma unroll
-            for (int e = 0; e < 16; ++e) accs[0][e] = 0.f;
             __builtin_amdgcn_s_waitcnt(0xC07F);
             wg_barrier();  // step 0 is staged
         }
         next_step();
         rows_of(cur);
 #pragma unroll
-        for (int kk = 0; kk < kWin; ++kk) af[kk] = read_frag(cur, kk);
+        for (int kk = 0; kk < kWin; ++kk) {
+            af[kk] = read_frag(cur, kk);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 
         // One step: `acc` collects this wave's block of step t, `prev` holds that of step t-1, which
         // is converted and staged in the shadow of the first MFMAs, then cleared for step t+1.  The
@@ -972,7 +985,14 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
                         __builtin_amdgcn_s_waitcnt(0xC07F | (kWin << 8));
                         wg_barrier();
                     }
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
+                    if (kk == 0) {
+                        float16_t zero;
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) zero[e] = 0.f;
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], zero, 0, 0, 0);
+                    } else {
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
+                    }
                     af[kk % kWin] = kk + kWin < KSUB ? read_frag(cur, kk + kWin) : read_frag(nxt, kk + kWin - KSUB);
                     if (kk >= 1 && kk < 5) {
                         const int a = kk - 1;
@@ -983,10 +1003,6 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
                             *reinterpret_cast<uint2_t *>(stg + 8 * a * 2) =
                                 uint2_t{pack_bf16(prev[4 * a], prev[4 * a + 1]), pack_bf16(prev[4 * a + 2], prev[4 * a + 3])};
                         }
-                    }
-                    if (kk >= 6 && kk < 10) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) prev[4 * (kk - 6) + e] = 0.f;
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -1023,7 +1039,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
         wg_barrier();  // the rows under steps 0 and 1 are complete
         TL_STAMP(wave == 4, 1, 4);
         // from here on the four memory waves share the fill: first the rows under step 2
-        fill_from((want1 + 63) / 64 + mw, 4);
+        fill_from(want1 + mw, 4);
         {
             const int want2 = fs.wanted(2);
             while (fs.fires(next_load, want2, cap0)) fire();
@@ -1048,7 +1064,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
         bool first_fill = true;
         auto fill_next = [&]() {
             const int rows = want_row + R < patch_rows ? want_row + R : patch_rows;
-            const int want = rows * row_chunks, cap = (busy_row + ring_rows) * row_chunks;
+            const int want = rows * groups, cap = (busy_row + ring_rows) * groups;
             for (int i = 0; i < kWsFill && fs.fires(next_load, want, cap); ++i) fire();
             want_col += 64;
 #pragma unroll
@@ -1402,12 +1418,11 @@ static WsplitPlan plan_wsplit(int64_t N, int64_t P, int64_t Q, int64_t R, int64_
     WsplitPlan plan;
     if (K % 64 != 0 || Q < 32) return plan;
     const int64_t nslab = K / 64, Mpix = N * P * Q;
-    const int row_chunks = (int)((9 * Q + 32 + 7) / 8 * 8);
-    // a fill load is 64 chunks of the linear patch and must not straddle the ring's end: the ring is a
-    // whole number of loads, i.e. (row_chunks being a multiple of 8) 8 rows, or 16 where they fit
-    const int ring_rows = (160 * 1024 - kWsStageBytes) / (row_chunks * 16) >= 16 ? 16 : 8;
+    const int row_chunks = (int)(9 * Q + 32);  // (the 128-channel kernel's pitch: a lane that wraps to the next row keeps its bank slot)
+    const int groups = (int)((Q + 2 + kWsGroup - 1) / kWsGroup);  // Q + 2 = W + 2 pad_w patch pixels per row
+    const int ring_rows = (int)std::min<int64_t>((160 * 1024 - kWsStageBytes) / (row_chunks * 16), 16);
     const size_t lds = (size_t)kWsStageBytes + (size_t)ring_rows * row_chunks * 16;
-    if (lds > 160 * 1024 || row_chunks < 256 || (ring_rows * row_chunks) % 64 != 0) return plan;
+    if (ring_rows < 5 || groups < 5) return plan;
     for (int64_t rounds = 1; rounds <= 8 && plan.px == 0; ++rounds) {
         int64_t ranges = 256 * rounds / nslab;
         if (ranges < 1) continue;
@@ -1419,26 +1434,25 @@ static WsplitPlan plan_wsplit(int64_t N, int64_t P, int64_t Q, int64_t R, int64_
         const int64_t rows = (q0max + nsteps * 64 - 1) / Q + R;
         bool ok = true;
         for (int64_t q0 = 0; q0 <= q0max && ok; ++q0) {
-            const WsplitFill fs{(int)Q, (int)R, (int)rows, row_chunks, ring_rows, (int)q0};
-            const int cap0 = ring_rows * row_chunks;
+            const WsplitFill fs{(int)Q, (int)R, (int)rows, groups, ring_rows, (int)q0};
+            const int cap0 = ring_rows * groups;
             // the kernel's first phase: all eight waves, wave v takes loads v, v + 8, ... below wanted(1);
             // the four memory waves then go on from the first load beyond it, every fourth each
-            const int want1 = fs.wanted(1), first = (want1 + 63) / 64;
-            for (int idx = 0; idx < first && ok; ++idx)
-                ok = fs.fires(idx, want1, cap0) || idx * 64 >= (int)rows * row_chunks;  // (issued, or past the patch)
+            const int first = fs.wanted(1);
+            ok = first <= cap0;
             int next[4] = {first, first + 1, first + 2, first + 3};
             auto run = [&](int want, int cap, int per_wave) {  // one fill iteration of the four memory waves
                 for (int mw = 0; mw < 4; ++mw)
                     for (int i = 0; i < per_wave && fs.fires(next[mw], want, cap); ++i) next[mw] += 4;
             };
-            auto covered = [&](int chunks) {  // every load that holds a chunk below `chunks` has been issued
-                const int loads = (std::min(chunks, (int)rows * row_chunks) + 63) / 64;
+            auto covered = [&](int want) {  // every load below `want` has been issued
+                const int loads = std::min(want, (int)rows * groups);
                 for (int mw = 0; mw < 4; ++mw)
                     if (next[mw] < loads) return false;  // (next[mw]: the first load of wave mw not yet issued)
                 return true;
             };
             run(fs.wanted(2), cap0, 1 << 20);
-            ok = ok && covered(fs.wanted(std::min<int64_t>(2, nsteps - 1)));  // at the end of the tap phase
+            ok = ok && covered(fs.wanted((int)std::min<int64_t>(2, nsteps - 1)));  // at the end of the first two steps
             if (nsteps >= 2) run(fs.wanted(3), fs.writable(2), kWsFill);
             for (int64_t t = 2; t < nsteps && ok; ++t) {
                 ok = covered(fs.wanted((int)std::min<int64_t>(t + 1, nsteps - 1)));  // at the barrier of step t
