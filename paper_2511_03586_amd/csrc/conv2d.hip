@@ -787,39 +787,49 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
     const WsplitFill fs{g.Q, R, patch_rows, groups, ring_rows, q0};
     const int lane_px = lane / kChunks, lane_ch = lane - lane_px * kChunks;
     const uint32_t lane_off = (uint32_t)(lane_px * (C * 2) + lane_ch * 16);
-    int next_load, fill_row, fill_grp, fill_slot, fill_stride;  // the wave's next load: patch row, group, ring row
+    // the wave's next load: its index, group, input row (may lie outside the image), that row's first patch
+    // pixel as a pixel index into x (left of the image by the padding), and its ring row's byte offset
+    int next_load, fill_grp, fill_ih, fill_rowpix, fill_slot_byte, fill_stride;
+    const int ring_bytes = ring_rows * (int)row_pitch;
     auto fill_from = [&](int idx, int stride) {  // (one division per phase, none per load)
+        const int row = idx / groups;
         next_load = idx;
-        fill_row = idx / groups;
-        fill_grp = idx - fill_row * groups;
-        fill_slot = fill_row % ring_rows;
+        fill_grp = idx - row * groups;
+        fill_ih = oh0 - g.ph + row;
+        fill_rowpix = (n0 * g.H + fill_ih) * g.W - g.pw;
+        fill_slot_byte = (row % ring_rows) * (int)row_pitch;
         fill_stride = stride;
     };
-    auto fire = [&]() {
-        const int ih = oh0 - g.ph + fill_row, px0 = min(fill_grp * kWsGroup, Wv - kWsGroup);
+    // (`wraps`: how many row ends one stride can cross: rows have at least 5 groups, strides are 4 or 8)
+    auto fire = [&](auto wraps) {
+        const int px0 = min(fill_grp * kWsGroup, Wv - kWsGroup);
         // columns of the image this row offers: none if the row lies above or below it (zeros are written)
-        const uint32_t cols = (unsigned)ih < (unsigned)g.H ? (uint32_t)g.W : 0u;
-        const uint32_t row_byte = (uint32_t)((n0 * g.H + ih) * g.W + px0 - g.pw) * (uint32_t)(C * 2);  // (wraps for unused rows)
+        const uint32_t cols = (unsigned)fill_ih < (unsigned)g.H ? (uint32_t)g.W : 0u;
+        const uint32_t base = (uint32_t)(fill_rowpix + px0) * (uint32_t)(C * 2);  // (wraps for unused pixels)
         const uint32_t iw = (uint32_t)(px0 - g.pw + lane_px);
-        const uint32_t vo = (lane_ch < kChunks - 1 && iw < cols) ? row_byte + lane_off : kOutOfRange;
+        const uint32_t vo = (lane_ch < kChunks - 1 && iw < cols) ? base + lane_off : kOutOfRange;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            xr, (__attribute__((address_space(3))) void *)(ring + fill_slot * (int)row_pitch + px0 * kPix), 16, vo, 0, 0, 0);
+            xr, (__attribute__((address_space(3))) void *)(ring + fill_slot_byte + px0 * kPix), 16, vo, 0, 0, 0);
         next_load += fill_stride;
         fill_grp += fill_stride;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)  // (at least 5 groups per row, strides of 4 or 8)
+        for (int i = 0; i < decltype(wraps)::value; ++i)
             if (fill_grp >= groups) {
                 fill_grp -= groups;
-                ++fill_row;
-                fill_slot = fill_slot + 1 == ring_rows ? 0 : fill_slot + 1;
+                ++fill_ih;
+                fill_rowpix += g.W;
+                fill_slot_byte += (int)row_pitch;
+                fill_slot_byte = fill_slot_byte == ring_bytes ? 0 : fill_slot_byte;
             }
     };
+    const std::integral_constant<int, 1> one_wrap{};
+    const std::integral_constant<int, 2> two_wraps{};
     // the rows under steps 0 and 1 are issued by all eight waves, every eighth load each (the MFMA
     // waves behind their weight loads, whose first-touch latency then overlaps the rows')
     const int cap0 = ring_rows * groups, want1 = fs.wanted(1);
     if (wave >= 4) {
         fill_from(wave, 8);
-        while (fs.fires(next_load, want1, cap0)) fire();
+        while (fs.fires(next_load, want1, cap0)) fire(two_wraps);
     }
 
     if (wave < 4) {
@@ -851,7 +861,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
                 }
         }
         fill_from(wave, 8);
-        while (fs.fires(next_load, want1, cap0)) fire();
+        while (fs.fires(next_load, want1, cap0)) fire(two_wraps);
         uint32_t wrd[kPerTap];
 #pragma unroll
         for (int j = 0; j < kPerTap; ++j)
@@ -1042,7 +1052,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
         fill_from(want1 + mw, 4);
         {
             const int want2 = fs.wanted(2);
-            while (fs.fires(next_load, want2, cap0)) fire();
+            while (fs.fires(next_load, want2, cap0)) fire(one_wrap);
         }
         wait_vmem_and_lds<0>();
         wg_barrier();  // end of the first two steps: the rows under step 2 are complete; steps 0 and 1 no longer read the ring
@@ -1065,7 +1075,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
         auto fill_next = [&]() {
             const int rows = want_row + R < patch_rows ? want_row + R : patch_rows;
             const int want = rows * groups, cap = (busy_row + ring_rows) * groups;
-            for (int i = 0; i < kWsFill && fs.fires(next_load, want, cap); ++i) fire();
+            for (int i = 0; i < kWsFill && fs.fires(next_load, want, cap); ++i) fire(one_wrap);
             want_col += 64;
 #pragma unroll
             for (int i = 0; i < 2; ++i)
