@@ -1646,11 +1646,13 @@ static perf_status conv2d_impl(const void *x, const void *w, void *y, int64_t N,
     if (variant == kConvAuto)
         // (the channel-blocked kernel has one thread per pixel: below ~64 workgroups of pixels the
         // thread-per-output kernel has more parallelism and measured faster)
-        // (every workgroup of the input-resident kernel pays the weight prologue: measured ahead of the ring
-        // kernel with one or two rounds of workgroups, 65 us against 63 with four, 128x56x56)
-        variant = (wres_ok && wres_rounds <= 2) ? kConvWres
+        // (the 64-channel-slab kernel measured ahead of both 128-channel kernels wherever all of them run:
+        // 12.3 us against 12.9 on 32x56x56 64 -> 128 with zero operands, 15.4 against 15.8 with random ones,
+        // 27.4 against 29.1 on 64x56x56; of those two, the input-resident one pays the weight prologue per
+        // workgroup and is ahead of the ring kernel with one or two rounds of workgroups only)
+        variant = wsplit_ok                     ? kConvWsplit
+                  : (wres_ok && wres_rounds <= 2) ? kConvWres
                   : wreg_ok                     ? kConvWreg
-                  : wsplit_ok                   ? kConvWsplit  // (other multiples of 64 output channels: 10.8 us against 22.2, 32x56x56 64->64)
                   : mfma_ok ? kConvMfma
                   : (f32mfma_ok && (xw_dt == PERF_F32 || C >= 32)) ? kConvF32Mfma
                   : (rowmfma_ok && N * P * Q >= 16384)          ? kConvRowMfma

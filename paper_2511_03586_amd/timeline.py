@@ -126,8 +126,8 @@ def main():
               f"{100.0 * 131072 / loop:.0f} | {t4} | {t0} |")
     print()
     names = {6: "`conv2d_wres_kernel<3,3,64,bf16>` (128 channels per workgroup, input rows resident)",
-             8: "`conv2d_wsplit_kernel<3,3,64,bf16>` (64-channel slabs, input-row ring)"}
-    for variant in (6, 8):
+             8: "`conv2d_wsplit_kernel<3,3,64,bf16>` (64-channel slabs, input-row ring; the library's choice)"}
+    for variant in (8, 6):
         print(f"## conv 32x56x56x64 -> 128, 3x3, bf16: {names[variant]}, 256 workgroups\n")
         print("MFMA wave 0 and memory wave 4 of each workgroup, cycles since the workgroup started, median over workgroups. "
               "Phase stamps only (the steady-state figure is undisturbed):\n")
@@ -137,9 +137,9 @@ def main():
                   "MFMA minimum 1152 = % |")
             print("|---|---|---|---|---|---|---|---|---|---|---|---|")
         else:
-            print("| operands | us / launch (events) | clock GHz | first rows issued (memory wave) | first rows landed | first tap "
-                  "of weights landed, first MFMA | tap phase ends (steps 0, 1 done) | last step done | end | steps after the "
-                  "tap phase | cycles per step | MFMA minimum 1152 = % |")
+            print("| operands | us / launch (events) | clock GHz | first rows issued (memory wave) | first rows landed | weights and "
+                  "rows complete, first MFMA | steps 0 and 1 done | last step done | end | steps after the first two | "
+                  "cycles per step | MFMA minimum 1152 = % |")
             print("|---|---|---|---|---|---|---|---|---|---|---|---|")
         for zeros in (False, True):
             buf, us = conv_timeline(torch, l1, variant, zeros)
