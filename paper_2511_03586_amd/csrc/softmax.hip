@@ -284,7 +284,8 @@ static void launch_rows(const float *x, float *y, int64_t rows, int cols, int64_
                         hipStream_t st, int64_t grid = 0)
 {
     int64_t blocks = (rows + 4 * RPW - 1) / (4 * RPW);
-    if (blocks > 256 * 64) blocks = 256 * 64;  // then waves loop over rows
+    // (one pass up to 256K workgroups: 167.5 us against 170.8 on 131072 x 1024 with waves looping over two rows each)
+    if (blocks > 256 * 1024) blocks = 256 * 1024;  // then waves loop over rows
     if (grid > 0 && grid < blocks) blocks = grid;  // (a caller's choice of a persistent grid)
     hipLaunchKernelGGL((softmax_rows_kernel<NV, RPW>), dim3((unsigned)blocks), dim3(256), 0, st, x, y, rows, cols, ldx,
                        ldy, k);
