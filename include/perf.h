@@ -236,8 +236,9 @@ perf_status perf_eltwise(perf_eltwise_op op, const void *a, const void *b, void 
  *     7 = implicit GEMM on the fp32 matrix instruction (any dtype, stride, padding, channel count),
  *     8 = weights in registers with a workgroup per (pixel range, slab of 64 output channels)
  *     and the input rows passing through a ring in LDS (3x3, 64 input channels, bf16, stride 1,
- *     K any multiple of 64, 32 <= Q and a ring of at least 6 rows of 144 Q + 512 bytes within
- *     88 KiB; some range length N*P*Q / (256 r / (K/64)), r = 1 .. 8, must divide P*Q). */
+ *     K any multiple of 64, 32 <= Q and a ring of at least 5 rows of 144 Q + 512 bytes within
+ *     88 KiB; some range length N*P*Q / (256 r / (K/64)), r = 1 .. 8, must divide P*Q and leave
+ *     the ring's fill one step ahead of the MFMAs from every column a range can start in). */
 /* The reduction operators with their launch shape chosen by the caller (same arguments, results
  * and errors as perf_softmax / perf_layernorm; every variant computes the same arithmetic, only
  * the summation tree differs with waves_per_row).  A knob left 0 keeps the library's rule; all

@@ -695,8 +695,10 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
 //     blocks of parity w >> 1: in step t the four waves work on blocks 2t and 2t+1, 64 pixels.
 //     An operand read serves 32 channels of one wave, so per pixel the LDS carries half the reads
 //     of the 128-channel kernels.
-//   * The input rows under a range do not fit the LDS any more; they pass through a ring of kNR
-//     rows, filled in linear order by the memory waves one step ahead of their use.
+//   * The input rows under a range do not fit the LDS any more; they pass through a ring of 8 to 16
+//     rows, filled row by row, in groups of 7 pixels, by the memory waves one step ahead of their
+//     use.  Wants and free space are counted in whole rows, so a load never writes into a row that
+//     is not entirely writable (its 64th lane reaches 16 bytes into the next group of its row).
 //   * The MFMA waves issue their weight loads first (a tap's loads are split between the two waves
 //     that need it), then a share of the first rows, and wait for all of them before the first
 //     barrier: behind it every weight is in LDS, and the first two steps run tap-major, reading each
