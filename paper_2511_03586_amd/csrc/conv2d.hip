@@ -878,6 +878,10 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
                 ow -= g.Q;
                 ++slot;
             }
+        // (Per lane on purpose: a wave-uniform form, two scalar bases per row and a select, replaces most of
+        // this vector work by about 60 scalar instructions per step and measured 100-200 cycles per step
+        // slower, whether bunched under one MFMA or spread over several.  With the next step's rows simply
+        // set equal to this step's, the step is 80 cycles shorter: that is what this arithmetic costs.)
         const uint32_t lane_base = (uint32_t)kWsStageBytes + (uint32_t)(lane >> 5) * 16u;
         auto rows_of = [&](uint32_t (&a)[R]) {
 #pragma unroll
