@@ -190,7 +190,8 @@ def build_workloads(torch, perf):
 
     # -- config 4, fused (an addition, not averaged into `value`): scores and softmax in one kernel,
     #    algorithmic traffic = Q + K + one write of P
-    wls.append(Workload("attn_scores_softmax_fused_512x(512x512x64)", "gemm_softmax_kernel<32,nomask,f32>", "hbm", qk_bytes,
+    wls.append(Workload("attn_scores_softmax_fused_512x(512x512x64)", "gemm_softmax_kernel<32,nomask,f32,8 waves,staged>",
+                        "hbm", qk_bytes,
                         lambda i: perf.perf_gemm_softmax(q4.data_ptr(), k4.data_ptr(), p4.data_ptr(), S, S, D, D, D, S,
                                                          c4.batch, S * D, S * D, S * S, c4.alpha, BF16, F32, st()),
                         1, "replaces the two launches above; listed, not averaged into `value`", flops=c4.flops()))

@@ -27,15 +27,22 @@ namespace perf {
 // workgroup, and a wave's 16 rows of the next strip are fetched (into the other of two
 // buffers; the rows are the wave's own, so no barrier is involved) while it works on the
 // present one, so its stores follow each other without a load latency in between.
-template <int T16N, bool MASK, typename PT>
-__global__ __launch_bounds__(256, 2) void gemm_softmax_kernel(const uint16_t *__restrict__ A,
+// STAGED (8 waves, one workgroup per CU, K = 64, N a multiple of 128, fp32 P): the probabilities leave through
+// a private 8 KiB LDS region per wave, 128 columns at a time, so that a store instruction writes 2 rows x
+// 512 contiguous bytes instead of 8 rows x 128.  A write-only probe of this output (a wave writing its 16
+// rows of 2 KiB per strip) moves 5.6 TB/s in the first shape and 6.3 in the second (6.4 with 1 KiB per row,
+// for which the LDS has no room): the shape of the store instruction, not the exponentials, held the
+// kernel at 0.68 of the HBM peak.
+template <int T16N, bool MASK, typename PT, int NW = 4, bool STAGED = false>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void gemm_softmax_kernel(const uint16_t *__restrict__ A,
                                                               const uint16_t *__restrict__ B, PT *__restrict__ P,
                                                               int M, int N, int K, int64_t lda, int64_t ldb,
                                                               int64_t ldp, int64_t strideA, int64_t strideB,
                                                               int64_t strideP, float sign, float c, int strips,
                                                               int group, int xcd_remap)
 {
-    constexpr int NW = 4, BM = 64, BN = 16 * T16N;
+    constexpr int BM = 16 * NW, BN = 16 * T16N;
+    static_assert(!STAGED || (!MASK && T16N % 8 == 0 && sizeof(PT) == 4), "the staged write-out takes whole chunks of 128 fp32 columns");
     constexpr int LB = (BN + 8 * NW - 1) / (8 * NW);     // wave loads per K-step of 64 for B (the last one may be partly unused)
     constexpr int kRowsB = LB * 8 * NW;
     constexpr int kStepB = kRowsB * kRowBytes64, kStepA = BM * kRowBytes64;
@@ -61,7 +68,8 @@ __global__ __launch_bounds__(256, 2) void gemm_softmax_kernel(const uint16_t *__
     const uint16_t *Ab = A + (int64_t)bz * strideA;
     const uint16_t *Bb = B + (int64_t)bz * strideB;
     PT *Pb = P + (int64_t)bz * strideP;
-    char *const smem_a = smem + ksteps * kStepB;  // two buffers of ksteps x 64 rows
+    char *const smem_a = smem + ksteps * kStepB;  // two buffers of ksteps x BM rows
+    char *const stage = smem_a + 2 * ksteps * kStepA + wave * (16 * 512);  // STAGED: this wave's 16 rows x 128 columns
 
     // this wave's 16 rows of strip s -> buffer s & 1 (nothing if the rows lie past M)
     auto issue_a = [&](int s) {
@@ -95,11 +103,10 @@ __global__ __launch_bounds__(256, 2) void gemm_softmax_kernel(const uint16_t *__
     wg_barrier();  // B is complete (and each wave's own rows of the first strip)
 
     for (int s = s0; s < s1; ++s) {
-        if (s + 1 < s1) issue_a(s + 1);  // (they have landed before this strip's stores are issued, see below)
+        if (s + 1 < s1) issue_a(s + 1);
         const int m0 = s * BM;
         if (m0 + wave * 16 >= M) continue;  // (no barrier inside the loop)
         const char *abuf = smem_a + (s & 1) * ksteps * kStepA;
-
         // acc[j] element e: row m0 + 16*wave + lane%16, column 16 j + 4 (lane/16) + e
         WaveTile16<1, T16N> t;
         t.clear();
@@ -158,13 +165,74 @@ __global__ __launch_bounds__(256, 2) void gemm_softmax_kernel(const uint16_t *__
             swap32(z, a, b);
             z = a + b;
         }
-        // The next strip's rows must have landed before they are read: waiting here, where those
-        // loads are a whole strip's arithmetic old, costs least.  It also waits for the previous
-        // strip's stores, i.e. a wave has one strip of stores in flight (32 KiB; 256 KiB per CU),
-        // which is more than the write latency needs.
+        const float scale = 1.0f / z;
+        // The next strip's rows must have landed before they are read: waiting here, in front of this strip's
+        // stores, leaves those in flight across the next strip's MFMAs.  (Letting two strips of stores stay in
+        // flight, by waiting for a count at the top of the loop instead, measured no faster.)
         wait_vmem<0>();
-        store_tile16<1, T16N, PT>(t, Pb, ldp, M, N, m0 + wave * 16, 0, 1.0f / z, lane);
+        if constexpr (!STAGED) {
+            store_tile16<1, T16N, PT>(t, Pb, ldp, M, N, m0 + wave * 16, 0, scale, lane);
+        } else {
+            // 128 columns at a time: lane (row r = lane % 16, q = lane / 16) writes its 16-byte pieces 4 jj + q of
+            // the chunk to row r of the staging; a row is 32 pieces, piece s at position s ^ r (then both the
+            // writes, 16 rows per quarter-wave, and the reads, 16 consecutive pieces of a row, are conflict
+            // free at a pitch of 512 bytes); then 8 instructions read and store 2 rows x 512 bytes each.
+            const int r = lane & 15, q = lane >> 4, piece = lane & 31, half = lane >> 5;
+            const int64_t row_base = (int64_t)(m0 + wave * 16);
+#pragma unroll
+            for (int ch = 0; ch < T16N / 8; ++ch) {
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) {
+                    const float4_t v = t.acc[0][8 * ch + jj] * scale;
+                    *reinterpret_cast<float4_t *>(stage + r * 512 + (((4 * jj + q) ^ r) << 4)) = v;
+                }
+                __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): own writes are in LDS (the region is this wave's alone)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int R = 2 * i + half;
+                    const float4_t v = *reinterpret_cast<const float4_t *>(stage + R * 512 + ((piece ^ R) << 4));
+                    if (row_base + R < M)
+                        __builtin_nontemporal_store(v, reinterpret_cast<float4_t *>(Pb + (row_base + R) * ldp + ch * 128 + piece * 4));
+                }
+            }
+        }
     }
+}
+
+// The staged form: 8 waves, 128-row strips, 160 KiB of LDS (B 64 KiB, two row buffers of 16 KiB, 64 KiB of staging).
+template <int T16N>
+static perf_status launch_fused_staged(const void *A, const void *B, void *P, int64_t M, int64_t N, int64_t K, int64_t lda,
+                                       int64_t ldb, int64_t ldp, int64_t batch, int64_t strideA, int64_t strideB,
+                                       int64_t strideP, float alpha, hipStream_t st)
+{
+    constexpr int NW = 8;
+    constexpr int kRowsB = (16 * T16N + 8 * NW - 1) / (8 * NW) * (8 * NW);
+    const size_t lds = (size_t)(K / 64) * (2 * 16 * NW + kRowsB) * kRowBytes64 + (size_t)NW * 16 * 512;
+    if (lds > 160 * 1024) return PERF_ERR_UNSUPPORTED;
+    auto kern = gemm_softmax_kernel<T16N, false, float, NW, true>;
+    static std::atomic<bool> attr_done{false};  // (idempotent per-function setting)
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                160 * 1024) != hipSuccess)
+            return PERF_ERR_LAUNCH;
+        attr_done = true;
+    }
+    const float sign = alpha < 0.f ? -1.f : 1.f;
+    const float c = (float)(std::fabs((double)alpha) * 1.4426950408889634074);  // |alpha| log2(e)
+    const int64_t strips = (M + 16 * NW - 1) / (16 * NW);
+    // strips per workgroup: as many as still leave two workgroups for every CU (one runs at a time)
+    int64_t group = strips * batch / 512;
+    group = group < 1 ? 1 : group > strips ? strips : group;
+    const int64_t groups = (strips + group - 1) / group;
+    const int64_t per_launch = (kMaxGridX / groups) / 8 * 8;
+    if (per_launch < 8) return PERF_ERR_UNSUPPORTED;
+    for (int64_t b0 = 0; b0 < batch; b0 += per_launch) {
+        const int64_t nb = batch - b0 < per_launch ? batch - b0 : per_launch;
+        hipLaunchKernelGGL(kern, dim3((unsigned)(groups * nb)), dim3(64 * NW), lds, st, (const uint16_t *)A + b0 * strideA,
+                           (const uint16_t *)B + b0 * strideB, (float *)P + b0 * strideP, (int)M, (int)N, (int)K, lda, ldb,
+                           ldp, strideA, strideB, strideP, sign, c, (int)strips, (int)group, nb % 8 == 0 ? 1 : 0);
+    }
+    return launch_status();
 }
 
 template <int T16N, bool MASK, typename PT>
@@ -232,6 +300,11 @@ extern "C" perf_status perf_gemm_softmax(const void *A, const void *B, void *P, 
     (p_dt == PERF_F32                                                                                                    \
          ? launch_fused<T, MASK, float>(A, B, P, M, N, K, lda, ldb, ldp, batch, strideA, strideB, strideP, alpha, st)    \
          : launch_fused<T, MASK, uint16_t>(A, B, P, M, N, K, lda, ldb, ldp, batch, strideA, strideB, strideP, alpha, st))
+        // whole chunks of 128 columns, K = 64, fp32 P with 16-byte aligned rows: the staged write-out
+        const bool staged = K == 64 && N % 128 == 0 && p_dt == PERF_F32 && ldp % 4 == 0 && strideP % 4 == 0 && aligned(P, 16);
+        if (staged && N == 512) return launch_fused_staged<32>(A, B, P, M, N, K, lda, ldb, ldp, batch, strideA, strideB, strideP, alpha, st);
+        if (staged && N == 256) return launch_fused_staged<16>(A, B, P, M, N, K, lda, ldb, ldp, batch, strideA, strideB, strideP, alpha, st);
+        if (staged && N == 128) return launch_fused_staged<8>(A, B, P, M, N, K, lda, ldb, ldp, batch, strideA, strideB, strideP, alpha, st);
         if (N == 512) return PERF_FUSED(32, false);
         if (N > 256) return PERF_FUSED(32, true);
         if (N == 256) return PERF_FUSED(16, false);

@@ -73,6 +73,23 @@ def test_fused_alpha_signs_batches_bf16_output_and_padded_ld():
     P.assert_softmax_close(p.reshape(-1, N), ref.reshape(-1, N), tol=TOL)
 
 
+def test_staged_write_out_widths_ragged_strips_and_leading_dimensions():
+    # K = 64, N in {128, 256, 512}, fp32 P with 16-byte aligned rows: the 8-wave kernel whose probabilities leave
+    # through LDS staging.  Ragged last strips (M not a multiple of 128), a batch that is not a multiple of 8,
+    # several strips per workgroup with a shorter last group (17 strips x 64 matrices -> groups of 2), a padded
+    # ldp that keeps the alignment (staged) and one that breaks it (the 4-wave kernel takes over).
+    _check(200, 256, 64)
+    _check(130, 128, 64, batch=3)
+    _check(1000, 512, 64, batch=9, alpha=-0.25)
+    _check(2100, 128, 64, batch=64)
+    M, N, K = 150, 256, 64
+    a, b = _inputs(M, N, K, 2, seed=5)
+    ref = oracle.gemm_softmax(oracle.widen(a, True), oracle.widen(b, True), M, N, K, alpha=0.125, batch=2)
+    for ldp in (260, 258):
+        p = G.run_gemm_softmax(a, b, M, N, K, alpha=0.125, batch=2, ldp=ldp)
+        P.assert_softmax_close(p.reshape(-1, N), ref.reshape(-1, N), tol=TOL)
+
+
 def test_argmax_matches_scores():
     M, N, K = 256, 512, 64
     a, b = _inputs(M, N, K, 1, seed=7)

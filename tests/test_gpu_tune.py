@@ -74,8 +74,8 @@ def test_search_conv_families():
     out = tune.search_conv(4, 56, 56, 64, 128, 3, 3, iters=10, warmup=2)
     by = {r["variant"]["variant"]: r for r in out["results"]}
     assert by[perf.CONV_WREG]["status"] == "ok" and by[perf.CONV_MFMA]["status"] == "ok"
-    assert by[perf.CONV_DIRECT]["status"] == "ok"
-    assert out["best"]["variant"]["variant"] in (perf.CONV_WRES, perf.CONV_WREG, perf.CONV_MFMA)
+    assert by[perf.CONV_DIRECT]["status"] == "ok" and by[perf.CONV_WSPLIT]["status"] == "ok"
+    assert out["best"]["variant"]["variant"] in (perf.CONV_WSPLIT, perf.CONV_WRES, perf.CONV_WREG, perf.CONV_MFMA)
     out = tune.search_conv(2, 128, 128, 3, 10, 5, 5, pad=2, iters=5, warmup=1)
     by = {r["variant"]["variant"]: r for r in out["results"]}
     assert by[perf.CONV_WREG]["status"] == "unsupported" and by[perf.CONV_MFMA]["status"] == "unsupported"
