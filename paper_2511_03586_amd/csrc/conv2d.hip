@@ -699,10 +699,10 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
 //     rows, filled row by row, in groups of 7 pixels, by the memory waves one step ahead of their
 //     use.  Wants and free space are counted in whole rows, so a load never writes into a row that
 //     is not entirely writable (its 64th lane reaches 16 bytes into the next group of its row).
-//   * The MFMA waves issue their weight loads first (a tap's loads are split between the two waves
-//     that need it), then a share of the first rows, and wait for all of them before the first
-//     barrier: behind it every weight is in LDS, and the first two steps run tap-major, reading each
-//     tap's weights into registers just ahead of its MFMAs.  (Starting the taps one by one as they
+//   * Every wave first issues one of the rows under the first two steps; the MFMA waves then issue the
+//     weight loads (a tap's loads are split between the two waves that need it), and every wave waits
+//     for its own loads before the first barrier: behind it every weight is in LDS, and the first two steps
+//     run tap-major, reading each tap's weights into registers just ahead of its MFMAs.  (Starting the taps one by one as they
 //     land, with a barrier per tap, measured 2.4K cycles slower: every barrier also waited for the
 //     memory waves, which were busy issuing the next rows into a saturated memory pipeline.)
 //   * Barriers: one when the first rows and the weights are there, one at the end of the first two
@@ -742,10 +742,25 @@ struct WsplitFill {
     __host__ __device__ bool fires(int idx, int want, int cap) const { return idx < want && idx < cap && idx < patch_rows * groups; }
 };
 
+// n / d for 0 <= n < 2^32 and d >= 1 with the host's m = min(floor(2^32 / d), 2^32 - 1): the high product is the
+// quotient or one less (it falls short of n / d by less than n / 2^32 < 1).  A handful of scalar instructions
+// where the compiler's division of two run-time values takes about forty, in a prologue whose waves issue one
+// instruction every five cycles or so with nothing to hide behind.
+struct WsplitMagic {
+    uint32_t nslab, pq, q;  // multipliers for K / 64, P * Q and Q
+};
+static inline uint32_t magic_of(int64_t d) { return d <= 1 ? 0xFFFFFFFFu : (uint32_t)((1ull << 32) / (uint64_t)d); }
+__device__ __forceinline__ int fast_div(int n, int d, uint32_t m)
+{
+    const uint32_t q = __umulhi((uint32_t)n, m);
+    return (int)((uint32_t)n - q * (uint32_t)d >= (uint32_t)d ? q + 1 : q);
+}
+
 template <int R, int S, int C, typename CT>
 __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__restrict__ x,
                                                             const uint16_t *__restrict__ w, CT *__restrict__ y,
-                                                            ConvGeom g, int px_per_wg, int patch_rows, int row_chunks, int ring_rows)
+                                                            ConvGeom g, int px_per_wg, int patch_rows, int row_chunks, int ring_rows,
+                                                            WsplitMagic mg)
 {
     constexpr int KWG = 64;                 // output channels per workgroup
     constexpr int KSUB = R * S * C / 16;    // MFMA k-substeps per pixel block
@@ -769,11 +784,11 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
     const int Mtot = g.N * g.P * g.Q;
     const int nslab = g.K / KWG;
     const int wg = gridDim.x % 8 == 0 ? (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
-    const int range = wg / nslab, slab = wg - range * nslab;
+    const int range = fast_div(wg, nslab, mg.nslab), slab = wg - range * nslab;
     const int start = range * px_per_wg, end = min(start + px_per_wg, Mtot);
     const int nblocks = (end - start + 31) / 32, nsteps = (nblocks + 1) / 2;
-    const int n0 = start / (g.P * g.Q), pq0 = start - n0 * (g.P * g.Q);
-    const int oh0 = pq0 / g.Q, q0 = pq0 - oh0 * g.Q;
+    const int n0 = fast_div(start, g.P * g.Q, mg.pq), pq0 = start - n0 * (g.P * g.Q);
+    const int oh0 = fast_div(pq0, g.Q, mg.q), q0 = pq0 - oh0 * g.Q;
     const uint32_t row_pitch = (uint32_t)(row_chunks * 16);
     // Both kinds of wave execute 1 + 1 + (nsteps >= 2) + max(nsteps - 2, 0) + 1 barriers.
     TL_BEGIN();
@@ -793,17 +808,16 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
     // pixel as a pixel index into x (left of the image by the padding), and its ring row's byte offset
     int next_load, fill_grp, fill_ih, fill_rowpix, fill_slot_byte, fill_stride;
     const int ring_bytes = ring_rows * (int)row_pitch;
-    auto fill_from = [&](int idx, int stride) {  // (one division per phase, none per load)
-        const int row = idx / groups;
-        next_load = idx;
-        fill_grp = idx - row * groups;
+    auto fill_from = [&](int row, int grp, int stride) {  // (row <= ring_rows)
+        next_load = row * groups + grp;
+        fill_grp = grp;
         fill_ih = oh0 - g.ph + row;
         fill_rowpix = (n0 * g.H + fill_ih) * g.W - g.pw;
-        fill_slot_byte = (row % ring_rows) * (int)row_pitch;
+        fill_slot_byte = (row == ring_rows ? 0 : row) * (int)row_pitch;
         fill_stride = stride;
     };
-    // (`wraps`: how many row ends one stride can cross: rows have at least 5 groups, strides are 4 or 8)
-    auto fire = [&](auto wraps) {
+    // (a stride of 4 crosses one row end at most: rows have at least 5 groups)
+    auto fire = [&]() {
         const int px0 = min(fill_grp * kWsGroup, Wv - kWsGroup);
         // columns of the image this row offers: none if the row lies above or below it (zeros are written)
         const uint32_t cols = (unsigned)fill_ih < (unsigned)g.H ? (uint32_t)g.W : 0u;
@@ -814,24 +828,35 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
             xr, (__attribute__((address_space(3))) void *)(ring + fill_slot_byte + px0 * kPix), 16, vo, 0, 0, 0);
         next_load += fill_stride;
         fill_grp += fill_stride;
-#pragma unroll
-        for (int i = 0; i < decltype(wraps)::value; ++i)
-            if (fill_grp >= groups) {
-                fill_grp -= groups;
-                ++fill_ih;
-                fill_rowpix += g.W;
-                fill_slot_byte += (int)row_pitch;
-                fill_slot_byte = fill_slot_byte == ring_bytes ? 0 : fill_slot_byte;
-            }
+        if (fill_grp >= groups) {
+            fill_grp -= groups;
+            ++fill_ih;
+            fill_rowpix += g.W;
+            fill_slot_byte += (int)row_pitch;
+            fill_slot_byte = fill_slot_byte == ring_bytes ? 0 : fill_slot_byte;
+        }
     };
-    const std::integral_constant<int, 1> one_wrap{};
-    const std::integral_constant<int, 2> two_wraps{};
-    // the rows under steps 0 and 1 are issued by all eight waves, every eighth load each (the MFMA
-    // waves behind their weight loads, whose first-touch latency then overlaps the rows')
-    const int cap0 = ring_rows * groups, want1 = fs.wanted(1);
-    if (wave >= 4) {
-        fill_from(wave, 8);
-        while (fs.fires(next_load, want1, cap0)) fire(two_wraps);
+    // The rows under steps 0 and 1 (the host has checked that the ring holds them) are the first thing every
+    // wave issues, one whole row each (the memory waves rows 0 .. 3, the MFMA waves 4 .. 7, then every eighth):
+    // they come from HBM, all 256 workgroups ask at once, and they are what the first MFMA ends up waiting
+    // for; the weights behind them come from the L2 and land first.  (With the weights first, the rows dealt out
+    // load by load through the general fill below, and the compiler's division sequences in this prologue, the
+    // rows had landed 600 cycles later.)
+    const int rows_first = fast_div(q0 + 127, g.Q, mg.q) + R < patch_rows ? fast_div(q0 + 127, g.Q, mg.q) + R : patch_rows;
+    const int cap0 = ring_rows * groups, want1 = rows_first * groups;
+    for (int row = wave >= 4 ? wave - 4 : wave + 4; row < rows_first; row += 8) {
+        const int ih = oh0 - g.ph + row;
+        const uint32_t cols = (unsigned)ih < (unsigned)g.H ? (uint32_t)g.W : 0u;
+        const int rowpix = (n0 * g.H + ih) * g.W - g.pw;
+        char *const slot = ring + row * (int)row_pitch;
+        for (int grp = 0; grp < groups; ++grp) {
+            const int px0 = min(grp * kWsGroup, Wv - kWsGroup);
+            const uint32_t base = (uint32_t)(rowpix + px0) * (uint32_t)(C * 2);
+            const uint32_t iw = (uint32_t)(px0 - g.pw + lane_px);
+            const uint32_t vo = (lane_ch < kChunks - 1 && iw < cols) ? base + lane_off : kOutOfRange;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void *)(slot + px0 * kPix), 16, vo,
+                                                     0, 0, 0);
+        }
     }
 
     if (wave < 4) {
@@ -862,8 +887,6 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
                         16, vo, t * (C * 2), 0, 0);
                 }
         }
-        fill_from(wave, 8);
-        while (fs.fires(next_load, want1, cap0)) fire(two_wraps);
         uint32_t wrd[kPerTap];
 #pragma unroll
         for (int j = 0; j < kPerTap; ++j)
@@ -916,7 +939,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
 #pragma unroll
         for (int e = 0; e < 16; ++e) accs[0][e] = accs[1][e] = 0.f;
 
-        wait_vmem<0>();  // own weight loads and own part of the first rows have landed
+        wait_vmem<0>();  // own weight loads and own first row have landed
         TL_STAMP(wave == 0, 0, 2);
         wg_barrier();    // the weights and the rows under steps 0 and 1 are complete
         TL_STAMP(wave == 0, 0, 3);
@@ -1055,10 +1078,11 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
         wg_barrier();  // the rows under steps 0 and 1 are complete
         TL_STAMP(wave == 4, 1, 4);
         // from here on the four memory waves share the fill: first the rows under step 2
-        fill_from(want1 + mw, 4);
+        fill_from(rows_first, mw, 4);
         {
-            const int want2 = fs.wanted(2);
-            while (fs.fires(next_load, want2, cap0)) fire(one_wrap);
+            const int rows2 = fast_div(q0 + 191, g.Q, mg.q) + R;
+            const int want2 = (rows2 < patch_rows ? rows2 : patch_rows) * groups;
+            while (fs.fires(next_load, want2, cap0)) fire();
         }
         wait_vmem_and_lds<0>();
         wg_barrier();  // end of the first two steps: the rows under step 2 are complete; steps 0 and 1 no longer read the ring
@@ -1081,7 +1105,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
         auto fill_next = [&]() {
             const int rows = want_row + R < patch_rows ? want_row + R : patch_rows;
             const int want = rows * groups, cap = (busy_row + ring_rows) * groups;
-            for (int i = 0; i < kWsFill && fs.fires(next_load, want, cap); ++i) fire(one_wrap);
+            for (int i = 0; i < kWsFill && fs.fires(next_load, want, cap); ++i) fire();
             want_col += 64;
 #pragma unroll
             for (int i = 0; i < 2; ++i)
@@ -1421,7 +1445,8 @@ static perf_status launch_conv_wsplit(const void *x, const void *w, void *y, con
         attr_done = true;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)(pl.ranges * (g.K / 64))), dim3(512), pl.lds, st, (const uint16_t *)x,
-                       (const uint16_t *)w, (CT *)y, g, pl.px, pl.patch_rows, pl.row_chunks, pl.ring_rows);
+                       (const uint16_t *)w, (CT *)y, g, pl.px, pl.patch_rows, pl.row_chunks, pl.ring_rows,
+                       WsplitMagic{magic_of(g.K / 64), magic_of((int64_t)g.P * g.Q), magic_of(g.Q)});
     return launch_status();
 }
 
@@ -1452,8 +1477,9 @@ static WsplitPlan plan_wsplit(int64_t N, int64_t P, int64_t Q, int64_t R, int64_
         for (int64_t q0 = 0; q0 <= q0max && ok; ++q0) {
             const WsplitFill fs{(int)Q, (int)R, (int)rows, groups, ring_rows, (int)q0};
             const int cap0 = ring_rows * groups;
-            // the kernel's first phase: all eight waves, wave v takes loads v, v + 8, ... below wanted(1);
-            // the four memory waves then go on from the first load beyond it, every fourth each
+            // the kernel's first phase: the eight waves issue every load below wanted(1), whole rows each (rows
+            // that the ring must hold); the four memory waves then go on from the first load beyond it, every
+            // fourth each
             const int first = fs.wanted(1);
             ok = first <= cap0;
             int next[4] = {first, first + 1, first + 2, first + 3};
