@@ -68,6 +68,9 @@ def parse():
     ap.add_argument("--lds-probe", action="store_true",
                     help="print the LDS read probes (bytes per clock and CU by waves per CU and read width; "
                          "cycles per MFMA of the MFMA + operand-read pattern) as one JSON line and exit")
+    ap.add_argument("--feed-probe", action="store_true",
+                    help="print the L2 -> CU feed probe (bytes per clock and CU through buffer_load ... lds and through "
+                         "registers, by window size and waves per CU) as one JSON line and exit")
     ap.add_argument("--copy-study", action="store_true",
                     help="instead of the benchmark: sweep the streaming probe (copy / read / write, vectors per thread, "
                          "workgroup size, grid, cache policy) and print one JSON line with every point")
@@ -483,6 +486,38 @@ def lds_probe(torch, perf, iters=2000):
     return rows
 
 
+def feed_probe(torch, perf, iters=400):
+    """Bytes per clock and CU that a CU takes in from the L2 (windows beyond the 32 KiB L1) and from the L1, through
+    buffer_load ... lds and through registers, all 256 CUs at once, from the library's probe kernel."""
+    st = torch.cuda.current_stream().cuda_stream
+    cyc = torch.zeros(1, dtype=torch.int64, device="cuda")
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    src = torch.zeros(256 * 65536, dtype=torch.uint8, device="cuda")
+    names = {0: "buffer_load ... lds, whole KiB", 1: "load to registers + ds_write_b128", 2: "load to registers only",
+             3: "buffer_load ... lds, 7 pixels x (8 lanes + 1 out of range)"}
+    rows = []
+    for shared, span in ((0, 32768), (0, 65536), (1, 131072), (1, 1 << 20)):
+        for waves in (4, 8):
+            for mode in (0, 3, 1, 2):
+                best = None
+                for _ in range(3):
+                    cyc.zero_()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    perf.perf_feed_probe(src.data_ptr(), src.numel(), cyc.data_ptr(), sink.data_ptr(), waves, mode, shared, span, iters, st)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    us = e0.elapsed_time(e1) * 1e3
+                    if best is None or us < best[0]:
+                        best = (us, int(cyc.item()))
+                per_wg = waves * iters * 8192
+                rows.append({"window": ("one for all workgroups, " if shared else "per workgroup, ") + f"{span >> 10} KiB",
+                             "waves_per_cu": waves, "path": names[mode], "us": round(best[0], 1), "cycles": best[1],
+                             "bytes_per_clk_per_cu": round(per_wg / best[1], 1),
+                             "chip_tbs": round(per_wg * 256 / best[0] / 1e6, 1)})
+    return rows
+
+
 def measure_mfma_ceiling(torch, perf, iters=2000, reps=5, random_operands=False):
     """Measured matrix-core ceiling: the library's register-only bf16 MFMA loop (TFLOP/s), with
     constant small-integer operands or with pseudo-random ones that toggle the multipliers."""
@@ -590,6 +625,9 @@ def main():
         return
     if args.lds_probe:
         print(json.dumps({"lds_probe": lds_probe(torch, perf)}))
+        return
+    if args.feed_probe:
+        print(json.dumps({"feed_probe": feed_probe(torch, perf)}))
         return
 
     wls, keep = build_workloads(torch, perf)

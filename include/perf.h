@@ -322,6 +322,22 @@ perf_status perf_mfma_probe_random(float *sink, int64_t iters, perf_stream strea
 perf_status perf_lds_probe(long long *cycles, float *sink, int waves, int bytes_per_lane, int with_mfma,
                            int64_t iters, perf_stream stream);
 
+/* L2 -> CU feed probe behind the convolution and GEMM analysis (not one of the paper's operators): 256
+ * workgroups of `waves` wavefronts (4 or 8) stream 1 KiB wave loads from a window of `span` bytes (a power
+ * of two from 1 KiB to 1 GiB), the workgroup's own (shared = 0: window b of src for workgroup b) or one
+ * window for all (shared = 1), iters * 8 loads per wavefront with eight more in flight; a window beyond the
+ * L1's 32 KiB is served by the L2.  Bytes per clock and CU = waves * iters * 8192 / cycles.
+ *   mode 0  buffer_load ... lds, whole KiB          mode 1  load to registers, then ds_write_b128
+ *   mode 2  load to registers only                  mode 3  buffer_load ... lds in the slab convolution's
+ *           row pattern (7 pixels x 8 lanes of 16 bytes, every ninth lane out of range)
+ *   src     device, 16-byte aligned, src_bytes >= span (shared) or 256 * span; read only
+ *   cycles  device, one 64-bit value the caller has set to 0: raised (atomic max) to the shader cycles the
+ *           slowest wavefront of workgroup 0 spent in the loop
+ *   sink    device, one float, never written for finite input (keeps the loads live)
+ * Errors: NULL, SHAPE (waves, mode, shared, span, src_bytes, iters < 1 or > 2^14), ALIGN, LAUNCH. */
+perf_status perf_feed_probe(const void *src, int64_t src_bytes, long long *cycles, float *sink, int waves, int mode,
+                            int shared, int64_t span, int64_t iters, perf_stream stream);
+
 /* Human-readable name of a status code; static storage, never freed. */
 const char *perf_status_string(perf_status s);
 

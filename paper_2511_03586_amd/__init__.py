@@ -53,6 +53,7 @@ SIGNATURES = {
     "perf_mfma_probe": (_int, [_ptr, _i64, _ptr]),
     "perf_mfma_probe_random": (_int, [_ptr, _i64, _ptr]),
     "perf_lds_probe": (_int, [_ptr, _ptr, _int, _int, _int, _i64, _ptr]),
+    "perf_feed_probe": (_int, [_ptr, _i64, _ptr, _ptr, _int, _int, _int, _i64, _i64, _ptr]),
     "perf_status_string": (ctypes.c_char_p, [_int]),
     "perf_version": (_int, []),
 }
@@ -231,3 +232,8 @@ def perf_mfma_probe_random(sink, iters, stream=None, check=True) -> int:
 
 def perf_lds_probe(cycles, sink, waves, bytes_per_lane, with_mfma, iters, stream=None, check=True) -> int:
     return _check("perf_lds_probe", lib().perf_lds_probe(cycles, sink, waves, bytes_per_lane, with_mfma, iters, stream), check)
+
+
+def perf_feed_probe(src, src_bytes, cycles, sink, waves, mode, shared, span, iters, stream=None, check=True) -> int:
+    return _check("perf_feed_probe",
+                  lib().perf_feed_probe(src, src_bytes, cycles, sink, waves, mode, shared, span, iters, stream), check)

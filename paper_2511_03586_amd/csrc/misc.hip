@@ -2,6 +2,7 @@
 // figures: a streaming copy (HBM) and a register-only MFMA loop (matrix cores).
 #include "device_utils.h"
 #include "host_utils.h"
+#include "mfma_tile.h"
 #include <type_traits>
 
 namespace perf {
@@ -235,6 +236,67 @@ __global__ __launch_bounds__(1024) void lds_probe_kernel(long long *__restrict__
     if (keep == 12345.678f) sink[0] = keep;  // (never true: the reads stay live)
 }
 
+// L2 -> CU feed probe: every workgroup streams 1 KiB wave loads from a window of `span` bytes (its own, or one all
+// workgroups share), eight per wavefront and iteration with another eight in flight, window offset
+// ((it * 8 + u) * waves + wave) KiB mod span, so a window larger than the L1 is served by the L2.
+//   MODE 0: buffer_load ... lds, lane i -> bytes 16 i of the KiB      MODE 1: load to registers, then ds_write_b128
+//   MODE 2: load to registers only                                     MODE 3: buffer_load ... lds in the slab
+//   convolution's row pattern (7 pixels x 8 lanes of 16 bytes, every ninth lane out of range: zeros)
+template <int MODE>
+__global__ __launch_bounds__(512) void feed_probe_kernel(const char *__restrict__ src, long long *__restrict__ cycles,
+                                                         float *__restrict__ sink, int iters, int shared, uint32_t span)
+{
+    __shared__ __attribute__((aligned(1024))) char smem[65536];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
+    const rsrc_t r = make_rsrc(src + (shared ? 0 : (size_t)blockIdx.x * span), span);
+    float keep = 0.f;
+    __syncthreads();
+    const long long c0 = __builtin_readcyclecounter();
+    if constexpr (MODE == 0 || MODE == 3) {
+        uint32_t vo = (uint32_t)(lane * 16);
+        if constexpr (MODE == 3) vo = lane % 9 < 8 ? (uint32_t)(lane / 9 * 128 + lane % 9 * 16) : kOutOfRange;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const uint32_t kib = (uint32_t)(((it * 8 + u) * nw + wave) * 1024);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void *)(smem + (kib & 65535)), 16, vo,
+                                                         kib & (span - 1), 0, 0);
+            }
+            wait_vmem<8>();
+        }
+        wait_vmem<0>();
+    } else {
+        uint4_t a[8], b[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            a[u] = __builtin_amdgcn_raw_buffer_load_b128(r, (uint32_t)(lane * 16), (uint32_t)(((u * nw + wave) * 1024) & (span - 1)), 0);
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                b[u] = __builtin_amdgcn_raw_buffer_load_b128(r, (uint32_t)(lane * 16),
+                                                             (uint32_t)((((it + 1) * 8 + u) * nw + wave) * 1024) & (span - 1), 0);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if constexpr (MODE == 1) {
+                    *reinterpret_cast<uint4_t *>(smem + (((u * nw + wave) * 1024) & 65535) + lane * 16) = a[u];
+                } else {
+                    asm volatile("" : "+v"(a[u]));
+                    keep += __builtin_bit_cast(float, a[u][0]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a[u] = b[u];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) keep += __builtin_bit_cast(float, a[u][1]);
+    }
+    __syncthreads();
+    const long long c1 = __builtin_readcyclecounter();
+    if (MODE != 2) keep += reinterpret_cast<float *>(smem)[threadIdx.x];
+    if (blockIdx.x == 0 && lane == 0) atomicMax(reinterpret_cast<unsigned long long *>(cycles), (unsigned long long)(c1 - c0));
+    if (keep == 12345.678f) sink[0] = keep;  // (never true for the zero-filled or finite inputs a caller passes: the loads stay live)
+}
+
 }  // namespace perf
 
 static perf_status mfma_probe(float *sink, int64_t iters, bool random, perf_stream stream)
@@ -274,6 +336,26 @@ extern "C" perf_status perf_lds_probe(long long *cycles, float *sink, int waves,
     else if (bytes_per_lane == 16) hipLaunchKernelGGL((lds_probe_kernel<16, false>), grid, block, 0, st, cycles, sink, iters);
     else if (bytes_per_lane == 8) hipLaunchKernelGGL((lds_probe_kernel<8, false>), grid, block, 0, st, cycles, sink, iters);
     else hipLaunchKernelGGL((lds_probe_kernel<4, false>), grid, block, 0, st, cycles, sink, iters);
+    return launch_status();
+}
+
+extern "C" perf_status perf_feed_probe(const void *src, int64_t src_bytes, long long *cycles, float *sink, int waves, int mode,
+                                       int shared, int64_t span, int64_t iters, perf_stream stream)
+{
+    using namespace perf;
+    if (!src || !cycles || !sink) return PERF_ERR_NULL;
+    if ((waves != 4 && waves != 8) || mode < 0 || mode > 3 || (shared != 0 && shared != 1) || iters < 1 || iters > (1 << 14))
+        return PERF_ERR_SHAPE;  // (the byte offset (iters + 1) * 8 * waves KiB stays below 2^31)
+    if (span < 1024 || span > (1 << 30) || (span & (span - 1)) != 0) return PERF_ERR_SHAPE;
+    if (src_bytes < (shared ? span : 256 * span)) return PERF_ERR_SHAPE;
+    if (!aligned(src, 16) || !aligned(cycles, 8) || !aligned(sink, 4)) return PERF_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const dim3 grid(256), block(64 * waves);
+    const char *s = static_cast<const char *>(src);
+    if (mode == 0) hipLaunchKernelGGL(feed_probe_kernel<0>, grid, block, 0, st, s, cycles, sink, (int)iters, shared, (uint32_t)span);
+    else if (mode == 1) hipLaunchKernelGGL(feed_probe_kernel<1>, grid, block, 0, st, s, cycles, sink, (int)iters, shared, (uint32_t)span);
+    else if (mode == 2) hipLaunchKernelGGL(feed_probe_kernel<2>, grid, block, 0, st, s, cycles, sink, (int)iters, shared, (uint32_t)span);
+    else hipLaunchKernelGGL(feed_probe_kernel<3>, grid, block, 0, st, s, cycles, sink, (int)iters, shared, (uint32_t)span);
     return launch_status();
 }
 

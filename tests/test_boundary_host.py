@@ -118,6 +118,14 @@ def test_mfma_probe_argument_errors():
     assert perf.perf_lds_probe(FAKE, FAKE, 4, 16, 0, 0, check=False) == perf.PERF_ERR_SHAPE
     assert perf.perf_lds_probe(FAKE, FAKE, 4, 8, 1, 1, check=False) == perf.PERF_ERR_UNSUPPORTED
     assert perf.perf_lds_probe(FAKE + 4, FAKE, 4, 16, 0, 1, check=False) == perf.PERF_ERR_ALIGN
+    # feed probe: src, src_bytes, cycles, sink, waves, mode, shared, span, iters
+    assert perf.perf_feed_probe(None, 1 << 24, FAKE, FAKE, 4, 0, 0, 65536, 1, check=False) == perf.PERF_ERR_NULL
+    assert perf.perf_feed_probe(FAKE, 1 << 24, FAKE, FAKE, 16, 0, 0, 65536, 1, check=False) == perf.PERF_ERR_SHAPE
+    assert perf.perf_feed_probe(FAKE, 1 << 24, FAKE, FAKE, 4, 4, 0, 65536, 1, check=False) == perf.PERF_ERR_SHAPE
+    assert perf.perf_feed_probe(FAKE, 1 << 24, FAKE, FAKE, 4, 0, 0, 65536 + 1024, 1, check=False) == perf.PERF_ERR_SHAPE   # not a power of two
+    assert perf.perf_feed_probe(FAKE, (1 << 24) - 1, FAKE, FAKE, 4, 0, 0, 65536, 1, check=False) == perf.PERF_ERR_SHAPE   # 256 windows do not fit
+    assert perf.perf_feed_probe(FAKE, 65536, FAKE, FAKE, 4, 0, 1, 65536, (1 << 14) + 1, check=False) == perf.PERF_ERR_SHAPE
+    assert perf.perf_feed_probe(FAKE + 8, 1 << 24, FAKE, FAKE, 4, 0, 0, 65536, 1, check=False) == perf.PERF_ERR_ALIGN
     assert perf.perf_mfma_probe_random(None, 1, check=False) == perf.PERF_ERR_NULL
     assert perf.perf_mfma_probe_random(FAKE, 0, check=False) == perf.PERF_ERR_SHAPE
     assert perf.perf_mfma_probe_random(FAKE + 2, 1, check=False) == perf.PERF_ERR_ALIGN

@@ -254,6 +254,27 @@ def test_lds_probe_reports_plausible_rates():
     assert float(sink.item()) == 0.0
 
 
+def test_feed_probe_reports_plausible_rates():
+    """The L2 -> CU feed probe: every mode runs, leaves its source untouched, and reports a rate between a trickle
+    and what one CU's L1 can take in (64 bytes per clock; the register path with its LDS write can exceed that in
+    the probe's own accounting when the window fits the L1, hence the margin)."""
+    import torch
+    cyc = torch.zeros(1, dtype=torch.int64, device="cuda")
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    src = torch.zeros(256 * 65536, dtype=torch.uint8, device="cuda")
+    iters = 100
+    for shared, span in ((0, 65536), (1, 1 << 20)):
+        for waves in (4, 8):
+            for mode in range(4):
+                cyc.zero_()
+                perf.perf_feed_probe(src.data_ptr(), src.numel(), cyc.data_ptr(), sink.data_ptr(), waves, mode, shared, span,
+                                     iters, G.stream())
+                torch.cuda.synchronize()
+                rate = waves * iters * 8192 / int(cyc.item())
+                assert 8.0 < rate < 100.0, (shared, span, waves, mode, rate)
+    assert float(sink.item()) == 0.0 and not bool(src.any())
+
+
 def test_copy_any_alignment_and_size():
     """perf_copy (the measured HBM ceiling) must copy bit for bit whatever the alignment of either
     pointer; misaligned cases run grid-wide kernels too (64 MiB in well under a second)."""
