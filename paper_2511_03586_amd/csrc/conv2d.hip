@@ -930,7 +930,7 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
         };
         const int stage_wr = (lane & 31) * kOutPitch + (grp * 32 + 4 * (lane >> 5)) * (int)sizeof(CT);
 
-        uint32_t a0[R], a1[R], cur[R], nxt[R];
+        uint32_t a0[R], a1[R], cur[R], nxt[R], nxt_px = 0;
         rows_of(a0);
         next_step();
         rows_of(a1);
@@ -1011,13 +1011,33 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
                 char *stg = out_stage + (((t - 1) & 1) * 2 + par) * kOutBytes + stage_wr;
 #pragma unroll
                 for (int kk = 0; kk < KSUB; ++kk) {
-                    // the next step's row addresses, computed in the shadow of MFMAs well before their first use
-                    if (kk == 12) next_step();
+                    // The next step's row addresses, well before their first use and a few instructions per MFMA: vector
+                    // work hides behind an MFMA only up to the 32 cycles that the MFMA itself takes (all of it in one
+                    // place, with 64-bit multiply-adds, cost the step 80 cycles).
+                    if (kk == 8) {
+                        ow += 64;
+                        asm volatile("" : "+v"(ow));
+                    }
+                    if (kk == 9 || kk == 10) {
+                        if (ow >= g.Q) {
+                            ow -= g.Q;
+                            ++slot;
+                        }
+                        asm volatile("" : "+v"(ow), "+v"(slot));
+                    }
+                    if (kk == 11) {
+                        slot = slot >= ring_rows ? slot - ring_rows : slot;
+                        asm volatile("" : "+v"(slot));
+                    }
+                    if (kk == 12) {
+                        nxt_px = lane_base + __umul24((uint32_t)ow, (uint32_t)kPix);
+                        asm volatile("" : "+v"(nxt_px));
+                    }
                     if (kk >= 13 && kk < 13 + R) {
                         const int r = kk - 13;
                         int sl = slot + r;
                         sl = sl >= ring_rows ? sl - ring_rows : sl;
-                        nxt[r] = lane_base + (uint32_t)sl * row_pitch + (uint32_t)(ow * kPix);
+                        nxt[r] = nxt_px + __umul24((uint32_t)sl, row_pitch);
                         asm volatile("" : "+v"(nxt[r]));
                     }
                     if (kk == kBar) {
