@@ -483,6 +483,13 @@ def lds_probe(torch, perf, iters=2000):
         c = int(cyc.item())
         rows.append({"waves_per_cu": waves, "pattern": "mfma_32x32x16 + ds_read_b128, window 9",
                      "cycles_per_mfma_of_the_slowest_wave": round(c / (iters // 4 * 36), 2)})
+        for _ in range(2):
+            cyc.zero_()
+            perf.perf_lds_probe(cyc.data_ptr(), sink.data_ptr(), waves, 16, 2, iters // 4, st)
+        torch.cuda.synchronize()
+        c = int(cyc.item())
+        rows.append({"waves_per_cu": waves, "pattern": "the same + 5 dependent 32-bit multiply-adds behind each of 4 of the 36 MFMAs",
+                     "cycles_per_mfma_of_the_slowest_wave": round(c / (iters // 4 * 36), 2)})
     return rows
 
 

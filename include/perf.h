@@ -314,10 +314,12 @@ perf_status perf_mfma_probe_random(float *sink, int64_t iters, perf_stream strea
  * with_mfma = 1 (bytes_per_lane 16): the weights-in-registers kernels' inner pattern, one
  * v_mfma_f32_32x32x16_bf16 plus the ds_read_b128 of the operand used nine MFMAs later,
  * iters * 36 of them; cycles / (iters * 36) against 32 is what that pattern costs a wavefront.
+ * with_mfma = 2: the same with five dependent 32-bit multiply-adds behind each of 4 of the 36 MFMAs (vector
+ * work hides behind an MFMA only for as long as the MFMA takes).
  *   cycles  device, one 64-bit value the caller has set to 0: raised (atomic max) to the shader cycles
  *           the slowest wavefront of workgroup 0 spent in the loop
  *   sink    device, one float, never written (keeps the reads live)
- * Errors: NULL, SHAPE (waves, bytes_per_lane, iters < 1 or > 2^24), UNSUPPORTED (with_mfma and
+ * Errors: NULL, SHAPE (waves, bytes_per_lane, with_mfma, iters < 1 or > 2^24), UNSUPPORTED (with_mfma and
  * bytes_per_lane != 16), ALIGN, LAUNCH. */
 perf_status perf_lds_probe(long long *cycles, float *sink, int waves, int bytes_per_lane, int with_mfma,
                            int64_t iters, perf_stream stream);

@@ -177,7 +177,7 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ sin
 //   MFMA = true:  the convolution kernels' inner pattern, one v_mfma_f32_32x32x16_bf16 and one
 //                 ds_read_b128 of the operand needed nine MFMAs later, 36 per iteration; cycles of
 //                 the slowest wave for iters * 36 MFMAs (32 each is the matrix core's own time).
-template <int BYTES, bool MFMA>
+template <int BYTES, bool MFMA, bool VALU = false>
 __global__ __launch_bounds__(1024) void lds_probe_kernel(long long *__restrict__ cycles, float *__restrict__ sink, int64_t iters)
 {
     __shared__ __attribute__((aligned(1024))) char smem[65536];
@@ -202,18 +202,27 @@ __global__ __launch_bounds__(1024) void lds_probe_kernel(long long *__restrict__
         float16_t acc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+        uint32_t x = (uint32_t)lane;
         c0 = __builtin_readcyclecounter();
         for (int64_t it = 0; it < iters; ++it) {
 #pragma unroll
             for (int kk = 0; kk < 36; ++kk) {
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wgt, af[kk % 9], acc, 0, 0, 0);
                 af[kk % 9] = *(lds_frag_t *)(base + addr + ((kk + 9) % 16) * 32);
+                if (VALU && kk >= 12 && kk < 16) {  // 5 dependent 32-bit multiply-adds behind each of 4 MFMAs
+#pragma unroll
+                    for (int r = 0; r < 5; ++r) {
+                        x = x * 1664525u + 1013904223u;
+                        asm volatile("" : "+v"(x));
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
         c1 = __builtin_readcyclecounter();
 #pragma unroll
         for (int e = 0; e < 16; ++e) keep += acc[e];
+        if (VALU && x == 77u) keep = 12345.678f;  // (x is live; whether this ever holds is irrelevant to the timing)
     } else {
         typedef float vecn_t __attribute__((ext_vector_type(BYTES == 4 ? 2 : BYTES / 4)));
         using vec_t = std::conditional_t<BYTES == 4, float, vecn_t>;
@@ -328,11 +337,13 @@ extern "C" perf_status perf_lds_probe(long long *cycles, float *sink, int waves,
     if ((waves != 4 && waves != 8 && waves != 16) || (bytes_per_lane != 4 && bytes_per_lane != 8 && bytes_per_lane != 16) ||
         iters < 1 || iters > (int64_t(1) << 24))
         return PERF_ERR_SHAPE;
+    if (with_mfma < 0 || with_mfma > 2) return PERF_ERR_SHAPE;
     if (with_mfma && bytes_per_lane != 16) return PERF_ERR_UNSUPPORTED;
     if (!aligned(cycles, 8) || !aligned(sink, 4)) return PERF_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const dim3 grid(256), block(64 * waves);
-    if (with_mfma) hipLaunchKernelGGL((lds_probe_kernel<16, true>), grid, block, 0, st, cycles, sink, iters);
+    if (with_mfma == 2) hipLaunchKernelGGL((lds_probe_kernel<16, true, true>), grid, block, 0, st, cycles, sink, iters);
+    else if (with_mfma) hipLaunchKernelGGL((lds_probe_kernel<16, true>), grid, block, 0, st, cycles, sink, iters);
     else if (bytes_per_lane == 16) hipLaunchKernelGGL((lds_probe_kernel<16, false>), grid, block, 0, st, cycles, sink, iters);
     else if (bytes_per_lane == 8) hipLaunchKernelGGL((lds_probe_kernel<8, false>), grid, block, 0, st, cycles, sink, iters);
     else hipLaunchKernelGGL((lds_probe_kernel<4, false>), grid, block, 0, st, cycles, sink, iters);

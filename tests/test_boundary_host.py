@@ -117,6 +117,7 @@ def test_mfma_probe_argument_errors():
     assert perf.perf_lds_probe(FAKE, FAKE, 4, 12, 0, 1, check=False) == perf.PERF_ERR_SHAPE
     assert perf.perf_lds_probe(FAKE, FAKE, 4, 16, 0, 0, check=False) == perf.PERF_ERR_SHAPE
     assert perf.perf_lds_probe(FAKE, FAKE, 4, 8, 1, 1, check=False) == perf.PERF_ERR_UNSUPPORTED
+    assert perf.perf_lds_probe(FAKE, FAKE, 4, 16, 3, 1, check=False) == perf.PERF_ERR_SHAPE
     assert perf.perf_lds_probe(FAKE + 4, FAKE, 4, 16, 0, 1, check=False) == perf.PERF_ERR_ALIGN
     # feed probe: src, src_bytes, cycles, sink, waves, mode, shared, span, iters
     assert perf.perf_feed_probe(None, 1 << 24, FAKE, FAKE, 4, 0, 0, 65536, 1, check=False) == perf.PERF_ERR_NULL

@@ -251,6 +251,11 @@ def test_lds_probe_reports_plausible_rates():
         torch.cuda.synchronize()
         per_mfma = int(cyc.item()) / (iters * 36)
         assert 31.0 < per_mfma < 80.0, (waves, per_mfma)
+        cyc.zero_()
+        perf.perf_lds_probe(cyc.data_ptr(), sink.data_ptr(), waves, 16, 2, iters, G.stream())
+        torch.cuda.synchronize()
+        with_valu = int(cyc.item()) / (iters * 36)
+        assert per_mfma - 0.5 < with_valu < 80.0, (waves, per_mfma, with_valu)   # extra vector work never makes it faster
     assert float(sink.item()) == 0.0
 
 
