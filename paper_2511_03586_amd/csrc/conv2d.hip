@@ -1053,8 +1053,14 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
                         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
                     }
                     af[kk % kWin] = kk + kWin < KSUB ? read_frag(cur, kk + kWin) : read_frag(nxt, kk + kWin - KSUB);
-                    if (kk >= 1 && kk < 5) {
-                        const int a = kk - 1;
+                    // The previous step's results go to the staging in four pieces, two early and two late in the
+                    // step (all four right behind the step's first MFMAs cost 30 cycles per step more).  The last one
+                    // must be complete when the barrier below lets the memory waves read it: LDS operations complete
+                    // in order and the barrier's wait leaves kWin of them in flight, so kWin operand reads follow it.
+                    constexpr int kStageAt[4] = {4, 6, 16, 17};
+                    static_assert(kStageAt[3] + kWin < kBar, "the last staging write is out of the window at the barrier");
+                    if (kk == kStageAt[0] || kk == kStageAt[1] || kk == kStageAt[2] || kk == kStageAt[3]) {
+                        const int a = kk == kStageAt[0] ? 0 : kk == kStageAt[1] ? 1 : kk == kStageAt[2] ? 2 : 3;
                         if constexpr (sizeof(CT) == 4) {
                             *reinterpret_cast<float4_t *>(stg + 8 * a * 4) =
                                 float4_t{prev[4 * a], prev[4 * a + 1], prev[4 * a + 2], prev[4 * a + 3]};
