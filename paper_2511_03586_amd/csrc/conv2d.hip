@@ -992,89 +992,92 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
             __builtin_amdgcn_sched_barrier(0);
         }
 
-        // One step: `acc` collects this wave's block of step t, `prev` holds that of step t-1, which
-        // is converted and staged in the shadow of the first MFMAs, then cleared for step t+1.  The
-        // barrier tells the memory waves that it is staged, and the MFMA waves that the rows under
-        // step t+1 have landed.
-        for (int t0 = 2; t0 < nsteps; t0 += 2) {
+        // One step: `acc` collects this wave's block of step t (its first MFMA takes a literal zero as C), `prev`
+        // holds that of step t-1, which is converted and staged in the shadow of the MFMAs.  The barrier tells
+        // the memory waves that it is staged, and the MFMA waves that the rows under step t+1 have landed.
+        // (steps come in pairs that swap the two accumulators; the pair is the loop's unit, so a step boundary
+        // carries no loop control: the step's first MFMAs are where vector and scalar work is least hidden)
+        auto do_step = [&](int t, auto hc) {
+            constexpr int h = decltype(hc)::value;
+            float16_t &acc = accs[h];
+            float16_t &prev = accs[h ^ 1];
+            // (opaque to the optimiser: folded with the tap offsets the row addresses would turn into one
+            // register per read)
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int t = t0 + h;
-                if (t >= nsteps) break;
-                float16_t &acc = accs[h];
-                float16_t &prev = accs[h ^ 1];
-                // (opaque to the optimiser: folded with the tap offsets the row addresses would turn into one
-                // register per read)
+            for (int r = 0; r < R; ++r) asm volatile("" : "+v"(cur[r]));
+            TL_STEP(wave == 0, 0, 8 + t);
+            char *stg = out_stage + ((h ^ 1) * 2 + par) * kOutBytes + stage_wr;  // (t is even where h is 0: step t - 1's buffer)
 #pragma unroll
-                for (int r = 0; r < R; ++r) asm volatile("" : "+v"(cur[r]));
-                TL_STEP(wave == 0, 0, 8 + t);
-                char *stg = out_stage + (((t - 1) & 1) * 2 + par) * kOutBytes + stage_wr;
-#pragma unroll
-                for (int kk = 0; kk < KSUB; ++kk) {
-                    // The next step's row addresses, well before their first use and a few instructions per MFMA: vector
-                    // work hides behind an MFMA only up to the 32 cycles that the MFMA itself takes (all of it in one
-                    // place, with 64-bit multiply-adds, cost the step 80 cycles).
-                    if (kk == 8) {
-                        ow += 64;
-                        asm volatile("" : "+v"(ow));
-                    }
-                    if (kk == 9 || kk == 10) {
-                        if (ow >= g.Q) {
-                            ow -= g.Q;
-                            ++slot;
-                        }
-                        asm volatile("" : "+v"(ow), "+v"(slot));
-                    }
-                    if (kk == 11) {
-                        slot = slot >= ring_rows ? slot - ring_rows : slot;
-                        asm volatile("" : "+v"(slot));
-                    }
-                    if (kk == 12) {
-                        nxt_px = lane_base + __umul24((uint32_t)ow, (uint32_t)kPix);
-                        asm volatile("" : "+v"(nxt_px));
-                    }
-                    if (kk >= 13 && kk < 13 + R) {
-                        const int r = kk - 13;
-                        int sl = slot + r;
-                        sl = sl >= ring_rows ? sl - ring_rows : sl;
-                        nxt[r] = nxt_px + __umul24((uint32_t)sl, row_pitch);
-                        asm volatile("" : "+v"(nxt[r]));
-                    }
-                    if (kk == kBar) {
-                        __builtin_amdgcn_s_waitcnt(0xC07F | (kWin << 8));
-                        wg_barrier();
-                    }
-                    if (kk == 0) {
-                        float16_t zero;
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) zero[e] = 0.f;
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], zero, 0, 0, 0);
-                    } else {
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
-                    }
-                    af[kk % kWin] = kk + kWin < KSUB ? read_frag(cur, kk + kWin) : read_frag(nxt, kk + kWin - KSUB);
-                    // The previous step's results go to the staging in four pieces, two early and two late in the
-                    // step (all four right behind the step's first MFMAs cost 30 cycles per step more).  The last one
-                    // must be complete when the barrier below lets the memory waves read it: LDS operations complete
-                    // in order and the barrier's wait leaves kWin of them in flight, so kWin operand reads follow it.
-                    constexpr int kStageAt[4] = {4, 6, 16, 17};
-                    static_assert(kStageAt[3] + kWin < kBar, "the last staging write is out of the window at the barrier");
-                    if (kk == kStageAt[0] || kk == kStageAt[1] || kk == kStageAt[2] || kk == kStageAt[3]) {
-                        const int a = kk == kStageAt[0] ? 0 : kk == kStageAt[1] ? 1 : kk == kStageAt[2] ? 2 : 3;
-                        if constexpr (sizeof(CT) == 4) {
-                            *reinterpret_cast<float4_t *>(stg + 8 * a * 4) =
-                                float4_t{prev[4 * a], prev[4 * a + 1], prev[4 * a + 2], prev[4 * a + 3]};
-                        } else {
-                            *reinterpret_cast<uint2_t *>(stg + 8 * a * 2) =
-                                uint2_t{pack_bf16(prev[4 * a], prev[4 * a + 1]), pack_bf16(prev[4 * a + 2], prev[4 * a + 3])};
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
+            for (int kk = 0; kk < KSUB; ++kk) {
+                // The next step's row addresses, well before their first use and a few instructions per MFMA: vector
+                // work hides behind an MFMA only up to the 32 cycles that the MFMA itself takes (all of it in one
+                // place, with 64-bit multiply-adds, cost the step 80 cycles).
+                if (kk == 8) {
+                    ow += 64;
+                    asm volatile("" : "+v"(ow));
                 }
+                if (kk == 9 || kk == 10) {
+                    if (ow >= g.Q) {
+                        ow -= g.Q;
+                        ++slot;
+                    }
+                    asm volatile("" : "+v"(ow), "+v"(slot));
+                }
+                if (kk == 11) {
+                    slot = slot >= ring_rows ? slot - ring_rows : slot;
+                    asm volatile("" : "+v"(slot));
+                }
+                if (kk == 12) {
+                    nxt_px = lane_base + __umul24((uint32_t)ow, (uint32_t)kPix);
+                    asm volatile("" : "+v"(nxt_px));
+                }
+                if (kk >= 13 && kk < 13 + R) {
+                    const int r = kk - 13;
+                    int sl = slot + r;
+                    sl = sl >= ring_rows ? sl - ring_rows : sl;
+                    nxt[r] = nxt_px + __umul24((uint32_t)sl, row_pitch);
+                    asm volatile("" : "+v"(nxt[r]));
+                }
+                if (kk == kBar) {
+                    __builtin_amdgcn_s_waitcnt(0xC07F | (kWin << 8));
+                    wg_barrier();
+                }
+                if (kk == 0) {
+                    float16_t zero;
 #pragma unroll
-                for (int r = 0; r < R; ++r) cur[r] = nxt[r];
+                    for (int e = 0; e < 16; ++e) zero[e] = 0.f;
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], zero, 0, 0, 0);
+                } else {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
+                }
+                af[kk % kWin] = kk + kWin < KSUB ? read_frag(cur, kk + kWin) : read_frag(nxt, kk + kWin - KSUB);
+                // The previous step's results go to the staging in four pieces, two early and two late in the
+                // step (all four right behind the step's first MFMAs cost 30 cycles per step more).  The last one
+                // must be complete when the barrier below lets the memory waves read it: LDS operations complete
+                // in order and the barrier's wait leaves kWin of them in flight, so kWin operand reads follow it.
+                constexpr int kStageAt[4] = {4, 6, 16, 17};
+                static_assert(kStageAt[3] + kWin < kBar, "the last staging write is out of the window at the barrier");
+                if (kk == kStageAt[0] || kk == kStageAt[1] || kk == kStageAt[2] || kk == kStageAt[3]) {
+                    const int a = kk == kStageAt[0] ? 0 : kk == kStageAt[1] ? 1 : kk == kStageAt[2] ? 2 : 3;
+                    if constexpr (sizeof(CT) == 4) {
+                        *reinterpret_cast<float4_t *>(stg + 8 * a * 4) =
+                            float4_t{prev[4 * a], prev[4 * a + 1], prev[4 * a + 2], prev[4 * a + 3]};
+                    } else {
+                        *reinterpret_cast<uint2_t *>(stg + 8 * a * 2) =
+                            uint2_t{pack_bf16(prev[4 * a], prev[4 * a + 1]), pack_bf16(prev[4 * a + 2], prev[4 * a + 3])};
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
+#pragma unroll
+            for (int r = 0; r < R; ++r) cur[r] = nxt[r];
+        };
+        int t0 = 2;
+        for (; t0 + 1 < nsteps; t0 += 2) {
+            do_step(t0, std::integral_constant<int, 0>{});
+            do_step(t0 + 1, std::integral_constant<int, 1>{});
         }
+        if (t0 < nsteps) do_step(t0, std::integral_constant<int, 0>{});
         // the last step's results
         TL_STAMP(wave == 0, 0, 6);
         const float16_t last = ((nsteps - 1) & 1) ? accs[1] : accs[0];
