@@ -979,17 +979,19 @@ __global__ __launch_bounds__(512) void conv2d_wsplit_kernel(const uint16_t *__re
         __builtin_amdgcn_s_waitcnt(0xC07F);
         wg_barrier();  // every wave is done with the weight staging; the rows under step 2 have landed
         TL_STAMP(wave == 0, 0, 5);
-        if (nsteps >= 2) {
-            stage_acc<CT>(accs[0], out_stage + par * kOutBytes + stage_wr);
-            __builtin_amdgcn_s_waitcnt(0xC07F);
-            wg_barrier();  // step 0 is staged
-        }
+        // step 2's first operands are asked for before step 0's results are staged: their latency passes behind the
+        // conversions and the barrier
         next_step();
         rows_of(cur);
 #pragma unroll
         for (int kk = 0; kk < kWin; ++kk) {
             af[kk] = read_frag(cur, kk);
             __builtin_amdgcn_sched_barrier(0);
+        }
+        if (nsteps >= 2) {
+            stage_acc<CT>(accs[0], out_stage + par * kOutBytes + stage_wr);
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            wg_barrier();  // step 0 is staged
         }
 
         // One step: `acc` collects this wave's block of step t (its first MFMA takes a literal zero as C), `prev`
