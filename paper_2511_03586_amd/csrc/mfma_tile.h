@@ -462,8 +462,11 @@ __device__ __forceinline__ void mfma_mainloop_k64(WaveTile16<2 * TM, 2 * TN> &t,
 #pragma unroll
     for (int j = 0; j < T16N; ++j) fb[0][j] = *reinterpret_cast<const bf16x8_t *>(smem + frag_b(j, 0));
 
-    for (int p = 0; p < ksteps; ++p) {
-        char *cur = smem + (p & 1) * kStageBytes64, *nxt = smem + ((p + 1) & 1) * kStageBytes64;
+    // (Steps are taken in pairs, so that the stage addresses are constants and a step boundary carries
+    // no loop control: a 16-cycle MFMA hides three or four other instructions, not twenty.)
+    auto k_step = [&](auto stage_c) {
+        constexpr int ST = decltype(stage_c)::value;
+        char *cur = smem + ST * kStageBytes64, *nxt = smem + (ST ^ 1) * kStageBytes64;
         wait_vmem_and_lds<kLoads>();  // the fragments of half 0 are back (loads of step p+1 may still fly)
         half_step(c0{}, c1{}, std::false_type{}, cur, cur);
         wait_vmem_and_lds<kLa>();  // own loads of step p+1 have landed (only this half's loads of step p+2 are younger)
@@ -471,7 +474,13 @@ __device__ __forceinline__ void mfma_mainloop_k64(WaveTile16<2 * TM, 2 * TN> &t,
         half_step(c1{}, c0{}, std::true_type{}, nxt, cur);
         src_a.advance();
         src_b.advance();
+    };
+    int p = 0;
+    for (; p + 1 < ksteps; p += 2) {
+        k_step(c0{});
+        k_step(c1{});
     }
+    if (p < ksteps) k_step(c0{});
     wait_vmem_and_lds<0>();  // drain the over-issued loads and reads before LDS is reused or released
     t.finish();  // MFMA -> VALU read distance (see mfma16)
 }
@@ -577,8 +586,9 @@ __device__ __forceinline__ void mfma_mainloop_k64_mi32(WaveTile<TM, TN> &t, char
 #pragma unroll
     for (int j = 0; j < kFb; ++j) fb[0][j] = *reinterpret_cast<const bf16x8_t *>(smem + frag_b(j, 0));
 
-    for (int p = 0; p < ksteps; ++p) {
-        char *cur = smem + (p & 1) * kStageBytes64, *nxt = smem + ((p + 1) & 1) * kStageBytes64;
+    auto k_step = [&](auto stage_c) {  // (in pairs, as in mfma_mainloop_k64)
+        constexpr int ST = decltype(stage_c)::value;
+        char *cur = smem + ST * kStageBytes64, *nxt = smem + (ST ^ 1) * kStageBytes64;
         wait_vmem_and_lds<kLoads>();  // the fragments of half 0 are back (loads of step p+1 may still fly)
         half_step(c0{}, c1{}, std::false_type{}, cur, cur);
         wait_vmem_and_lds<kLa>();  // own loads of step p+1 have landed (only this half's loads of step p+2 are younger)
@@ -586,7 +596,13 @@ __device__ __forceinline__ void mfma_mainloop_k64_mi32(WaveTile<TM, TN> &t, char
         half_step(c1{}, c0{}, std::true_type{}, nxt, cur);
         src_a.advance();
         src_b.advance();
+    };
+    int p = 0;
+    for (; p + 1 < ksteps; p += 2) {
+        k_step(c0{});
+        k_step(c1{});
     }
+    if (p < ksteps) k_step(c0{});
     wait_vmem_and_lds<0>();  // drain the over-issued loads and reads before LDS is reused or released
 }
 
