@@ -283,50 +283,54 @@ __global__ __launch_bounds__(512) void conv2d_wreg_kernel(const uint16_t *__rest
         // staged but never written out).  In the shadow of the first MFMAs `prev` is converted
         // and staged, then cleared for block b+1.  Before the barrier every read of this
         // block's slot has returned; after it block b+1 is complete in LDS.
-        for (int b0 = 0; b0 < nblocks; b0 += 2) {
+        // (blocks come in pairs that swap the two accumulators; the pair is the loop's unit, so that a block
+        // boundary carries no loop control)
+        auto do_block = [&](int b, auto hc) {
+            constexpr int h = decltype(hc)::value;
+            float16_t &acc = accs[h];
+            float16_t &prev = accs[h ^ 1];
+            const uint32_t cur = (uint32_t)(b % kSlots) * kSlot, nxt = (uint32_t)((b + 1) % kSlots) * kSlot;
+            uint32_t cur_lo = cur + frag_lo, cur_hi = cur + frag_hi;
+            uint32_t nxt_lo = nxt + frag_lo, nxt_hi = nxt + frag_hi;
+            // opaque to the optimiser: folded with the sub-tile offsets they turn into one address
+            // register per read, which does not fit the register budget of two waves per SIMD
+            asm volatile("" : "+v"(cur_lo), "+v"(cur_hi), "+v"(nxt_lo), "+v"(nxt_hi));
+            char *stg = out_stage + ((b - 1) & 1) * kOutBytes + stage_wr;
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int b = b0 + h;
-                if (b >= nblocks) break;
-                float16_t &acc = accs[h];
-                float16_t &prev = accs[h ^ 1];
-                const uint32_t cur = (uint32_t)(b % kSlots) * kSlot, nxt = (uint32_t)((b + 1) % kSlots) * kSlot;
-                uint32_t cur_lo = cur + frag_lo, cur_hi = cur + frag_hi;
-                uint32_t nxt_lo = nxt + frag_lo, nxt_hi = nxt + frag_hi;
-                // opaque to the optimiser: folded with the sub-tile offsets they turn into one address
-                // register per read, which does not fit the register budget of two waves per SIMD
-                asm volatile("" : "+v"(cur_lo), "+v"(cur_hi), "+v"(nxt_lo), "+v"(nxt_hi));
-                char *stg = out_stage + ((b - 1) & 1) * kOutBytes + stage_wr;
-#pragma unroll
-                for (int kk = 0; kk < KSUB - kWin; ++kk) {
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
-                    af[kk % kWin] = read_frag(cur_lo, cur_hi, kk + kWin);
-                    if (kk >= 1 && kk < 5) {
-                        const int a = kk - 1;
-                        if constexpr (sizeof(CT) == 4) {
-                            *reinterpret_cast<float4_t *>(stg + 8 * a * 4) =
-                                float4_t{prev[4 * a], prev[4 * a + 1], prev[4 * a + 2], prev[4 * a + 3]};
-                        } else {
-                            *reinterpret_cast<uint2_t *>(stg + 8 * a * 2) =
-                                uint2_t{pack_bf16(prev[4 * a], prev[4 * a + 1]), pack_bf16(prev[4 * a + 2], prev[4 * a + 3])};
-                        }
+            for (int kk = 0; kk < KSUB - kWin; ++kk) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
+                af[kk % kWin] = read_frag(cur_lo, cur_hi, kk + kWin);
+                if (kk >= 1 && kk < 5) {
+                    const int a = kk - 1;
+                    if constexpr (sizeof(CT) == 4) {
+                        *reinterpret_cast<float4_t *>(stg + 8 * a * 4) =
+                            float4_t{prev[4 * a], prev[4 * a + 1], prev[4 * a + 2], prev[4 * a + 3]};
+                    } else {
+                        *reinterpret_cast<uint2_t *>(stg + 8 * a * 2) =
+                            uint2_t{pack_bf16(prev[4 * a], prev[4 * a + 1]), pack_bf16(prev[4 * a + 2], prev[4 * a + 3])};
                     }
-                    if (kk >= 6 && kk < 10) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) prev[4 * (kk - 6) + e] = 0.f;
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
                 }
-                wait_vmem_and_lds<0>();
-                wg_barrier();
+                if (kk >= 6 && kk < 10) {
 #pragma unroll
-                for (int kk = KSUB - kWin; kk < KSUB; ++kk) {
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
-                    af[kk % kWin] = read_frag(nxt_lo, nxt_hi, kk + kWin - KSUB);
-                    __builtin_amdgcn_sched_barrier(0);
+                    for (int e = 0; e < 4; ++e) prev[4 * (kk - 6) + e] = 0.f;
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
+            wait_vmem_and_lds<0>();
+            wg_barrier();
+#pragma unroll
+            for (int kk = KSUB - kWin; kk < KSUB; ++kk) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
+                af[kk % kWin] = read_frag(nxt_lo, nxt_hi, kk + kWin - KSUB);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        int b0 = 0;
+        for (; b0 + 1 < nblocks; b0 += 2) {
+            do_block(b0, std::integral_constant<int, 0>{});
+            do_block(b0 + 1, std::integral_constant<int, 1>{});
         }
+        if (b0 < nblocks) do_block(b0, std::integral_constant<int, 0>{});
         // the last block's results
         const float16_t last = ((nblocks - 1) & 1) ? accs[1] : accs[0];
         stage_acc<CT>(last, out_stage + ((nblocks - 1) & 1) * kOutBytes + stage_wr);
@@ -546,59 +550,63 @@ __global__ __launch_bounds__(512) void conv2d_wres_kernel(const uint16_t *__rest
         // staged but never written out).  In the shadow of the first MFMAs `prev` is converted
         // and staged, then cleared for block b+1.  The barrier tells the memory waves that it is
         // staged, and the MFMA waves that the patch rows under block b+1 have landed.
-        for (int b0 = 0; b0 < nblocks; b0 += 2) {
+        // (blocks come in pairs that swap the two accumulators; the pair is the loop's unit, so that a block
+        // boundary carries no loop control)
+        auto do_block = [&](int b, auto hc) {
+            constexpr int h = decltype(hc)::value;
+            float16_t &acc = accs[h];
+            float16_t &prev = accs[h ^ 1];
+            next_block();
+            rows_of(nxt);
+            // opaque to the optimiser: folded with the tap offsets they would turn into one address
+            // register per read, which does not fit the register budget of two waves per SIMD
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int b = b0 + h;
-                if (b >= nblocks) break;
-                float16_t &acc = accs[h];
-                float16_t &prev = accs[h ^ 1];
-                next_block();
-                rows_of(nxt);
-                // opaque to the optimiser: folded with the tap offsets they would turn into one address
-                // register per read, which does not fit the register budget of two waves per SIMD
+            for (int r = 0; r < R; ++r) asm volatile("" : "+v"(cur[r]), "+v"(nxt[r]));
+            TL_STEP(wave == 0, 0, 8 + b);
+            char *stg = out_stage + ((b - 1) & 1) * kOutBytes + stage_wr;
+            char *stg16 = out_stage + ((b - 1) & 1) * kOutBytes + stage_wr16;
 #pragma unroll
-                for (int r = 0; r < R; ++r) asm volatile("" : "+v"(cur[r]), "+v"(nxt[r]));
-                TL_STEP(wave == 0, 0, 8 + b);
-                char *stg = out_stage + ((b - 1) & 1) * kOutBytes + stage_wr;
-                char *stg16 = out_stage + ((b - 1) & 1) * kOutBytes + stage_wr16;
-#pragma unroll
-                for (int kk = 0; kk < KSUB; ++kk) {
-                    if (kk == kBar) {
-                        // the staging writes are older than the window's reads: at most kWin LDS
-                        // operations outstanding means they are done (lgkmcnt only)
-                        __builtin_amdgcn_s_waitcnt(0xC07F | (kWin << 8));
-                        wg_barrier();
-                    }
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
-                    af[kk % kWin] = kk + kWin < KSUB ? read_frag(cur, kk + kWin) : read_frag(nxt, kk + kWin - KSUB);
-                    if constexpr (sizeof(CT) == 4) {
-                        if (kk >= 1 && kk < 5) {
-                            const int a = kk - 1;
-                            *reinterpret_cast<float4_t *>(stg + 8 * a * 4) =
-                                float4_t{prev[4 * a], prev[4 * a + 1], prev[4 * a + 2], prev[4 * a + 3]};
-                        }
-                    } else {
-                        if (kk == 1 || kk == 3) {
-                            const int a = kk - 1;  // element groups a and a + 1
-                            const uint32_t x0 = pack_bf16(prev[4 * a], prev[4 * a + 1]), x1 = pack_bf16(prev[4 * a + 2], prev[4 * a + 3]);
-                            const uint32_t y0 = pack_bf16(prev[4 * a + 4], prev[4 * a + 5]), y1 = pack_bf16(prev[4 * a + 6], prev[4 * a + 7]);
-                            // (lower half-wave: own group a, then the upper lane's; upper: the lower lane's group a+1, then own)
-                            const auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
-                            const auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
-                            *reinterpret_cast<uint4_t *>(stg16 + 8 * a * 2) = uint4_t{s0[0], s1[0], s0[1], s1[1]};
-                        }
-                    }
-                    if (kk >= 6 && kk < 10) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) prev[4 * (kk - 6) + e] = 0.f;
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
+            for (int kk = 0; kk < KSUB; ++kk) {
+                if (kk == kBar) {
+                    // the staging writes are older than the window's reads: at most kWin LDS
+                    // operations outstanding means they are done (lgkmcnt only)
+                    __builtin_amdgcn_s_waitcnt(0xC07F | (kWin << 8));
+                    wg_barrier();
                 }
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk], af[kk % kWin], acc, 0, 0, 0);
+                af[kk % kWin] = kk + kWin < KSUB ? read_frag(cur, kk + kWin) : read_frag(nxt, kk + kWin - KSUB);
+                if constexpr (sizeof(CT) == 4) {
+                    if (kk >= 1 && kk < 5) {
+                        const int a = kk - 1;
+                        *reinterpret_cast<float4_t *>(stg + 8 * a * 4) =
+                            float4_t{prev[4 * a], prev[4 * a + 1], prev[4 * a + 2], prev[4 * a + 3]};
+                    }
+                } else {
+                    if (kk == 1 || kk == 3) {
+                        const int a = kk - 1;  // element groups a and a + 1
+                        const uint32_t x0 = pack_bf16(prev[4 * a], prev[4 * a + 1]), x1 = pack_bf16(prev[4 * a + 2], prev[4 * a + 3]);
+                        const uint32_t y0 = pack_bf16(prev[4 * a + 4], prev[4 * a + 5]), y1 = pack_bf16(prev[4 * a + 6], prev[4 * a + 7]);
+                        // (lower half-wave: own group a, then the upper lane's; upper: the lower lane's group a+1, then own)
+                        const auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+                        const auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+                        *reinterpret_cast<uint4_t *>(stg16 + 8 * a * 2) = uint4_t{s0[0], s1[0], s0[1], s1[1]};
+                    }
+                }
+                if (kk >= 6 && kk < 10) {
 #pragma unroll
-                for (int r = 0; r < R; ++r) cur[r] = nxt[r];
+                    for (int e = 0; e < 4; ++e) prev[4 * (kk - 6) + e] = 0.f;
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
+#pragma unroll
+            for (int r = 0; r < R; ++r) cur[r] = nxt[r];
+        };
+        int b0 = 0;
+        for (; b0 + 1 < nblocks; b0 += 2) {
+            do_block(b0, std::integral_constant<int, 0>{});
+            do_block(b0 + 1, std::integral_constant<int, 1>{});
         }
+        if (b0 < nblocks) do_block(b0, std::integral_constant<int, 0>{});
         // the last block's results
         TL_STAMP(wave == 0, 0, 4);
         const float16_t last = ((nblocks - 1) & 1) ? accs[1] : accs[0];
